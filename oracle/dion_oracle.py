@@ -1,0 +1,259 @@
+"""CPU oracle of the Dion optimizer step.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, fp64 numpy written from the paper's algorithm statement (Algorithm
+"Unsharded Dion update rule" with its PowerIter1 sub-routine, the outer step of
+Algorithm 1, the error-feedback equation of Section 3.1 and the Orthonormalize
+discussion of Section 3.2 / Appendix A).  It shares no code with the HIP library and
+must never be imported by the product path: only tests, the smoke check and the
+benchmark's cpu_baseline leg may call it.
+
+Names: the paper's current text writes V, P, U, W, beta; this file uses the names of
+the paper's future-work paragraph and of the library's interface:
+    Q = V (right factor, n x r)     Z = P (power-iteration product, m x r)
+    P = U (orthonormal left factor) R = W (right factor before ColNorm)
+    mu = 1 - beta                   B = M + G (buffer after accumulation)
+
+Every function is pinned by tests that do not use the function itself (closed forms,
+a brute-force Jacobi SVD, LAPACK's QR, hand-computed tiny cases); nothing here is
+"parity unpinned".  Two conventions are ours because the paper is silent: the ColNorm
+guard COLNORM_EPS and the rank-deficiency threshold BREAKDOWN_TOL.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+COLNORM_EPS = 1e-8      # ColNorm divides by (||R_j|| + eps): a zero column stays zero
+BREAKDOWN_TOL = 1e-12   # |T_jj| <= tol * max|T_kk|  => Z is numerically rank deficient
+
+STATUS_OK = 0
+STATUS_BREAKDOWN = 1
+
+
+def _f64(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+def accumulate(M, G):
+    """B = M + G (first line of the unsharded update rule)."""
+    return _f64(M) + _f64(G)
+
+
+def householder_qr(Z):
+    """Thin QR of Z (m x r, m >= r) by Householder reflections, unblocked, fp64.
+
+    Returns (P, T): P is m x r with orthonormal columns, T is r x r upper triangular with
+    a non-negative diagonal and Z = P T.  For full-column-rank Z this factorisation is
+    unique, which is what makes "Orthonormalize" (Section 3.2: a QR decomposition or one of
+    its faster variants) a well-defined function up to the column signs fixed here.
+    """
+    A = _f64(Z).copy()
+    m, r = A.shape
+    if m < r:
+        raise ValueError("householder_qr needs m >= r")
+    V = []
+    for k in range(r):
+        x = A[k:, k]
+        normx = np.sqrt(np.dot(x, x))
+        v = x.copy()
+        if normx == 0.0:
+            # nothing to annihilate; identity reflector (v = 0)
+            V.append(np.zeros_like(v))
+            continue
+        alpha = -normx if x[0] >= 0.0 else normx
+        v[0] -= alpha
+        v /= np.sqrt(np.dot(v, v))
+        V.append(v)
+        # apply H = I - 2 v v^T to the trailing block
+        A[k:, k:] -= 2.0 * np.outer(v, v @ A[k:, k:])
+    T = np.triu(A[:r, :r])
+    # P = H_0 H_1 ... H_{r-1} applied to the first r columns of the identity
+    P = np.zeros((m, r))
+    P[np.arange(r), np.arange(r)] = 1.0
+    for k in range(r - 1, -1, -1):
+        v = V[k]
+        P[k:, :] -= 2.0 * np.outer(v, v @ P[k:, :])
+    # make diag(T) >= 0:  Z = (P S)(S T) for any sign matrix S
+    sgn = np.where(np.diag(T) < 0.0, -1.0, 1.0)
+    P *= sgn[None, :]
+    T *= sgn[:, None]
+    return P, T
+
+
+def lapack_qr(Z):
+    """The same thin-QR factor through the library routine (for sizes where the
+    unblocked loop above would take minutes).  Same sign convention."""
+    P, T = np.linalg.qr(_f64(Z), mode="reduced")
+    sgn = np.where(np.diag(T) < 0.0, -1.0, 1.0)
+    return P * sgn[None, :], T * sgn[:, None]
+
+
+def orthonormalize(Z, method="householder"):
+    """P = Orthonormalize(Z): the Q-factor of the thin QR of Z (PowerIter1, Section 3.2).
+
+    Returns (P, T, status).  status is STATUS_BREAKDOWN when Z is numerically rank
+    deficient (Appendix A: the fast orthonormalisation reports failure instead of
+    returning garbage); P is then not meaningful.
+    """
+    if method == "householder":
+        P, T = householder_qr(Z)
+    elif method == "lapack":
+        P, T = lapack_qr(Z)
+    else:
+        raise ValueError(method)
+    d = np.abs(np.diag(T))
+    status = STATUS_OK
+    if not np.all(np.isfinite(d)) or d.max() == 0.0 or d.min() <= BREAKDOWN_TOL * d.max():
+        status = STATUS_BREAKDOWN
+    return P, T, status
+
+
+def power_iter1(B, Q, method="householder"):
+    """One power-iteration step (PowerIter1, without the data-parallel all-reduces):
+    Z = B Q;  P = Orthonormalize(Z);  R = B^T P.  Returns (P, R, Z, T, status)."""
+    B = _f64(B)
+    Q = _f64(Q)
+    Z = B @ Q
+    P, T, status = orthonormalize(Z, method)
+    R = B.T @ P
+    return P, R, Z, T, status
+
+
+def col_norm(R):
+    """ColNorm: divide every column by its Euclidean norm.  Returns (Q_new, s), s_j = ||R_j||."""
+    R = _f64(R)
+    s = np.sqrt(np.sum(R * R, axis=0))
+    return R / (s + COLNORM_EPS)[None, :], s
+
+
+def dion_step(X, G, M, Q, mu, eta, method="householder"):
+    """One Dion step for one m x n matrix (unsharded update rule + X_new = X - eta * O).
+
+    Inputs are the stored values (any float dtype; bf16 gradients are passed already
+    upcast, which is exact); all arithmetic is fp64.  Returns a dict with X, M, Q (new
+    state, fp64), the intermediates Z, P, R, T, s and `status`.  On STATUS_BREAKDOWN the
+    state is returned unchanged.
+    """
+    X = _f64(X)
+    m, n = X.shape
+    B = accumulate(M, G)                                   # M <- M + G
+    P, R, Z, T, status = power_iter1(B, Q, method)         # U, W <- PowerIter1(M, V)
+    if status != STATUS_OK:
+        return dict(X=X, M=_f64(M), Q=_f64(Q), Z=Z, P=P, R=R, T=T, s=None, B=B, status=status)
+    beta = 1.0 - mu
+    M_new = B - beta * (P @ R.T)                           # error feedback
+    Q_new, s = col_norm(R)                                 # V_new <- ColNorm(W)
+    O = P @ Q_new.T                                        # orthonormal update
+    X_new = X - eta * np.sqrt(m / n) * O                   # scaled by sqrt(|I|/|J|)
+    return dict(X=X_new, M=M_new, Q=Q_new, Z=Z, P=P, R=R, T=T, s=s, B=B, status=status)
+
+
+def init_state(m, n, Q_raw):
+    """Initial optimizer state: M = 0 and Q = ColNorm(Q_raw) with Q_raw i.i.d. N(0,1).
+    (The paper gives the state as (M, V) without an initialiser; this is the
+    benchmark configurations' choice.)"""
+    Q, _ = col_norm(Q_raw)
+    return np.zeros((m, n)), Q
+
+
+def run_steps(X, grads, M, Q, mu, eta, method="householder", store=np.float32):
+    """Run len(grads) steps, rounding the state to the storage dtype (fp32) after each step,
+    as the library's caller-owned fp32 buffers do.  Returns the list of per-step dicts
+    (state entries already rounded)."""
+    out = []
+    X = np.asarray(X, dtype=store)
+    M = np.asarray(M, dtype=store)
+    Q = np.asarray(Q, dtype=store)
+    for G in grads:
+        res = dion_step(X, G, M, Q, mu, eta, method)
+        X = res["X"].astype(store)
+        M = res["M"].astype(store)
+        Q = res["Q"].astype(store)
+        res = dict(res, X=X, M=M, Q=Q)
+        out.append(res)
+    return out
+
+
+# ---- per-entry forms, for sampled checks at sizes where a full fp64 step is too slow ----
+
+def entry_Z(M, G, Q, rows, cols):
+    """Z[i, a] = sum_j (M[i,j] + G[i,j]) Q[j,a] for the listed (i, a) pairs."""
+    Qd = _f64(Q)
+    out = np.empty(len(rows))
+    for t, (i, a) in enumerate(zip(rows, cols)):
+        out[t] = np.dot(_f64(M[i, :]) + _f64(G[i, :]), Qd[:, a])
+    return out
+
+
+def entry_R(M, G, P, rows, cols):
+    """R[j, a] = sum_i (M[i,j] + G[i,j]) P[i,a] for the listed (j, a) pairs."""
+    out = np.empty(len(rows))
+    for t, (j, a) in enumerate(zip(rows, cols)):
+        out[t] = np.dot(_f64(M[:, j]) + _f64(G[:, j]), _f64(P[:, a]))
+    return out
+
+
+def entry_update(X, G, M, P, R, mu, eta, rows, cols):
+    """(X_new[i,j], M_new[i,j]) for listed (i, j) pairs, given the factors P and R:
+    M_new = B - (1-mu) P R^T;  X_new = X - eta sqrt(m/n) P ColNorm(R)^T."""
+    m, n = X.shape
+    R = _f64(R)
+    s = np.sqrt(np.sum(R * R, axis=0))
+    d = 1.0 / (s + COLNORM_EPS)
+    xs = np.empty(len(rows))
+    ms = np.empty(len(rows))
+    c = eta * np.sqrt(m / n)
+    for t, (i, j) in enumerate(zip(rows, cols)):
+        p = _f64(P[i, :])
+        rj = R[j, :]
+        ms[t] = (float(M[i, j]) + float(G[i, j])) - (1.0 - mu) * np.dot(p, rj)
+        xs[t] = float(X[i, j]) - c * np.dot(p, rj * d)
+    return xs, ms
+
+
+# ---- counter-based Gaussian fill used by the library's init call when it draws Q itself ----
+
+_PHILOX_M0 = 0xD2511F53
+_PHILOX_M1 = 0xCD9E8D57
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """Philox-4x32 with 10 rounds (Salmon et al., "Parallel random numbers: as easy as
+    1, 2, 3", SC'11).  counter: (..., 4) uint32, key: (2,) uint32.  Returns (..., 4) uint32."""
+    c = np.array(counter, dtype=np.uint64)
+    k0 = np.uint64(key[0])
+    k1 = np.uint64(key[1])
+    mask = np.uint64(0xFFFFFFFF)
+    c0, c1, c2, c3 = c[..., 0], c[..., 1], c[..., 2], c[..., 3]
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c0
+        p1 = np.uint64(_PHILOX_M1) * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & mask
+        hi1, lo1 = p1 >> np.uint64(32), p1 & mask
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ k0) & mask, lo1, (hi0 ^ c3 ^ k1) & mask, lo0
+        k0 = (k0 + np.uint64(_PHILOX_W0)) & mask
+        k1 = (k1 + np.uint64(_PHILOX_W1)) & mask
+    return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
+
+
+def gaussian_fill(count, seed, stream):
+    """count N(0,1) values, element e drawn from Philox block e//4 (counter = (e//4, 0,
+    stream, 0), key = (seed low, seed high)): words (0,1) and (2,3) of a block feed two
+    Box-Muller transforms, u1 = (w+1)/2^32 in (0,1], u2 = w'/2^32; elements 4b..4b+3 are
+    (r1 cos, r1 sin, r2 cos, r2 sin)."""
+    nblk = (count + 3) // 4
+    ctr = np.zeros((nblk, 4), dtype=np.uint64)
+    ctr[:, 0] = np.arange(nblk, dtype=np.uint64) & np.uint64(0xFFFFFFFF)
+    ctr[:, 1] = np.arange(nblk, dtype=np.uint64) >> np.uint64(32)
+    ctr[:, 2] = np.uint64(stream)
+    key = (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    w = philox4x32_10(ctr, key).astype(np.float64)
+    out = np.empty((nblk, 4))
+    for h in range(2):
+        u1 = (w[:, 2 * h] + 1.0) / 4294967296.0
+        u2 = w[:, 2 * h + 1] / 4294967296.0
+        rad = np.sqrt(-2.0 * np.log(u1))
+        out[:, 2 * h] = rad * np.cos(2.0 * np.pi * u2)
+        out[:, 2 * h + 1] = rad * np.sin(2.0 * np.pi * u2)
+    return out.reshape(-1)[:count]
