@@ -1,0 +1,126 @@
+/*
+ * dion.h — C ABI of the MI355X (gfx950) Dion optimizer-step library (libdion.so).
+ *
+ * The library computes one step of the Dion optimizer for one matrix parameter, or for a
+ * batch of them, following the paper's Algorithm 1 (outer step) with the unsharded update
+ * rule and its PowerIter1 sub-routine (Section 3), the error-feedback equation of
+ * Section 3.1, and Cholesky-QR orthonormalisation (Section 3.2, Appendix A):
+ *
+ *     B     = M + G                        (never stored; fused into operand loads)
+ *     Z     = B Q                          (m x r)
+ *     P     = Orthonormalize(Z)            (thin-QR factor, by CholeskyQR2)
+ *     R     = B^T P                        (n x r)
+ *     M_new = B - (1 - mu) P R^T           (error feedback; the paper's beta = 1 - mu)
+ *     Q_new = ColNorm(R)                   (each column divided by (its 2-norm + 1e-8))
+ *     X_new = X - eta sqrt(m/n) P Q_new^T  (m = "out" rows, n = "in" columns)
+ *
+ * Names: the paper's V, P, U, W, beta are Q, Z, P, R, 1 - mu here.
+ *
+ * Conventions
+ *   - All matrices are row-major and contiguous: X, G, M have leading dimension n, Q has r.
+ *   - X, M, Q are fp32 and updated in place; G is read only (fp32 or bf16, see DION_G_*).
+ *   - Every pointer named *_dev / X / G / M / Q is DEVICE memory owned by the caller and must
+ *     be 16-byte aligned; pointer arrays and shape arrays are HOST memory, read during the call.
+ *   - X, G, M, Q and the workspace must not overlap one another.
+ *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without waiting; only dion_last_status and
+ *     dion_stage_times synchronise.
+ *   - Return value: 0 on success, < 0 for a usage or runtime error found on the host (then
+ *     nothing was launched by that call and no state was touched).  Numerical trouble is
+ *     found on the device and reported later by dion_last_status.
+ *   - No function throws; the library keeps no global state; one dion_state_t must not be
+ *     used from two threads at once, and steps sharing a state must run on one stream.
+ *   - Precondition 1 <= r <= min(m, n).
+ */
+#ifndef DION_H
+#define DION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DION_OK = 0,
+  DION_EINVAL = -1,      /* null/misaligned pointer, m|n|r <= 0, r > min(m,n), mu outside [0,1], non-finite mu/eta,
+                            shapes that were not declared to dion_init_state */
+  DION_EWORKSPACE = -2,  /* workspace too small */
+  DION_ELAUNCH = -3,     /* a HIP runtime call failed */
+  DION_ENOMEM = -4,      /* host allocation failed */
+  DION_NUM_BREAKDOWN = 1 /* Cholesky met a non-positive or non-finite pivot: Z is rank deficient or too ill
+                            conditioned for Cholesky-QR (Appendix A); X, M, Q of that matrix were left untouched */
+};
+
+enum { DION_G_F32 = 0, DION_G_BF16 = 1 };       /* storage type of the gradient G */
+enum { DION_MATH_F32 = 0, DION_MATH_BF16 = 1 }; /* operand type of the four large products (Z, R and the two
+                                                   rank-r updates); accumulation, the orthonormalisation and all
+                                                   state are fp32 in both modes */
+
+typedef struct dion_state dion_state_t; /* opaque host object: declared shapes, flags, carved workspace */
+
+/* Bytes of device workspace needed for `count` matrices of shapes (m[i], n[i], r[i]).
+ * m, n, r: host arrays of length count.  Writes *bytes_out. */
+int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const int64_t* r,
+                         int g_dtype, int math, size_t* bytes_out);
+
+/* Creates the optimizer state for `count` matrices (Algorithm 1: the state of a matrix is its
+ * momentum M and right factor Q) and initialises it on the device:
+ *   M[i] <- 0;   Q[i] <- ColNorm(Q[i]) if q_is_filled, else ColNorm of an m x r draw of N(0,1)
+ *   (Philox-4x32-10 keyed by `seed`, stream = i, Box-Muller).
+ * workspace_dev: device buffer of at least dion_workspace_bytes(...) bytes, 256-byte aligned,
+ * owned by the caller and kept alive until dion_destroy_state.  M_dev / Q_dev: host arrays of
+ * `count` device pointers.  *st receives the new state (release with dion_destroy_state). */
+int dion_init_state(dion_state_t** st, int count, const int64_t* m, const int64_t* n, const int64_t* r,
+                    int g_dtype, int math, void* workspace_dev, size_t workspace_bytes,
+                    void* const* M_dev, void* const* Q_dev, int q_is_filled, uint64_t seed,
+                    void* hip_stream);
+
+/* One Dion step for one matrix (Algorithm 1 with the unsharded update rule).  The shape
+ * (m, n, r) must be one declared to dion_init_state.  mu in [0,1] (the paper's 1 - beta),
+ * eta = learning rate. */
+int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q,
+              int64_t m, int64_t n, int64_t r, float mu, float eta, void* hip_stream);
+
+/* One Dion step for `count` matrices (the paper's batch axis over same-shaped matrices,
+ * Section 4.1): matrices of equal shape are processed together by grouped kernel launches.
+ * X, G, M, Q: host arrays of device pointers; m, n, r: host arrays; matrix i must have the
+ * shape declared as entry i of dion_init_state.  count = 0 is a no-op. */
+int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* const* G,
+                      void* const* M, void* const* Q, const int64_t* m, const int64_t* n,
+                      const int64_t* r, float mu, float eta, void* hip_stream);
+
+/* Waits for the stream of the last step and reports its numerical status: *status_out is
+ * DION_OK or DION_NUM_BREAKDOWN; *first_bad_index is the lowest matrix index that broke
+ * down (-1 if none).  Either pointer may be NULL. */
+int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
+
+/* Stage timing.  With enable != 0 every later step brackets its stages with HIP events on
+ * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <
+ * DION_STAGE_COUNT, the summed duration in milliseconds of that stage over the last call. */
+enum {
+  DION_STAGE_K1_BQ = 0,     /* Z = (M+G) Q */
+  DION_STAGE_ORTH = 1,      /* CholeskyQR2 */
+  DION_STAGE_K2_BTP = 2,    /* R = (M+G)^T P */
+  DION_STAGE_COLNORM = 3,   /* column norms of R and Q_new = R diag(d) */
+  DION_STAGE_K5_UPDATE = 4, /* fused M and X update */
+  DION_STAGE_COUNT = 5
+};
+int dion_set_stage_timing(dion_state_t* st, int enable);
+int dion_stage_times(dion_state_t* st, float* ms_out /* [DION_STAGE_COUNT] */);
+
+/* Test access to the intermediates of matrix `index` left in the workspace by the last step:
+ * which = 0: Z of the first pass' input (m x r, overwritten by P), 1: P (m x r), 2: R (n x r),
+ * 3: column norms s (r), 4: status word (int32).  Writes the device pointer and the leading
+ * dimension (elements). */
+int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, int64_t* ld_out);
+
+int dion_destroy_state(dion_state_t* st);
+
+const char* dion_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DION_H */

@@ -1,0 +1,226 @@
+"""ctypes binding of libdion.so: the same entry points as include/dion.h, argument marshalling only.
+
+PyTorch tensors are used as handles to device memory (``data_ptr()``) and for the current HIP
+stream; every step of the Dion update runs in the library's HIP kernels.  There is no CPU
+fallback: if the library has not been built, importing works but every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdion.so")
+
+DION_OK = 0
+DION_EINVAL = -1
+DION_EWORKSPACE = -2
+DION_ELAUNCH = -3
+DION_ENOMEM = -4
+DION_NUM_BREAKDOWN = 1
+DION_G_F32, DION_G_BF16 = 0, 1
+DION_MATH_F32, DION_MATH_BF16 = 0, 1
+STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
+DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D = range(10)
+
+EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_last_status",
+           "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+
+_lib = None
+
+
+class DionError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, strerror(code), code))
+
+
+def lib() -> C.CDLL:
+    """Loads libdion.so (built by ``python -m paper_2504_05295_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libdion.so is not built: run `python -m paper_2504_05295_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        i64p, vpp = C.POINTER(C.c_int64), C.POINTER(C.c_void_p)
+        L.dion_workspace_bytes.argtypes = [C.c_int, i64p, i64p, i64p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+        L.dion_init_state.argtypes = [C.POINTER(C.c_void_p), C.c_int, i64p, i64p, i64p, C.c_int, C.c_int, C.c_void_p,
+                                      C.c_size_t, vpp, vpp, C.c_int, C.c_uint64, C.c_void_p]
+        L.dion_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                C.c_int64, C.c_float, C.c_float, C.c_void_p]
+        L.dion_step_batched.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
+                                        C.c_float, C.c_void_p]
+        L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
+        L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+        L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
+        L.dion_destroy_state.argtypes = [C.c_void_p]
+        L.dion_strerror.argtypes = [C.c_int]
+        L.dion_strerror.restype = C.c_char_p
+        for name in EXPORTS:
+            if name != "dion_strerror":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().dion_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code < 0:
+        raise DionError(code, where)
+    return code
+
+
+def _i64(vals: Sequence[int]):
+    return (C.c_int64 * len(vals))(*[int(v) for v in vals])
+
+
+def _ptrs(tensors) -> "C.Array":
+    return (C.c_void_p * len(tensors))(*[C.c_void_p(_ptr(t)) for t in tensors])
+
+
+def _ptr(t) -> int:
+    return int(t) if isinstance(t, int) else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    elif hasattr(stream, "cuda_stream"):
+        stream = stream.cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def _check_tensor(t, dtype, shape, name):
+    import torch
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("%s must be a torch tensor" % name)
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must be a contiguous device tensor of dtype %s and shape %s (got %s %s)"
+                         % (name, dtype, tuple(shape), t.dtype, tuple(t.shape)))
+
+
+class DionState:
+    """Owner of a dion_state_t* (and of the references that keep its workspace alive)."""
+
+    def __init__(self, handle, shapes, g_dtype, math, workspace):
+        self.handle = handle
+        self.shapes = list(shapes)
+        self.g_dtype = g_dtype
+        self.math = math
+        self.workspace = workspace
+
+    def close(self):
+        if self.handle:
+            lib().dion_destroy_state(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def dion_workspace_bytes(shapes: Sequence[Tuple[int, int, int]], g_dtype: int, math: int) -> int:
+    m, n, r = _i64([s[0] for s in shapes]), _i64([s[1] for s in shapes]), _i64([s[2] for s in shapes])
+    out = C.c_size_t(0)
+    _check(lib().dion_workspace_bytes(len(shapes), m, n, r, g_dtype, math, C.byref(out)), "dion_workspace_bytes")
+    return int(out.value)
+
+
+def dion_init_state(shapes, g_dtype, math, M: List, Q: List, q_is_filled: bool = True, seed: int = 0,
+                    workspace=None, stream=None) -> DionState:
+    """Creates the state for matrices of `shapes` = [(m, n, r), ...]; zero-fills M, column-normalises Q
+    (drawing it first when q_is_filled is False).  `workspace`: a uint8 device tensor, allocated here if None."""
+    import torch
+    need = dion_workspace_bytes(shapes, g_dtype, math)
+    if workspace is None:
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    base = workspace.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    avail = workspace.numel() - (aligned - base)
+    for i, (m, n, r) in enumerate(shapes):
+        _check_tensor(M[i], torch.float32, (m, n), "M[%d]" % i)
+        _check_tensor(Q[i], torch.float32, (n, r), "Q[%d]" % i)
+    handle = C.c_void_p(None)
+    m, n, r = _i64([s[0] for s in shapes]), _i64([s[1] for s in shapes]), _i64([s[2] for s in shapes])
+    _check(lib().dion_init_state(C.byref(handle), len(shapes), m, n, r, g_dtype, math, C.c_void_p(aligned), avail,
+                                 _ptrs(M), _ptrs(Q), 1 if q_is_filled else 0, int(seed), _stream(stream)),
+           "dion_init_state")
+    return DionState(handle, shapes, g_dtype, math, workspace)
+
+
+def _g_dtype(state):
+    import torch
+    return torch.bfloat16 if state.g_dtype == DION_G_BF16 else torch.float32
+
+
+def dion_step(state: DionState, X, G, M, Q, mu: float, eta: float, stream=None) -> None:
+    import torch
+    m, n = X.shape
+    r = Q.shape[1]
+    _check_tensor(X, torch.float32, (m, n), "X")
+    _check_tensor(G, _g_dtype(state), (m, n), "G")
+    _check_tensor(M, torch.float32, (m, n), "M")
+    _check_tensor(Q, torch.float32, (n, r), "Q")
+    _check(lib().dion_step(state.handle, _ptr(X), _ptr(G), _ptr(M), _ptr(Q), m, n, r, mu, eta, _stream(stream)), "dion_step")
+
+
+def dion_step_batched(state: DionState, X: List, G: List, M: List, Q: List, mu: float, eta: float, stream=None) -> None:
+    import torch
+    count = len(X)
+    for i in range(count):
+        m, n, r = state.shapes[i]
+        _check_tensor(X[i], torch.float32, (m, n), "X[%d]" % i)
+        _check_tensor(G[i], _g_dtype(state), (m, n), "G[%d]" % i)
+        _check_tensor(M[i], torch.float32, (m, n), "M[%d]" % i)
+        _check_tensor(Q[i], torch.float32, (n, r), "Q[%d]" % i)
+    sh = state.shapes[:count]
+    _check(lib().dion_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(Q), _i64([s[0] for s in sh]),
+                                   _i64([s[1] for s in sh]), _i64([s[2] for s in sh]), mu, eta, _stream(stream)),
+           "dion_step_batched")
+
+
+def dion_last_status(state: DionState) -> Tuple[int, int]:
+    """Synchronises the last step's stream; returns (status, first_bad_index)."""
+    st, bad = C.c_int(0), C.c_int(-1)
+    _check(lib().dion_last_status(state.handle, C.byref(st), C.byref(bad)), "dion_last_status")
+    return int(st.value), int(bad.value)
+
+
+def dion_set_stage_timing(state: DionState, enable: bool) -> None:
+    _check(lib().dion_set_stage_timing(state.handle, 1 if enable else 0), "dion_set_stage_timing")
+
+
+def dion_stage_times(state: DionState) -> dict:
+    arr = (C.c_float * len(STAGES))()
+    _check(lib().dion_stage_times(state.handle, arr), "dion_stage_times")
+    return {k: float(arr[i]) for i, k in enumerate(STAGES)}
+
+
+def dion_debug_buffer(state: DionState, index: int, which: int):
+    """Returns a torch view (no copy) of an intermediate left in the workspace by the last step."""
+    import torch
+    p, ld = C.c_void_p(None), C.c_int64(0)
+    _check(lib().dion_debug_buffer(state.handle, index, which, C.byref(p), C.byref(ld)), "dion_debug_buffer")
+    m, n, r = state.shapes[index]
+    rows = {DEBUG_Z: m, DEBUG_P: m, DEBUG_P1: m, DEBUG_R: n, DEBUG_S: r, DEBUG_D: r, DEBUG_STATUS: 1,
+            DEBUG_C: int(ld.value), DEBUG_L: int(ld.value), DEBUG_W: int(ld.value)}[which]
+    cols = int(ld.value)
+    dtype = torch.int32 if which == DEBUG_STATUS else torch.float32
+    nbytes = rows * cols * 4
+    ws = state.workspace
+    off = int(p.value) - ws.data_ptr()
+    assert 0 <= off and off + nbytes <= ws.numel()
+    return ws[off:off + nbytes].view(dtype).view(rows, cols)
+
+
+def dion_destroy_state(state: DionState) -> None:
+    state.close()

@@ -1,0 +1,579 @@
+// C ABI of libdion.so and the host-side sequencing of one Dion step (see include/dion.h).
+//
+// Sequence per shape group (Algorithm 1 + unsharded update rule + PowerIter1 of the paper; the
+// data-parallel all-reduces of PowerIter1 are absent because everything runs on one GPU):
+//   K1  Z = (M+G) Q                      MFMA GEMM, M+G fused into the operand load
+//   orth: CholeskyQR2 (Appendix A applied twice): Gram, blocked Cholesky, triangular inverse, Z L^-T
+//   K2  R = (M+G)^T P                    MFMA GEMM, transposing operand load
+//   K6  s_j = ||R_j||, d_j = 1/(s_j + eps);   K7  Q = R diag(d)
+//   K5  M = (M+G) - (1-mu) P R^T ;  X = X - eta sqrt(m/n) P Q^T     one fused pass
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "../../include/dion.h"
+#include "internal.hpp"
+
+using namespace dion;
+
+namespace dion {
+int pick_variant(long long M, long long N, long long K, long long batch, bool aligned) {
+  const bool big_ok = aligned && M % 128 == 0 && N % 128 == 0 && K % 32 == 0;
+  const bool small_ok = aligned && M % 64 == 0 && N % 64 == 0 && K % 64 == 0;
+  if (big_ok) {
+    const long long tiles = (M / 128) * (N / 128) * batch;
+    return (tiles >= 256 || !small_ok) ? VAR_BIG : VAR_SMALL;
+  }
+  return small_ok ? VAR_SMALL : VAR_SMALL_CHECKED;
+}
+}  // namespace dion
+
+namespace {
+
+struct Entry {
+  int64_t m, n, r;
+  int group;
+  int row;  // row of the pointer table (group-sorted order)
+};
+struct Group {
+  int64_t m, n, r;
+  int rp;          // r padded to CHOL_NB * 2^p
+  int first_row, count;
+  int gram_variant, gram_splitk, gram_kps;
+  size_t bytes_per_entry;
+};
+
+constexpr int kEventsPerGroup = DION_STAGE_COUNT + 1;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int padded_rank(int64_t r) {
+  int64_t rp = CHOL_NB;
+  while (rp < r) rp *= 2;
+  return (int)rp;
+}
+
+void plan_gram(Group& g) {
+  g.gram_variant = pick_variant(g.r, g.r, g.m, g.count, true);
+  const int bt = (g.gram_variant == VAR_BIG) ? 128 : 64;
+  const int bk = (g.gram_variant == VAR_BIG) ? 32 : 64;
+  const long long t1 = (g.r + bt - 1) / bt;
+  const long long tiles = t1 * (t1 + 1) / 2 * g.count;
+  long long want = (512 + tiles - 1) / tiles;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  long long kps = (g.m + want - 1) / want;
+  kps = (kps + 2 * bk - 1) / (2 * bk) * (2 * bk);
+  g.gram_kps = (int)kps;
+  g.gram_splitk = (int)((g.m + kps - 1) / kps);
+}
+
+// workspace floats of one matrix, in slot order
+struct Carve {
+  size_t off[NSLOTS];
+  size_t total;
+};
+Carve carve_entry(const Group& g) {
+  Carve c;
+  memset(&c, 0, sizeof(c));
+  size_t pos = 0;
+  auto take = [&](int slot, size_t floats) {
+    c.off[slot] = pos;
+    pos += align_up(floats * sizeof(float), 256);
+  };
+  const size_t mr = (size_t)g.m * g.r, nr = (size_t)g.n * g.r, rr = (size_t)g.rp * g.rp;
+  take(SLOT_Z, mr);
+  take(SLOT_P1, mr);
+  take(SLOT_P, mr);
+  take(SLOT_R, nr);
+  take(SLOT_C, rr);
+  take(SLOT_L, rr);
+  take(SLOT_W, rr);
+  take(SLOT_T, rr);
+  take(SLOT_CPART, g.gram_splitk > 1 ? rr * g.gram_splitk : 0);
+  take(SLOT_SPART, (size_t)((g.n + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
+  take(SLOT_S, g.r);
+  take(SLOT_D, g.r);
+  c.total = pos;
+  return c;
+}
+
+bool shapes_ok(int count, const int64_t* m, const int64_t* n, const int64_t* r) {
+  if (count < 0) return false;
+  if (count > 0 && (!m || !n || !r)) return false;
+  for (int i = 0; i < count; ++i) {
+    if (m[i] <= 0 || n[i] <= 0 || r[i] <= 0) return false;
+    if (r[i] > m[i] || r[i] > n[i]) return false;
+    if (m[i] > 0x7fffff00LL || n[i] > 0x7fffff00LL) return false;
+    if (r[i] > 32768) return false;
+  }
+  return true;
+}
+
+bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r, std::vector<Entry>& entries,
+                std::vector<Group>& groups) {
+  entries.resize(count);
+  groups.clear();
+  for (int i = 0; i < count; ++i) {
+    int gi = -1;
+    for (size_t k = 0; k < groups.size(); ++k)
+      if (groups[k].m == m[i] && groups[k].n == n[i] && groups[k].r == r[i]) gi = (int)k;
+    if (gi < 0) {
+      Group g;
+      memset(&g, 0, sizeof(g));
+      g.m = m[i]; g.n = n[i]; g.r = r[i];
+      g.rp = padded_rank(r[i]);
+      groups.push_back(g);
+      gi = (int)groups.size() - 1;
+    }
+    entries[i].m = m[i]; entries[i].n = n[i]; entries[i].r = r[i];
+    entries[i].group = gi;
+    groups[gi].count++;
+  }
+  int row = 0;
+  for (auto& g : groups) {
+    g.first_row = row;
+    row += g.count;
+    plan_gram(g);
+    g.bytes_per_entry = carve_entry(g).total;
+  }
+  std::vector<int> next(groups.size());
+  for (size_t k = 0; k < groups.size(); ++k) next[k] = groups[k].first_row;
+  for (int i = 0; i < count; ++i) entries[i].row = next[entries[i].group]++;
+  return true;
+}
+
+size_t header_bytes(int count) {
+  return align_up((size_t)count * NSLOTS * sizeof(void*), 256) + align_up((size_t)count * sizeof(int), 256);
+}
+
+}  // namespace
+
+struct dion_state {
+  int count, g_dtype, math;
+  std::vector<Entry> entries;
+  std::vector<Group> groups;
+  char* ws;
+  size_t ws_bytes;
+  void** table;   // device, count * NSLOTS
+  int* status;    // device, count ints (table-row order)
+  hipStream_t last_stream;
+  bool timing;
+  std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
+  std::vector<char> group_timed;       // which groups ran in the last call with timing on
+};
+
+#define HIPCHK(expr)                          \
+  do {                                        \
+    hipError_t e_ = (expr);                   \
+    if (e_ != hipSuccess) return DION_ELAUNCH; \
+  } while (0)
+
+namespace {
+
+GemmArgs base_args(const dion_state* st, const Group& g) {
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.table = st->table + (size_t)g.first_row * NSLOTS;
+  a.nslots = NSLOTS;
+  a.splitk = 1;
+  a.sub_count = 1;
+  a.status_slot = -1;
+  a.E.alpha = 1.f;
+  return a;
+}
+GemmArgs rebase(GemmArgs a, int row_offset) {
+  a.table = a.table + (size_t)row_offset * NSLOTS;
+  return a;
+}
+Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, int slot1 = 0) {
+  Operand o;
+  o.slot0 = slot0; o.slot1 = slot1; o.off = off; o.ld = ld; o.sub_stride = sub_stride;
+  return o;
+}
+
+// One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices starting at
+// table row `row0` of group g.
+int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, hipStream_t s) {
+  void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
+  const int r = (int)g.r, rp = g.rp;
+  const long long rr = (long long)rp * rp;
+  GemmArgs base = rebase(base_args(st, g), row0);
+  // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
+  {
+    GemmArgs a = base;
+    a.M = r; a.N = r; a.K = (int)g.m;
+    a.A = opnd(slot_in, 0, r);
+    a.B = opnd(slot_in, 0, r);
+    a.lower_only = 1;
+    a.splitk = g.gram_splitk;
+    a.k_per_split = g.gram_kps;
+    a.E.slot = (g.gram_splitk > 1) ? SLOT_CPART : SLOT_C;
+    a.E.ld = rp;
+    a.E.split_stride = rr;
+    HIPCHK(gemm_f32_tn(g.gram_variant, a, batch, s));
+    if (g.gram_splitk > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, g.gram_splitk, rr, s));
+  }
+  HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
+  HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s));
+  // blocked right-looking Cholesky, panel width CHOL_NB
+  for (int k = 0; k < rp; k += CHOL_NB) {
+    const long long dk = (long long)k * rp + k;
+    HIPCHK(launch_chol_diag(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, dk, rp, s));
+    const int rem = rp - k - CHOL_NB;
+    if (rem <= 0) break;
+    const long long below = (long long)(k + CHOL_NB) * rp + k;
+    {
+      GemmArgs a = base;  // L21 = C21 W11^T
+      a.M = rem; a.N = CHOL_NB; a.K = CHOL_NB;
+      a.A = opnd(SLOT_C, below, rp);
+      a.B = opnd(SLOT_W, dk, rp);
+      a.E.slot = SLOT_L; a.E.off = below; a.E.ld = rp;
+      HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
+    }
+    {
+      GemmArgs a = base;  // C22 -= L21 L21^T (lower tiles)
+      a.M = rem; a.N = rem; a.K = CHOL_NB;
+      a.A = opnd(SLOT_L, below, rp);
+      a.B = opnd(SLOT_L, below, rp);
+      a.lower_only = 1;
+      a.E.slot = SLOT_C; a.E.off = below + CHOL_NB; a.E.ld = rp;
+      a.E.alpha = -1.f; a.E.beta = 1.f;
+      HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
+    }
+  }
+  // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]]
+  for (int sz = CHOL_NB; sz < rp; sz *= 2) {
+    const int pairs = rp / (2 * sz);
+    const long long stride = 2LL * sz * (rp + 1);
+    const long long o21 = (long long)sz * rp;
+    {
+      GemmArgs a = base;  // T = L21 W11
+      a.M = sz; a.N = sz; a.K = sz; a.sub_count = pairs;
+      a.A = opnd(SLOT_L, o21, rp, stride);
+      a.B = opnd(SLOT_W, 0, rp, stride);
+      a.E.slot = SLOT_T; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
+      HIPCHK(gemm_f32_nn(pick_variant(sz, sz, sz, (long long)batch * pairs, true), a, batch, s));
+    }
+    {
+      GemmArgs a = base;  // W21 = -W22 T
+      a.M = sz; a.N = sz; a.K = sz; a.sub_count = pairs;
+      a.A = opnd(SLOT_W, o21 + sz, rp, stride);
+      a.B = opnd(SLOT_T, o21, rp, stride);
+      a.E.slot = SLOT_W; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
+      a.E.alpha = -1.f;
+      HIPCHK(gemm_f32_nn(pick_variant(sz, sz, sz, (long long)batch * pairs, true), a, batch, s));
+    }
+  }
+  {
+    GemmArgs a = base;  // out = in W^T   (= in L^-T)
+    a.M = (int)g.m; a.N = r; a.K = r;
+    a.A = opnd(slot_in, 0, r);
+    a.B = opnd(SLOT_W, 0, rp);
+    a.E.slot = slot_out; a.E.ld = r;
+    a.xcd_remap = 1;
+    HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
+  }
+  return DION_OK;
+}
+
+int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
+  const Group& g = st->groups[gi];
+  void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
+  const bool bf16 = st->math == DION_MATH_BF16, gbf16 = st->g_dtype == DION_G_BF16;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  GemmArgs base = rebase(base_args(st, g), row0);
+  hipEvent_t* ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
+  if (ev) { HIPCHK(hipEventRecord(ev[0], s)); st->group_timed[gi] = 1; }
+
+  HIPCHK(launch_fill_i32(tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  {
+    GemmArgs a = base;  // K1: Z = (M+G) Q
+    a.M = m; a.N = r; a.K = n;
+    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+    a.B = opnd(SLOT_Q, 0, r);
+    a.E.slot = SLOT_Z; a.E.ld = r;
+    a.xcd_remap = 1;
+    HIPCHK(gemm_k1(pick_variant(m, r, n, batch, true), bf16, gbf16, a, batch, s));
+  }
+  if (ev) HIPCHK(hipEventRecord(ev[1], s));
+  {
+    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, s);
+    if (rc != DION_OK) return rc;
+    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, s);
+    if (rc != DION_OK) return rc;
+  }
+  if (ev) HIPCHK(hipEventRecord(ev[2], s));
+  {
+    GemmArgs a = base;  // K2: R = (M+G)^T P
+    a.M = n; a.N = r; a.K = m;
+    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+    a.B = opnd(SLOT_P, 0, r);
+    a.E.slot = SLOT_R; a.E.ld = r;
+    a.xcd_remap = 1;
+    HIPCHK(gemm_k2(pick_variant(n, r, m, batch, true), bf16, gbf16, a, batch, s));
+  }
+  if (ev) HIPCHK(hipEventRecord(ev[3], s));
+  HIPCHK(launch_colnorm(tab, NSLOTS, batch, SLOT_R, n, r, s));
+  HIPCHK(launch_scale_cols(tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, s));
+  if (ev) HIPCHK(hipEventRecord(ev[4], s));
+  {
+    GemmArgs a = base;  // K5: fused M and X update
+    a.M = m; a.N = n; a.K = r;
+    a.A = opnd(SLOT_P, 0, r);
+    a.B = opnd(SLOT_R, 0, r);
+    a.B2 = opnd(SLOT_Q, 0, r);
+    a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
+    a.E.c_m = 1.0f - mu;
+    a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
+    a.status_slot = SLOT_STATUS;
+    HIPCHK(gemm_k5(pick_variant(m, n, r, batch, true), bf16, gbf16, a, batch, s));
+  }
+  if (ev) HIPCHK(hipEventRecord(ev[5], s));
+  return DION_OK;
+}
+
+bool aligned16(const void* p) { return p && ((uintptr_t)p & 15u) == 0; }
+bool coeffs_ok(float mu, float eta) { return mu >= 0.f && mu <= 1.f && isfinite(eta) && isfinite(mu); }
+
+}  // namespace
+
+extern "C" {
+
+int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const int64_t* r, int g_dtype, int math,
+                         size_t* bytes_out) {
+  if (!bytes_out || !shapes_ok(count, m, n, r)) return DION_EINVAL;
+  if ((g_dtype != DION_G_F32 && g_dtype != DION_G_BF16) || (math != DION_MATH_F32 && math != DION_MATH_BF16)) return DION_EINVAL;
+  try {
+    std::vector<Entry> entries;
+    std::vector<Group> groups;
+    build_plan(count, m, n, r, entries, groups);
+    size_t total = header_bytes(count);
+    for (auto& g : groups) total += g.bytes_per_entry * g.count;
+    *bytes_out = total + 256;
+  } catch (const std::bad_alloc&) {
+    return DION_ENOMEM;
+  }
+  return DION_OK;
+}
+
+int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64_t* n, const int64_t* r, int g_dtype,
+                    int math, void* workspace_dev, size_t workspace_bytes, void* const* M_dev, void* const* Q_dev,
+                    int q_is_filled, uint64_t seed, void* hip_stream) {
+  if (!out) return DION_EINVAL;
+  *out = nullptr;
+  size_t need = 0;
+  int rc = dion_workspace_bytes(count, m, n, r, g_dtype, math, &need);
+  if (rc != DION_OK) return rc;
+  if (count > 0 && (!M_dev || !Q_dev)) return DION_EINVAL;
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255u)) return DION_EINVAL;
+  if (workspace_bytes < need) return DION_EWORKSPACE;
+  for (int i = 0; i < count; ++i)
+    if (!aligned16(M_dev[i]) || !aligned16(Q_dev[i])) return DION_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  dion_state* st = nullptr;
+  try {
+    st = new dion_state();
+    st->count = count; st->g_dtype = g_dtype; st->math = math;
+    build_plan(count, m, n, r, st->entries, st->groups);
+    st->ws = (char*)workspace_dev;
+    st->ws_bytes = workspace_bytes;
+    st->table = (void**)st->ws;
+    st->status = (int*)(st->ws + align_up((size_t)count * NSLOTS * sizeof(void*), 256));
+    st->last_stream = s;
+    st->timing = false;
+    st->group_timed.assign(st->groups.size(), 0);
+    // host image of the pointer table
+    std::vector<void*> host((size_t)count * NSLOTS, nullptr);
+    size_t pos = header_bytes(count);
+    std::vector<size_t> group_base(st->groups.size());
+    for (size_t k = 0; k < st->groups.size(); ++k) {
+      group_base[k] = pos;
+      pos += st->groups[k].bytes_per_entry * st->groups[k].count;
+    }
+    for (int i = 0; i < count; ++i) {
+      const Entry& e = st->entries[i];
+      const Group& g = st->groups[e.group];
+      const Carve c = carve_entry(g);
+      char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
+      void** rowp = &host[(size_t)e.row * NSLOTS];
+      for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
+      rowp[SLOT_STATUS] = st->status + e.row;
+      rowp[SLOT_M] = M_dev[i];
+      rowp[SLOT_Q] = Q_dev[i];
+    }
+    if (count > 0) {
+      if (hipMemcpy(st->table, host.data(), host.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess) {
+        delete st;
+        return DION_ELAUNCH;
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    delete st;
+    return DION_ENOMEM;
+  }
+  // device-side initialisation: M = 0, Q = ColNorm(Q or Gaussian draw)
+  auto fail = [&](int code) { delete st; return code; };
+  for (int i = 0; i < count; ++i) {
+    const Entry& e = st->entries[i];
+    void* const* rowtab = st->table + (size_t)e.row * NSLOTS;
+    if (launch_fill(rowtab, NSLOTS, 1, SLOT_M, (long long)e.m * e.n, 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (!q_is_filled)
+      if (launch_gaussian_fill(rowtab, NSLOTS, 1, SLOT_Q, (long long)e.n * e.r, seed, i, s) != hipSuccess) return fail(DION_ELAUNCH);
+  }
+  for (auto& g : st->groups) {
+    void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
+    if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, g.n, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
+  }
+  *out = st;
+  return DION_OK;
+}
+
+int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M, void* const* Q,
+                      const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta, void* hip_stream) {
+  if (!st || count < 0) return DION_EINVAL;
+  if (count == 0) return DION_OK;
+  if (count != st->count || !X || !G || !M || !Q || !m || !n || !r || !coeffs_ok(mu, eta)) return DION_EINVAL;
+  for (int i = 0; i < count; ++i) {
+    const Entry& e = st->entries[i];
+    if (m[i] != e.m || n[i] != e.n || r[i] != e.r) return DION_EINVAL;
+    if (!aligned16(X[i]) || !aligned16(G[i]) || !aligned16(M[i]) || !aligned16(Q[i])) return DION_EINVAL;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  st->last_stream = s;
+  std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
+  try {
+    // user pointers in table-row order
+    std::vector<void*> xs(count), ms(count), qs(count);
+    std::vector<const void*> gs(count);
+    for (int i = 0; i < count; ++i) {
+      const int row = st->entries[i].row;
+      xs[row] = X[i]; gs[row] = G[i]; ms[row] = M[i]; qs[row] = Q[i];
+    }
+    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+  } catch (const std::bad_alloc&) {
+    return DION_ENOMEM;
+  }
+  for (size_t gi = 0; gi < st->groups.size(); ++gi) {
+    int rc = step_rows(st, (int)gi, 0, st->groups[gi].count, mu, eta, s);
+    if (rc != DION_OK) return rc;
+  }
+  return DION_OK;
+}
+
+int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q, int64_t m, int64_t n, int64_t r, float mu,
+              float eta, void* hip_stream) {
+  if (!st || !coeffs_ok(mu, eta)) return DION_EINVAL;
+  if (!aligned16(X) || !aligned16(G) || !aligned16(M) || !aligned16(Q)) return DION_EINVAL;
+  int idx = -1;
+  for (int i = 0; i < st->count && idx < 0; ++i)
+    if (st->entries[i].m == m && st->entries[i].n == n && st->entries[i].r == r) idx = i;
+  if (idx < 0) return DION_EINVAL;
+  const Entry& e = st->entries[idx];
+  const Group& g = st->groups[e.group];
+  hipStream_t s = (hipStream_t)hip_stream;
+  st->last_stream = s;
+  std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
+  void* xs[1] = {X};
+  const void* gs[1] = {G};
+  void* ms[1] = {M};
+  void* qs[1] = {Q};
+  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
+  return step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
+}
+
+int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {
+  if (!st) return DION_EINVAL;
+  HIPCHK(hipStreamSynchronize(st->last_stream));
+  int status = DION_OK, bad = -1;
+  if (st->count > 0) {
+    try {
+      std::vector<int> host(st->count);
+      HIPCHK(hipMemcpy(host.data(), st->status, sizeof(int) * st->count, hipMemcpyDeviceToHost));
+      for (int i = 0; i < st->count; ++i)
+        if (host[st->entries[i].row] != 0) {
+          status = DION_NUM_BREAKDOWN;
+          if (bad < 0) bad = i;
+        }
+    } catch (const std::bad_alloc&) {
+      return DION_ENOMEM;
+    }
+  }
+  if (status_out) *status_out = status;
+  if (first_bad_index) *first_bad_index = bad;
+  return DION_OK;
+}
+
+int dion_set_stage_timing(dion_state_t* st, int enable) {
+  if (!st) return DION_EINVAL;
+  if (enable && st->events.empty()) {
+    try {
+      st->events.resize(st->groups.size() * kEventsPerGroup, nullptr);
+    } catch (const std::bad_alloc&) {
+      return DION_ENOMEM;
+    }
+    for (auto& e : st->events) HIPCHK(hipEventCreate(&e));
+  }
+  st->timing = enable != 0;
+  return DION_OK;
+}
+
+int dion_stage_times(dion_state_t* st, float* ms_out) {
+  if (!st || !ms_out) return DION_EINVAL;
+  for (int i = 0; i < DION_STAGE_COUNT; ++i) ms_out[i] = 0.f;
+  if (st->events.empty()) return DION_EINVAL;
+  HIPCHK(hipStreamSynchronize(st->last_stream));
+  for (size_t gi = 0; gi < st->groups.size(); ++gi) {
+    if (!st->group_timed[gi]) continue;
+    hipEvent_t* ev = &st->events[gi * kEventsPerGroup];
+    for (int sidx = 0; sidx < DION_STAGE_COUNT; ++sidx) {
+      float ms = 0.f;
+      HIPCHK(hipEventElapsedTime(&ms, ev[sidx], ev[sidx + 1]));
+      ms_out[sidx] += ms;
+    }
+  }
+  return DION_OK;
+}
+
+int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, int64_t* ld_out) {
+  if (!st || index < 0 || index >= st->count || !ptr_out) return DION_EINVAL;
+  static const int slots[] = {SLOT_Z, SLOT_P, SLOT_R, SLOT_S, SLOT_STATUS, SLOT_P1, SLOT_C, SLOT_L, SLOT_W, SLOT_D};
+  if (which < 0 || which >= (int)(sizeof(slots) / sizeof(slots[0]))) return DION_EINVAL;
+  const Entry& e = st->entries[index];
+  void* p = nullptr;
+  HIPCHK(hipMemcpy(&p, st->table + (size_t)e.row * NSLOTS + slots[which], sizeof(void*), hipMemcpyDeviceToHost));
+  *ptr_out = p;
+  if (ld_out) {
+    const int sl = slots[which];
+    *ld_out = (sl == SLOT_C || sl == SLOT_L || sl == SLOT_W) ? st->groups[e.group].rp
+              : (sl == SLOT_S || sl == SLOT_D || sl == SLOT_STATUS) ? 1 : e.r;
+  }
+  return DION_OK;
+}
+
+int dion_destroy_state(dion_state_t* st) {
+  if (!st) return DION_OK;
+  for (auto& e : st->events)
+    if (e) (void)hipEventDestroy(e);
+  delete st;
+  return DION_OK;
+}
+
+const char* dion_strerror(int code) {
+  switch (code) {
+    case DION_OK: return "ok";
+    case DION_EINVAL: return "invalid argument";
+    case DION_EWORKSPACE: return "workspace too small";
+    case DION_ELAUNCH: return "HIP runtime error";
+    case DION_ENOMEM: return "host allocation failed";
+    case DION_NUM_BREAKDOWN: return "Cholesky breakdown: Z rank deficient or too ill conditioned";
+    default: return "unknown code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Declarations shared by the translation units of libdion.so (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_core.hpp"
+
+namespace dion {
+
+// Pointer-table slots of one matrix parameter.  Slots 0-3 are the caller's buffers and are
+// refreshed on every step; the rest point into the workspace and are fixed at init.
+enum Slot {
+  SLOT_X = 0, SLOT_G, SLOT_M, SLOT_Q,
+  SLOT_Z,      // Z = B Q                      m x r
+  SLOT_P1,     // Z after the first Cholesky-QR pass
+  SLOT_P,      // P = orth(Z)                  m x r
+  SLOT_R,      // R = B^T P                    n x r
+  SLOT_C,      // Gram matrix                  rp x rp  (rp = padded r)
+  SLOT_L,      // its Cholesky factor          rp x rp
+  SLOT_W,      // L^-1                         rp x rp
+  SLOT_T,      // scratch of the inverse       rp x rp
+  SLOT_CPART,  // split-K partial Gram matrices
+  SLOT_SPART,  // partial column sums of squares
+  SLOT_S,      // column norms of R            r
+  SLOT_D,      // 1 / (s + eps)                r
+  SLOT_STATUS, // int32 breakdown flag
+  NSLOTS = 20
+};
+
+constexpr int CHOL_NB = 128;       // Cholesky panel width (diagonal block factored in LDS)
+constexpr float COLNORM_EPS = 1e-8f;
+constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares
+
+// Tile configurations of the MFMA GEMM core.
+using CfgBig = TileCfg<128, 128, 32, 2, 2>;
+using CfgSmall = TileCfg<64, 64, 64, 2, 2>;
+enum { VAR_BIG = 0, VAR_SMALL = 1, VAR_SMALL_CHECKED = 2 };
+
+// Picks the tile variant for a product with output M x N and contraction K whose operands all
+// have leading dimensions that are multiples of 8 whenever the dimensions are multiples of 64.
+int pick_variant(long long M, long long N, long long K, long long batch, bool aligned);
+
+// GEMM families (each defined in its own translation unit).  `bf16`: MMA operand type.
+hipError_t gemm_k1(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // A = M+G (KC), B = fp32 KS
+hipError_t gemm_k2(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // A = M+G (KS), B = fp32 KS
+hipError_t gemm_k5(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // dual B, fused update
+hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
+hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
+hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KS, B KS
+
+// Small kernels (small_kernels.hip).  All take the pointer table and a batch count.
+hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
+                                void* const* M, void* const* Q, hipStream_t s);
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
+hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
+hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s);
+hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
+                                  int nsplit, long long split_stride, hipStream_t s);
+hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s);
+hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
+                             int status_slot, hipStream_t s);
+hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
+                                int first_stream, hipStream_t s);
+hipError_t launch_chol_diag(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, long long off,
+                            long long ld, hipStream_t s);
+
+}  // namespace dion

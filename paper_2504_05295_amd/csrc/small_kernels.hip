@@ -1,0 +1,285 @@
+// Element-wise, reduction and panel kernels of the Dion step (everything that is not a tiled GEMM).
+#include "internal.hpp"
+
+namespace dion {
+
+// ---------------------------------------------------------------- pointer table refresh
+struct UserPtrChunk {
+  void* p[48][4];
+  int first_row, count, nslots;
+};
+__global__ void set_user_ptrs_kernel(void** table, const UserPtrChunk c) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= c.count * 4) return;
+  table[(size_t)(c.first_row + t / 4) * c.nslots + (t % 4)] = c.p[t / 4][t % 4];
+}
+hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
+                                void* const* M, void* const* Q, hipStream_t s) {
+  for (int done = 0; done < count; done += 48) {
+    UserPtrChunk c;
+    c.first_row = first_row + done;
+    c.count = (count - done < 48) ? count - done : 48;
+    c.nslots = nslots;
+    for (int i = 0; i < c.count; ++i) {
+      c.p[i][SLOT_X] = X[done + i];
+      c.p[i][SLOT_G] = const_cast<void*>(G[done + i]);
+      c.p[i][SLOT_M] = M[done + i];
+      c.p[i][SLOT_Q] = Q[done + i];
+    }
+    hipLaunchKernelGGL(set_user_ptrs_kernel, dim3(1), dim3(256), 0, s, table, c);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------- fills
+__global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value) {
+  float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long long)gridDim.x * blockDim.x)
+    p[i] = value;
+}
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s) {
+  if (count <= 0 || batch <= 0) return hipSuccess;
+  long long blocks = (count + 1023) / 1024;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value);
+  return hipGetLastError();
+}
+__global__ void fill_i32_kernel(void* const* table, int nslots, int slot, long long count, int value) {
+  int* p = (int*)table[(size_t)blockIdx.y * nslots + slot];
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long long)gridDim.x * blockDim.x)
+    p[i] = value;
+}
+hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s) {
+  if (count <= 0 || batch <= 0) return hipSuccess;
+  long long blocks = (count + 1023) / 1024;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value);
+  return hipGetLastError();
+}
+
+// Gram matrix padding: rows/columns r..rp-1 of the rp x rp matrix become those of the identity, so
+// that the Cholesky factor of the padded matrix is diag(L, I).
+__global__ void pad_identity_kernel(void* const* table, int nslots, int slot, int r, int rp) {
+  float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
+  const long long total = (long long)rp * rp;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int row = (int)(i / rp), col = (int)(i % rp);
+    if (row >= r || col >= r) p[i] = (row == col) ? 1.f : 0.f;
+  }
+}
+hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s) {
+  if (rp == r || batch <= 0) return hipSuccess;
+  long long blocks = ((long long)rp * rp + 1023) / 1024;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(pad_identity_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, r, rp);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- split-K reduction (fixed order => deterministic)
+__global__ void reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r, long long ld,
+                                       int nsplit, long long split_stride) {
+  const float* part = (const float*)table[(size_t)blockIdx.y * nslots + slot_part];
+  float* out = (float*)table[(size_t)blockIdx.y * nslots + slot_out];
+  const long long total = (long long)r * r;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    if ((i % r) > (i / r)) continue;  // only the lower triangle is produced and consumed
+    const long long idx = (i / r) * ld + (i % r);
+    float acc = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) acc += part[sp * split_stride + idx];
+    out[idx] = acc;
+  }
+}
+hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
+                                  int nsplit, long long split_stride, hipStream_t s) {
+  long long blocks = ((long long)r * r + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_part, slot_out, r,
+                     ld, nsplit, split_stride);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- ColNorm (update rule: V_new <- ColNorm(W))
+// Stage 1: partial[chunk][col] = sum over the chunk's COLNORM_ROWS rows of in[row][col]^2.
+__global__ void __launch_bounds__(256) colnorm_partial_kernel(void* const* table, int nslots, int slot_in, long long rows, int r) {
+  const float* in = (const float*)table[(size_t)blockIdx.z * nslots + slot_in];
+  float* part = (float*)table[(size_t)blockIdx.z * nslots + SLOT_SPART];
+  __shared__ float red[4][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cx;
+  const long long row_begin = (long long)blockIdx.y * COLNORM_ROWS;
+  long long row_end = row_begin + COLNORM_ROWS;
+  if (row_end > rows) row_end = rows;
+  float acc = 0.f;
+  if (col < r)
+    for (long long row = row_begin + ry; row < row_end; row += 4) {
+      const float v = in[row * r + col];
+      acc += v * v;
+    }
+  red[ry][cx] = acc;
+  __syncthreads();
+  if (ry == 0 && col < r) part[(long long)blockIdx.y * r + col] = (red[0][cx] + red[1][cx]) + (red[2][cx] + red[3][cx]);
+}
+// Stage 2: s = sqrt(sum of partials), d = 1/(s + eps).
+__global__ void colnorm_final_kernel(void* const* table, int nslots, int nchunks, int r) {
+  const float* part = (const float*)table[(size_t)blockIdx.y * nslots + SLOT_SPART];
+  float* sn = (float*)table[(size_t)blockIdx.y * nslots + SLOT_S];
+  float* d = (float*)table[(size_t)blockIdx.y * nslots + SLOT_D];
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= r) return;
+  float acc = 0.f;
+  for (int c = 0; c < nchunks; ++c) acc += part[(long long)c * r + col];
+  const float nrm = sqrtf(acc);
+  sn[col] = nrm;
+  d[col] = 1.0f / (nrm + COLNORM_EPS);
+}
+hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s) {
+  const int nchunks = (int)((rows + COLNORM_ROWS - 1) / COLNORM_ROWS);
+  hipLaunchKernelGGL(colnorm_partial_kernel, dim3((r + 63) / 64, nchunks, batch), dim3(256), 0, s, table, nslots, slot_in, rows, r);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, s, table, nslots, nchunks, r);
+  return hipGetLastError();
+}
+
+// out[row][col] = in[row][col] * d[col]   (in may alias out)
+__global__ void scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows, int r, int status_slot) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  if (status_slot >= 0 && *(const int*)tab[status_slot] != 0) return;
+  const float* in = (const float*)tab[slot_in];
+  float* out = (float*)tab[slot_out];
+  const float* d = (const float*)tab[SLOT_D];
+  const long long total = rows * r;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x)
+    out[i] = in[i] * d[i % r];
+}
+hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
+                             int status_slot, hipStream_t s) {
+  long long blocks = (rows * r + 1023) / 1024;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(scale_cols_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_in, slot_out, rows, r,
+                     status_slot);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- Gaussian fill (Philox-4x32-10 + Box-Muller)
+__device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
+  const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
+  const uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
+  const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c[1] ^ k0;
+  const uint32_t n1 = (uint32_t)p1;
+  const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c[3] ^ k1;
+  const uint32_t n3 = (uint32_t)p0;
+  c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+}
+// Element e comes from block e/4 (counter = (block lo, block hi, stream, 0), key = seed): words (0,1)
+// and (2,3) feed two Box-Muller transforms, u1 = (w+1)/2^32, u2 = w'/2^32.
+__global__ void gaussian_fill_kernel(void* const* table, int nslots, int slot, long long count, uint64_t seed, int first_stream) {
+  float* out = (float*)table[(size_t)blockIdx.y * nslots + slot];
+  const long long nblk = (count + 3) / 4;
+  for (long long blk = (long long)blockIdx.x * blockDim.x + threadIdx.x; blk < nblk; blk += (long long)gridDim.x * blockDim.x) {
+    uint32_t c[4] = {(uint32_t)blk, (uint32_t)((uint64_t)blk >> 32), (uint32_t)(first_stream + blockIdx.y), 0u};
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int rd = 0; rd < 10; ++rd) {
+      philox_round(c, k0, k1);
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    float v[4];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const double u1 = ((double)c[2 * h] + 1.0) * (1.0 / 4294967296.0);
+      const double u2 = (double)c[2 * h + 1] * (1.0 / 4294967296.0);
+      const double rad = sqrt(-2.0 * log(u1));
+      double sn, cs;
+      sincos(6.283185307179586476925286766559 * u2, &sn, &cs);
+      v[2 * h] = (float)(rad * cs);
+      v[2 * h + 1] = (float)(rad * sn);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (blk * 4 + e < count) out[blk * 4 + e] = v[e];
+  }
+}
+hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
+                                int first_stream, hipStream_t s) {
+  if (count <= 0 || batch <= 0) return hipSuccess;
+  long long blocks = ((count + 3) / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(gaussian_fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, seed,
+                     first_stream);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- Cholesky of one diagonal block + its inverse
+// Factors the NB x NB diagonal block at element offset `off` of C (lower triangle) into L (written
+// to the same position of the L matrix, upper part zero) and writes W = L^-1 to the same position of
+// the W matrix.  A non-positive or non-finite pivot sets the status word (Cholesky-QR breakdown,
+// Appendix A) and the block is completed with that pivot replaced by 1.
+template <int NB>
+__global__ void __launch_bounds__(256) chol_diag_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
+                                                        long long off, long long ld) {
+  void* const* tab = table + (size_t)blockIdx.x * nslots;
+  const float* C = (const float*)tab[slotC] + off;
+  float* L = (float*)tab[slotL] + off;
+  float* W = (float*)tab[slotW] + off;
+  int* status = (int*)tab[SLOT_STATUS];
+  // strictly-lower part: L.  upper part incl. diagonal: W^T (W[i][c] at A[c][i], i >= c).
+  __shared__ float A[NB][NB + 1];
+  __shared__ float dinv[NB];
+  const int t = threadIdx.x;
+  for (int idx = t; idx < NB * NB; idx += 256) {
+    const int i = idx / NB, j = idx % NB;
+    A[i][j] = (j <= i) ? C[i * ld + j] : 0.f;
+  }
+  const int ty = t >> 4, tx = t & 15;
+  bool bad = false;
+  for (int j = 0; j < NB; ++j) {
+    __syncthreads();
+    float piv = A[j][j];
+    if (!(piv > 0.f) || !(piv < 3.0e38f)) { bad = true; piv = 1.f; }
+    const float sq = sqrtf(piv);
+    const float rs = 1.0f / sq;
+    __syncthreads();
+    for (int i = j + 1 + t; i < NB; i += 256) A[i][j] *= rs;
+    if (t == 0) { A[j][j] = sq; dinv[j] = rs; }
+    __syncthreads();
+    const int rem = NB - j - 1;
+    for (int ii = ty; ii < rem; ii += 16) {
+      const float lij = A[j + 1 + ii][j];
+      for (int kk = tx; kk <= ii; kk += 16) A[j + 1 + ii][j + 1 + kk] -= lij * A[j + 1 + kk][j];
+    }
+  }
+  __syncthreads();
+  if (bad && t == 0) *status = 1;
+  // write L (lower incl. diagonal, zeros above)
+  for (int idx = t; idx < NB * NB; idx += 256) {
+    const int i = idx / NB, j = idx % NB;
+    L[i * ld + j] = (j <= i) ? A[i][j] : 0.f;
+  }
+  __syncthreads();
+  // inverse by forward substitution, one thread per column c: w_i = -(sum_{k=c}^{i-1} L[i][k] w_k) / L[i][i]
+  if (t < NB) {
+    const int c = t;
+    A[c][c] = dinv[c];
+    for (int i = c + 1; i < NB; ++i) {
+      float acc = 0.f;
+      for (int k = c; k < i; ++k) acc += A[i][k] * A[c][k];   // A[i][k] = L (k < i), A[c][k] = W[k][c] (k >= c)
+      A[c][i] = -acc * dinv[i];
+    }
+  }
+  __syncthreads();
+  for (int idx = t; idx < NB * NB; idx += 256) {
+    const int i = idx / NB, j = idx % NB;
+    W[i * ld + j] = (j <= i) ? A[j][i] : 0.f;
+  }
+}
+hipError_t launch_chol_diag(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, long long off,
+                            long long ld, hipStream_t s) {
+  hipLaunchKernelGGL(chol_diag_kernel<CHOL_NB>, dim3(batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, off, ld);
+  return hipGetLastError();
+}
+
+}  // namespace dion

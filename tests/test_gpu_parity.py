@@ -1,0 +1,74 @@
+"""GPU-vs-oracle parity of dion_step / dion_step_batched through the C ABI.
+
+Tolerances (from the benchmark's statement): relative Frobenius error <= 1e-4 on X and M in fp32
+mode, <= 2e-2 with bf16 operands, max|P^T P - I| <= 1e-5 in fp32 mode.  P, Q, R carry a column-sign
+ambiguity, so they are compared only through P Q^T, P R^T and |<q_j, q_j_ref>|.  On top of that the
+tests bound the error of the *update* itself (dX, dM relative to the update), which is far stricter.
+"""
+import numpy as np
+import pytest
+
+from oracle import dion_oracle as orc
+from paper_2504_05295_amd import inputs
+from gpu_harness import GpuProblem, one_step_report, relf
+
+pytestmark = pytest.mark.gpu
+
+MU, ETA = inputs.MU, inputs.ETA
+TOL = {"f32": dict(X=1e-4, M=1e-4, d=2e-4, orth=1e-5), "bf16": dict(X=2e-2, M=2e-2, d=2e-2, orth=1e-3)}
+
+
+def run_trajectory(shape, g_bf16, math, steps, method, kind="gaussian", check_every=1):
+    m, n, r = shape
+    gp = GpuProblem([shape], g_bf16, math)
+    tol = TOL[math]
+    # oracle trajectory from the same inputs
+    Mo, Qo = orc.init_state(m, n, gp.q_raw[0])
+    Xo, Mo, Qo = gp.x0[0].copy(), Mo.astype(np.float32), Qo.astype(np.float32)
+    _, m0, q0 = gp.host()
+    assert np.all(m0 == 0)
+    assert relf(q0, Qo) < 1e-6
+    worst = {}
+    for t in range(steps):
+        g = gp.grads_np(t, kind)[0]
+        g32 = gp.grad_as_f32(g, g_bf16)
+        x_in, m_in, q_in = gp.host()
+        gp.upload_grads([g])
+        status, bad = gp.step(MU, ETA)
+        assert status == 0 and bad == -1, "step %d status %d" % (t, status)
+        ref_traj = orc.run_steps(Xo, [g32], Mo, Qo, MU, ETA, method)[-1]
+        Xo, Mo, Qo = ref_traj["X"], ref_traj["M"], ref_traj["Q"]
+        if t % check_every == 0 or t == steps - 1:
+            rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, g32, MU, ETA, method)
+            X, M, Q = gp.host()
+            rep["X_traj"], rep["M_traj"] = relf(X, Xo), relf(M, Mo)
+            print("step", t, {k: ("%.2e" % v) for k, v in rep.items()}, flush=True)
+            assert rep["X"] <= tol["X"] and rep["M"] <= tol["M"]
+            assert rep["X_traj"] <= tol["X"] and rep["M_traj"] <= tol["M"]
+            assert rep["dX"] <= tol["d"] and rep["dM"] <= tol["d"]
+            assert rep["PQt"] <= tol["d"] and rep["PRt"] <= tol["d"]
+            assert rep["orth"] <= tol["orth"]
+            assert rep["qdot"] >= 1 - 10 * tol["d"] and rep["qnorm"] < 1e-5
+            for k, v in rep.items():
+                worst[k] = max(worst.get(k, 0.0), v) if k != "qdot" else min(worst.get(k, 1.0), v)
+    return worst
+
+
+def test_c1_256_fp32_ten_steps():
+    run_trajectory((256, 256, 64), False, "f32", 10, "householder")
+
+
+@pytest.mark.parametrize("shape", [(200, 136, 24), (77, 130, 5), (129, 65, 65), (64, 40, 1), (300, 72, 72), (96, 520, 33)])
+@pytest.mark.parametrize("g_bf16,math", [(False, "f32"), (True, "bf16")])
+def test_ragged_shapes(shape, g_bf16, math):
+    run_trajectory(shape, g_bf16, math, 3, "householder")
+
+
+@pytest.mark.parametrize("math", ["f32", "bf16"])
+def test_c2_2048_twenty_steps(math):
+    run_trajectory((2048, 2048, 512), True, math, 20, "lapack", check_every=5)
+
+
+def test_structured_gradient_fp32():
+    # power-law spectrum: B Q is markedly worse conditioned than for Gaussian inputs
+    run_trajectory((512, 384, 64), False, "f32", 4, "householder", kind="structured")
