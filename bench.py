@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the Dion step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3a] [--no-cpu-baseline]
+
+A "step" is one full Dion step (Z = (M+G)Q, CholeskyQR2, R = (M+G)^T P, ColNorm, fused M and X
+update) of the workload's matrices, inputs resident in HBM.  Prints ONE JSON line: ms per step as
+`value`, the roofline of the dominant kernel (stage durations from HIP events recorded by the
+library on the step's stream) and the CPU oracle timed on the host cores as `cpu_baseline`.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2504_05295_amd import inputs  # noqa: E402
+
+PEAK_BF16 = 2.5e15   # dense bf16 MFMA FLOP/s
+PEAK_F32 = 157.3e12  # fp32 MFMA FLOP/s
+PEAK_HBM = 8.0e12    # B/s
+
+WORKLOAD_NAMES = {
+    "C1": "C1: 256x256 r=64, fp32 G, fp32 math",
+    "C2": "C2: 2048x2048 r=512, bf16 G, fp32 math",
+    "C2b": "C2: 2048x2048 r=512, bf16 G, bf16 operands",
+    "C3a": "C3: 8192x8192 r=2048, bf16 G, bf16 operands, fp32 state",
+    "C3b": "C3: 8192x8192 r=512, bf16 G, bf16 operands, fp32 state",
+    "C4a": "C4: 16384x53248 r=1024 (Llama-3-405B MLP shape), bf16 G, bf16 operands",
+    "C4b": "C4: 16384x53248 r=4096 (Llama-3-405B MLP shape), bf16 G, bf16 operands",
+    "C5": "C5: 196 matrices of a 3B decoder (28 layers, d=3072, ffn=8192), r=768, batched",
+}
+
+
+def kernel_models(shapes, g_bytes, math):
+    """Algorithmic FLOPs and HBM bytes of the three large kernels, summed over the workload."""
+    peak = PEAK_BF16 if math == "bf16" else PEAK_F32
+    out = {}
+    k1f = k1b = k2f = k2b = k5f = k5b = 0.0
+    for (m, n, r) in shapes:
+        mn, mr, nr = float(m) * n, float(m) * r, float(n) * r
+        k1f += 2 * mn * r
+        k1b += (4 + g_bytes) * mn + 4 * nr + 4 * mr            # read M, G, Q; write Z
+        k2f += 2 * mn * r
+        k2b += (4 + g_bytes) * mn + 4 * mr + 4 * nr            # read M, G, P; write R
+        k5f += 4 * mn * r
+        k5b += (16 + g_bytes) * mn + 4 * mr + 8 * nr           # read M, G, X; write M, X; read P, R, Q
+    for name, fl, by in (("k1_BQ", k1f, k1b), ("k2_BtP", k2f, k2b), ("k5_update", k5f, k5b)):
+        bound = "mfma" if fl / peak > by / PEAK_HBM else "hbm"
+        out[name] = dict(flops=fl, bytes=by, bound=bound, peak=peak if bound == "mfma" else PEAK_HBM)
+    return out
+
+
+def build_problem(cfg, seed=0, n_grads=2):
+    import torch
+    from paper_2504_05295_amd import binding as B
+    shapes = cfg["shapes"]
+    dev = "cuda"
+    X, M, Q, G = [], [], [], []
+    uniq = {}
+    for i, (m, n, r) in enumerate(shapes):
+        # one host draw per distinct shape is enough for timing; every matrix still gets its own buffers
+        if (m, n, r) not in uniq:
+            gs = [inputs.gradient(m, n, t, seed, 0, bf16=cfg["g_bf16"]) for t in range(n_grads)]
+            uniq[(m, n, r)] = (inputs.weight(m, n, seed + 1, 0), inputs.right_factor_raw(n, r, seed + 2, 0), gs)
+        x, q, gs = uniq[(m, n, r)]
+        X.append(torch.from_numpy(x).to(dev))
+        M.append(torch.empty((m, n), dtype=torch.float32, device=dev))
+        Q.append(torch.from_numpy(q).to(dev))
+        if cfg["g_bf16"]:
+            G.append([torch.from_numpy(g.view(np.int16)).view(torch.bfloat16).to(dev) for g in gs])
+        else:
+            G.append([torch.from_numpy(g).to(dev) for g in gs])
+    state = B.dion_init_state(shapes, B.DION_G_BF16 if cfg["g_bf16"] else B.DION_G_F32,
+                              B.DION_MATH_BF16 if cfg["math"] == "bf16" else B.DION_MATH_F32, M, Q, q_is_filled=True)
+    return dict(B=B, shapes=shapes, X=X, M=M, Q=Q, G=G, state=state, uniq=uniq)
+
+
+def do_step(p, t):
+    B = p["B"]
+    ng = len(p["G"][0])
+    if len(p["shapes"]) == 1:
+        B.dion_step(p["state"], p["X"][0], p["G"][0][t % ng], p["M"][0], p["Q"][0], inputs.MU, inputs.ETA)
+    else:
+        B.dion_step_batched(p["state"], p["X"], [g[t % ng] for g in p["G"]], p["M"], p["Q"], inputs.MU, inputs.ETA)
+
+
+def cpu_baseline(cfg, p, budget_s=30.0):
+    """Times the CPU oracle (as it stands, fp64 numpy) on a bounded sample of the workload."""
+    from oracle import dion_oracle as orc
+    shapes = cfg["shapes"]
+    # sample: one step of the largest-work distinct matrix that fits the budget, else one smaller square matrix
+    (m, n, r) = max(set(shapes), key=lambda s: s[0] * s[1] * s[2])
+    est = (8.0 * m * n * r + 4.0 * m * r * r) / 1.5e11
+    sample = "one full oracle step of %dx%d r=%d" % (m, n, r)
+    scale = 1.0
+    if est > budget_s:
+        m2 = n2 = 4096
+        r2 = max(1, int(round(4096 * r / min(m, n))))
+        scale = (8.0 * m * n * r + 4.0 * m * r * r) / (8.0 * m2 * n2 * r2 + 4.0 * m2 * r2 * r2)
+        sample = "one oracle step of %dx%d r=%d, scaled by FLOP count (x%.1f) to %dx%d r=%d" % (m2, n2, r2, scale, m, n, r)
+        x = inputs.weight(m2, n2, 1, 0)
+        q = inputs.right_factor_raw(n2, r2, 2, 0)
+        g = inputs.gradient(m2, n2, 0, 0, 0, bf16=cfg["g_bf16"])
+    else:
+        x, q, gs = p["uniq"][(m, n, r)]
+        g = gs[0]
+    g32 = inputs.bf16_bits_to_f32(g) if cfg["g_bf16"] else g
+    M0, Q0 = orc.init_state(x.shape[0], x.shape[1], q)
+    t0 = time.perf_counter()
+    res = orc.dion_step(x, g32, M0, Q0, inputs.MU, inputs.ETA, method="lapack")
+    dt = time.perf_counter() - t0
+    assert res["status"] == 0
+    per_matrix_ms = dt * 1e3 * scale
+    # whole workload: every matrix costs the same FLOP-scaled time
+    total = 0.0
+    ref = 8.0 * m * n * r + 4.0 * m * r * r
+    for (a, b, c) in shapes:
+        total += per_matrix_ms * (8.0 * a * b * c + 4.0 * a * c * c) / ref
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS") or os.environ.get("OPENBLAS_NUM_THREADS")
+    if env:
+        cores = min(cores, int(env))
+    return dict(value=total, unit="ms/step", cores=cores, kind="oracle", sample=sample, measured_s=dt)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3a", choices=sorted(inputs.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = inputs.CONFIGS[args.workload]
+    p = build_problem(cfg)
+    B = p["B"]
+    for t in range(args.warmup):
+        do_step(p, t)
+    status, bad = B.dion_last_status(p["state"])
+    assert status == 0, "warm-up step reported numerical breakdown"
+    # timed region: exactly K steps, inputs resident in HBM
+    B.dion_set_stage_timing(p["state"], not args.no_stage_timing)
+    stage_sum = {k: 0.0 for k in B.STAGES}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if args.no_stage_timing:
+        for t in range(args.steps):
+            do_step(p, args.warmup + t)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        # stage events are read back after each step (a host wait, also inside the timed region)
+        for t in range(args.steps):
+            do_step(p, args.warmup + t)
+            for k, v in B.dion_stage_times(p["state"]).items():
+                stage_sum[k] += v
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    status, bad = B.dion_last_status(p["state"])
+    assert status == 0, "timed step reported numerical breakdown"
+
+    g_bytes = 2 if cfg["g_bf16"] else 4
+    models = kernel_models(cfg["shapes"], g_bytes, cfg["math"])
+    stages = {k: v / args.steps for k, v in stage_sum.items()}
+    rooflines = {}
+    for name, mdl in models.items():
+        ms = stages.get(name, 0.0)
+        if ms <= 0:
+            continue
+        work = mdl["flops"] if mdl["bound"] == "mfma" else mdl["bytes"]
+        ach = work / (ms * 1e-3)
+        unit = "TFLOP/s" if mdl["bound"] == "mfma" else "GB/s"
+        div = 1e12 if mdl["bound"] == "mfma" else 1e9
+        rooflines[name] = dict(bound=mdl["bound"], achieved=ach / div, peak=mdl["peak"] / div, unit=unit,
+                               frac=ach / mdl["peak"], traffic=None, ms=ms,
+                               tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
+    dominant = max(rooflines, key=lambda k: rooflines[k]["ms"]) if rooflines else None
+    out = {
+        "metric": "ms per Dion step per m x n matrix at rank r",
+        "value": ms_per_step, "unit": "ms/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["math"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.workload], "matrices": len(cfg["shapes"]),
+                   "shape": list(cfg["shapes"][0]) if len(set(cfg["shapes"])) == 1 else "mixed",
+                   "mu": inputs.MU, "eta": inputs.ETA, "g_dtype": "bf16" if cfg["g_bf16"] else "f32"},
+        "stage_ms": stages,
+        "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
+        "rooflines": rooflines,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, p)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -197,7 +197,8 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 
 // One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices starting at
 // table row `row0` of group g.
-int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, hipStream_t s) {
+int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, float piv_lo, float piv_hi,
+                hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -219,32 +220,9 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   }
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
   HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s));
-  // blocked right-looking Cholesky, panel width CHOL_NB
-  for (int k = 0; k < rp; k += CHOL_NB) {
-    const long long dk = (long long)k * rp + k;
-    HIPCHK(launch_chol_diag(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, dk, rp, s));
-    const int rem = rp - k - CHOL_NB;
-    if (rem <= 0) break;
-    const long long below = (long long)(k + CHOL_NB) * rp + k;
-    {
-      GemmArgs a = base;  // L21 = C21 W11^T
-      a.M = rem; a.N = CHOL_NB; a.K = CHOL_NB;
-      a.A = opnd(SLOT_C, below, rp);
-      a.B = opnd(SLOT_W, dk, rp);
-      a.E.slot = SLOT_L; a.E.off = below; a.E.ld = rp;
-      HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
-    }
-    {
-      GemmArgs a = base;  // C22 -= L21 L21^T (lower tiles)
-      a.M = rem; a.N = rem; a.K = CHOL_NB;
-      a.A = opnd(SLOT_L, below, rp);
-      a.B = opnd(SLOT_L, below, rp);
-      a.lower_only = 1;
-      a.E.slot = SLOT_C; a.E.off = below + CHOL_NB; a.E.ld = rp;
-      a.E.alpha = -1.f; a.E.beta = 1.f;
-      HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
-    }
-  }
+  // blocked right-looking Cholesky, one fused launch per 64-wide panel
+  for (int k = 0; k < rp; k += CHOL_NB)
+    HIPCHK(launch_chol_panel(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, k, rp, piv_lo, piv_hi, s));
   // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]]
   for (int sz = CHOL_NB; sz < rp; sz *= 2) {
     const int pairs = rp / (2 * sz);
@@ -287,9 +265,8 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs base = rebase(base_args(st, g), row0);
   hipEvent_t* ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
-  if (ev) { HIPCHK(hipEventRecord(ev[0], s)); st->group_timed[gi] = 1; }
-
   HIPCHK(launch_fill_i32(tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  if (ev) { HIPCHK(hipEventRecord(ev[0], s)); st->group_timed[gi] = 1; }
   {
     GemmArgs a = base;  // K1: Z = (M+G) Q
     a.M = m; a.N = r; a.K = n;
@@ -301,9 +278,10 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   }
   if (ev) HIPCHK(hipEventRecord(ev[1], s));
   {
-    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, s);
+    // pass 1: any positive finite pivot; pass 2: the Gram matrix of a nearly orthonormal P1 has pivots near 1
+    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, s);
     if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, s);
+    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, s);
     if (rc != DION_OK) return rc;
   }
   if (ev) HIPCHK(hipEventRecord(ev[2], s));

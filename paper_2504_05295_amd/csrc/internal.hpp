@@ -27,7 +27,7 @@ enum Slot {
   NSLOTS = 20
 };
 
-constexpr int CHOL_NB = 128;       // Cholesky panel width (diagonal block factored in LDS)
+constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
 constexpr float COLNORM_EPS = 1e-8f;
 constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares
 
@@ -61,7 +61,7 @@ hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot
                              int status_slot, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
                                 int first_stream, hipStream_t s);
-hipError_t launch_chol_diag(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, long long off,
-                            long long ld, hipStream_t s);
+hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,
+                             float piv_lo, float piv_hi, hipStream_t s);
 
 }  // namespace dion

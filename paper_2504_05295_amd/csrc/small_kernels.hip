@@ -213,73 +213,4 @@ hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int s
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- Cholesky of one diagonal block + its inverse
-// Factors the NB x NB diagonal block at element offset `off` of C (lower triangle) into L (written
-// to the same position of the L matrix, upper part zero) and writes W = L^-1 to the same position of
-// the W matrix.  A non-positive or non-finite pivot sets the status word (Cholesky-QR breakdown,
-// Appendix A) and the block is completed with that pivot replaced by 1.
-template <int NB>
-__global__ void __launch_bounds__(256) chol_diag_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
-                                                        long long off, long long ld) {
-  void* const* tab = table + (size_t)blockIdx.x * nslots;
-  const float* C = (const float*)tab[slotC] + off;
-  float* L = (float*)tab[slotL] + off;
-  float* W = (float*)tab[slotW] + off;
-  int* status = (int*)tab[SLOT_STATUS];
-  // strictly-lower part: L.  upper part incl. diagonal: W^T (W[i][c] at A[c][i], i >= c).
-  __shared__ float A[NB][NB + 1];
-  __shared__ float dinv[NB];
-  const int t = threadIdx.x;
-  for (int idx = t; idx < NB * NB; idx += 256) {
-    const int i = idx / NB, j = idx % NB;
-    A[i][j] = (j <= i) ? C[i * ld + j] : 0.f;
-  }
-  const int ty = t >> 4, tx = t & 15;
-  bool bad = false;
-  for (int j = 0; j < NB; ++j) {
-    __syncthreads();
-    float piv = A[j][j];
-    if (!(piv > 0.f) || !(piv < 3.0e38f)) { bad = true; piv = 1.f; }
-    const float sq = sqrtf(piv);
-    const float rs = 1.0f / sq;
-    __syncthreads();
-    for (int i = j + 1 + t; i < NB; i += 256) A[i][j] *= rs;
-    if (t == 0) { A[j][j] = sq; dinv[j] = rs; }
-    __syncthreads();
-    const int rem = NB - j - 1;
-    for (int ii = ty; ii < rem; ii += 16) {
-      const float lij = A[j + 1 + ii][j];
-      for (int kk = tx; kk <= ii; kk += 16) A[j + 1 + ii][j + 1 + kk] -= lij * A[j + 1 + kk][j];
-    }
-  }
-  __syncthreads();
-  if (bad && t == 0) *status = 1;
-  // write L (lower incl. diagonal, zeros above)
-  for (int idx = t; idx < NB * NB; idx += 256) {
-    const int i = idx / NB, j = idx % NB;
-    L[i * ld + j] = (j <= i) ? A[i][j] : 0.f;
-  }
-  __syncthreads();
-  // inverse by forward substitution, one thread per column c: w_i = -(sum_{k=c}^{i-1} L[i][k] w_k) / L[i][i]
-  if (t < NB) {
-    const int c = t;
-    A[c][c] = dinv[c];
-    for (int i = c + 1; i < NB; ++i) {
-      float acc = 0.f;
-      for (int k = c; k < i; ++k) acc += A[i][k] * A[c][k];   // A[i][k] = L (k < i), A[c][k] = W[k][c] (k >= c)
-      A[c][i] = -acc * dinv[i];
-    }
-  }
-  __syncthreads();
-  for (int idx = t; idx < NB * NB; idx += 256) {
-    const int i = idx / NB, j = idx % NB;
-    W[i * ld + j] = (j <= i) ? A[j][i] : 0.f;
-  }
-}
-hipError_t launch_chol_diag(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, long long off,
-                            long long ld, hipStream_t s) {
-  hipLaunchKernelGGL(chol_diag_kernel<CHOL_NB>, dim3(batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, off, ld);
-  return hipGetLastError();
-}
-
 }  // namespace dion

@@ -41,7 +41,7 @@ class GpuProblem:
             if kind == "gaussian":
                 g = inputs.gradient(m, n, step, self.seed, i, bf16=self.g_bf16)
             else:
-                g = inputs.structured_gradient(m, n, step, k=max(4, r // 2), seed=self.seed, index=i, bf16=self.g_bf16)
+                g = inputs.structured_gradient(m, n, step, k=2 * r, seed=self.seed, index=i, bf16=self.g_bf16, noise=1e-2)
             out.append(g)
         return out
 
