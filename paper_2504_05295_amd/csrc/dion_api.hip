@@ -97,6 +97,12 @@ Carve carve_entry(const Group& g) {
   take(SLOT_SPART, (size_t)((g.n + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
+  // bf16 operand copies (two bf16 values per float slot)
+  take(SLOT_QT16, (nr + 1) / 2);
+  take(SLOT_P16, (mr + 1) / 2);
+  take(SLOT_PT16, (mr + 1) / 2);
+  take(SLOT_R16, (nr + 1) / 2);
+  take(SLOT_Q16, (nr + 1) / 2);
   c.total = pos;
   return c;
 }
@@ -267,7 +273,21 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   hipEvent_t* ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
   HIPCHK(launch_fill_i32(tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (ev) { HIPCHK(hipEventRecord(ev[0], s)); st->group_timed[gi] = 1; }
-  {
+  // Large-tile bf16 kernels need tile-aligned shapes and bf16 copies of the small operands.
+  const bool big = bf16 && m % 256 == 0 && n % 256 == 0 && r % 128 == 0;
+  auto cfg2 = [&](long long Mo, long long No) {
+    return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
+  };
+  if (big) {
+    HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_Q, -1, SLOT_QT16, n, r, s));
+    GemmArgs a = base;  // K1: Z = (M+G) Q
+    a.M = m; a.N = r; a.K = n;
+    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+    a.B = opnd(SLOT_QT16, 0, n);
+    a.E.slot = SLOT_Z; a.E.ld = r;
+    a.xcd_remap = 1;
+    HIPCHK(gemm2_k1(cfg2(m, r), gbf16, a, batch, s));
+  } else {
     GemmArgs a = base;  // K1: Z = (M+G) Q
     a.M = m; a.N = r; a.K = n;
     a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
@@ -284,8 +304,17 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
     rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, s);
     if (rc != DION_OK) return rc;
   }
+  if (big) HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
   if (ev) HIPCHK(hipEventRecord(ev[2], s));
-  {
+  if (big) {
+    GemmArgs a = base;  // K2: R = (M+G)^T P
+    a.M = n; a.N = r; a.K = m;
+    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+    a.B = opnd(SLOT_PT16, 0, m);
+    a.E.slot = SLOT_R; a.E.ld = r;
+    a.xcd_remap = 1;
+    HIPCHK(gemm2_k2(cfg2(n, r), gbf16, a, batch, s));
+  } else {
     GemmArgs a = base;  // K2: R = (M+G)^T P
     a.M = n; a.N = r; a.K = m;
     a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
@@ -296,9 +325,20 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   }
   if (ev) HIPCHK(hipEventRecord(ev[3], s));
   HIPCHK(launch_colnorm(tab, NSLOTS, batch, SLOT_R, n, r, s));
-  HIPCHK(launch_scale_cols(tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, s));
+  HIPCHK(launch_scale_cols(tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, big ? SLOT_Q16 : -1, big ? SLOT_R16 : -1, s));
   if (ev) HIPCHK(hipEventRecord(ev[4], s));
-  {
+  if (big) {
+    GemmArgs a = base;  // K5: fused M and X update
+    a.M = m; a.N = n; a.K = r;
+    a.A = opnd(SLOT_P16, 0, r);
+    a.B = opnd(SLOT_R16, 0, r);
+    a.B2 = opnd(SLOT_Q16, 0, r);
+    a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
+    a.E.c_m = 1.0f - mu;
+    a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
+    a.status_slot = SLOT_STATUS;
+    HIPCHK(gemm2_k5(G2_256x256, gbf16, a, batch, s));
+  } else {
     GemmArgs a = base;  // K5: fused M and X update
     a.M = m; a.N = n; a.K = r;
     a.A = opnd(SLOT_P, 0, r);
@@ -379,6 +419,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_Q16; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];
@@ -406,7 +447,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, g.n, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
-    if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
   }
   *out = st;
   return DION_OK;

@@ -1,0 +1,273 @@
+// Large-tile bf16 MFMA GEMM core for gfx950 (v_mfma_f32_32x32x16_bf16), used by the three big
+// products of the Dion step when the shapes are multiples of the tile:
+//   K1  Z = (M+G) Q          A = fused sum read along k,           B = Q^T  (bf16 copy, k contiguous)
+//   K2  R = (M+G)^T P        A = fused sum transposed into LDS,    B = P^T  (bf16 copy, k contiguous)
+//   K5  M, X updates         A = P (bf16 copy), B = R, B2 = Q_new (bf16 copies), fused epilogue
+// Same conventions as gemm_core.hpp: C[i,j] = sum_k A(i,k) B(j,k), LDS tiles [row][k] with 16 bytes
+// of padding per row, register prefetch of the next k-slab while the MFMAs of the current one run.
+#pragma once
+#include "gemm_core.hpp"
+
+namespace dion {
+
+enum { SRC2_BF16_KC = 0, SRC2_SUM_KC = 1, SRC2_SUM_KS = 2 };
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int MINW_>
+struct TileCfg2 {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NT = 64 * WAVES_M_ * WAVES_N_;
+  static constexpr int WTM = BM_ / WAVES_M_, WTN = BN_ / WAVES_N_;
+  static constexpr int MI = WTM / 32, NI = WTN / 32;
+  static constexpr int STAGES = STAGES_, MINW = MINW_;
+  static constexpr int BKP = BK_ + 8;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK_ % 16 == 0, "tile shape");
+};
+
+// Global -> registers -> LDS mover of one ROWS x BK bf16 operand tile.
+template <class Cfg, int ROWS, int SRC, bool GBF16>
+struct Mover2 {
+  static constexpr int BK = Cfg::BK, NT = Cfg::NT, BKP = Cfg::BKP;
+  static constexpr bool KS = (SRC == SRC2_SUM_KS);
+  static constexpr bool SUM = (SRC != SRC2_BF16_KC);
+  // KC: item = 1 row x 8 k.   KS: item = 8 k x 4 rows.
+  static constexpr int ITEMS = KS ? (ROWS / 4) * (BK / 8) : ROWS * (BK / 8);
+  static constexpr int PER = ITEMS / NT;
+  static_assert(ITEMS % NT == 0 && PER >= 1, "tile does not divide over the workgroup");
+  static constexpr int AW = !SUM ? 4 : (KS ? 32 : 8);                 // 32-bit words of the main operand per item
+  static constexpr int GW = !SUM ? 1 : (GBF16 ? AW / 2 : AW);         // words of G per item
+
+  uint32_t a[PER][AW];
+  uint32_t g[PER][GW];
+
+  __device__ __forceinline__ void load(const void* __restrict__ p0, const void* __restrict__ p1, long long ld, int row0, int k0) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int item = t + i * NT;
+      if constexpr (!KS) {
+        const int row = item / (BK / 8), kc = item % (BK / 8);
+        const long long idx = (long long)(row0 + row) * ld + (k0 + kc * 8);
+        if constexpr (!SUM) {
+          const u32x4_t x = *(const u32x4_t*)((const uint16_t*)p0 + idx);
+          a[i][0] = x[0]; a[i][1] = x[1]; a[i][2] = x[2]; a[i][3] = x[3];
+        } else {
+          const u32x4_t x0 = *(const u32x4_t*)((const float*)p0 + idx);
+          const u32x4_t x1 = *(const u32x4_t*)((const float*)p0 + idx + 4);
+          a[i][0] = x0[0]; a[i][1] = x0[1]; a[i][2] = x0[2]; a[i][3] = x0[3];
+          a[i][4] = x1[0]; a[i][5] = x1[1]; a[i][6] = x1[2]; a[i][7] = x1[3];
+          if constexpr (GBF16) {
+            const u32x4_t y = *(const u32x4_t*)((const uint16_t*)p1 + idx);
+            g[i][0] = y[0]; g[i][1] = y[1]; g[i][2] = y[2]; g[i][3] = y[3];
+          } else {
+            const u32x4_t y0 = *(const u32x4_t*)((const float*)p1 + idx);
+            const u32x4_t y1 = *(const u32x4_t*)((const float*)p1 + idx + 4);
+            g[i][0] = y0[0]; g[i][1] = y0[1]; g[i][2] = y0[2]; g[i][3] = y0[3];
+            g[i][4] = y1[0]; g[i][5] = y1[1]; g[i][6] = y1[2]; g[i][7] = y1[3];
+          }
+        }
+      } else {
+        const int rg = item % (ROWS / 4), kc = item / (ROWS / 4);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          const long long idx = (long long)(k0 + kc * 8 + kk) * ld + (row0 + rg * 4);
+          const u32x4_t x = *(const u32x4_t*)((const float*)p0 + idx);
+          a[i][4 * kk + 0] = x[0]; a[i][4 * kk + 1] = x[1]; a[i][4 * kk + 2] = x[2]; a[i][4 * kk + 3] = x[3];
+          if constexpr (GBF16) {
+            const u32x2_t y = *(const u32x2_t*)((const uint16_t*)p1 + idx);
+            g[i][2 * kk + 0] = y[0]; g[i][2 * kk + 1] = y[1];
+          } else {
+            const u32x4_t y = *(const u32x4_t*)((const float*)p1 + idx);
+            g[i][4 * kk + 0] = y[0]; g[i][4 * kk + 1] = y[1]; g[i][4 * kk + 2] = y[2]; g[i][4 * kk + 3] = y[3];
+          }
+        }
+      }
+    }
+  }
+
+  // fp32 value e of item i of the fused sum M + G
+  __device__ __forceinline__ float sum(int i, int e) const {
+    float x = __builtin_bit_cast(float, a[i][e]);
+    if constexpr (GBF16) x += (e & 1) ? bf16_hi(g[i][e >> 1]) : bf16_lo(g[i][e >> 1]);
+    else x += __builtin_bit_cast(float, g[i][e]);
+    return x;
+  }
+
+  __device__ __forceinline__ void store(uint16_t* __restrict__ lds) const {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int item = t + i * NT;
+      if constexpr (!KS) {
+        const int row = item / (BK / 8), kc = item % (BK / 8);
+        u32x4_t w;
+        if constexpr (!SUM) {
+          w[0] = a[i][0]; w[1] = a[i][1]; w[2] = a[i][2]; w[3] = a[i][3];
+        } else {
+          w[0] = pack_bf16x2(sum(i, 0), sum(i, 1)); w[1] = pack_bf16x2(sum(i, 2), sum(i, 3));
+          w[2] = pack_bf16x2(sum(i, 4), sum(i, 5)); w[3] = pack_bf16x2(sum(i, 6), sum(i, 7));
+        }
+        *(u32x4_t*)(lds + row * BKP + kc * 8) = w;
+      } else {
+        const int rg = item % (ROWS / 4), kc = item / (ROWS / 4);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          u32x4_t w;
+          w[0] = pack_bf16x2(sum(i, 0 * 4 + rr), sum(i, 1 * 4 + rr));
+          w[1] = pack_bf16x2(sum(i, 2 * 4 + rr), sum(i, 3 * 4 + rr));
+          w[2] = pack_bf16x2(sum(i, 4 * 4 + rr), sum(i, 5 * 4 + rr));
+          w[3] = pack_bf16x2(sum(i, 6 * 4 + rr), sum(i, 7 * 4 + rr));
+          *(u32x4_t*)(lds + (rg * 4 + rr) * BKP + kc * 8) = w;
+        }
+      }
+    }
+  }
+};
+
+template <class Cfg, int ASRC, bool GBF16, int EPI, bool DUAL>
+__global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, BKP = Cfg::BKP;
+  constexpr int MI = Cfg::MI, NI = Cfg::NI, ST = Cfg::STAGES;
+  __shared__ __attribute__((aligned(16))) uint16_t As[ST * BM * BKP];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[ST * BN * BKP];
+  __shared__ __attribute__((aligned(16))) uint16_t B2s[DUAL ? ST * BN * BKP : 8];
+
+  int bid = blockIdx.x;
+  if (g.xcd_remap) {
+    const int per = gridDim.x >> 3;
+    bid = (bid & 7) * per + (bid >> 3);
+  }
+  const int ntile = g.tiles_m * g.tiles_n;
+  const int tile = bid % ntile;
+  const int b = bid / ntile;
+  const int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+
+  void* const* tab = g.table + (size_t)b * g.nslots;
+  if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
+
+  const void* A0 = tab[g.A.slot0];
+  const void* A1 = (ASRC != SRC2_BF16_KC) ? tab[g.A.slot1] : nullptr;
+  const void* B0 = tab[g.B.slot0];
+  const void* B20 = DUAL ? tab[g.B2.slot0] : nullptr;
+
+  const int row0 = tm * BM, col0 = tn * BN;
+
+  Mover2<Cfg, BM, ASRC, GBF16> ma;
+  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb;
+  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb2;
+
+  f32x16_t acc[MI][NI];
+  f32x16_t acc2[DUAL ? MI : 1][DUAL ? NI : 1];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      if constexpr (DUAL) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0.f;
+      }
+    }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
+  const int lr = lane & 31, lk = lane >> 5;
+  const int K = g.K;
+
+  ma.load(A0, A1, g.A.ld, row0, 0);
+  mb.load(B0, nullptr, g.B.ld, col0, 0);
+  if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, 0);
+  ma.store(As);
+  mb.store(Bs);
+  if constexpr (DUAL) mb2.store(B2s);
+  __syncthreads();
+
+  int cur = 0;
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    const bool more = k0 + BK < K;
+    if (more) {
+      ma.load(A0, A1, g.A.ld, row0, k0 + BK);
+      mb.load(B0, nullptr, g.B.ld, col0, k0 + BK);
+      if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, k0 + BK);
+    }
+    const uint16_t* Ac = As + cur * BM * BKP;
+    const uint16_t* Bc = Bs + cur * BN * BKP;
+    const uint16_t* B2c = B2s + (DUAL ? cur * BN * BKP : 0);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8_t af[MI], bf[NI], bf2[DUAL ? NI : 1];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(Ac + (wm * Cfg::WTM + i * 32 + lr) * BKP + kk + lk * 8);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        bf[j] = *(const bf16x8_t*)(Bc + (wn * Cfg::WTN + j * 32 + lr) * BKP + kk + lk * 8);
+        if constexpr (DUAL) bf2[j] = *(const bf16x8_t*)(B2c + (wn * Cfg::WTN + j * 32 + lr) * BKP + kk + lk * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+          if constexpr (DUAL) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf2[j], acc2[i][j], 0, 0, 0);
+        }
+    }
+    if constexpr (ST == 1) __syncthreads();
+    const int nxt = (ST == 2) ? (cur ^ 1) : 0;
+    if (more) {
+      ma.store(As + nxt * BM * BKP);
+      mb.store(Bs + nxt * BN * BKP);
+      if constexpr (DUAL) mb2.store(B2s + nxt * BN * BKP);
+    }
+    __syncthreads();
+    cur = nxt;
+  }
+
+  if constexpr (EPI == EPI_STORE) {
+    float* C = (float*)tab[g.E.slot] + g.E.off;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+          const int col = col0 + wn * Cfg::WTN + j * 32 + lr;
+          C[(long long)row * g.E.ld + col] = acc[i][j][v];
+        }
+  } else {
+    // M <- (M + G) - (1-mu) (P R^T);   X <- X - eta sqrt(m/n) (P Q_new^T)
+    float* Xp = (float*)tab[g.E.slotX];
+    float* Mp = (float*)tab[g.E.slotM];
+    const void* Gp = tab[g.E.slotG];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+          const int col = col0 + wn * Cfg::WTN + j * 32 + lr;
+          const long long idx = (long long)row * g.E.ld + col;
+          const float gv = GBF16 ? bf16_to_f32(((const uint16_t*)Gp)[idx]) : ((const float*)Gp)[idx];
+          const float bv = Mp[idx] + gv;
+          Mp[idx] = bv - g.E.c_m * acc[i][j][v];
+          if constexpr (DUAL) Xp[idx] = Xp[idx] - g.E.c_x * acc2[i][j][v];
+        }
+  }
+}
+
+template <class Cfg, int ASRC, bool GBF16, int EPI, bool DUAL>
+inline hipError_t launch_gemm2(GemmArgs g, int batch, hipStream_t stream) {
+  if (g.M % Cfg::BM || g.N % Cfg::BN || g.K % Cfg::BK) return hipErrorInvalidValue;
+  g.tiles_m = g.M / Cfg::BM;
+  g.tiles_n = g.N / Cfg::BN;
+  const long long blocks = (long long)g.tiles_m * g.tiles_n * batch;
+  if (blocks <= 0) return hipSuccess;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
+  hipLaunchKernelGGL((gemm2_kernel<Cfg, ASRC, GBF16, EPI, DUAL>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace dion

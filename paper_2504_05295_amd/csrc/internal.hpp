@@ -24,7 +24,12 @@ enum Slot {
   SLOT_S,      // column norms of R            r
   SLOT_D,      // 1 / (s + eps)                r
   SLOT_STATUS, // int32 breakdown flag
-  NSLOTS = 20
+  SLOT_QT16,   // Q^T as bf16                  r x n   (B operand of K1, k = n contiguous)
+  SLOT_P16,    // P as bf16                    m x r   (A operand of K5)
+  SLOT_PT16,   // P^T as bf16                  r x m   (B operand of K2, k = m contiguous)
+  SLOT_R16,    // R as bf16                    n x r   (B operand of K5)
+  SLOT_Q16,    // Q_new as bf16                n x r   (second B operand of K5)
+  NSLOTS = 24
 };
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
@@ -44,6 +49,12 @@ int pick_variant(long long M, long long N, long long K, long long batch, bool al
 hipError_t gemm_k1(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // A = M+G (KC), B = fp32 KS
 hipError_t gemm_k2(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // A = M+G (KS), B = fp32 KS
 hipError_t gemm_k5(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // dual B, fused update
+// Large-tile bf16 versions (gemm_core2.hpp); `cfg` selects the tile, see gemm2_*.hip.  They return
+// hipErrorInvalidValue when the shape is not a multiple of the tile.
+enum { G2_256x256 = 0, G2_128x128 = 1 };
+hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
+hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
+hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
 hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
 hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KS, B KS
@@ -58,7 +69,11 @@ hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int
                                   int nsplit, long long split_stride, hipStream_t s);
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s);
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
-                             int status_slot, hipStream_t s);
+                             int status_slot, int slot_out16, int slot_in16, hipStream_t s);
+// fp32 [rows][cols] -> bf16 copy [rows][cols] (slot_out16 >= 0) and bf16 transpose [cols][rows] (slot_outT16 >= 0);
+// rows and cols must be multiples of 64.
+hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
+                               long long rows, long long cols, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
                                 int first_stream, hipStream_t s);
 hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,

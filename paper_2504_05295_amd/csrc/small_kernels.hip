@@ -143,23 +143,69 @@ hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in
   return hipGetLastError();
 }
 
-// out[row][col] = in[row][col] * d[col]   (in may alias out)
-__global__ void scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows, int r, int status_slot) {
+// out[row][col] = in[row][col] * d[col]   (in may alias out).  Optionally also stores bf16 copies of the
+// result (slot_out16) and of the input (slot_in16): the operands of the fused update kernel.
+__global__ void scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows, int r, int status_slot,
+                                  int slot_out16, int slot_in16) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   if (status_slot >= 0 && *(const int*)tab[status_slot] != 0) return;
   const float* in = (const float*)tab[slot_in];
   float* out = (float*)tab[slot_out];
+  uint16_t* out16 = slot_out16 >= 0 ? (uint16_t*)tab[slot_out16] : nullptr;
+  uint16_t* in16 = slot_in16 >= 0 ? (uint16_t*)tab[slot_in16] : nullptr;
   const float* d = (const float*)tab[SLOT_D];
   const long long total = rows * r;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x)
-    out[i] = in[i] * d[i % r];
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const float v = in[i];
+    const float q = v * d[i % r];
+    out[i] = q;
+    if (out16) out16[i] = (uint16_t)(pack_bf16x2(q, 0.f) & 0xffffu);
+    if (in16) in16[i] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+  }
 }
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
-                             int status_slot, hipStream_t s) {
+                             int status_slot, int slot_out16, int slot_in16, hipStream_t s) {
   long long blocks = (rows * r + 1023) / 1024;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(scale_cols_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_in, slot_out, rows, r,
-                     status_slot);
+                     status_slot, slot_out16, slot_in16);
+  return hipGetLastError();
+}
+
+// fp32 [rows][cols] -> bf16 [rows][cols] and / or bf16 [cols][rows], 64x64 tiles transposed through LDS.
+__global__ void __launch_bounds__(256) convert_bf16_kernel(void* const* table, int nslots, int slot_in, int slot_out16,
+                                                           int slot_outT16, long long rows, long long cols) {
+  void* const* tab = table + (size_t)blockIdx.z * nslots;
+  const float* in = (const float*)tab[slot_in];
+  uint16_t* out16 = slot_out16 >= 0 ? (uint16_t*)tab[slot_out16] : nullptr;
+  uint16_t* outT = slot_outT16 >= 0 ? (uint16_t*)tab[slot_outT16] : nullptr;
+  __shared__ float tile[64][65];
+  const long long row0 = (long long)blockIdx.y * 64, col0 = (long long)blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int rr = p * 16 + (t >> 4), c4 = (t & 15) * 4;
+    const f32x4_t v = *(const f32x4_t*)(in + (row0 + rr) * cols + col0 + c4);
+    tile[rr][c4 + 0] = v[0]; tile[rr][c4 + 1] = v[1]; tile[rr][c4 + 2] = v[2]; tile[rr][c4 + 3] = v[3];
+    if (out16) {
+      u32x2_t w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+      *(u32x2_t*)(out16 + (row0 + rr) * cols + col0 + c4) = w;
+    }
+  }
+  if (!outT) return;
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int cc = p * 16 + (t >> 4), r4 = (t & 15) * 4;
+    u32x2_t w = {pack_bf16x2(tile[r4 + 0][cc], tile[r4 + 1][cc]), pack_bf16x2(tile[r4 + 2][cc], tile[r4 + 3][cc])};
+    *(u32x2_t*)(outT + (col0 + cc) * rows + row0 + r4) = w;
+  }
+}
+hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
+                               long long rows, long long cols, hipStream_t s) {
+  if (rows % 64 || cols % 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(convert_bf16_kernel, dim3((unsigned)(cols / 64), (unsigned)(rows / 64), batch), dim3(256), 0, s, table, nslots,
+                     slot_in, slot_out16, slot_outT16, rows, cols);
   return hipGetLastError();
 }
 

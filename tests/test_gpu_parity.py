@@ -72,3 +72,9 @@ def test_c2_2048_twenty_steps(math):
 def test_structured_gradient_fp32():
     # power-law spectrum: B Q is markedly worse conditioned than for Gaussian inputs
     run_trajectory((512, 384, 64), False, "f32", 4, "householder", kind="structured")  # cond(Z) about 170
+
+
+@pytest.mark.parametrize("r", [512, 2048])
+def test_c3_8192_bf16_steps(r):
+    # full-size configuration, same launch configuration as the benchmark; oracle uses LAPACK's QR here
+    run_trajectory((8192, 8192, r), True, "bf16", 2, "lapack")
