@@ -43,6 +43,7 @@ struct Group {
   int rp;          // r padded to CHOL_NB * 2^p
   int first_row, count;
   int gram_variant, gram_splitk, gram_kps;
+  int gram2_splitk;   // split-K of the split-bf16 Gram product (large-tile path)
   size_t bytes_per_entry;
 };
 
@@ -69,6 +70,12 @@ void plan_gram(Group& g) {
   kps = (kps + 2 * bk - 1) / (2 * bk) * (2 * bk);
   g.gram_kps = (int)kps;
   g.gram_splitk = (int)((g.m + kps - 1) / kps);
+  // large-tile path: 128x128 tiles, lower triangle only
+  const long long t2 = (g.r + 127) / 128;
+  long long want2 = (768 + t2 * (t2 + 1) / 2 * g.count - 1) / (t2 * (t2 + 1) / 2 * g.count);
+  if (want2 > 32) want2 = 32;
+  if (want2 < 1) want2 = 1;
+  g.gram2_splitk = (int)want2;
 }
 
 // workspace floats of one matrix, in slot order
@@ -93,7 +100,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_L, rr);
   take(SLOT_W, rr);
   take(SLOT_T, rr);
-  take(SLOT_CPART, g.gram_splitk > 1 ? rr * g.gram_splitk : 0);
+  take(SLOT_CPART, rr * (size_t)std::max(g.gram_splitk, g.gram2_splitk));
   take(SLOT_SPART, (size_t)((g.n + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
@@ -103,6 +110,10 @@ Carve carve_entry(const Group& g) {
   take(SLOT_PT16, (mr + 1) / 2);
   take(SLOT_R16, (nr + 1) / 2);
   take(SLOT_Q16, (nr + 1) / 2);
+  take(SLOT_ZL16, (mr + 1) / 2);
+  take(SLOT_ZLT16, (mr + 1) / 2);
+  take(SLOT_WH16, ((size_t)g.r * g.r + 1) / 2);
+  take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
   c.total = pos;
   return c;
 }
@@ -203,14 +214,35 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 
 // One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices starting at
 // table row `row0` of group g.
+// With `split` the two large products run on the bf16 matrix pipe with split operands (x = hi + lo,
+// three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
+// Cholesky factorisation and the triangular inverse stay in fp32.
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, float piv_lo, float piv_hi,
-                hipStream_t s) {
+                bool split, hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
   GemmArgs base = rebase(base_args(st, g), row0);
   // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
-  {
+  if (split) {
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, g.m, r, SLOT_P16, SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
+    GemmArgs a = base;
+    a.M = r; a.N = r; a.K = 3 * (int)g.m;
+    a.nseg = 3; a.kseg = (int)g.m;
+    a.segA[0] = SLOT_PT16; a.segB[0] = SLOT_PT16;
+    a.segA[1] = SLOT_PT16; a.segB[1] = SLOT_ZLT16;
+    a.segA[2] = SLOT_ZLT16; a.segB[2] = SLOT_PT16;
+    a.A = opnd(SLOT_PT16, 0, g.m);
+    a.B = opnd(SLOT_PT16, 0, g.m);
+    a.lower_only = 1;
+    a.splitk = g.gram2_splitk;
+    const int eff = gemm2_nt_splitk(G2_128x128, a);
+    a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
+    a.E.ld = rp;
+    a.E.split_stride = rr;
+    HIPCHK(gemm2_nt(G2_128x128, a, batch, s));
+    if (eff > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, eff, rr, s));
+  } else {
     GemmArgs a = base;
     a.M = r; a.N = r; a.K = (int)g.m;
     a.A = opnd(slot_in, 0, r);
@@ -252,7 +284,22 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
       HIPCHK(gemm_f32_nn(pick_variant(sz, sz, sz, (long long)batch * pairs, true), a, batch, s));
     }
   }
-  {
+  if (split) {
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s));
+    GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
+    a.M = (int)g.m; a.N = r; a.K = 3 * r;
+    a.nseg = 3; a.kseg = r;
+    a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;
+    a.segA[1] = SLOT_P16; a.segB[1] = SLOT_WL16;
+    a.segA[2] = SLOT_ZL16; a.segB[2] = SLOT_WH16;
+    a.A = opnd(SLOT_P16, 0, r);
+    a.B = opnd(SLOT_WH16, 0, r);
+    a.tri_k = 1;
+    a.E.slot = slot_out; a.E.ld = r;
+    a.xcd_remap = 1;
+    const int cfg = (g.m % 256 == 0 && r % 256 == 0 && (g.m / 256) * (r / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
+    HIPCHK(gemm2_nt(cfg, a, batch, s));
+  } else {
     GemmArgs a = base;  // out = in W^T   (= in L^-T)
     a.M = (int)g.m; a.N = r; a.K = r;
     a.A = opnd(slot_in, 0, r);
@@ -299,9 +346,9 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (ev) HIPCHK(hipEventRecord(ev[1], s));
   {
     // pass 1: any positive finite pivot; pass 2: the Gram matrix of a nearly orthonormal P1 has pivots near 1
-    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, s);
+    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, s);
     if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, s);
+    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, s);
     if (rc != DION_OK) return rc;
   }
   if (big) HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
@@ -419,7 +466,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_Q16; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_WL16; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];

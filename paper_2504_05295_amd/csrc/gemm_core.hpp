@@ -54,6 +54,11 @@ struct GemmArgs {
   int lower_only;       // skip tiles strictly above the diagonal
   int status_slot;      // >= 0: skip the whole problem when *status != 0
   int xcd_remap;        // spread consecutive logical tiles over one XCD (grid must be a multiple of 8)
+  // Large-tile kernels only: the contraction may run over up to three (A, B) operand pairs of length kseg
+  // each (split-bf16 products: hi*hi + hi*lo + lo*hi), all sharing A.ld / B.ld.  nseg == 0 means one pair.
+  int nseg, kseg;
+  int segA[3], segB[3];
+  int tri_k;            // B is lower triangular: column tile tn only needs k < (tn+1)*BN of every segment
   Operand A, B, B2;
   EpilogueDesc E;
 };

@@ -139,15 +139,16 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   }
   const int ntile = g.tiles_m * g.tiles_n;
   const int tile = bid % ntile;
-  const int b = bid / ntile;
+  int rest = bid / ntile;
+  const int ks = rest % g.splitk;
+  const int b = rest / g.splitk;
   const int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+  if (g.lower_only && tn * BN > tm * BM + BM - 1) return;
 
   void* const* tab = g.table + (size_t)b * g.nslots;
   if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
 
-  const void* A0 = tab[g.A.slot0];
   const void* A1 = (ASRC != SRC2_BF16_KC) ? tab[g.A.slot1] : nullptr;
-  const void* B0 = tab[g.B.slot0];
   const void* B20 = DUAL ? tab[g.B2.slot0] : nullptr;
 
   const int row0 = tm * BM, col0 = tn * BN;
@@ -173,24 +174,36 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
   const int lr = lane & 31, lk = lane >> 5;
-  const int K = g.K;
 
-  ma.load(A0, A1, g.A.ld, row0, 0);
-  mb.load(B0, nullptr, g.B.ld, col0, 0);
-  if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, 0);
-  ma.store(As);
-  mb.store(Bs);
-  if constexpr (DUAL) mb2.store(B2s);
+  // The contraction is a list of k-slabs: nseg operand pairs, each contributing kseg_eff / BK slabs.
+  const int nseg = g.nseg > 0 ? g.nseg : 1;
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
+  const int slabs_per_seg = kseg_eff / BK;
+  const int total = nseg * slabs_per_seg;
+  const int s_begin = ks * g.k_per_split;                     // k_per_split counts slabs here
+  const int s_end = min(total, s_begin + g.k_per_split);
+  auto issue = [&](int sl) {
+    const int seg = sl / slabs_per_seg, k0 = (sl - seg * slabs_per_seg) * BK;
+    const void* Ap = tab[g.nseg > 0 ? g.segA[seg] : g.A.slot0];
+    const void* Bp = tab[g.nseg > 0 ? g.segB[seg] : g.B.slot0];
+    ma.load(Ap, A1, g.A.ld, row0, k0);
+    mb.load(Bp, nullptr, g.B.ld, col0, k0);
+    if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, k0);
+  };
+
+  if (s_begin < s_end) {
+    issue(s_begin);
+    ma.store(As);
+    mb.store(Bs);
+    if constexpr (DUAL) mb2.store(B2s);
+  }
   __syncthreads();
 
   int cur = 0;
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    const bool more = k0 + BK < K;
-    if (more) {
-      ma.load(A0, A1, g.A.ld, row0, k0 + BK);
-      mb.load(B0, nullptr, g.B.ld, col0, k0 + BK);
-      if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, k0 + BK);
-    }
+  for (int sl = s_begin; sl < s_end; ++sl) {
+    const bool more = sl + 1 < s_end;
+    if (more) issue(sl + 1);
     const uint16_t* Ac = As + cur * BM * BKP;
     const uint16_t* Bc = Bs + cur * BN * BKP;
     const uint16_t* B2c = B2s + (DUAL ? cur * BN * BKP : 0);
@@ -224,7 +237,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   }
 
   if constexpr (EPI == EPI_STORE) {
-    float* C = (float*)tab[g.E.slot] + g.E.off;
+    float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -259,15 +272,35 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
 
 template <class Cfg, int ASRC, bool GBF16, int EPI, bool DUAL>
 inline hipError_t launch_gemm2(GemmArgs g, int batch, hipStream_t stream) {
-  if (g.M % Cfg::BM || g.N % Cfg::BN || g.K % Cfg::BK) return hipErrorInvalidValue;
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  if (g.M % Cfg::BM || g.N % Cfg::BN || kseg % Cfg::BK || kseg <= 0) return hipErrorInvalidValue;
+  if (g.tri_k && Cfg::BN % Cfg::BK) return hipErrorInvalidValue;
   g.tiles_m = g.M / Cfg::BM;
   g.tiles_n = g.N / Cfg::BN;
-  const long long blocks = (long long)g.tiles_m * g.tiles_n * batch;
+  if (g.splitk < 1) g.splitk = 1;
+  // k_per_split counts k-slabs of the longest column tile; every split gets at least one slab
+  const int total = (g.nseg > 0 ? g.nseg : 1) * (kseg / Cfg::BK);
+  if (g.splitk > total) g.splitk = total;
+  g.k_per_split = (total + g.splitk - 1) / g.splitk;
+  g.splitk = (total + g.k_per_split - 1) / g.k_per_split;
+  const long long blocks = (long long)g.tiles_m * g.tiles_n * g.splitk * batch;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
   hipLaunchKernelGGL((gemm2_kernel<Cfg, ASRC, GBF16, EPI, DUAL>), dim3((unsigned)blocks), dim3(Cfg::NT), 0, stream, g);
   return hipGetLastError();
+}
+
+// Number of split-K partial results launch_gemm2 will produce for these arguments (needed to size and
+// reduce the partial buffers).
+template <class Cfg>
+inline int gemm2_effective_splitk(const GemmArgs& g) {
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  const int total = (g.nseg > 0 ? g.nseg : 1) * (kseg / Cfg::BK);
+  int sk = g.splitk < 1 ? 1 : g.splitk;
+  if (sk > total) sk = total;
+  const int per = (total + sk - 1) / sk;
+  return (total + per - 1) / per;
 }
 
 }  // namespace dion

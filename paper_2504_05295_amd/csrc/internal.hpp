@@ -29,7 +29,13 @@ enum Slot {
   SLOT_PT16,   // P^T as bf16                  r x m   (B operand of K2, k = m contiguous)
   SLOT_R16,    // R as bf16                    n x r   (B operand of K5)
   SLOT_Q16,    // Q_new as bf16                n x r   (second B operand of K5)
-  NSLOTS = 24
+  // split-bf16 copies used by the orthonormalisation in bf16 mode (x = hi + lo, both bf16).  The hi parts
+  // of the m x r matrix live in SLOT_P16 / SLOT_PT16, which are free until P is final.
+  SLOT_ZL16,   // lo part                      m x r
+  SLOT_ZLT16,  // lo part, transposed          r x m
+  SLOT_WH16,   // hi part of L^-1              r x r
+  SLOT_WL16,   // lo part of L^-1              r x r
+  NSLOTS = 28
 };
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
@@ -55,6 +61,8 @@ enum { G2_256x256 = 0, G2_128x128 = 1 };
 hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
+hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s);   // bf16 A (KC) x bf16 B (KC), up to 3 operand pairs
+int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
 hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
 hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KS, B KS
@@ -72,6 +80,10 @@ hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot
                              int status_slot, int slot_out16, int slot_in16, hipStream_t s);
 // fp32 [rows][cols] -> bf16 copy [rows][cols] (slot_out16 >= 0) and bf16 transpose [cols][rows] (slot_outT16 >= 0);
 // rows and cols must be multiples of 64.
+// fp32 [rows][cols] (leading dimension ld_in) -> split bf16 x = hi + lo: plain copies [rows][cols] and transposed
+// copies [cols][rows]; any output slot may be -1.  rows and cols must be multiples of 64.
+hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot_in, long long ld_in, long long rows,
+                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s);
 hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
                                long long rows, long long cols, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,

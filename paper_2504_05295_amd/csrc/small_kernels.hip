@@ -209,6 +209,52 @@ hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int sl
   return hipGetLastError();
 }
 
+// x = hi + lo with hi = bf16(x), lo = bf16(x - hi): the three products hi*hi + hi*lo + lo*hi then carry about
+// 16 mantissa bits on the bf16 matrix pipe.
+__global__ void __launch_bounds__(256) split_bf16_kernel(void* const* table, int nslots, int slot_in, long long ld_in,
+                                                         long long rows, long long cols, int slot_hi, int slot_lo,
+                                                         int slot_hiT, int slot_loT) {
+  void* const* tab = table + (size_t)blockIdx.z * nslots;
+  const float* in = (const float*)tab[slot_in];
+  uint16_t* hi = slot_hi >= 0 ? (uint16_t*)tab[slot_hi] : nullptr;
+  uint16_t* lo = slot_lo >= 0 ? (uint16_t*)tab[slot_lo] : nullptr;
+  uint16_t* hiT = slot_hiT >= 0 ? (uint16_t*)tab[slot_hiT] : nullptr;
+  uint16_t* loT = slot_loT >= 0 ? (uint16_t*)tab[slot_loT] : nullptr;
+  __shared__ uint32_t tile[64][65];   // (lo << 16) | hi per element
+  const long long row0 = (long long)blockIdx.y * 64, col0 = (long long)blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int rr = p * 16 + (t >> 4), c4 = (t & 15) * 4;
+    const f32x4_t v = *(const f32x4_t*)(in + (row0 + rr) * ld_in + col0 + c4);
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      h[e] = pack_bf16x2(v[e], 0.f) & 0xffffu;
+      l[e] = pack_bf16x2(v[e] - bf16_to_f32((uint16_t)h[e]), 0.f) & 0xffffu;
+      tile[rr][c4 + e] = (l[e] << 16) | h[e];
+    }
+    if (hi) { u32x2_t w = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)}; *(u32x2_t*)(hi + (row0 + rr) * cols + col0 + c4) = w; }
+    if (lo) { u32x2_t w = {l[0] | (l[1] << 16), l[2] | (l[3] << 16)}; *(u32x2_t*)(lo + (row0 + rr) * cols + col0 + c4) = w; }
+  }
+  if (!hiT && !loT) return;
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int cc = p * 16 + (t >> 4), r4 = (t & 15) * 4;
+    const uint32_t e0 = tile[r4 + 0][cc], e1 = tile[r4 + 1][cc], e2 = tile[r4 + 2][cc], e3 = tile[r4 + 3][cc];
+    if (hiT) { u32x2_t w = {(e0 & 0xffffu) | (e1 << 16), (e2 & 0xffffu) | (e3 << 16)}; *(u32x2_t*)(hiT + (col0 + cc) * rows + row0 + r4) = w; }
+    if (loT) { u32x2_t w = {(e0 >> 16) | (e1 & 0xffff0000u), (e2 >> 16) | (e3 & 0xffff0000u)}; *(u32x2_t*)(loT + (col0 + cc) * rows + row0 + r4) = w; }
+  }
+}
+hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot_in, long long ld_in, long long rows,
+                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s) {
+  if (rows % 64 || cols % 64 || ld_in % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(cols / 64), (unsigned)(rows / 64), batch), dim3(256), 0, s, table, nslots,
+                     slot_in, ld_in, rows, cols, slot_hi, slot_lo, slot_hiT, slot_loT);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- Gaussian fill (Philox-4x32-10 + Box-Muller)
 __device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
   const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
