@@ -128,9 +128,13 @@ template <class Cfg, int ASRC, bool GBF16, int EPI, bool DUAL>
 __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArgs g) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, BKP = Cfg::BKP;
   constexpr int MI = Cfg::MI, NI = Cfg::NI, ST = Cfg::STAGES;
-  __shared__ __attribute__((aligned(16))) uint16_t As[ST * BM * BKP];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[ST * BN * BKP];
-  __shared__ __attribute__((aligned(16))) uint16_t B2s[DUAL ? ST * BN * BKP : 8];
+  constexpr int SP = 36;   // epilogue patch row stride in floats (16-byte aligned rows, conflict-free)
+  constexpr size_t OPER_BYTES = (size_t)(ST * BM * BKP + ST * BN * BKP + (DUAL ? ST * BN * BKP : 0)) * sizeof(uint16_t);
+  constexpr size_t PATCH_BYTES = (size_t)(Cfg::NT / 64) * 32 * SP * sizeof(float);
+  __shared__ __attribute__((aligned(16))) unsigned char smem[OPER_BYTES > PATCH_BYTES ? OPER_BYTES : PATCH_BYTES];
+  uint16_t* const As = (uint16_t*)smem;
+  uint16_t* const Bs = As + ST * BM * BKP;
+  uint16_t* const B2s = Bs + ST * BN * BKP;
 
   int bid = blockIdx.x;
   if (g.xcd_remap) {
@@ -236,18 +240,29 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
     cur = nxt;
   }
 
+  // ---- epilogue.  Each 32x32 accumulator tile goes through a wave-private LDS patch so that a lane ends
+  // up with four consecutive columns of one row: global accesses are then 16 bytes per lane, 128 bytes per
+  // row segment.  (The operand tiles in LDS are dead here: the k loop ended with a barrier.)
+  float* patch = (float*)smem + wave * 32 * SP;
+  const int prow = lane >> 3, pcol = (lane & 7) * 4;
+  auto to_patch = [&](const f32x16_t& t) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) patch[(8 * (v / 4) + 4 * lk + (v % 4)) * SP + lr] = t[v];
+  };
   if constexpr (EPI == EPI_STORE) {
     float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
+      for (int j = 0; j < NI; ++j) {
+        to_patch(acc[i][j]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-          const int col = col0 + wn * Cfg::WTN + j * 32 + lr;
-          C[(long long)row * g.E.ld + col] = acc[i][j][v];
+        for (int p = 0; p < 4; ++p) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+          *(f32x4_t*)(C + (long long)row * g.E.ld + col) = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
         }
+      }
   } else {
     // M <- (M + G) - (1-mu) (P R^T);   X <- X - eta sqrt(m/n) (P Q_new^T)
     float* Xp = (float*)tab[g.E.slotX];
@@ -256,17 +271,38 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
+      for (int j = 0; j < NI; ++j) {
+        long long idx[4];
+        f32x4_t mv[4], xv[4], gv[4];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-          const int col = col0 + wn * Cfg::WTN + j * 32 + lr;
-          const long long idx = (long long)row * g.E.ld + col;
-          const float gv = GBF16 ? bf16_to_f32(((const uint16_t*)Gp)[idx]) : ((const float*)Gp)[idx];
-          const float bv = Mp[idx] + gv;
-          Mp[idx] = bv - g.E.c_m * acc[i][j][v];
-          if constexpr (DUAL) Xp[idx] = Xp[idx] - g.E.c_x * acc2[i][j][v];
+        for (int p = 0; p < 4; ++p) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+          idx[p] = (long long)row * g.E.ld + col;
+          mv[p] = *(const f32x4_t*)(Mp + idx[p]);
+          if constexpr (DUAL) xv[p] = *(const f32x4_t*)(Xp + idx[p]);
+          if constexpr (GBF16) {
+            const u32x2_t w = *(const u32x2_t*)((const uint16_t*)Gp + idx[p]);
+            gv[p] = f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
+          } else {
+            gv[p] = *(const f32x4_t*)((const float*)Gp + idx[p]);
+          }
         }
+        to_patch(acc[i][j]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          *(f32x4_t*)(Mp + idx[p]) = (mv[p] + gv[p]) - g.E.c_m * a4;
+        }
+        if constexpr (DUAL) {
+          to_patch(acc2[i][j]);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+            *(f32x4_t*)(Xp + idx[p]) = xv[p] - g.E.c_x * a4;
+          }
+        }
+      }
   }
 }
 

@@ -1,0 +1,200 @@
+"""GPU tests of the C-ABI's behaviour beyond plain parity: batched steps over mixed shapes, breakdown
+reporting with untouched state, the library's own Gaussian initialisation, argument validation,
+determinism and the stage timers."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import dion_oracle as orc
+from paper_2504_05295_amd import inputs
+from gpu_harness import GpuProblem, one_step_report, relf
+
+pytestmark = pytest.mark.gpu
+MU, ETA = inputs.MU, inputs.ETA
+
+
+def check_batch(shapes, g_bf16, math, steps=2):
+    tol = 1e-4 if math == "f32" else 2e-2
+    gp = GpuProblem(shapes, g_bf16, math)
+    for t in range(steps):
+        grads = gp.grads_np(t)
+        before = [gp.host(i) for i in range(len(shapes))]
+        gp.upload_grads(grads)
+        status, bad = gp.step(MU, ETA, batched=True)
+        assert (status, bad) == (0, -1)
+        for i in range(len(shapes)):
+            g32 = gp.grad_as_f32(grads[i], g_bf16)
+            rep, _ = one_step_report(gp, i, before[i][0], before[i][1], before[i][2], g32, MU, ETA)
+            assert rep["X"] <= tol and rep["M"] <= tol, (i, shapes[i], rep)
+            assert rep["dX"] <= 2 * tol and rep["dM"] <= 2 * tol, (i, shapes[i], rep)
+            assert rep["orth"] <= (1e-5 if math == "f32" else 1e-3)
+    return gp
+
+
+def test_batched_mixed_shapes_fp32():
+    check_batch([(256, 256, 64)] * 3 + [(128, 384, 32)] * 2 + [(200, 136, 24), (64, 96, 48)], False, "f32")
+
+
+def test_batched_mixed_shapes_bf16():
+    # includes shapes that take the large-tile kernels (multiples of 256 / 128) and shapes that do not
+    check_batch([(512, 256, 128)] * 3 + [(256, 768, 128)] * 2 + [(192, 320, 48)], True, "bf16")
+
+
+def test_batched_equals_single_and_is_deterministic():
+    shapes = [(256, 128, 32)] * 4
+    a = GpuProblem(shapes, True, "bf16")
+    b = GpuProblem(shapes, True, "bf16")
+    singles = [GpuProblem([shapes[i]], True, "bf16", x0=[a.x0[i]], q_raw=[a.q_raw[i]]) for i in range(4)]
+    for t in range(2):
+        grads = a.grads_np(t)
+        a.upload_grads(grads)
+        b.upload_grads(grads)
+        assert a.step(MU, ETA, batched=True) == (0, -1)
+        assert b.step(MU, ETA, batched=True) == (0, -1)
+        for i, sp in enumerate(singles):
+            sp.upload_grads([grads[i]])
+            assert sp.step(MU, ETA, batched=False) == (0, -1)
+    for i in range(4):
+        for u, v, w in zip(a.host(i), b.host(i), singles[i].host(0)):
+            assert np.array_equal(u, v)            # same call twice: bit-identical (no atomics on results)
+            assert np.array_equal(u, w)            # same tile configuration => batched == single, bit for bit
+
+
+def test_breakdown_is_reported_and_state_untouched():
+    m, n, r = 256, 192, 32
+    q_raw = inputs.right_factor_raw(n, r)
+    q_raw[:, 7] = q_raw[:, 3]                       # two identical columns: Z = B Q is rank deficient
+    good = inputs.right_factor_raw(n, r, seed=5)
+    gp = GpuProblem([(m, n, r), (m, n, r)], False, "f32", q_raw=[good, q_raw])
+    grads = gp.grads_np(0)
+    gp.upload_grads(grads)
+    before = [gp.host(i) for i in range(2)]
+    status, bad = gp.step(MU, ETA, batched=True)
+    assert status == gp.B.DION_NUM_BREAKDOWN and bad == 1
+    for u, v in zip(before[1], gp.host(1)):
+        assert np.array_equal(u, v)                 # X, M, Q of the failing matrix untouched
+    rep, ref = one_step_report(gp, 0, before[0][0], before[0][1], before[0][2], grads[0], MU, ETA)
+    assert rep["X"] < 1e-4 and rep["M"] < 1e-4      # its neighbour in the batch was stepped normally
+    assert orc.dion_step(before[1][0], grads[1], before[1][1], before[1][2], MU, ETA)["status"] == orc.STATUS_BREAKDOWN
+    # zero buffer (M = 0 and G = 0) is the other degenerate case
+    gp2 = GpuProblem([(128, 128, 16)], False, "f32")
+    gp2.upload_grads([np.zeros((128, 128), dtype=np.float32)])
+    x0 = gp2.host()
+    assert gp2.step(MU, ETA)[0] == gp2.B.DION_NUM_BREAKDOWN
+    for u, v in zip(x0, gp2.host()):
+        assert np.array_equal(u, v)
+    # and the state object keeps working afterwards
+    gp2.upload_grads(gp2.grads_np(0))
+    assert gp2.step(MU, ETA) == (0, -1)
+
+
+def test_ill_conditioned_input_is_right_or_reported():
+    # cond(B Q) about 1e4: beyond what Cholesky-QR in fp32 can promise.  Either the step is accurate or the
+    # library says so and leaves the state alone; silent garbage is the one thing not allowed.
+    m, n, r = 512, 384, 64
+    gp = GpuProblem([(m, n, r)], False, "f32")
+    g = inputs.structured_gradient(m, n, 0, k=r // 2, noise=1e-3)
+    gp.upload_grads([g])
+    x_in, m_in, q_in = gp.host()
+    status, _ = gp.step(MU, ETA)
+    if status == 0:
+        rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, g, MU, ETA)
+        assert rep["X"] < 1e-4 and rep["M"] < 1e-4 and rep["orth"] < 1e-4, rep
+    else:
+        for u, v in zip((x_in, m_in, q_in), gp.host()):
+            assert np.array_equal(u, v)
+
+
+def test_mu_one_eta_zero_is_plain_accumulation():
+    gp = GpuProblem([(256, 256, 64)], True, "bf16")
+    g = gp.grads_np(0)
+    gp.upload_grads(g)
+    assert gp.step(MU, ETA) == (0, -1)
+    x1, m1, _ = gp.host()
+    g2 = gp.grads_np(1)
+    gp.upload_grads(g2)
+    assert gp.step(1.0, 0.0) == (0, -1)
+    x2, m2, _ = gp.host()
+    assert np.array_equal(x2, x1)
+    assert np.array_equal(m2, m1 + inputs.bf16_bits_to_f32(g2[0]))      # fp32 add of the stored values, no error feedback
+
+
+def test_library_draws_and_normalises_q():
+    shapes = [(128, 96, 16), (64, 200, 8)]
+    gp = GpuProblem(shapes, False, "f32", q_is_filled=False, init_seed=1234)
+    for i, (m, n, r) in enumerate(shapes):
+        _, M, Q = gp.host(i)
+        assert np.all(M == 0)
+        raw = orc.gaussian_fill(n * r, seed=1234, stream=i).reshape(n, r)
+        ref, _ = orc.col_norm(raw)
+        assert np.abs(Q - ref).max() < 2e-6
+        assert np.abs(np.linalg.norm(Q.astype(np.float64), axis=0) - 1).max() < 1e-6
+
+
+def test_argument_validation_on_device():
+    import torch
+    from paper_2504_05295_amd import binding as B
+    m, n, r = 128, 128, 16
+    gp = GpuProblem([(m, n, r)], False, "f32")
+    gp.upload_grads(gp.grads_np(0))
+    lib = B.lib()
+    st = gp.state.handle
+    X, G, M, Q = gp.X[0], gp.G[0], gp.M[0], gp.Q[0]
+    before = gp.host()
+
+    def call(x=X.data_ptr(), g=G.data_ptr(), mm=m, nn=n, rr=r, mu=0.9, eta=0.1):
+        return lib.dion_step(st, C.c_void_p(x), C.c_void_p(g), C.c_void_p(M.data_ptr()), C.c_void_p(Q.data_ptr()), mm, nn, rr,
+                             C.c_float(mu), C.c_float(eta), None)
+    assert call(x=X.data_ptr() + 4) == B.DION_EINVAL          # misaligned
+    assert call(g=0) == B.DION_EINVAL                         # null
+    assert call(mm=64) == B.DION_EINVAL                       # undeclared shape
+    assert call(mu=1.5) == B.DION_EINVAL and call(mu=-0.1) == B.DION_EINVAL
+    assert call(mu=float("nan")) == B.DION_EINVAL and call(eta=float("inf")) == B.DION_EINVAL
+    torch.cuda.synchronize()
+    for u, v in zip(before, gp.host()):
+        assert np.array_equal(u, v)                           # rejected calls launch nothing
+    # workspace too small / misaligned
+    need = B.dion_workspace_bytes([(m, n, r)], B.DION_G_F32, B.DION_MATH_F32)
+    ws = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    h = C.c_void_p(None)
+    args = ((C.c_int64 * 1)(m), (C.c_int64 * 1)(n), (C.c_int64 * 1)(r))
+    Mp, Qp = (C.c_void_p * 1)(M.data_ptr()), (C.c_void_p * 1)(Q.data_ptr())
+    assert lib.dion_init_state(C.byref(h), 1, *args, 0, 0, C.c_void_p(base), need - 1, Mp, Qp, 1, 0, None) == B.DION_EWORKSPACE
+    assert lib.dion_init_state(C.byref(h), 1, *args, 0, 0, C.c_void_p(base + 8), need, Mp, Qp, 1, 0, None) == B.DION_EINVAL
+    assert h.value is None
+    assert call() == B.DION_OK
+
+
+def test_stage_timers():
+    gp = GpuProblem([(512, 512, 128)], True, "bf16")
+    gp.B.dion_set_stage_timing(gp.state, True)
+    gp.upload_grads(gp.grads_np(0))
+    assert gp.step(MU, ETA) == (0, -1)
+    times = gp.B.dion_stage_times(gp.state)
+    assert set(times) == set(gp.B.STAGES) and all(v > 0 for v in times.values())
+    gp.B.dion_set_stage_timing(gp.state, False)
+    assert gp.step(MU, ETA) == (0, -1)
+
+
+def test_ten_steps_equal_five_plus_resume():
+    # the whole optimizer state is (X, M, Q) in caller memory: a fresh state object continues bit-identically
+    shape = (256, 192, 48)
+    a = GpuProblem([shape], True, "bf16")
+    for t in range(6):
+        a.upload_grads(a.grads_np(t))
+        assert a.step(MU, ETA) == (0, -1)
+    b = GpuProblem([shape], True, "bf16")
+    for t in range(3):
+        b.upload_grads(b.grads_np(t))
+        assert b.step(MU, ETA) == (0, -1)
+    xs, ms, qs = b.host()
+    c = GpuProblem([shape], True, "bf16")
+    import torch
+    c.X[0].copy_(torch.from_numpy(xs)); c.M[0].copy_(torch.from_numpy(ms)); c.Q[0].copy_(torch.from_numpy(qs))
+    for t in range(3, 6):
+        c.upload_grads(c.grads_np(t))
+        assert c.step(MU, ETA) == (0, -1)
+    for u, v in zip(a.host(), c.host()):
+        assert np.array_equal(u, v)
