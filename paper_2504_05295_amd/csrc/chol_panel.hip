@@ -128,7 +128,11 @@ __device__ __noinline__ void invert_wave(float* S0, const float* LT, const float
 }
 
 __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
-                                                            int k0, int rp, float piv_lo, float piv_hi) {
+                                                            int k0, int rp, float piv_lo, float piv_hi, int mode) {
+  // mode 0: fused (workgroup 0 writes L11/W11, the others own tiles and redo the factorisation)
+  // mode 1: diagonal block only (one workgroup per matrix)      mode 2: tiles only, W11 read back from memory
+  // Modes 1+2 are used when there are so many tiles (large batches) that redoing the factorisation in
+  // every workgroup would cost more than a second launch.
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   float* C = (float*)tab[slotC];
   float* L = (float*)tab[slotL];
@@ -145,10 +149,10 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   const int wm = wave & 1, wn = wave >> 1, lr = lane & 31, lk = lane >> 5;
 
   // tile (i, j), 1 <= j <= i, in units of 64 rows/columns below/right of the diagonal block
-  const bool writer = blockIdx.x == 0;
+  const bool writer = mode != 2 && blockIdx.x == 0;
   int i = 1, j = 1;
   if (!writer) {
-    const int q = blockIdx.x - 1;
+    const int q = (mode == 2) ? blockIdx.x : blockIdx.x - 1;
     i = (int)((sqrtf(8.f * q + 1.f) - 1.f) * 0.5f) + 1;
     while ((i - 1) * i / 2 > q) --i;
     while (i * (i + 1) / 2 <= q) ++i;
@@ -158,7 +162,8 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
 
   for (int idx = t; idx < CB * CB; idx += 256) {
     const int rr = idx >> 6, cc = idx & 63;
-    S0[rr * CBP + cc] = (cc <= rr) ? C[(long long)(k0 + rr) * ld + k0 + cc] : 0.f;
+    const long long at = (long long)(k0 + rr) * ld + k0 + cc;
+    S0[rr * CBP + cc] = (mode == 2) ? W[at] : ((cc <= rr) ? C[at] : 0.f);
   }
   if (t == 0) progress = 0;
   // this thread's 16 entries of the trailing tile, fetched now so that they arrive during the factorisation
@@ -172,7 +177,13 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   }
   __syncthreads();
 
-  if (wave == 0) {
+  if (mode == 2) {
+    for (int idx = t; idx < CB * CB; idx += 256) {
+      const int rr = idx >> 6, cc = idx & 63;
+      S1[rr * CBP + cc] = C[(rowi + rr) * ld + k0 + cc];
+      if (j != i) S2[rr * CBP + cc] = C[(rowj + rr) * ld + k0 + cc];
+    }
+  } else if (wave == 0) {
     factor_wave(S0, LT, col, rsv, &progress, lane, piv_lo, piv_hi, writer ? L + (long long)k0 * ld + k0 : nullptr, ld,
                 (int*)tab[SLOT_STATUS]);
   } else if (wave == 1) {
@@ -216,8 +227,16 @@ hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slot
                              float piv_lo, float piv_hi, hipStream_t s) {
   const int nb = (rp - k0 - CB) / CB;
   const int tiles = nb * (nb + 1) / 2;
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo,
-                     piv_hi);
+  if ((long long)(1 + tiles) * batch <= 1024 || tiles == 0) {
+    hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp,
+                       piv_lo, piv_hi, 0);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo, piv_hi, 1);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(chol_panel_kernel, dim3(tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo,
+                     piv_hi, 2);
   return hipGetLastError();
 }
 

@@ -40,7 +40,7 @@ struct Entry {
 };
 struct Group {
   int64_t m, n, r;
-  int rp;          // r padded to CHOL_NB * 2^p
+  int rp;          // r rounded up to a multiple of CHOL_NB
   int first_row, count;
   int gram_variant, gram_splitk, gram_kps;
   int gram2_splitk;   // split-K of the split-bf16 Gram product (large-tile path)
@@ -51,11 +51,7 @@ constexpr int kEventsPerGroup = DION_STAGE_COUNT + 1;
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int padded_rank(int64_t r) {
-  int64_t rp = CHOL_NB;
-  while (rp < r) rp *= 2;
-  return (int)rp;
-}
+int padded_rank(int64_t r) { return (int)((r + CHOL_NB - 1) / CHOL_NB * CHOL_NB); }
 
 void plan_gram(Group& g) {
   g.gram_variant = pick_variant(g.r, g.r, g.m, g.count, true);
@@ -261,27 +257,49 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   // blocked right-looking Cholesky, one fused launch per 64-wide panel
   for (int k = 0; k < rp; k += CHOL_NB)
     HIPCHK(launch_chol_panel(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, k, rp, piv_lo, piv_hi, s));
-  // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]]
-  for (int sz = CHOL_NB; sz < rp; sz *= 2) {
-    const int pairs = rp / (2 * sz);
-    const long long stride = 2LL * sz * (rp + 1);
-    const long long o21 = (long long)sz * rp;
-    {
-      GemmArgs a = base;  // T = L21 W11
-      a.M = sz; a.N = sz; a.K = sz; a.sub_count = pairs;
-      a.A = opnd(SLOT_L, o21, rp, stride);
-      a.B = opnd(SLOT_W, 0, rp, stride);
-      a.E.slot = SLOT_T; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
-      HIPCHK(gemm_f32_nn(pick_variant(sz, sz, sz, (long long)batch * pairs, true), a, batch, s));
-    }
-    {
-      GemmArgs a = base;  // W21 = -W22 T
-      a.M = sz; a.N = sz; a.K = sz; a.sub_count = pairs;
-      a.A = opnd(SLOT_W, o21 + sz, rp, stride);
-      a.B = opnd(SLOT_T, o21, rp, stride);
-      a.E.slot = SLOT_W; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
-      a.E.alpha = -1.f;
-      HIPCHK(gemm_f32_nn(pick_variant(sz, sz, sz, (long long)batch * pairs, true), a, batch, s));
+  // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]].
+  // Blocks start as the 64-wide inverses left by the panel kernel; an odd block is carried to the next level,
+  // so any multiple of 64 works.  Runs of equal, evenly spaced pairs go out as one launch.
+  {
+    struct Blk { int off, size; };
+    static_assert(32768 / CHOL_NB <= 512, "block list size");
+    Blk cur[512], nxt[512];
+    int ncur = 0;
+    for (int o = 0; o < rp; o += CHOL_NB) cur[ncur++] = Blk{o, CHOL_NB};
+    while (ncur > 1) {
+      int nn = 0, i = 0;
+      while (i + 1 < ncur) {
+        const int sa = cur[i].size, sd = cur[i + 1].size, o = cur[i].off;
+        int pairs = 0, j = i;
+        while (j + 1 < ncur && cur[j].size == sa && cur[j + 1].size == sd && cur[j].off == o + pairs * (sa + sd)) {
+          nxt[nn++] = Blk{cur[j].off, sa + sd};
+          ++pairs;
+          j += 2;
+        }
+        const long long stride = (long long)(sa + sd) * (rp + 1);
+        const long long o11 = (long long)o * rp + o, o21 = (long long)(o + sa) * rp + o, o22 = (long long)(o + sa) * rp + (o + sa);
+        {
+          GemmArgs a = base;  // T = L21 W11
+          a.M = sd; a.N = sa; a.K = sa; a.sub_count = pairs;
+          a.A = opnd(SLOT_L, o21, rp, stride);
+          a.B = opnd(SLOT_W, o11, rp, stride);
+          a.E.slot = SLOT_T; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
+          HIPCHK(gemm_f32_nn(pick_variant(a.M, a.N, a.K, (long long)batch * pairs, true), a, batch, s));
+        }
+        {
+          GemmArgs a = base;  // W21 = -W22 T
+          a.M = sd; a.N = sa; a.K = sd; a.sub_count = pairs;
+          a.A = opnd(SLOT_W, o22, rp, stride);
+          a.B = opnd(SLOT_T, o21, rp, stride);
+          a.E.slot = SLOT_W; a.E.off = o21; a.E.ld = rp; a.E.sub_stride = stride;
+          a.E.alpha = -1.f;
+          HIPCHK(gemm_f32_nn(pick_variant(a.M, a.N, a.K, (long long)batch * pairs, true), a, batch, s));
+        }
+        i = j;
+      }
+      if (i < ncur) nxt[nn++] = cur[i];
+      for (int k = 0; k < nn; ++k) cur[k] = nxt[k];
+      ncur = nn;
     }
   }
   if (split) {

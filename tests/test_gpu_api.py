@@ -198,3 +198,23 @@ def test_ten_steps_equal_five_plus_resume():
         assert c.step(MU, ETA) == (0, -1)
     for u, v in zip(a.host(), c.host()):
         assert np.array_equal(u, v)
+
+
+def test_large_batch_uses_split_cholesky_launches():
+    # 40 x 29 Cholesky tiles per panel: the library switches to separate diagonal / tile launches here
+    shape = (768, 512, 384)
+    x0 = inputs.weight(*shape[:2])
+    q0 = inputs.right_factor_raw(shape[1], shape[2])
+    n_mat = 40
+    for g_bf16, math, tol in [(False, "f32", 1e-4), (True, "bf16", 2e-2)]:
+        gp = GpuProblem([shape] * n_mat, g_bf16, math, x0=[x0] * n_mat, q_raw=[q0] * n_mat)
+        g = inputs.gradient(shape[0], shape[1], 0, bf16=g_bf16)
+        before = gp.host(0)
+        gp.upload_grads([g] * n_mat)
+        assert gp.step(MU, ETA, batched=True) == (0, -1)
+        rep, _ = one_step_report(gp, 0, before[0], before[1], before[2], gp.grad_as_f32(g, g_bf16), MU, ETA, "lapack")
+        assert rep["X"] <= tol and rep["M"] <= tol and rep["dX"] <= 2 * tol and rep["dM"] <= 2 * tol, rep
+        ref = gp.host(0)
+        for i in (1, 17, 39):
+            for u, v in zip(ref, gp.host(i)):
+                assert np.array_equal(u, v)
