@@ -37,6 +37,24 @@ WORKLOAD_NAMES = {
 }
 
 
+PROFILE_TAGS = {"C3a": "C3_8192x8192_r2048", "C3b": "C3_8192x8192_r512", "C4a": "C4_16384x53248_r1024",
+                "C4b": "C4_16384x53248_r4096", "C5": "C5_3B_decoder_196", "C2b": "C2_2048x2048_r512"}
+
+
+def measured_traffic(workload):
+    """HBM-side bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, calibrated against
+    a plain copy), as recorded in the committed summary of this workload; {} if there is none."""
+    tag = PROFILE_TAGS.get(workload)
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % tag) if tag else None
+    out = {}
+    if path and os.path.exists(path):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch":
+                out[f[1]] = float(f[2])
+    return out
+
+
 def kernel_models(shapes, g_bytes, math):
     """Algorithmic FLOPs and HBM bytes of the three large kernels, summed over the workload."""
     peak = PEAK_BF16 if math == "bf16" else PEAK_F32
@@ -140,6 +158,8 @@ def main():
     ap.add_argument("--workload", default="C3a", choices=sorted(inputs.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -155,6 +175,12 @@ def main():
         do_step(p, t)
     status, bad = B.dion_last_status(p["state"])
     assert status == 0, "warm-up step reported numerical breakdown"
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     # timed region: exactly K steps, inputs resident in HBM
     B.dion_set_stage_timing(p["state"], not args.no_stage_timing)
     stage_sum = {k: 0.0 for k in B.STAGES}
@@ -181,6 +207,7 @@ def main():
     models = kernel_models(cfg["shapes"], g_bytes, cfg["math"])
     stages = {k: v / args.steps for k, v in stage_sum.items()}
     rooflines = {}
+    traffic = measured_traffic(args.workload)
     for name, mdl in models.items():
         ms = stages.get(name, 0.0)
         if ms <= 0:
@@ -190,7 +217,7 @@ def main():
         unit = "TFLOP/s" if mdl["bound"] == "mfma" else "GB/s"
         div = 1e12 if mdl["bound"] == "mfma" else 1e9
         rooflines[name] = dict(bound=mdl["bound"], achieved=ach / div, peak=mdl["peak"] / div, unit=unit,
-                               frac=ach / mdl["peak"], traffic=None, ms=ms,
+                               frac=ach / mdl["peak"], traffic=traffic.get(name), ms=ms,
                                tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
     dominant = max(rooflines, key=lambda k: rooflines[k]["ms"]) if rooflines else None
     out = {
