@@ -128,12 +128,13 @@ __device__ __noinline__ void invert_wave(float* S0, const float* LT, const float
 }
 
 __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
-                                                            int k0, int rp, float piv_lo, float piv_hi, int mode) {
+                                                            int k0, int rp, float piv_lo, float piv_hi, int mode, int skip_slot) {
   // mode 0: fused (workgroup 0 writes L11/W11, the others own tiles and redo the factorisation)
   // mode 1: diagonal block only (one workgroup per matrix)      mode 2: tiles only, W11 read back from memory
   // Modes 1+2 are used when there are so many tiles (large batches) that redoing the factorisation in
   // every workgroup would cost more than a second launch.
   void* const* tab = table + (size_t)blockIdx.y * nslots;
+  if (skip_slot >= 0 && *(const int*)tab[skip_slot] != 0) return;   // uniform for the whole workgroup
   float* C = (float*)tab[slotC];
   float* L = (float*)tab[slotL];
   float* W = (float*)tab[slotW];
@@ -224,19 +225,19 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
 }
 
 hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,
-                             float piv_lo, float piv_hi, hipStream_t s) {
+                             float piv_lo, float piv_hi, int skip_slot, hipStream_t s) {
   const int nb = (rp - k0 - CB) / CB;
   const int tiles = nb * (nb + 1) / 2;
   if ((long long)(1 + tiles) * batch <= 1024 || tiles == 0) {
     hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp,
-                       piv_lo, piv_hi, 0);
+                       piv_lo, piv_hi, 0, skip_slot);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo, piv_hi, 1);
+  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo, piv_hi, 1, skip_slot);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(chol_panel_kernel, dim3(tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo,
-                     piv_hi, 2);
+                     piv_hi, 2, skip_slot);
   return hipGetLastError();
 }
 

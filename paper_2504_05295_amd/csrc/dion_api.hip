@@ -110,6 +110,8 @@ Carve carve_entry(const Group& g) {
   take(SLOT_ZLT16, (mr + 1) / 2);
   take(SLOT_WH16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
+  take(SLOT_EPART, 256);
+  take(SLOT_FAST, 1);
   c.total = pos;
   return c;
 }
@@ -214,7 +216,7 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 // three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
 // Cholesky factorisation and the triangular inverse stay in fp32.
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, float piv_lo, float piv_hi,
-                bool split, hipStream_t s) {
+                bool split, bool adaptive, hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -254,9 +256,16 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   }
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
   HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s));
+  // Second pass: the input is already orthonormal to about 1e-5, so its Gram matrix is I + E with tiny E
+  // and chol(I + E)^-1 = I - Phi(E) + O(E^2): no factorisation needed.  The decision is taken on the device
+  // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
+  // factorisation, otherwise they return at once.
+  const int skip = adaptive ? SLOT_FAST : -1;
+  if (adaptive) HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, s));
+  base.status_slot = skip;
   // blocked right-looking Cholesky, one fused launch per 64-wide panel
   for (int k = 0; k < rp; k += CHOL_NB)
-    HIPCHK(launch_chol_panel(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, k, rp, piv_lo, piv_hi, s));
+    HIPCHK(launch_chol_panel(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, k, rp, piv_lo, piv_hi, skip, s));
   // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]].
   // Blocks start as the 64-wide inverses left by the panel kernel; an odd block is carried to the next level,
   // so any multiple of 64 works.  Runs of equal, evenly spaced pairs go out as one launch.
@@ -302,6 +311,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
       ncur = nn;
     }
   }
+  base.status_slot = -1;
   if (split) {
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
@@ -364,9 +374,9 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (ev) HIPCHK(hipEventRecord(ev[1], s));
   {
     // pass 1: any positive finite pivot; pass 2: the Gram matrix of a nearly orthonormal P1 has pivots near 1
-    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, s);
+    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, s);
     if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, s);
+    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, true, s);
     if (rc != DION_OK) return rc;
   }
   if (big) HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
@@ -484,7 +494,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_WL16; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_FAST; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];

@@ -35,7 +35,9 @@ enum Slot {
   SLOT_ZLT16,  // lo part, transposed          r x m
   SLOT_WH16,   // hi part of L^-1              r x r
   SLOT_WL16,   // lo part of L^-1              r x r
-  NSLOTS = 28
+  SLOT_EPART,  // 256 partial sums of the squared Gram defect ||C - I||_F^2
+  SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
+  NSLOTS = 32
 };
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
@@ -88,7 +90,12 @@ hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int sl
                                long long rows, long long cols, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
                                 int first_stream, hipStream_t s);
+// skip_slot >= 0: the launch does nothing for matrices whose int32 at that slot is non-zero
 hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,
-                             float piv_lo, float piv_hi, hipStream_t s);
+                             float piv_lo, float piv_hi, int skip_slot, hipStream_t s);
+// Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
+// identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
+// Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, hipStream_t s);
 
 }  // namespace dion

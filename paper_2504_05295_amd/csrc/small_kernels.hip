@@ -255,6 +255,65 @@ hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- first-order inverse Cholesky factor near the identity
+__global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, int nslots, int r, long long ld) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  const float* C = (const float*)tab[SLOT_C];
+  float* part = (float*)tab[SLOT_EPART];
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int i = blockIdx.x; i < r; i += gridDim.x)
+    for (int j = threadIdx.x; j <= i; j += 256) {
+      const float e = C[(long long)i * ld + j] - (i == j ? 1.f : 0.f);
+      acc += (i == j ? 1.f : 2.f) * e * e;
+    }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int sft = 128; sft > 0; sft >>= 1) {
+    if ((int)threadIdx.x < sft) red[threadIdx.x] += red[threadIdx.x + sft];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+__global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* table, int nslots, int r, int rp, float tau2) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  const float* part = (const float*)tab[SLOT_EPART];
+  // every block adds the 256 partials in the same order, so all blocks take the same decision
+  __shared__ float total;
+  if (threadIdx.x == 0) {
+    float acc = 0.f;
+    for (int k = 0; k < 256; ++k) acc += part[k];
+    total = acc;
+  }
+  __syncthreads();
+  const bool fast = total <= tau2;   // false for NaN
+  if (blockIdx.x == 0 && threadIdx.x == 0) *(int*)tab[SLOT_FAST] = fast ? 1 : 0;
+  if (!fast) return;
+  const float* C = (const float*)tab[SLOT_C];
+  float* W = (float*)tab[SLOT_W];
+  const long long n = (long long)rp * rp;
+  for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (long long)gridDim.x * 256) {
+    const int i = (int)(idx / rp), j = (int)(idx % rp);
+    float v = 0.f;
+    if (i < r && j < r) {
+      if (i == j) v = 1.f - 0.5f * (C[idx] - 1.f);
+      else if (j < i) v = -C[idx];
+    } else if (i == j) {
+      v = 1.f;
+    }
+    W[idx] = v;
+  }
+}
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, hipStream_t s) {
+  hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  long long blocks = ((long long)rp * rp + 2047) / 2048;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(first_order_inverse_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, r, rp, tau * tau);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- Gaussian fill (Philox-4x32-10 + Box-Muller)
 __device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t k0, uint32_t k1) {
   const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];

@@ -218,3 +218,19 @@ def test_large_batch_uses_split_cholesky_launches():
         for i in (1, 17, 39):
             for u, v in zip(ref, gp.host(i)):
                 assert np.array_equal(u, v)
+
+
+def test_second_pass_takes_full_factorisation_when_needed():
+    # cond(B Q) about 1100: after the first Cholesky-QR pass P1^T P1 is far from the identity, so the second pass
+    # cannot use its first-order shortcut and must run the full factorisation; the result must still be right.
+    m, n, r = 512, 384, 64
+    gp = GpuProblem([(m, n, r)], False, "f32")
+    g = inputs.structured_gradient(m, n, 0, k=64, noise=5e-3)
+    gp.upload_grads([g])
+    x_in, m_in, q_in = gp.host()
+    assert gp.step(MU, ETA) == (0, -1)
+    P1 = gp.debug(0, gp.B.DEBUG_P1).astype(np.float64)
+    assert np.linalg.norm(P1.T @ P1 - np.eye(r)) > 1e-3          # the shortcut's precondition does not hold
+    rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, g, MU, ETA)
+    assert rep["X"] < 1e-4 and rep["M"] < 1e-4 and rep["orth"] < 1e-5, rep
+    assert rep["dX"] < 1e-3 and rep["dM"] < 1e-3, rep
