@@ -73,6 +73,18 @@ struct TileCfg {
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32x32");
 };
 
+// Accesses through the global address space: the compiler then emits global_load / global_store, which count
+// only against vmcnt.  A generic (flat) access also counts against lgkmcnt, so every wait for an LDS read
+// would wait for all outstanding global prefetches as well and nothing would overlap.
+template <class T>
+__device__ __forceinline__ T gload(const void* p) {
+  return *(const __attribute__((address_space(1))) T*)(p);
+}
+template <class T>
+__device__ __forceinline__ void gstore(void* p, T v) {
+  *(__attribute__((address_space(1))) T*)(p) = v;
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2_t f = {lo, hi};
   bf16x2_t v = __builtin_convertvector(f, bf16x2_t);
@@ -117,24 +129,24 @@ struct TileMover {
         if constexpr (!CHECKED) {
 #pragma unroll
           for (int v = 0; v < VEC / 4; ++v) {
-            f32x4_t x = *(const f32x4_t*)(p0 + idx + 4 * v);
+            f32x4_t x = gload<f32x4_t>(p0 + idx + 4 * v);
             a[i][4 * v + 0] = x[0]; a[i][4 * v + 1] = x[1]; a[i][4 * v + 2] = x[2]; a[i][4 * v + 3] = x[3];
           }
           if constexpr (SUM) {
             if constexpr (GBF16) {
               const uint16_t* gp = (const uint16_t*)p1 + idx;
               if constexpr (VEC == 8) {
-                u32x4_t x = *(const u32x4_t*)gp;
+                u32x4_t x = gload<u32x4_t>(gp);
                 g[i][0] = x[0]; g[i][1] = x[1]; g[i][2] = x[2]; g[i][3] = x[3];
               } else {
-                u32x2_t x = *(const u32x2_t*)gp;
+                u32x2_t x = gload<u32x2_t>(gp);
                 g[i][0] = x[0]; g[i][1] = x[1];
               }
             } else {
               const float* gp = (const float*)p1 + idx;
 #pragma unroll
               for (int v = 0; v < VEC / 4; ++v) {
-                u32x4_t x = *(const u32x4_t*)(gp + 4 * v);
+                u32x4_t x = gload<u32x4_t>(gp + 4 * v);
                 g[i][4 * v + 0] = x[0]; g[i][4 * v + 1] = x[1]; g[i][4 * v + 2] = x[2]; g[i][4 * v + 3] = x[3];
               }
             }
@@ -144,10 +156,10 @@ struct TileMover {
 #pragma unroll
           for (int e = 0; e < VEC; ++e) {
             const bool ok = rok && (k0 + kc * VEC + e) < k_end;
-            a[i][e] = ok ? p0[idx + e] : 0.f;
+            a[i][e] = ok ? gload<float>(p0 + idx + e) : 0.f;
             if constexpr (SUM) {
               float gv = 0.f;
-              if (ok) gv = GBF16 ? bf16_to_f32(((const uint16_t*)p1)[idx + e]) : ((const float*)p1)[idx + e];
+              if (ok) gv = GBF16 ? bf16_to_f32(gload<uint16_t>((const uint16_t*)p1 + idx + e)) : gload<float>((const float*)p1 + idx + e);
               g[i][e] = __builtin_bit_cast(uint32_t, gv);
             }
           }
@@ -158,14 +170,14 @@ struct TileMover {
         for (int kk = 0; kk < 4; ++kk) {
           const long long idx = (long long)(k0 + kc * 4 + kk) * ld + (row0 + rg * 4);
           if constexpr (!CHECKED) {
-            f32x4_t x = *(const f32x4_t*)(p0 + idx);
+            f32x4_t x = gload<f32x4_t>(p0 + idx);
             a[i][4 * kk + 0] = x[0]; a[i][4 * kk + 1] = x[1]; a[i][4 * kk + 2] = x[2]; a[i][4 * kk + 3] = x[3];
             if constexpr (SUM) {
               if constexpr (GBF16) {
-                u32x2_t y = *(const u32x2_t*)((const uint16_t*)p1 + idx);
+                u32x2_t y = gload<u32x2_t>((const uint16_t*)p1 + idx);
                 g[i][2 * kk + 0] = y[0]; g[i][2 * kk + 1] = y[1];
               } else {
-                u32x4_t y = *(const u32x4_t*)((const float*)p1 + idx);
+                u32x4_t y = gload<u32x4_t>((const float*)p1 + idx);
                 g[i][4 * kk + 0] = y[0]; g[i][4 * kk + 1] = y[1]; g[i][4 * kk + 2] = y[2]; g[i][4 * kk + 3] = y[3];
               }
             }
@@ -174,10 +186,10 @@ struct TileMover {
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
               const bool ok = kok && (row0 + rg * 4 + rr) < rows_total;
-              a[i][4 * kk + rr] = ok ? p0[idx + rr] : 0.f;
+              a[i][4 * kk + rr] = ok ? gload<float>(p0 + idx + rr) : 0.f;
               if constexpr (SUM) {
                 float gv = 0.f;
-                if (ok) gv = GBF16 ? bf16_to_f32(((const uint16_t*)p1)[idx + rr]) : ((const float*)p1)[idx + rr];
+                if (ok) gv = GBF16 ? bf16_to_f32(gload<uint16_t>((const uint16_t*)p1 + idx + rr)) : gload<float>((const float*)p1 + idx + rr);
                 g[i][4 * kk + rr] = __builtin_bit_cast(uint32_t, gv);
               }
             }
@@ -380,8 +392,8 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmArgs g) {
           if (CHECKED && (row >= g.M || col >= g.N)) continue;
           float* c = C + (long long)row * g.E.ld + col;
           float out = g.E.alpha * acc[i][j][v];
-          if (g.E.beta != 0.f) out += g.E.beta * *c;
-          *c = out;
+          if (g.E.beta != 0.f) out += g.E.beta * gload<float>(c);
+          gstore<float>(c, out);
         }
   } else {
     // Fused error feedback and weight update (unsharded update rule):
@@ -399,10 +411,10 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmArgs g) {
           const int col = col0 + wn * Cfg::WTN + j * 32 + lr;
           if (CHECKED && (row >= g.M || col >= g.N)) continue;
           const long long idx = (long long)row * g.E.ld + col;
-          const float gv = GBF16 ? bf16_to_f32(((const uint16_t*)Gp)[idx]) : ((const float*)Gp)[idx];
-          const float bv = Mp[idx] + gv;
-          Mp[idx] = bv - g.E.c_m * acc[i][j][v];
-          if constexpr (DUAL) Xp[idx] = Xp[idx] - g.E.c_x * acc2[i][j][v];
+          const float gv = GBF16 ? bf16_to_f32(gload<uint16_t>((const uint16_t*)Gp + idx)) : gload<float>((const float*)Gp + idx);
+          const float bv = gload<float>(Mp + idx) + gv;
+          gstore<float>(Mp + idx, bv - g.E.c_m * acc[i][j][v]);
+          if constexpr (DUAL) gstore<float>(Xp + idx, gload<float>(Xp + idx) - g.E.c_x * acc2[i][j][v]);
         }
   }
 }

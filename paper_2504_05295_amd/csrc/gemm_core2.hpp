@@ -49,19 +49,19 @@ struct Mover2 {
         const int row = item / (BK / 8), kc = item % (BK / 8);
         const long long idx = (long long)(row0 + row) * ld + (k0 + kc * 8);
         if constexpr (!SUM) {
-          const u32x4_t x = *(const u32x4_t*)((const uint16_t*)p0 + idx);
+          const u32x4_t x = gload<u32x4_t>((const uint16_t*)p0 + idx);
           a[i][0] = x[0]; a[i][1] = x[1]; a[i][2] = x[2]; a[i][3] = x[3];
         } else {
-          const u32x4_t x0 = *(const u32x4_t*)((const float*)p0 + idx);
-          const u32x4_t x1 = *(const u32x4_t*)((const float*)p0 + idx + 4);
+          const u32x4_t x0 = gload<u32x4_t>((const float*)p0 + idx);
+          const u32x4_t x1 = gload<u32x4_t>((const float*)p0 + idx + 4);
           a[i][0] = x0[0]; a[i][1] = x0[1]; a[i][2] = x0[2]; a[i][3] = x0[3];
           a[i][4] = x1[0]; a[i][5] = x1[1]; a[i][6] = x1[2]; a[i][7] = x1[3];
           if constexpr (GBF16) {
-            const u32x4_t y = *(const u32x4_t*)((const uint16_t*)p1 + idx);
+            const u32x4_t y = gload<u32x4_t>((const uint16_t*)p1 + idx);
             g[i][0] = y[0]; g[i][1] = y[1]; g[i][2] = y[2]; g[i][3] = y[3];
           } else {
-            const u32x4_t y0 = *(const u32x4_t*)((const float*)p1 + idx);
-            const u32x4_t y1 = *(const u32x4_t*)((const float*)p1 + idx + 4);
+            const u32x4_t y0 = gload<u32x4_t>((const float*)p1 + idx);
+            const u32x4_t y1 = gload<u32x4_t>((const float*)p1 + idx + 4);
             g[i][0] = y0[0]; g[i][1] = y0[1]; g[i][2] = y0[2]; g[i][3] = y0[3];
             g[i][4] = y1[0]; g[i][5] = y1[1]; g[i][6] = y1[2]; g[i][7] = y1[3];
           }
@@ -71,13 +71,13 @@ struct Mover2 {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
           const long long idx = (long long)(k0 + kc * 8 + kk) * ld + (row0 + rg * 4);
-          const u32x4_t x = *(const u32x4_t*)((const float*)p0 + idx);
+          const u32x4_t x = gload<u32x4_t>((const float*)p0 + idx);
           a[i][4 * kk + 0] = x[0]; a[i][4 * kk + 1] = x[1]; a[i][4 * kk + 2] = x[2]; a[i][4 * kk + 3] = x[3];
           if constexpr (GBF16) {
-            const u32x2_t y = *(const u32x2_t*)((const uint16_t*)p1 + idx);
+            const u32x2_t y = gload<u32x2_t>((const uint16_t*)p1 + idx);
             g[i][2 * kk + 0] = y[0]; g[i][2 * kk + 1] = y[1];
           } else {
-            const u32x4_t y = *(const u32x4_t*)((const float*)p1 + idx);
+            const u32x4_t y = gload<u32x4_t>((const float*)p1 + idx);
             g[i][4 * kk + 0] = y[0]; g[i][4 * kk + 1] = y[1]; g[i][4 * kk + 2] = y[2]; g[i][4 * kk + 3] = y[3];
           }
         }
@@ -127,7 +127,10 @@ struct Mover2 {
 template <class Cfg, int ASRC, bool GBF16, int EPI, bool DUAL>
 __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArgs g) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, BKP = Cfg::BKP;
-  constexpr int MI = Cfg::MI, NI = Cfg::NI, ST = Cfg::STAGES;
+  // STAGES: 1 = one LDS buffer, 2 = two LDS buffers, 3 = two LDS buffers and two register sets (the global
+  // loads of k-slab s+2 are issued while slab s is multiplied: two slabs in flight instead of one)
+  constexpr int MI = Cfg::MI, NI = Cfg::NI, ST = Cfg::STAGES >= 2 ? 2 : 1;
+  constexpr bool DEEP = Cfg::STAGES == 3;
   constexpr int SP = 36;   // epilogue patch row stride in floats (16-byte aligned rows, conflict-free)
   constexpr size_t OPER_BYTES = (size_t)(ST * BM * BKP + ST * BN * BKP + (DUAL ? ST * BN * BKP : 0)) * sizeof(uint16_t);
   constexpr size_t PATCH_BYTES = (size_t)(Cfg::NT / 64) * 32 * SP * sizeof(float);
@@ -157,9 +160,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
 
   const int row0 = tm * BM, col0 = tn * BN;
 
-  Mover2<Cfg, BM, ASRC, GBF16> ma;
-  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb;
-  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb2;
+  Mover2<Cfg, BM, ASRC, GBF16> ma, ma1;
+  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb, mb1;
+  Mover2<Cfg, BN, SRC2_BF16_KC, false> mb2, mb21;
 
   f32x16_t acc[MI][NI];
   f32x16_t acc2[DUAL ? MI : 1][DUAL ? NI : 1];
@@ -187,57 +190,88 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   const int total = nseg * slabs_per_seg;
   const int s_begin = ks * g.k_per_split;                     // k_per_split counts slabs here
   const int s_end = min(total, s_begin + g.k_per_split);
-  auto issue = [&](int sl) {
+  auto issue = [&](int sl, auto& xa, auto& xb, auto& xb2) __attribute__((always_inline)) {
     const int seg = sl / slabs_per_seg, k0 = (sl - seg * slabs_per_seg) * BK;
     const void* Ap = tab[g.nseg > 0 ? g.segA[seg] : g.A.slot0];
     const void* Bp = tab[g.nseg > 0 ? g.segB[seg] : g.B.slot0];
-    ma.load(Ap, A1, g.A.ld, row0, k0);
-    mb.load(Bp, nullptr, g.B.ld, col0, k0);
-    if constexpr (DUAL) mb2.load(B20, nullptr, g.B2.ld, col0, k0);
+    xa.load(Ap, A1, g.A.ld, row0, k0);
+    xb.load(Bp, nullptr, g.B.ld, col0, k0);
+    if constexpr (DUAL) xb2.load(B20, nullptr, g.B2.ld, col0, k0);
   };
-
-  if (s_begin < s_end) {
-    issue(s_begin);
-    ma.store(As);
-    mb.store(Bs);
-    if constexpr (DUAL) mb2.store(B2s);
-  }
-  __syncthreads();
-
-  int cur = 0;
-  for (int sl = s_begin; sl < s_end; ++sl) {
-    const bool more = sl + 1 < s_end;
-    if (more) issue(sl + 1);
-    const uint16_t* Ac = As + cur * BM * BKP;
-    const uint16_t* Bc = Bs + cur * BN * BKP;
-    const uint16_t* B2c = B2s + (DUAL ? cur * BN * BKP : 0);
+  auto stash = [&](int stage, const auto& xa, const auto& xb, const auto& xb2) __attribute__((always_inline)) {
+    xa.store(As + stage * BM * BKP);
+    xb.store(Bs + stage * BN * BKP);
+    if constexpr (DUAL) xb2.store(B2s + stage * BN * BKP);
+  };
+  // MFMAs of one k-slab.  The fragments of k-step s+1 are requested from LDS before the MFMAs of step s are
+  // issued (two fragment sets), so the LDS latency hides behind the matrix pipe instead of in front of it.
+  auto multiply = [&](int stage) __attribute__((always_inline)) {
+    const uint16_t* Ac = As + stage * BM * BKP + (wm * Cfg::WTM + lr) * BKP + lk * 8;
+    const uint16_t* Bc = Bs + stage * BN * BKP + (wn * Cfg::WTN + lr) * BKP + lk * 8;
+    const uint16_t* B2c = B2s + (DUAL ? stage * BN * BKP + (wn * Cfg::WTN + lr) * BKP + lk * 8 : 0);
+    constexpr int KS = BK / 16;
+    bf16x8_t af[2][MI], bf[2][NI], bf2[2][DUAL ? NI : 1];
+    auto fetch = [&](int set, int kk) __attribute__((always_inline)) {
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8_t af[MI], bf[NI], bf2[DUAL ? NI : 1];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(Ac + (wm * Cfg::WTM + i * 32 + lr) * BKP + kk + lk * 8);
+      for (int i = 0; i < MI; ++i) af[set][i] = *(const bf16x8_t*)(Ac + i * 32 * BKP + kk);
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        bf[j] = *(const bf16x8_t*)(Bc + (wn * Cfg::WTN + j * 32 + lr) * BKP + kk + lk * 8);
-        if constexpr (DUAL) bf2[j] = *(const bf16x8_t*)(B2c + (wn * Cfg::WTN + j * 32 + lr) * BKP + kk + lk * 8);
+        bf[set][j] = *(const bf16x8_t*)(Bc + j * 32 * BKP + kk);
+        if constexpr (DUAL) bf2[set][j] = *(const bf16x8_t*)(B2c + j * 32 * BKP + kk);
       }
+    };
+    fetch(0, 0);
+#pragma unroll
+    for (int st = 0; st < KS; ++st) {
+      if (st + 1 < KS) fetch((st + 1) & 1, (st + 1) * 16);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
-          if constexpr (DUAL) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf2[j], acc2[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][i], bf[st & 1][j], acc[i][j], 0, 0, 0);
+          if constexpr (DUAL) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[st & 1][i], bf2[st & 1][j], acc2[i][j], 0, 0, 0);
         }
     }
-    if constexpr (ST == 1) __syncthreads();
-    const int nxt = (ST == 2) ? (cur ^ 1) : 0;
-    if (more) {
-      ma.store(As + nxt * BM * BKP);
-      mb.store(Bs + nxt * BN * BKP);
-      if constexpr (DUAL) mb2.store(B2s + nxt * BN * BKP);
+  };
+
+  if constexpr (!DEEP) {
+    if (s_begin < s_end) {
+      issue(s_begin, ma, mb, mb2);
+      stash(0, ma, mb, mb2);
     }
     __syncthreads();
-    cur = nxt;
+    int cur = 0;
+    for (int sl = s_begin; sl < s_end; ++sl) {
+      const bool more = sl + 1 < s_end;
+      if (more) issue(sl + 1, ma, mb, mb2);
+      multiply(cur);
+      if constexpr (ST == 1) __syncthreads();
+      const int nxt = (ST == 2) ? (cur ^ 1) : 0;
+      if (more) stash(nxt, ma, mb, mb2);
+      __syncthreads();
+      cur = nxt;
+    }
+  } else {
+    // register set 0 carries even slabs (relative to s_begin), set 1 odd ones; LDS stage = slab parity
+    if (s_begin < s_end) {
+      issue(s_begin, ma, mb, mb2);
+      if (s_begin + 1 < s_end) issue(s_begin + 1, ma1, mb1, mb21);
+      stash(0, ma, mb, mb2);
+    }
+    __syncthreads();
+    int sl = s_begin;
+    for (; sl + 1 < s_end; sl += 2) {
+      if (sl + 2 < s_end) issue(sl + 2, ma, mb, mb2);
+      multiply(0);
+      stash(1, ma1, mb1, mb21);
+      __syncthreads();
+      if (sl + 3 < s_end) issue(sl + 3, ma1, mb1, mb21);
+      multiply(1);
+      if (sl + 2 < s_end) stash(0, ma, mb, mb2);
+      __syncthreads();
+    }
+    if (sl < s_end) multiply(0);   // odd slab count: the last slab is already in LDS buffer 0
+    __syncthreads();
   }
 
   // ---- epilogue.  Each 32x32 accumulator tile goes through a wave-private LDS patch so that a lane ends
@@ -260,7 +294,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
         for (int p = 0; p < 4; ++p) {
           const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
-          *(f32x4_t*)(C + (long long)row * g.E.ld + col) = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          gstore<f32x4_t>(C + (long long)row * g.E.ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
         }
       }
   } else {
@@ -279,27 +313,27 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
           const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
           idx[p] = (long long)row * g.E.ld + col;
-          mv[p] = *(const f32x4_t*)(Mp + idx[p]);
-          if constexpr (DUAL) xv[p] = *(const f32x4_t*)(Xp + idx[p]);
+          mv[p] = gload<f32x4_t>(Mp + idx[p]);
+          if constexpr (DUAL) xv[p] = gload<f32x4_t>(Xp + idx[p]);
           if constexpr (GBF16) {
-            const u32x2_t w = *(const u32x2_t*)((const uint16_t*)Gp + idx[p]);
+            const u32x2_t w = gload<u32x2_t>((const uint16_t*)Gp + idx[p]);
             gv[p] = f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
           } else {
-            gv[p] = *(const f32x4_t*)((const float*)Gp + idx[p]);
+            gv[p] = gload<f32x4_t>((const float*)Gp + idx[p]);
           }
         }
         to_patch(acc[i][j]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          *(f32x4_t*)(Mp + idx[p]) = (mv[p] + gv[p]) - g.E.c_m * a4;
+          gstore<f32x4_t>(Mp + idx[p], (mv[p] + gv[p]) - g.E.c_m * a4);
         }
         if constexpr (DUAL) {
           to_patch(acc2[i][j]);
 #pragma unroll
           for (int p = 0; p < 4; ++p) {
             const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-            *(f32x4_t*)(Xp + idx[p]) = xv[p] - g.E.c_x * a4;
+            gstore<f32x4_t>(Xp + idx[p], xv[p] - g.E.c_x * a4);
           }
         }
       }
