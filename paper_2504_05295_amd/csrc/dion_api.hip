@@ -44,6 +44,7 @@ struct Group {
   int first_row, count;
   int gram_variant, gram_splitk, gram_kps;
   int gram2_splitk;   // split-K of the split-bf16 Gram product (large-tile path)
+  int k12_splitk;     // split-K of K1 / K2 on the large-tile path when their outputs have too few tiles
   size_t bytes_per_entry;
 };
 
@@ -72,6 +73,13 @@ void plan_gram(Group& g) {
   if (want2 > 32) want2 = 32;
   if (want2 < 1) want2 = 1;
   g.gram2_splitk = (int)want2;
+  // K1 (m x r output) and K2 (n x r output) on 128x128 tiles: split the contraction until about 512 workgroups exist
+  g.k12_splitk = 1;
+  if (g.m % 256 == 0 && g.n % 256 == 0 && g.r % 128 == 0) {
+    const long long tiles = std::min(g.m, g.n) / 128 * (g.r / 128) * g.count;
+    const bool big_tiles = g.r % 256 == 0 && (std::min(g.m, g.n) / 256) * (g.r / 256) * g.count >= 128;
+    if (!big_tiles && tiles < 512) g.k12_splitk = (int)std::min<long long>(8, (512 + tiles - 1) / tiles);
+  }
 }
 
 // workspace floats of one matrix, in slot order
@@ -112,6 +120,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_EPART, 256);
   take(SLOT_FAST, 1);
+  take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
   c.total = pos;
   return c;
 }
@@ -361,7 +370,15 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
     a.B = opnd(SLOT_QT16, 0, n);
     a.E.slot = SLOT_Z; a.E.ld = r;
     a.xcd_remap = 1;
-    HIPCHK(gemm2_k1(cfg2(m, r), gbf16, a, batch, s));
+    const int c1 = cfg2(m, r);
+    if (c1 == G2_128x128 && g.k12_splitk > 1) {
+      a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)m * r;
+      const int eff = gemm2_k1_splitk(c1, a);
+      HIPCHK(gemm2_k1(c1, gbf16, a, batch, s));
+      HIPCHK(launch_sum_partials(tab, NSLOTS, batch, SLOT_KPART, SLOT_Z, (long long)m * r, eff, s));
+    } else {
+      HIPCHK(gemm2_k1(c1, gbf16, a, batch, s));
+    }
   } else {
     GemmArgs a = base;  // K1: Z = (M+G) Q
     a.M = m; a.N = r; a.K = n;
@@ -388,7 +405,15 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
     a.B = opnd(SLOT_PT16, 0, m);
     a.E.slot = SLOT_R; a.E.ld = r;
     a.xcd_remap = 1;
-    HIPCHK(gemm2_k2(cfg2(n, r), gbf16, a, batch, s));
+    const int c2 = cfg2(n, r);
+    if (c2 == G2_128x128 && g.k12_splitk > 1) {
+      a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)n * r;
+      const int eff = gemm2_k2_splitk(c2, a);
+      HIPCHK(gemm2_k2(c2, gbf16, a, batch, s));
+      HIPCHK(launch_sum_partials(tab, NSLOTS, batch, SLOT_KPART, SLOT_R, (long long)n * r, eff, s));
+    } else {
+      HIPCHK(gemm2_k2(c2, gbf16, a, batch, s));
+    }
   } else {
     GemmArgs a = base;  // K2: R = (M+G)^T P
     a.M = n; a.N = r; a.K = m;
@@ -494,7 +519,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_FAST; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_KPART; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];

@@ -3,12 +3,16 @@
 #include "internal.hpp"
 namespace dion {
 hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
-  using Big = TileCfg2<256, 256, 32, 2, 4, 2, 1>;
+  using Big = TileCfg2<256, 256, 64, 2, 4, 2, 1>;
   using Mid = TileCfg2<128, 128, 64, 2, 2, 1, 2>;
   if (cfg == G2_256x256)
     return gbf16 ? launch_gemm2<Big, SRC2_SUM_KC, true, EPI_STORE, false>(g, batch, s)
                  : launch_gemm2<Big, SRC2_SUM_KC, false, EPI_STORE, false>(g, batch, s);
   return gbf16 ? launch_gemm2<Mid, SRC2_SUM_KC, true, EPI_STORE, false>(g, batch, s)
                : launch_gemm2<Mid, SRC2_SUM_KC, false, EPI_STORE, false>(g, batch, s);
+}
+int gemm2_k1_splitk(int cfg, const GemmArgs& g) {
+  return cfg == G2_256x256 ? gemm2_effective_splitk<TileCfg2<256, 256, 64, 2, 4, 2, 1>>(g)
+                           : gemm2_effective_splitk<TileCfg2<128, 128, 64, 2, 2, 1, 2>>(g);
 }
 }  // namespace dion

@@ -12,4 +12,8 @@ hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
   return gbf16 ? launch_gemm2<Mid, SRC2_SUM_KS, true, EPI_STORE, false>(g, batch, s)
                : launch_gemm2<Mid, SRC2_SUM_KS, false, EPI_STORE, false>(g, batch, s);
 }
+int gemm2_k2_splitk(int cfg, const GemmArgs& g) {
+  return cfg == G2_256x256 ? gemm2_effective_splitk<TileCfg2<256, 256, 64, 2, 4, 2, 1>>(g)
+                           : gemm2_effective_splitk<TileCfg2<128, 128, 64, 2, 2, 1, 2>>(g);
+}
 }  // namespace dion

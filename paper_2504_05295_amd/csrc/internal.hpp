@@ -37,6 +37,7 @@ enum Slot {
   SLOT_WL16,   // lo part of L^-1              r x r
   SLOT_EPART,  // 256 partial sums of the squared Gram defect ||C - I||_F^2
   SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
+  SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   NSLOTS = 32
 };
 
@@ -63,6 +64,8 @@ enum { G2_256x256 = 0, G2_128x128 = 1 };
 hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
+int gemm2_k1_splitk(int cfg, const GemmArgs& g);   // number of split-K partials the launch will write
+int gemm2_k2_splitk(int cfg, const GemmArgs& g);
 hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s);   // bf16 A (KC) x bf16 B (KC), up to 3 operand pairs
 int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
@@ -77,6 +80,9 @@ hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, 
 hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s);
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
                                   int nsplit, long long split_stride, hipStream_t s);
+// out = sum over `nsplit` partial matrices of `count` floats each, stored back to back in slot_part (fixed order)
+hipError_t launch_sum_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, long long count,
+                               int nsplit, hipStream_t s);
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s);
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
                              int status_slot, int slot_out16, int slot_in16, hipStream_t s);

@@ -100,6 +100,26 @@ hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int
   return hipGetLastError();
 }
 
+__global__ void sum_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, long long count, int nsplit) {
+  const f32x4_t* part = (const f32x4_t*)table[(size_t)blockIdx.y * nslots + slot_part];
+  f32x4_t* out = (f32x4_t*)table[(size_t)blockIdx.y * nslots + slot_out];
+  const long long n4 = count / 4;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) {
+    f32x4_t acc = part[i];
+    for (int sp = 1; sp < nsplit; ++sp) acc += part[sp * n4 + i];
+    out[i] = acc;
+  }
+}
+hipError_t launch_sum_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, long long count,
+                               int nsplit, hipStream_t s) {
+  if (count % 4) return hipErrorInvalidValue;
+  long long blocks = (count / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_part, slot_out, count,
+                     nsplit);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- ColNorm (update rule: V_new <- ColNorm(W))
 // Stage 1: partial[chunk][col] = sum over the chunk's COLNORM_ROWS rows of in[row][col]^2.
 __global__ void __launch_bounds__(256) colnorm_partial_kernel(void* const* table, int nslots, int slot_in, long long rows, int r) {
