@@ -437,6 +437,11 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
     a.E.c_m = 1.0f - mu;
     a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
     a.status_slot = SLOT_STATUS;
+    a.xcd_remap = 1;
+    // keep about 2.5 MB of R / Q_new column panels (128 rows x r, two bf16 matrices) resident in an XCD's L2
+    // (only worth it when at least four panels fit; for larger r the row-major tile order measured faster)
+    a.group_n = (int)(2621440LL / (128LL * r * 4));
+    if (a.group_n < 4) a.group_n = 0;
     HIPCHK(gemm2_k5(G2_256x256, gbf16, a, batch, s));
   } else {
     GemmArgs a = base;  // K5: fused M and X update

@@ -59,6 +59,8 @@ struct GemmArgs {
   int nseg, kseg;
   int segA[3], segB[3];
   int tri_k;            // B is lower triangular: column tile tn only needs k < (tn+1)*BN of every segment
+  int group_n;          // > 0: tiles are visited column group by column group (group_n column tiles wide, all row
+                        // tiles inside a group before the next group), so the B panels of a group stay in L2
   Operand A, B, B2;
   EpilogueDesc E;
 };

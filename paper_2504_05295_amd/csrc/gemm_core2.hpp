@@ -149,7 +149,16 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   int rest = bid / ntile;
   const int ks = rest % g.splitk;
   const int b = rest / g.splitk;
-  const int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+  int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+  if (g.group_n > 0) {
+    const int gw = g.group_n * g.tiles_m;                   // tiles of one full column group
+    const int cg = tile / gw;
+    const int first = cg * g.group_n;
+    const int width = min(g.group_n, g.tiles_n - first);    // the last group may be narrower
+    const int rem = tile - cg * gw;
+    tm = rem / width;
+    tn = first + rem % width;
+  }
   if (g.lower_only && tn * BN > tm * BM + BM - 1) return;
 
   void* const* tab = g.table + (size_t)b * g.nslots;
