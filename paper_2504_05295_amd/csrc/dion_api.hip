@@ -242,12 +242,16 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
     a.A = opnd(SLOT_PT16, 0, g.m);
     a.B = opnd(SLOT_PT16, 0, g.m);
     a.lower_only = 1;
-    a.splitk = g.gram2_splitk;
-    const int eff = gemm2_nt_splitk(G2_128x128, a);
+    // 256x256 tiles when the lower triangle of such tiles alone fills the GPU (large batches), else 128x128 + split-K
+    const long long t256 = r / 256;
+    const bool gram_big = r % 256 == 0 && g.m % 64 == 0 && t256 * (t256 + 1) / 2 * batch >= 256;
+    const int gcfg = gram_big ? G2_256x256 : G2_128x128;
+    a.splitk = gram_big ? 1 : g.gram2_splitk;
+    const int eff = gemm2_nt_splitk(gcfg, a);
     a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
     a.E.split_stride = rr;
-    HIPCHK(gemm2_nt(G2_128x128, a, batch, s));
+    HIPCHK(gemm2_nt(gcfg, a, batch, s));
     if (eff > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, eff, rr, s));
   } else {
     GemmArgs a = base;

@@ -165,30 +165,45 @@ hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in
 
 // out[row][col] = in[row][col] * d[col]   (in may alias out).  Optionally also stores bf16 copies of the
 // result (slot_out16) and of the input (slot_in16): the operands of the fused update kernel.
-__global__ void scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows, int r, int status_slot,
-                                  int slot_out16, int slot_in16) {
-  void* const* tab = table + (size_t)blockIdx.y * nslots;
+__global__ void __launch_bounds__(256) scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows,
+                                                         int r, int status_slot, int slot_out16, int slot_in16) {
+  void* const* tab = table + (size_t)blockIdx.z * nslots;
   if (status_slot >= 0 && *(const int*)tab[status_slot] != 0) return;
   const float* in = (const float*)tab[slot_in];
   float* out = (float*)tab[slot_out];
   uint16_t* out16 = slot_out16 >= 0 ? (uint16_t*)tab[slot_out16] : nullptr;
   uint16_t* in16 = slot_in16 >= 0 ? (uint16_t*)tab[slot_in16] : nullptr;
   const float* d = (const float*)tab[SLOT_D];
-  const long long total = rows * r;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    const float v = in[i];
-    const float q = v * d[i % r];
-    out[i] = q;
-    if (out16) out16[i] = (uint16_t)(pack_bf16x2(q, 0.f) & 0xffffu);
-    if (in16) in16[i] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+  // a block covers 64 rows x 256 columns; a thread owns 4 consecutive columns (or fewer at a ragged edge)
+  const int col = blockIdx.x * 256 + (threadIdx.x & 63) * 4;
+  if (col >= r) return;
+  const long long row_end = min(rows, ((long long)blockIdx.y + 1) * 64);
+  if ((r & 3) == 0) {
+    const f32x4_t dv = *(const f32x4_t*)(d + col);
+    for (long long row = (long long)blockIdx.y * 64 + (threadIdx.x >> 6); row < row_end; row += 4) {
+      const long long idx = row * r + col;
+      const f32x4_t v = *(const f32x4_t*)(in + idx);
+      const f32x4_t q = v * dv;
+      *(f32x4_t*)(out + idx) = q;
+      if (out16) { u32x2_t w = {pack_bf16x2(q[0], q[1]), pack_bf16x2(q[2], q[3])}; *(u32x2_t*)(out16 + idx) = w; }
+      if (in16) { u32x2_t w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *(u32x2_t*)(in16 + idx) = w; }
+    }
+  } else {
+    for (long long row = (long long)blockIdx.y * 64 + (threadIdx.x >> 6); row < row_end; row += 4)
+      for (int c = col; c < min(col + 4, r); ++c) {
+        const long long idx = row * r + c;
+        const float v = in[idx];
+        const float q = v * d[c];
+        out[idx] = q;
+        if (out16) out16[idx] = (uint16_t)(pack_bf16x2(q, 0.f) & 0xffffu);
+        if (in16) in16[idx] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+      }
   }
 }
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
                              int status_slot, int slot_out16, int slot_in16, hipStream_t s) {
-  long long blocks = (rows * r + 1023) / 1024;
-  if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(scale_cols_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_in, slot_out, rows, r,
-                     status_slot, slot_out16, slot_in16);
+  hipLaunchKernelGGL(scale_cols_kernel, dim3((r + 255) / 256, (unsigned)((rows + 63) / 64), batch), dim3(256), 0, s, table, nslots,
+                     slot_in, slot_out, rows, r, status_slot, slot_out16, slot_in16);
   return hipGetLastError();
 }
 
