@@ -96,6 +96,17 @@ int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* c
  * down (-1 if none).  Either pointer may be NULL. */
 int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
 
+/* Orthonormalisation variant used by later steps (Section 3.2 and Appendix A: Cholesky-QR is the fast
+ * choice, with a fallback for the rare inputs it cannot handle).
+ *   DION_ORTH_CHOLQR2          Cholesky-QR applied twice (default); reports DION_NUM_BREAKDOWN when B Q is
+ *                              rank deficient or its condition number exceeds a few thousand.
+ *   DION_ORTH_SHIFTED_CHOLQR3  a shifted Cholesky-QR pass in front of the two (about 1.5x the orthonormalisation
+ *                              cost): does not break down for condition numbers up to about 1e5; an exactly rank
+ *                              deficient B Q is still reported.  Since a breakdown leaves X, M, Q untouched, a
+ *                              caller can switch to this mode and repeat the step. */
+enum { DION_ORTH_CHOLQR2 = 0, DION_ORTH_SHIFTED_CHOLQR3 = 1 };
+int dion_set_orth_mode(dion_state_t* st, int mode);
+
 /* Stage timing.  With enable != 0 every later step brackets its stages with HIP events on
  * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <
  * DION_STAGE_COUNT, the summed duration in milliseconds of that stage over the last call. */

@@ -24,8 +24,10 @@ DION_MATH_F32, DION_MATH_BF16 = 0, 1
 STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
 DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D = range(10)
 
+DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
+
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_last_status",
-           "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+           "dion_set_orth_mode", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
 
@@ -54,6 +56,7 @@ def lib() -> C.CDLL:
                                         C.c_float, C.c_void_p]
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
+        L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
         L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
         L.dion_destroy_state.argtypes = [C.c_void_p]
@@ -193,6 +196,10 @@ def dion_last_status(state: DionState) -> Tuple[int, int]:
     st, bad = C.c_int(0), C.c_int(-1)
     _check(lib().dion_last_status(state.handle, C.byref(st), C.byref(bad)), "dion_last_status")
     return int(st.value), int(bad.value)
+
+
+def dion_set_orth_mode(state: DionState, mode: int) -> None:
+    _check(lib().dion_set_orth_mode(state.handle, int(mode)), "dion_set_orth_mode")
 
 
 def dion_set_stage_timing(state: DionState, enable: bool) -> None:

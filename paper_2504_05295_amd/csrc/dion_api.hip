@@ -186,6 +186,7 @@ struct dion_state {
   int* status;    // device, count ints (table-row order)
   hipStream_t last_stream;
   bool timing;
+  int orth_mode;
   std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
   std::vector<char> group_timed;       // which groups ran in the last call with timing on
 };
@@ -225,7 +226,7 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 // three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
 // Cholesky factorisation and the triangular inverse stay in fp32.
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, float piv_lo, float piv_hi,
-                bool split, bool adaptive, hipStream_t s) {
+                bool split, bool adaptive, float shift_rel, hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -267,6 +268,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
     HIPCHK(gemm_f32_tn(g.gram_variant, a, batch, s));
     if (g.gram_splitk > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, g.gram_splitk, rr, s));
   }
+  if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
   HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s));
   // Second pass: the input is already orthonormal to about 1e-5, so its Gram matrix is I + E with tiny E
@@ -395,9 +397,21 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (ev) HIPCHK(hipEventRecord(ev[1], s));
   {
     // pass 1: any positive finite pivot; pass 2: the Gram matrix of a nearly orthonormal P1 has pivots near 1
-    int rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, s);
-    if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, true, s);
+    int rc;
+    if (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) {
+      // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
+      // leaves a factor with a condition number of a few hundred), then CholeskyQR2 on that.  The product of
+      // the three triangular factors is still the QR factor.  Z's buffer is reused for the middle result.
+      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, 1e-5f, s);
+      if (rc != DION_OK) return rc;
+      rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_Z, 0.f, 3.0e38f, big, false, 0.f, s);
+      if (rc != DION_OK) return rc;
+      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P, 0.1f, 10.f, big, true, 0.f, s);
+    } else {
+      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, 0.f, s);
+      if (rc != DION_OK) return rc;
+      rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, true, 0.f, s);
+    }
     if (rc != DION_OK) return rc;
   }
   if (big) HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
@@ -512,6 +526,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     st->status = (int*)(st->ws + align_up((size_t)count * NSLOTS * sizeof(void*), 256));
     st->last_stream = s;
     st->timing = false;
+    st->orth_mode = DION_ORTH_CHOLQR2;
     st->group_timed.assign(st->groups.size(), 0);
     // host image of the pointer table
     std::vector<void*> host((size_t)count * NSLOTS, nullptr);
@@ -634,6 +649,12 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {
   }
   if (status_out) *status_out = status;
   if (first_bad_index) *first_bad_index = bad;
+  return DION_OK;
+}
+
+int dion_set_orth_mode(dion_state_t* st, int mode) {
+  if (!st || (mode != DION_ORTH_CHOLQR2 && mode != DION_ORTH_SHIFTED_CHOLQR3)) return DION_EINVAL;
+  st->orth_mode = mode;
   return DION_OK;
 }
 

@@ -77,6 +77,8 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
                                 void* const* M, void* const* Q, hipStream_t s);
 hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
+// C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
+hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s);
 hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s);
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
                                   int nsplit, long long split_stride, hipStream_t s);

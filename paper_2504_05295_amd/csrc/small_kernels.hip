@@ -77,6 +77,25 @@ hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int sl
   return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(256) shift_diagonal_kernel(void* const* table, int nslots, int r, int rp, float shift_rel) {
+  float* C = (float*)table[(size_t)blockIdx.x * nslots + SLOT_C];
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int j = threadIdx.x; j < r; j += 256) acc += C[(long long)j * rp + j];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int sft = 128; sft > 0; sft >>= 1) {
+    if ((int)threadIdx.x < sft) red[threadIdx.x] += red[threadIdx.x + sft];
+    __syncthreads();
+  }
+  const float shift = shift_rel * red[0];
+  for (int j = threadIdx.x; j < r; j += 256) C[(long long)j * rp + j] += shift;
+}
+hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s) {
+  hipLaunchKernelGGL(shift_diagonal_kernel, dim3(batch), dim3(256), 0, s, table, nslots, r, rp, shift_rel);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- split-K reduction (fixed order => deterministic)
 __global__ void reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r, long long ld,
                                        int nsplit, long long split_stride) {

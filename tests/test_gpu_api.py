@@ -14,9 +14,11 @@ pytestmark = pytest.mark.gpu
 MU, ETA = inputs.MU, inputs.ETA
 
 
-def check_batch(shapes, g_bf16, math, steps=2):
+def check_batch(shapes, g_bf16, math, steps=2, orth_mode=None):
     tol = 1e-4 if math == "f32" else 2e-2
     gp = GpuProblem(shapes, g_bf16, math)
+    if orth_mode is not None:
+        gp.B.dion_set_orth_mode(gp.state, orth_mode)
     for t in range(steps):
         grads = gp.grads_np(t)
         before = [gp.host(i) for i in range(len(shapes))]
@@ -234,3 +236,78 @@ def test_second_pass_takes_full_factorisation_when_needed():
     rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, g, MU, ETA)
     assert rep["X"] < 1e-4 and rep["M"] < 1e-4 and rep["orth"] < 1e-5, rep
     assert rep["dX"] < 1e-3 and rep["dM"] < 1e-3, rep
+
+
+def qr_properties(gp, i, m_in, q_in, g32):
+    """What defines P = thin-QR factor of Z = (M+G) Q with positive diagonal, measured without a reference P."""
+    B = gp.B
+    m, n, r = gp.shapes[i]
+    Z = orc.accumulate(m_in, g32) @ q_in.astype(np.float64)
+    P = gp.debug(i, B.DEBUG_P)[:, :r].astype(np.float64)
+    T = P.T @ Z
+    return dict(cond=float(np.linalg.cond(Z)),
+                orth=float(np.abs(P.T @ P - np.eye(r)).max()),
+                resid=relf(P @ np.triu(T), Z),                      # Z = P T with T upper triangular
+                diag_min=float(np.min(np.diag(T)) / np.linalg.norm(Z, 2)))
+
+
+def rest_of_step_from_P(gp, i, x_in, m_in, q_in, g32, mu, eta):
+    """Errors of R, M, Q, X against the paper's formulas evaluated in fp64, each from the library's own
+    inputs to that stage (the weak columns of R are tiny next to the strong ones when B Q is ill conditioned,
+    so their fp32 rounding, harmless in R, would dominate a comparison of the column-normalised Q)."""
+    B = gp.B
+    m, n, r = gp.shapes[i]
+    P = gp.debug(i, B.DEBUG_P)[:, :r].astype(np.float64)
+    Bm = orc.accumulate(m_in, g32)
+    R = Bm.T @ P
+    R_lib = gp.debug(i, B.DEBUG_R)[:, :r].astype(np.float64)
+    Qn, _ = orc.col_norm(R_lib)
+    X, M, Q = gp.host(i)
+    return dict(R=relf(R_lib, R), M=relf(M, Bm - (1 - mu) * P @ R.T), Q=relf(Q, Qn),
+                dX=relf(X.astype(np.float64) - x_in, -eta * np.sqrt(m / n) * P @ Q.astype(np.float64).T))
+
+
+def test_shifted_cholqr3_handles_what_cholqr2_reports():
+    # cond(B Q) of 1e4 and more: the default mode may report a breakdown (and then leaves the state alone);
+    # the shifted three-pass mode must produce the thin-QR factor, and the caller may simply repeat the step.
+    cases = [((512, 384, 64), inputs.structured_gradient(512, 384, 0, k=32, noise=1e-3)),
+             ((512, 384, 64), inputs.structured_gradient(512, 384, 0, k=32, noise=2e-4)),
+             ((64, 64, 64), inputs.gradient(64, 64, 0, 0, 0, bf16=False))]
+    for shape, g in cases:
+        gp = GpuProblem([shape], False, "f32")
+        gp.upload_grads([g])
+        x_in, m_in, q_in = gp.host()
+        status, _ = gp.step(MU, ETA)
+        if status != 0:
+            for u, v in zip((x_in, m_in, q_in), gp.host()):
+                assert np.array_equal(u, v)
+            gp.B.dion_set_orth_mode(gp.state, gp.B.DION_ORTH_SHIFTED_CHOLQR3)
+            assert gp.step(MU, ETA) == (0, -1), shape
+        else:
+            # default mode coped: the robust mode must agree with it
+            gp = GpuProblem([shape], False, "f32")
+            gp.B.dion_set_orth_mode(gp.state, gp.B.DION_ORTH_SHIFTED_CHOLQR3)
+            gp.upload_grads([g])
+            assert gp.step(MU, ETA) == (0, -1), shape
+        pr = qr_properties(gp, 0, m_in, q_in, g)
+        assert pr["cond"] < 3e5, pr                     # the range the mode is documented for
+        assert pr["orth"] < 1e-5 and pr["resid"] < 1e-5 and pr["diag_min"] > 0, (shape, pr)
+        rest = rest_of_step_from_P(gp, 0, x_in, m_in, q_in, g, MU, ETA)
+        assert max(rest.values()) < 1e-5, (shape, rest)
+        # the thin-QR factor is unique, so the oracle's is still the target; its forward error grows with cond(Z)
+        rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, g, MU, ETA)
+        assert rep["PQt"] < 1e-6 * pr["cond"] and rep["PRt"] < 1e-6 * pr["cond"], (shape, pr, rep)
+        print("shifted-cholqr3", shape, pr, rest, rep)
+
+
+def test_shifted_cholqr3_matches_oracle_on_regular_inputs():
+    check_batch([(256, 256, 64), (200, 136, 24)], False, "f32", orth_mode=1)
+    check_batch([(512, 256, 128)] * 2 + [(192, 320, 48)], True, "bf16", orth_mode=1)
+
+
+def test_orth_mode_validation():
+    gp = GpuProblem([(128, 128, 16)], False, "f32")
+    L = gp.B.lib()
+    assert L.dion_set_orth_mode(gp.state.handle, 2) == gp.B.DION_EINVAL
+    assert L.dion_set_orth_mode(None, 0) == gp.B.DION_EINVAL
+    assert L.dion_set_orth_mode(gp.state.handle, 1) == 0
