@@ -107,6 +107,17 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
 enum { DION_ORTH_CHOLQR2 = 0, DION_ORTH_SHIFTED_CHOLQR3 = 1 };
 int dion_set_orth_mode(dion_state_t* st, int mode);
 
+/* Fallback for matrices whose last step reported DION_NUM_BREAKDOWN (Appendix A: when Cholesky-QR fails the
+ * step falls back to a more robust orthonormalisation).  Waits for the last step, reads the per-matrix status
+ * words and repeats the step, with DION_ORTH_SHIFTED_CHOLQR3, for exactly the matrices that broke down (their
+ * X, M, Q were left untouched, so this completes the step; matrices that succeeded are not stepped again).
+ * Arguments as for the dion_step_batched call being completed, G unchanged since then.  *retried_out (may be
+ * NULL) receives the number of matrices repeated.  The state's orthonormalisation mode is left as it was;
+ * dion_last_status afterwards reports the outcome of the repeated steps. */
+int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M,
+                          void* const* Q, const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta,
+                          void* hip_stream, int* retried_out);
+
 /* Stage timing.  With enable != 0 every later step brackets its stages with HIP events on
  * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <
  * DION_STAGE_COUNT, the summed duration in milliseconds of that stage over the last call. */

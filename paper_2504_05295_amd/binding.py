@@ -27,7 +27,7 @@ DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DE
 DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_last_status",
-           "dion_set_orth_mode", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
 
@@ -54,6 +54,8 @@ def lib() -> C.CDLL:
                                 C.c_int64, C.c_float, C.c_float, C.c_void_p]
         L.dion_step_batched.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
                                         C.c_float, C.c_void_p]
+        L.dion_retry_breakdowns.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
+                                            C.c_float, C.c_void_p, C.POINTER(C.c_int)]
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
@@ -189,6 +191,16 @@ def dion_step_batched(state: DionState, X: List, G: List, M: List, Q: List, mu: 
     _check(lib().dion_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(Q), _i64([s[0] for s in sh]),
                                    _i64([s[1] for s in sh]), _i64([s[2] for s in sh]), mu, eta, _stream(stream)),
            "dion_step_batched")
+
+
+def dion_retry_breakdowns(state: DionState, X: List, G: List, M: List, Q: List, mu: float, eta: float, stream=None) -> int:
+    """Repeats the last batched step, with the robust orthonormalisation, for the matrices that broke down."""
+    sh = state.shapes[:len(X)]
+    n_retried = C.c_int(0)
+    _check(lib().dion_retry_breakdowns(state.handle, len(X), _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(Q),
+                                       _i64([s[0] for s in sh]), _i64([s[1] for s in sh]), _i64([s[2] for s in sh]),
+                                       mu, eta, _stream(stream), C.byref(n_retried)), "dion_retry_breakdowns")
+    return int(n_retried.value)
 
 
 def dion_last_status(state: DionState) -> Tuple[int, int]:

@@ -480,6 +480,17 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
 bool aligned16(const void* p) { return p && ((uintptr_t)p & 15u) == 0; }
 bool coeffs_ok(float mu, float eta) { return mu >= 0.f && mu <= 1.f && isfinite(eta) && isfinite(mu); }
 
+bool batch_args_ok(const dion_state* st, int count, void* const* X, const void* const* G, void* const* M, void* const* Q,
+                   const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta) {
+  if (count != st->count || !X || !G || !M || !Q || !m || !n || !r || !coeffs_ok(mu, eta)) return false;
+  for (int i = 0; i < count; ++i) {
+    const Entry& e = st->entries[i];
+    if (m[i] != e.m || n[i] != e.n || r[i] != e.r) return false;
+    if (!aligned16(X[i]) || !aligned16(G[i]) || !aligned16(M[i]) || !aligned16(Q[i])) return false;
+  }
+  return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -581,12 +592,7 @@ int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* c
                       const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta, void* hip_stream) {
   if (!st || count < 0) return DION_EINVAL;
   if (count == 0) return DION_OK;
-  if (count != st->count || !X || !G || !M || !Q || !m || !n || !r || !coeffs_ok(mu, eta)) return DION_EINVAL;
-  for (int i = 0; i < count; ++i) {
-    const Entry& e = st->entries[i];
-    if (m[i] != e.m || n[i] != e.n || r[i] != e.r) return DION_EINVAL;
-    if (!aligned16(X[i]) || !aligned16(G[i]) || !aligned16(M[i]) || !aligned16(Q[i])) return DION_EINVAL;
-  }
+  if (!batch_args_ok(st, count, X, G, M, Q, m, n, r, mu, eta)) return DION_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
   st->last_stream = s;
   std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
@@ -628,6 +634,44 @@ int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q, int64_
   void* qs[1] = {Q};
   HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
   return step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
+}
+
+int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M,
+                          void* const* Q, const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta,
+                          void* hip_stream, int* retried_out) {
+  if (!st || count < 0) return DION_EINVAL;
+  if (retried_out) *retried_out = 0;
+  if (count == 0) return DION_OK;
+  if (!batch_args_ok(st, count, X, G, M, Q, m, n, r, mu, eta)) return DION_EINVAL;
+  HIPCHK(hipStreamSynchronize(st->last_stream));
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<int> host;
+  try {
+    host.resize(count);
+  } catch (const std::bad_alloc&) {
+    return DION_ENOMEM;
+  }
+  HIPCHK(hipMemcpy(host.data(), st->status, sizeof(int) * count, hipMemcpyDeviceToHost));
+  st->last_stream = s;
+  std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
+  const int saved_mode = st->orth_mode;
+  st->orth_mode = DION_ORTH_SHIFTED_CHOLQR3;
+  int retried = 0, rc = DION_OK;
+  for (int i = 0; i < count && rc == DION_OK; ++i) {
+    const Entry& e = st->entries[i];
+    if (host[e.row] == 0) continue;
+    const Group& g = st->groups[e.group];
+    void* xs[1] = {X[i]};
+    const void* gs[1] = {G[i]};
+    void* ms[1] = {M[i]};
+    void* qs[1] = {Q[i]};
+    if (launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s) != hipSuccess) { rc = DION_ELAUNCH; break; }
+    rc = step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
+    ++retried;
+  }
+  st->orth_mode = saved_mode;
+  if (retried_out) *retried_out = retried;
+  return rc;
 }
 
 int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {

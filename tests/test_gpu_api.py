@@ -311,3 +311,34 @@ def test_orth_mode_validation():
     assert L.dion_set_orth_mode(gp.state.handle, 2) == gp.B.DION_EINVAL
     assert L.dion_set_orth_mode(None, 0) == gp.B.DION_EINVAL
     assert L.dion_set_orth_mode(gp.state.handle, 1) == 0
+
+
+def test_retry_completes_only_the_matrices_that_broke_down():
+    # a batch of three: the middle one is too ill conditioned for CholeskyQR2 in fp32
+    shape = (512, 384, 64)
+    gp = GpuProblem([shape] * 3, False, "f32")
+    grads = gp.grads_np(0)
+    grads[1] = inputs.structured_gradient(512, 384, 0, k=32, noise=2e-4)
+    gp.upload_grads(grads)
+    before = [gp.host(i) for i in range(3)]
+    status, bad = gp.step(MU, ETA, batched=True)
+    assert (status, bad) == (gp.B.DION_NUM_BREAKDOWN, 1)
+    after_first = [gp.host(i) for i in range(3)]
+    for u, v in zip(before[1], after_first[1]):
+        assert np.array_equal(u, v)
+    assert gp.B.dion_retry_breakdowns(gp.state, gp.X, gp.G, gp.M, gp.Q, MU, ETA) == 1
+    assert gp.B.dion_last_status(gp.state) == (0, -1)
+    for i in (0, 2):                                    # stepped once, not twice
+        for u, v in zip(after_first[i], gp.host(i)):
+            assert np.array_equal(u, v)
+    pr = qr_properties(gp, 1, before[1][1], before[1][2], grads[1])
+    assert pr["orth"] < 1e-5 and pr["resid"] < 1e-5 and pr["diag_min"] > 0, pr
+    rest = rest_of_step_from_P(gp, 1, *before[1], grads[1], MU, ETA)
+    assert max(rest.values()) < 1e-5, rest
+    rep, _ = one_step_report(gp, 1, *before[1], grads[1], MU, ETA)
+    assert rep["X"] < 1e-4 and rep["M"] < 1e-4, rep
+    # nothing to do when nothing broke down
+    assert gp.B.dion_retry_breakdowns(gp.state, gp.X, gp.G, gp.M, gp.Q, MU, ETA) == 0
+    for i in range(3):
+        ref = orc.dion_step(before[i][0], grads[i], before[i][1], before[i][2], MU, ETA)
+        assert relf(gp.host(i)[0], ref["X"]) < 1e-4 and relf(gp.host(i)[1], ref["M"]) < 1e-4
