@@ -11,12 +11,14 @@
 // of column j = 1 also store their L21_i into L.
 //
 // Inside a workgroup the diagonal block is the latency-critical part, so it is spread over the waves:
-//   wave 0  factors C11 column by column (row i of the block lives in the registers of lane i),
-//   wave 1  follows one column behind and builds W11 = L11^-1 by forward substitution,
-//   waves 2,3 meanwhile fetch the two panel blocks C21_i, C21_j into LDS.
-// Waves 0 and 1 talk through LDS: broadcast reads (all lanes read one address) replace cross-lane
-// shuffles, and a progress counter tells wave 1 which columns are final.  LDS operations of one wave
-// are processed in issue order, so data stored before the counter is visible to whoever sees the counter.
+//   wave 0  eliminates C11 column by column on unscaled values (row i of the block lives in the registers
+//           of lane i); it carries the chain of dependent pivots and does nothing that is not on it,
+//   wave 2  follows and scales the raw columns into columns of L11 (reciprocal square roots, bounds check),
+//   wave 1  follows wave 0 as well and builds W11 = L11^-1 by forward substitution on the raw columns,
+//   wave 3  meanwhile fetches the two panel blocks C21_i, C21_j into LDS.
+// The waves talk through LDS: broadcast reads (all lanes read one address) replace cross-lane shuffles, and
+// counters tell the followers which columns are final.  LDS operations of one wave are processed in issue
+// order, so data stored before a counter is visible to whoever sees the counter.
 #include <type_traits>
 #include <utility>
 
@@ -53,78 +55,178 @@ __device__ __forceinline__ f32x16_t mma_64(const float* As, const float* Bs, int
 }
 }  // namespace
 
-// Wave 0: factors the 64x64 block held in S0 (row i in lane i).  Publishes every finished column to
-// LT / rsv and bumps *progress.  When Lout is given (writer workgroup) also stores L11 and the status.
-__device__ __noinline__ void factor_wave(const float* S0, float* LT, float* col, float* rsv, volatile int* progress, int lane,
-                                         float piv_lo, float piv_hi, float* Lout, long long ld, int* status) {
+// LDS pointers carry their address space, so that volatile accesses too become ds_* instructions (a volatile
+// access through a generic pointer is a flat one, with a much longer round trip).
+typedef __attribute__((address_space(3))) float lds_float;
+typedef __attribute__((address_space(3))) f32x4_t lds_f32x4;
+typedef __attribute__((address_space(3))) volatile int lds_counter;
+
+__device__ __forceinline__ float lane_value(float x, int src_lane) {   // x of lane `src_lane`, uniform result
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
+}
+
+// Wave 0: eliminates the 64x64 block held in S0 (row i in lane i), right-looking, one column per step,
+// working on raw (unscaled) values: with g = a[i][j] / a[j][j] the update is a[i][k] -= g * a[k][j], which
+// equals L[i][j] L[k][j].  The dependency chain from one pivot to the next is kept free of LDS round trips:
+// the pivot and the two entries of the column that the next two columns need come through lane reads, and
+// column j's update of the entries further right (k >= j+3) is applied one step late, from the copy of the
+// raw column that went through LDS meanwhile.  Raw column j is left in row j of S0 (its first reader, this
+// wave, took the whole block into registers before the first column is written) and *raw_done counts them.
+__device__ __forceinline__ void eliminate_wave(lds_float* S0, lds_counter* raw_done, int lane) {
     float a[CB];
     static_for<0, CB>([&](auto kc) __attribute__((always_inline)) { a[decltype(kc)::value] = S0[lane * CBP + decltype(kc)::value]; });
-    bool bad = false;
+    f32x4_t cv0[CB / 4], cv1[CB / 4];   // raw columns j (even / odd) as read back from LDS
+    float gprev = 0.f;
     static_for<0, CB>([&](auto jc) __attribute__((always_inline)) {
       constexpr int jj = decltype(jc)::value;
-      f32x4_t cv[CB / 4];
-      col[lane] = a[jj];
-      float piv = col[jj];
-      static_for<(jj + 1) / 4, CB / 4>([&](auto qc) __attribute__((always_inline)) {
-        constexpr int q = decltype(qc)::value;
-        cv[q] = *(const f32x4_t*)(col + 4 * q);
-      });
+      f32x4_t* cur = (jj & 1) ? cv1 : cv0;
+      const f32x4_t* prev = (jj & 1) ? cv0 : cv1;
+      const float piv = lane_value(a[jj], jj);
+      const float gj = a[jj] * __builtin_amdgcn_rcpf(piv);
+      if constexpr (jj + 1 < CB) a[jj + 1] -= gj * lane_value(a[jj], jj + 1);
+      if constexpr (jj + 2 < CB) {
+        if constexpr (jj >= 1) a[jj + 2] -= gprev * prev[(jj + 2) / 4][(jj + 2) % 4];
+        a[jj + 2] -= gj * lane_value(a[jj], jj + 2);
+      }
+      lds_float* cb = S0 + jj * CBP;
+      cb[lane] = a[jj];
+      if constexpr (jj + 3 < CB) {
+        // entries below j+3 of the first group of four are not read at all: their registers would be reused at
+        // once, and the hardware then waits for the read before it lets them be overwritten
+        constexpr int q0 = (jj + 3) / 4;
+        static_for<jj + 3, (4 * q0 + 4 < CB ? 4 * q0 + 4 : CB)>([&](auto kc) __attribute__((always_inline)) {
+          constexpr int k = decltype(kc)::value;
+          cur[q0][k % 4] = cb[k];
+        });
+        static_for<q0 + 1, CB / 4>([&](auto qc) __attribute__((always_inline)) {
+          constexpr int q = decltype(qc)::value;
+          cur[q] = *(const lds_f32x4*)(cb + 4 * q);
+        });
+      }
       asm volatile("" ::: "memory");
-      if (!(piv > piv_lo) || !(piv < piv_hi)) { bad = true; piv = 1.f; }
-      float rs = __builtin_amdgcn_rsqf(piv);
-      rs = rs * (1.5f - 0.5f * piv * rs * rs);                 // one Newton step on the hardware estimate
-      const float lij = (lane == jj) ? piv * rs : a[jj] * rs;  // L[i][j]
-      const float gj = a[jj] * (rs * rs);                      // L[i][j] / L[j][j]
-      a[jj] = lij;
-      LT[lane * CBP + jj] = lij;
-      rsv[jj] = rs;   // every lane stores the same value: no branch in the column loop
-      asm volatile("" ::: "memory");
-      *progress = jj + 1;
-      // trailing update inside the block: a[k] -= L[i][j] * L[k][j] = gj * col[k]
-      static_for<(jj + 1) / 4, CB / 4>([&](auto qc) __attribute__((always_inline)) {
-        constexpr int q = decltype(qc)::value;
-        if constexpr (4 * q + 0 > jj) a[4 * q + 0] -= gj * cv[q][0];
-        if constexpr (4 * q + 1 > jj) a[4 * q + 1] -= gj * cv[q][1];
-        if constexpr (4 * q + 2 > jj) a[4 * q + 2] -= gj * cv[q][2];
-        if constexpr (4 * q + 3 > jj) a[4 * q + 3] -= gj * cv[q][3];
-      });
+      *raw_done = jj + 1;
+      // the reads above stay in flight across the rest of this step; nothing below may move up past them
+      __builtin_amdgcn_sched_barrier(0);
+      // late part of column j-1's update
+      if constexpr (jj >= 1) {
+        static_for<(jj + 3) / 4, CB / 4>([&](auto qc) __attribute__((always_inline)) {
+          constexpr int q = decltype(qc)::value;
+          if constexpr (4 * q + 0 >= jj + 3) a[4 * q + 0] -= gprev * prev[q][0];
+          if constexpr (4 * q + 1 >= jj + 3) a[4 * q + 1] -= gprev * prev[q][1];
+          if constexpr (4 * q + 2 >= jj + 3) a[4 * q + 2] -= gprev * prev[q][2];
+          if constexpr (4 * q + 3 >= jj + 3) a[4 * q + 3] -= gprev * prev[q][3];
+        });
+      }
+      gprev = gj;
+      __builtin_amdgcn_sched_barrier(0);
     });
+}
+
+// Wave 2: follows wave 0 and turns raw columns into columns of L: L[i][j] = raw[i][j] / sqrt(raw[j][j]).
+// Leaves 1 / sqrt(raw[j][j]) in rsv and sets *scaled when all of them are there.  When Lout is given
+// (writer workgroup) also stores L11 and the status.
+__device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw_done, lds_float* rsv, lds_counter* scaled, int lane,
+                                           float piv_lo, float piv_hi, float* Lout, long long ld, int* status) {
+    float l[CB];
+    bool bad = false;
+    int seen = 0;
+    float raw0 = 0.f, raw1 = 0.f, piv0 = 1.f, piv1 = 1.f;
+    // column j+1 is fetched while column j is being scaled; a column is only asked for once it is final
+    auto fetch = [&](auto jc, float& raw, float& piv) __attribute__((always_inline)) {
+      constexpr int jj = decltype(jc)::value;
+      if (seen <= jj) {
+        do { seen = *raw_done; } while (seen <= jj);   // wave 0 always gets there: it waits for nobody
+      }
+      asm volatile("" ::: "memory");
+      raw = S0[jj * CBP + lane];
+      piv = S0[jj * CBP + jj];
+    };
+    fetch(std::integral_constant<int, 0>{}, raw0, piv0);
+    static_for<0, CB>([&](auto jc) __attribute__((always_inline)) {
+      constexpr int jj = decltype(jc)::value;
+      const float raw = (jj & 1) ? raw1 : raw0, piv = (jj & 1) ? piv1 : piv0;
+      if constexpr (jj + 1 < CB) fetch(std::integral_constant<int, jj + 1>{}, (jj & 1) ? raw0 : raw1, (jj & 1) ? piv0 : piv1);
+      __builtin_amdgcn_sched_barrier(0);
+      bad = bad || !(piv > piv_lo) || !(piv < piv_hi);
+      float rs = __builtin_amdgcn_rsqf(piv);
+      rs = rs * (1.5f - 0.5f * piv * rs * rs);   // one Newton step on the hardware estimate
+      l[jj] = raw * rs;
+      rsv[jj] = rs;   // every lane stores the same value
+      asm volatile("" : "+v"(l[jj]));   // keeps this column's arithmetic from being moved past the next wait loop
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    asm volatile("" ::: "memory");
+    *scaled = 1;
     if (Lout) {
       static_for<0, CB>([&](auto kc) __attribute__((always_inline)) {
         constexpr int k = decltype(kc)::value;
-        Lout[(long long)lane * ld + k] = (k <= lane) ? a[k] : 0.f;
+        Lout[(long long)lane * ld + k] = (k <= lane) ? l[k] : 0.f;
       });
       if (bad && lane == 0) *status = 1;
     }
 }
 
 // Wave 1: W11 = L11^-1, following wave 0 column by column; leaves W11 (row-major) in S0.
-__device__ __noinline__ void invert_wave(float* S0, const float* LT, const float* rsv, volatile int* progress, int lane) {
-    // lane c builds column c of W = L^-1:  w_i = (delta_ic - sum_{k<i} L[i][k] w_k) / L[i][i]
+// Lane c builds column c of W by forward substitution in its right-looking form, on raw values as well:
+// with acc_i = delta_ic - sum_{k<j} L[i][k] w_k, step j sets acc_i -= raw[i][j] * (acc_j / raw[j][j]) for i > j,
+// and w_j = acc_j / sqrt(raw[j][j]) is applied to all rows at the end.  The work per step shrinks as the
+// elimination's does, so this wave finishes right behind wave 0.
+__device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done, const lds_float* rsv, lds_counter* scaled, int lane) {
     float w[CB];
-    static_for<0, CB>([&](auto ic) __attribute__((always_inline)) {
-      constexpr int ii = decltype(ic)::value;
-      while (*progress <= ii) __builtin_amdgcn_s_sleep(1);   // wave 0 always gets there: it waits for nobody
+    static_for<0, CB>([&](auto ic) __attribute__((always_inline)) { w[decltype(ic)::value] = (lane == decltype(ic)::value) ? 1.f : 0.f; });
+    f32x4_t cv0[CB / 4], cv1[CB / 4];
+    float piv0 = 1.f, piv1 = 1.f;
+    int seen = 0;
+    // raw column j+1 is fetched while column j is being used; a column is only asked for once it is final
+    auto fetch = [&](auto jc, f32x4_t* cv, float& piv) __attribute__((always_inline)) {
+      constexpr int jj = decltype(jc)::value;
+      if (seen <= jj) {
+        do { seen = *raw_done; } while (seen <= jj);   // wave 0 always gets there: it waits for nobody
+      }
       asm volatile("" ::: "memory");
-      f32x4_t lv[CB / 4];
-      static_for<0, (ii + 3) / 4>([&](auto qc) __attribute__((always_inline)) {
+      const lds_float* cb = S0 + jj * CBP;
+      piv = cb[jj];
+      if constexpr (jj + 1 < CB) {
+        constexpr int q0 = (jj + 1) / 4;   // entries up to j of the first group of four are not read (see wave 0)
+        static_for<jj + 1, (4 * q0 + 4 < CB ? 4 * q0 + 4 : CB)>([&](auto kc) __attribute__((always_inline)) {
+          constexpr int k = decltype(kc)::value;
+          cv[q0][k % 4] = cb[k];
+        });
+        static_for<q0 + 1, CB / 4>([&](auto qc) __attribute__((always_inline)) {
+          constexpr int q = decltype(qc)::value;
+          cv[q] = *(const lds_f32x4*)(cb + 4 * q);
+        });
+      }
+    };
+    fetch(std::integral_constant<int, 0>{}, cv0, piv0);
+    static_for<0, CB>([&](auto jc) __attribute__((always_inline)) {
+      constexpr int jj = decltype(jc)::value;
+      const f32x4_t* cv = (jj & 1) ? cv1 : cv0;
+      const float piv = (jj & 1) ? piv1 : piv0;
+      if constexpr (jj + 1 < CB) fetch(std::integral_constant<int, jj + 1>{}, (jj & 1) ? cv0 : cv1, (jj & 1) ? piv0 : piv1);
+      __builtin_amdgcn_sched_barrier(0);
+      const float u = w[jj] * __builtin_amdgcn_rcpf(piv);
+      static_for<(jj + 1) / 4, CB / 4>([&](auto qc) __attribute__((always_inline)) {
         constexpr int q = decltype(qc)::value;
-        lv[q] = *(const f32x4_t*)(LT + ii * CBP + 4 * q);
+        if constexpr (4 * q + 0 > jj) w[4 * q + 0] -= cv[q][0] * u;
+        if constexpr (4 * q + 1 > jj) w[4 * q + 1] -= cv[q][1] * u;
+        if constexpr (4 * q + 2 > jj) w[4 * q + 2] -= cv[q][2] * u;
+        if constexpr (4 * q + 3 > jj) w[4 * q + 3] -= cv[q][3] * u;
       });
-      const float rs = rsv[ii];
-      asm volatile("" ::: "memory");
-      float acc0 = (lane == ii) ? 1.f : 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-      static_for<0, (ii + 3) / 4>([&](auto qc) __attribute__((always_inline)) {
-        constexpr int q = decltype(qc)::value;
-        if constexpr (4 * q + 0 < ii) acc0 -= lv[q][0] * w[4 * q + 0];
-        if constexpr (4 * q + 1 < ii) acc1 -= lv[q][1] * w[4 * q + 1];
-        if constexpr (4 * q + 2 < ii) acc2 -= lv[q][2] * w[4 * q + 2];
-        if constexpr (4 * q + 3 < ii) acc3 -= lv[q][3] * w[4 * q + 3];
+      // keeps this step's arithmetic from being moved past the next wait loop
+      static_for<jj + 1, CB>([&](auto kc) __attribute__((always_inline)) {
+        float& wk = w[decltype(kc)::value];
+        asm volatile("" : "+v"(wk));
       });
-      w[ii] = ((acc0 + acc1) + (acc2 + acc3)) * rs;
-      asm volatile("" : "+v"(w[ii]));   // keeps this row's arithmetic ahead of the next wait loop
+      __builtin_amdgcn_sched_barrier(0);
     });
-    static_for<0, CB>([&](auto rc) __attribute__((always_inline)) { S0[decltype(rc)::value * CBP + lane] = w[decltype(rc)::value]; });  // wave 0 read S0 only before it started
+    while (*scaled == 0) __builtin_amdgcn_s_sleep(1);   // wave 2 always gets there: it waits only for wave 0
+    asm volatile("" ::: "memory");
+    // waves 0 and 2 are through with S0 by now
+    static_for<0, CB>([&](auto rc) __attribute__((always_inline)) {
+      constexpr int rr = decltype(rc)::value;
+      S0[rr * CBP + lane] = w[rr] * rsv[rr];
+    });
 }
 
 __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
@@ -142,11 +244,16 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   __shared__ __attribute__((aligned(16))) float S0[CB * CBP];   // C11, later W11
   __shared__ __attribute__((aligned(16))) float S1[CB * CBP];   // C21_i, later L21_i
   __shared__ __attribute__((aligned(16))) float S2[CB * CBP];   // C21_j, later L21_j
-  __shared__ __attribute__((aligned(16))) float LT[CB * CBP];   // finished rows of L11
-  __shared__ __attribute__((aligned(16))) float col[CB];        // current column, shared by the lanes of wave 0
+  __shared__ __attribute__((aligned(16))) float col[2 * CB];    // raw columns (even / odd) on their way between the lanes of wave 0
   __shared__ float rsv[CB];                                     // 1 / L[j][j]
-  __shared__ volatile int progress;                             // number of factored columns
+  __shared__ volatile int scaled;                               // set when rsv is complete
+  __shared__ volatile int raw_done;                             // number of eliminated (raw) columns
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+#ifdef CHOL_TIMING
+  long long* tlog = (long long*)((float*)tab[slotL] + 64) + (size_t)(k0 / CB) * 8;
+  const bool tl = blockIdx.x == 0 && mode != 2;
+  if (tl && t == 0) tlog[0] = wall_clock64();
+#endif
   const int wm = wave & 1, wn = wave >> 1, lr = lane & 31, lk = lane >> 5;
 
   // tile (i, j), 1 <= j <= i, in units of 64 rows/columns below/right of the diagonal block
@@ -161,12 +268,18 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   }
   const long long rowi = k0 + (long long)CB * i, rowj = k0 + (long long)CB * j;
 
-  for (int idx = t; idx < CB * CB; idx += 256) {
-    const int rr = idx >> 6, cc = idx & 63;
+  for (int idx = t; idx < CB * CB / 4; idx += 256) {
+    const int rr = idx >> 4, cc = (idx & 15) * 4;
     const long long at = (long long)(k0 + rr) * ld + k0 + cc;
-    S0[rr * CBP + cc] = (mode == 2) ? W[at] : ((cc <= rr) ? C[at] : 0.f);
+    f32x4_t v = *(const f32x4_t*)((mode == 2) ? W + at : C + at);
+    if (mode != 2) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (cc + e > rr) v[e] = 0.f;
+    }
+    *(f32x4_t*)(S0 + rr * CBP + cc) = v;
   }
-  if (t == 0) progress = 0;
+  if (t == 0) { scaled = 0; raw_done = 0; }
   // this thread's 16 entries of the trailing tile, fetched now so that they arrive during the factorisation
   float cold[16];
   if (!writer) {
@@ -179,29 +292,49 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   __syncthreads();
 
   if (mode == 2) {
-    for (int idx = t; idx < CB * CB; idx += 256) {
-      const int rr = idx >> 6, cc = idx & 63;
-      S1[rr * CBP + cc] = C[(rowi + rr) * ld + k0 + cc];
-      if (j != i) S2[rr * CBP + cc] = C[(rowj + rr) * ld + k0 + cc];
+    for (int idx = t; idx < CB * CB / 4; idx += 256) {
+      const int rr = idx >> 4, cc = (idx & 15) * 4;
+      *(f32x4_t*)(S1 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowi + rr) * ld + k0 + cc);
+      if (j != i) *(f32x4_t*)(S2 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowj + rr) * ld + k0 + cc);
     }
   } else if (wave == 0) {
-    factor_wave(S0, LT, col, rsv, &progress, lane, piv_lo, piv_hi, writer ? L + (long long)k0 * ld + k0 : nullptr, ld,
-                (int*)tab[SLOT_STATUS]);
+#ifdef CHOL_TIMING
+    if (tl && lane == 0) { tlog[1] = wall_clock64(); }
+#endif
+    eliminate_wave((lds_float*)S0, (lds_counter*)&raw_done, lane);
+#ifdef CHOL_TIMING
+    if (tl && lane == 0) { tlog[2] = wall_clock64(); }
+#endif
+  } else if (wave == 2) {
+    scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, piv_lo, piv_hi,
+               writer ? L + (long long)k0 * ld + k0 : nullptr, ld, (int*)tab[SLOT_STATUS]);
+#ifdef CHOL_TIMING
+    if (tl && lane == 0) tlog[6] = wall_clock64();
+#endif
   } else if (wave == 1) {
-    invert_wave(S0, LT, rsv, &progress, lane);
+    invert_wave((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane);
+#ifdef CHOL_TIMING
+    if (tl && lane == 0) tlog[3] = wall_clock64();
+#endif
   } else if (!writer) {
-    for (int idx = t - 128; idx < CB * CB; idx += 128) {
-      const int rr = idx >> 6, cc = idx & 63;
-      S1[rr * CBP + cc] = C[(rowi + rr) * ld + k0 + cc];
-      if (j != i) S2[rr * CBP + cc] = C[(rowj + rr) * ld + k0 + cc];
+    for (int idx = lane; idx < CB * CB / 4; idx += 64) {
+      const int rr = idx >> 4, cc = (idx & 15) * 4;
+      *(f32x4_t*)(S1 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowi + rr) * ld + k0 + cc);
+      if (j != i) *(f32x4_t*)(S2 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowj + rr) * ld + k0 + cc);
     }
   }
   __syncthreads();
   if (writer) {
-    for (int idx = t; idx < CB * CB; idx += 256) {
-      const int rr = idx >> 6, cc = idx & 63;
-      W[(long long)(k0 + rr) * ld + k0 + cc] = S0[rr * CBP + cc];
+#ifdef CHOL_TIMING
+    if (tl && t == 0) tlog[4] = wall_clock64();
+#endif
+    for (int idx = t; idx < CB * CB / 4; idx += 256) {
+      const int rr = idx >> 4, cc = (idx & 15) * 4;
+      *(f32x4_t*)(W + (long long)(k0 + rr) * ld + k0 + cc) = *(const f32x4_t*)(S0 + rr * CBP + cc);
     }
+#ifdef CHOL_TIMING
+    if (tl && t == 0) tlog[5] = wall_clock64();
+#endif
     return;
   }
   const f32x16_t li = mma_64(S1, S0, wm, wn, lr, lk);   // L21_i = C21_i W11^T
