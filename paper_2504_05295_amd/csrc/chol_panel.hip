@@ -229,28 +229,29 @@ __device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done
     });
 }
 
-__global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, int nslots, int slotC, int slotL, int slotW,
-                                                            int k0, int rp, float piv_lo, float piv_hi, int mode, int skip_slot) {
+__global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int k0, int rp, float piv_lo, float piv_hi, int mode) {
   // mode 0: fused (workgroup 0 writes L11/W11, the others own tiles and redo the factorisation)
   // mode 1: diagonal block only (one workgroup per matrix)      mode 2: tiles only, W11 read back from memory
   // Modes 1+2 are used when there are so many tiles (large batches) that redoing the factorisation in
   // every workgroup would cost more than a second launch.
-  void* const* tab = table + (size_t)blockIdx.y * nslots;
-  if (skip_slot >= 0 && *(const int*)tab[skip_slot] != 0) return;   // uniform for the whole workgroup
-  float* C = (float*)tab[slotC];
-  float* L = (float*)tab[slotL];
-  float* W = (float*)tab[slotW];
+  const long long mat = (long long)blockIdx.y * p.stride;
+  float* C = p.C + mat;
+  float* L = p.L + mat;
+  float* W = p.W + mat;
+  int* status = p.status + blockIdx.y;
+  // Only the second Cholesky-QR pass carries a skip flag (set when it needs no factorisation); the first pass
+  // starts its loads without this extra memory round trip.
+  if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole workgroup
   const long long ld = rp;
   __shared__ __attribute__((aligned(16))) float S0[CB * CBP];   // C11, later W11
   __shared__ __attribute__((aligned(16))) float S1[CB * CBP];   // C21_i, later L21_i
   __shared__ __attribute__((aligned(16))) float S2[CB * CBP];   // C21_j, later L21_j
-  __shared__ __attribute__((aligned(16))) float col[2 * CB];    // raw columns (even / odd) on their way between the lanes of wave 0
   __shared__ float rsv[CB];                                     // 1 / L[j][j]
   __shared__ volatile int scaled;                               // set when rsv is complete
   __shared__ volatile int raw_done;                             // number of eliminated (raw) columns
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
 #ifdef CHOL_TIMING
-  long long* tlog = (long long*)((float*)tab[slotL] + 64) + (size_t)(k0 / CB) * 8;
+  long long* tlog = (long long*)(L + 64) + (size_t)(k0 / CB) * 8;
   const bool tl = blockIdx.x == 0 && mode != 2;
   if (tl && t == 0) tlog[0] = wall_clock64();
 #endif
@@ -307,7 +308,7 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
 #endif
   } else if (wave == 2) {
     scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, piv_lo, piv_hi,
-               writer ? L + (long long)k0 * ld + k0 : nullptr, ld, (int*)tab[SLOT_STATUS]);
+               writer ? L + (long long)k0 * ld + k0 : nullptr, ld, status);
 #ifdef CHOL_TIMING
     if (tl && lane == 0) tlog[6] = wall_clock64();
 #endif
@@ -357,20 +358,320 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(void* const* table, 
   }
 }
 
-hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,
-                             float piv_lo, float piv_hi, int skip_slot, hipStream_t s) {
+// ---------------------------------------------------------------------------------------------------------
+// The whole factorisation in one launch, for one or a few matrices (where a launch per panel leaves the GPU
+// waiting on launch latencies and on workgroups that each redo the diagonal block).
+//
+// The 64x64 tiles of the lower triangle have fixed owners: tile (i, j) belongs to workgroup
+// (i mod pr) * pc + (j mod pc), except that (i, i-1) goes with (i, i).  An owner does everything that
+// happens to its tile, in panel order k = 0, 1, ...:
+//   D(k)      tile (k, k):        factor it, publish L11, W11 = L11^-1                  -> wflag[k]
+//   T(i, k)   tile (i, k), i > k: L[i][k] = C[i][k] W11^T, publish it                   -> lflag[i] = k + 1
+//   U(i,j,k)  tile (i, j), j > k: C[i][j] -= L[i][k] L[j][k]^T                          (needs lflag[i], lflag[j] > k)
+// so tile data never changes hands; only W11 and the finished tiles of L cross between workgroups, through
+// memory, with device-scope stores and loads, each announced by a flag that is written once the stores have
+// completed.  The owner of (k+1, k+1) also owns (k+1, k): the chain D(k) -> T(k+1, k) -> U(k+1, k+1, k)
+// -> D(k+1), which bounds the run time, crosses workgroups once per panel, and that workgroup takes it before
+// its other work.  Every workgroup handles its tasks in an order in which a task only waits for tasks that
+// come earlier in the common order (panel, then D < T < U), so somebody can always proceed.
+// Flags carry the number of the launch (epoch) and need no clearing.  Waits are bounded: a workgroup that
+// gives up raises the abort word, everybody else sees it at the next wait, and the status word reports the
+// matrix as failed; all workgroups must be resident at once, which the host guarantees by the grid size.
+namespace {
+typedef unsigned long long u64;
+typedef __attribute__((address_space(1))) float gfloat;
+typedef __attribute__((address_space(1))) int gint;
+typedef __attribute__((address_space(1))) u64 gu64;
+typedef __attribute__((address_space(1))) f32x4_t gf32x4;
+
+__device__ __forceinline__ u64 flag_load(const gu64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void flag_store(gu64* p, u64 v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Data that crosses between workgroups (W11 and the tiles of L) is written and read with device-scope
+// accesses, which go past the caches that are private to a compute unit or to one part of the chip; no
+// cache-wide write-back or invalidation is needed then, only that the writer's stores have completed
+// before its flag goes out.
+__device__ __forceinline__ float shared_load(const gfloat* p) {
+  return __int_as_float(__hip_atomic_load((const gint*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void shared_store(gfloat* p, float v) {
+  __hip_atomic_store((gint*)p, __float_as_int(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// 64x64 fp32 tile, global (leading dimension ld) <-> LDS (row stride CBP), by the whole workgroup.
+// Thread t handles column t % 64 of rows t / 64 + 4 e.
+__device__ __forceinline__ void shared_tile_to_lds(float* S, const gfloat* src, int ld, int t) {
+  float v[16];
+  const int r0 = t >> 6, c = t & 63;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] = shared_load(src + (r0 + 4 * e) * ld + c);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) S[(r0 + 4 * e) * CBP + c] = v[e];
+}
+__device__ __forceinline__ void lds_to_shared_tile(gfloat* dst, int ld, const float* S, int t) {
+  const int r0 = t >> 6, c = t & 63;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) shared_store(dst + (r0 + 4 * e) * ld + c, S[(r0 + 4 * e) * CBP + c]);
+}
+__device__ __forceinline__ void tile_to_lds(float* S, const gfloat* src, int ld, int t) {
+#pragma unroll
+  for (int idx = t; idx < CB * CB / 4; idx += 256) {
+    const int rr = idx >> 4, cc = (idx & 15) * 4;
+    *(f32x4_t*)(S + rr * CBP + cc) = *(const gf32x4*)(src + rr * ld + cc);
+  }
+}
+
+struct StreamCtx {
+  gfloat* C;
+  gfloat* L;
+  gfloat* W;
+  int* status;
+  gu64* wflag;
+  gu64* lflag;
+  gu64* abort_word;
+  u64 epoch;
+  unsigned spin_limit;
+  int ld;
+  float piv_lo, piv_hi;
+};
+
+// Polls until ready() holds, on behalf of the threads with `mine`; returns false for everybody when a wait
+// was given up (here or, as the abort word tells, elsewhere).
+template <class F>
+__device__ __forceinline__ bool wait_until(const StreamCtx& x, int* gave_up, bool mine, F ready) {
+  if (mine) {
+    unsigned n = 0;
+    while (!ready()) {
+      __builtin_amdgcn_s_sleep(2);
+      if ((++n & 31u) == 0) {
+        if (flag_load(x.abort_word) == x.epoch) { *(volatile int*)gave_up = 1; break; }
+        if (n > x.spin_limit) {
+          flag_store(x.abort_word, x.epoch);
+          *x.status = 1;
+          *(volatile int*)gave_up = 1;
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  return *(volatile int*)gave_up == 0;
+}
+}  // namespace
+
+__global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
+  const long long mat = (long long)blockIdx.y * p.stride;
+  if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole grid row of this matrix
+  const int nb = p.rp / CB, pr = p.pr, pc = p.pc;
+  StreamCtx x;
+  x.C = (gfloat*)(p.C + mat);
+  x.L = (gfloat*)(p.L + mat);
+  x.W = (gfloat*)(p.W + mat);
+  x.status = p.status + blockIdx.y;
+  x.wflag = (gu64*)(p.sync + (long long)blockIdx.y * p.sync_stride);
+  x.lflag = x.wflag + nb;
+  x.abort_word = x.lflag + nb;
+  x.epoch = p.epoch;
+  x.spin_limit = p.spin_limit;
+  x.ld = p.rp;
+  x.piv_lo = p.piv_lo;
+  x.piv_hi = p.piv_hi;
+  const int ld = p.rp;
+
+  __shared__ __attribute__((aligned(16))) float S0[CB * CBP];   // diagonal block / W11
+  __shared__ __attribute__((aligned(16))) float S1[CB * CBP];
+  __shared__ __attribute__((aligned(16))) float S2[CB * CBP];
+  __shared__ float rsv[CB];
+  __shared__ volatile int scaled;
+  __shared__ volatile int raw_done;
+  __shared__ int gave_up;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave & 1, wn = wave >> 1, lr = lane & 31, lk = lane >> 5;
+  const int wg = blockIdx.x, a = wg / pc, b = wg % pc;
+  // this thread's part of a 64x64 tile in the MFMA result layout: rows frow + 8 (v / 4) + v % 4, column fcol
+  const int frow = wm * 32 + 4 * lk, fcol = wn * 32 + lr;
+  const int foff = frow * ld + fcol;
+  if (t == 0) gave_up = 0;
+  __syncthreads();
+
+  int s0_holds = -1;             // panel whose W11 is in S0
+  // A tile of L that sits in S1 and still has to be written out and announced; the wave that has nothing
+  // to do during the next D does that, off the chain of dependent steps.
+  gu64* pending_flag = nullptr;
+  gfloat* pending_tile = nullptr;
+  u64 pending_value = 0;
+
+  // D(k).  in_lds: the block is already in S0 (lower part, zeros above the diagonal).
+  auto do_diag = [&](int k, bool in_lds) __attribute__((always_inline)) {
+    const int at = (k * CB) * ld + k * CB;
+    if (!in_lds) {
+      for (int idx = t; idx < CB * CB / 4; idx += 256) {
+        const int rr = idx >> 4, cc = (idx & 15) * 4;
+        f32x4_t v = *(const gf32x4*)(x.C + at + rr * ld + cc);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (cc + e > rr) v[e] = 0.f;
+        *(f32x4_t*)(S0 + rr * CBP + cc) = v;
+      }
+    }
+    if (t == 0) { scaled = 0; raw_done = 0; }
+    __syncthreads();
+    if (wave == 0) {
+      eliminate_wave((lds_float*)S0, (lds_counter*)&raw_done, lane);
+    } else if (wave == 2) {
+      scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, x.piv_lo, x.piv_hi,
+                 (float*)(x.L + at), ld, x.status);
+    } else if (wave == 1) {
+      invert_wave((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane);
+    } else if (pending_flag) {
+#pragma unroll 8
+      for (int rr = 0; rr < CB; ++rr) shared_store(pending_tile + rr * ld + lane, S1[rr * CBP + lane]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (lane == 0) flag_store(pending_flag, pending_value);
+    }
+    pending_flag = nullptr;
+    __syncthreads();
+    lds_to_shared_tile(x.W + at, ld, S0, t);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have completed before the barrier
+    __syncthreads();
+    if (t == 0) flag_store(x.wflag + k, x.epoch);
+    s0_holds = k;
+  };
+
+  // T(i, k); leaves L[i][k] in S1 as well.  defer_flag: the flag goes out during the next D
+  auto do_column_tile = [&](int i, int k, bool defer_flag) __attribute__((always_inline)) -> bool {
+    __syncthreads();   // earlier readers of S0 / S1 are through
+    tile_to_lds(S1, x.C + (i * CB) * ld + k * CB, ld, t);
+    if (s0_holds != k) {
+      if (!wait_until(x, &gave_up, t == 0, [&] { return flag_load(x.wflag + k) == x.epoch; })) return false;
+      shared_tile_to_lds(S0, x.W + (k * CB) * ld + k * CB, ld, t);
+      s0_holds = k;
+    }
+    __syncthreads();
+    const f32x16_t li = mma_64(S1, S0, wm, wn, lr, lk);   // L[i][k] = C[i][k] W11^T
+    __syncthreads();
+    gfloat* dst = x.L + (i * CB) * ld + k * CB;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      S1[(frow + 8 * (v / 4) + (v % 4)) * CBP + fcol] = li[v];
+      if (!defer_flag) shared_store(dst + foff + (8 * (v / 4) + (v % 4)) * ld, li[v]);
+    }
+    if (defer_flag) {
+      pending_flag = x.lflag + i;
+      pending_tile = dst;
+      pending_value = (x.epoch << 32) | (u64)(k + 1);
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();   // S1 is complete (and, unless deferred, everybody's stores have completed)
+    if (!defer_flag && t == 0) flag_store(x.lflag + i, (x.epoch << 32) | (u64)(k + 1));
+    return true;
+  };
+
+  // U(i, j, k)
+  auto do_update = [&](int i, int j, int k) __attribute__((always_inline)) {
+    gfloat* ct = x.C + (i * CB) * ld + j * CB + foff;
+    float cold[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cold[v] = ct[(8 * (v / 4) + (v % 4)) * ld];
+    __syncthreads();   // earlier readers of S1 / S2 are through
+    shared_tile_to_lds(S1, x.L + (i * CB) * ld + k * CB, ld, t);
+    if (j != i) shared_tile_to_lds(S2, x.L + (j * CB) * ld + k * CB, ld, t);
+    __syncthreads();
+    const f32x16_t up = mma_64(S1, (j != i) ? S2 : S1, wm, wn, lr, lk);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) ct[(8 * (v / 4) + (v % 4)) * ld] = cold[v] - up[v];
+  };
+
+  // U(k1, k1, k1 - 1) with L[k1][k1 - 1] in S1; the result goes straight into S0 for D(k1) and nowhere else
+  auto do_update_to_diag = [&](int k1) __attribute__((always_inline)) {
+    const gfloat* ct = x.C + (k1 * CB) * ld + k1 * CB + foff;
+    float cold[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cold[v] = ct[(8 * (v / 4) + (v % 4)) * ld];
+    const f32x16_t up = mma_64(S1, S1, wm, wn, lr, lk);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = frow + 8 * (v / 4) + (v % 4);
+      S0[row * CBP + fcol] = (fcol <= row) ? cold[v] - up[v] : 0.f;
+    }
+    s0_holds = -1;
+  };
+
+  // Step k handles panel k after the diagonal block k+1 has been taken care of (step -1: block 0 only).
+  for (int k = -1; k + 1 < nb; ++k) {
+    // the chain: T(k+1, k), U(k+1, k+1, k), D(k+1)
+    if (((k + 1) % pr) * pc + ((k + 1) % pc) == wg) {
+#ifdef CHOL_TIMING
+      long long* tlog = (long long*)(x.L + 64) + (size_t)(k < 0 ? 31 : k) * 8;
+      if (t == 0) tlog[0] = wall_clock64();
+#endif
+      if (k >= 0) {
+        if (!do_column_tile(k + 1, k, true)) return;
+#ifdef CHOL_TIMING
+        if (t == 0) tlog[1] = wall_clock64();
+#endif
+        do_update_to_diag(k + 1);
+      }
+#ifdef CHOL_TIMING
+      if (t == 0) tlog[2] = wall_clock64();
+#endif
+      do_diag(k + 1, k >= 0);
+#ifdef CHOL_TIMING
+      if (t == 0) tlog[3] = wall_clock64();
+#endif
+    }
+    if (k < 0) continue;
+    // the other tiles of column k
+    if (k % pc == b) {
+      for (int i = a + ((k + 1 - a + pr - 1) / pr) * pr; i < nb; i += pr) {
+        if (i <= k || i == k + 1) continue;
+        if (!do_column_tile(i, k, false)) return;
+      }
+    }
+    // wait for the tiles of L that this workgroup's updates need: one thread per block row
+    {
+      bool need = false;
+      if (t > k && t < nb) {
+        need = (t % pr) == a || (t % pc) == b;   // rows of regular tiles (as i or as j)
+        if ((t % pr) * pc + (t % pc) == wg || ((t + 1) < nb && ((t + 1) % pr) * pc + ((t + 1) % pc) == wg)) need = true;   // tiles (i, i-1)
+      }
+      if (!wait_until(x, &gave_up, need, [&] {
+            const u64 v = flag_load(x.lflag + t);
+            return (v >> 32) == x.epoch && (unsigned)v >= (unsigned)(k + 1);
+          }))
+        return;
+    }
+    for (int j = b + ((k + 1 - b + pc - 1) / pc) * pc; j < nb; j += pc) {
+      if (j <= k) continue;
+      for (int i = a + ((j - a + pr - 1) / pr) * pr; i < nb; i += pr) {
+        if (i < j || i == j + 1) continue;
+        if (i == j && j == k + 1) continue;   // went into D(k+1) above
+        do_update(i, j, k);
+      }
+    }
+    for (int i = k + 2; i < nb; ++i)
+      if ((i % pr) * pc + (i % pc) == wg) do_update(i, i - 1, k);
+  }
+}
+
+hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
+  // 32 KB of unused dynamic LDS on top of the 52 KB the kernel declares: one workgroup per compute unit, so the
+  // workgroup on the critical chain shares its unit with nobody
+  hipLaunchKernelGGL(chol_stream_kernel, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s) {
   const int nb = (rp - k0 - CB) / CB;
   const int tiles = nb * (nb + 1) / 2;
   if ((long long)(1 + tiles) * batch <= 1024 || tiles == 0) {
-    hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp,
-                       piv_lo, piv_hi, 0, skip_slot);
+    hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 0);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo, piv_hi, 1, skip_slot);
+  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 1);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(tiles, batch), dim3(256), 0, s, table, nslots, slotC, slotL, slotW, k0, rp, piv_lo,
-                     piv_hi, 2, skip_slot);
+  hipLaunchKernelGGL(chol_panel_kernel, dim3(tiles, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 2);
   return hipGetLastError();
 }
 

@@ -38,6 +38,11 @@ struct Entry {
   int group;
   int row;  // row of the pointer table (group-sorted order)
 };
+// byte offsets of the workspace slots of one matrix
+struct Carve {
+  size_t off[NSLOTS];
+  size_t total;
+};
 struct Group {
   int64_t m, n, r;
   int rp;          // r rounded up to a multiple of CHOL_NB
@@ -46,6 +51,8 @@ struct Group {
   int gram2_splitk;   // split-K of the split-bf16 Gram product (large-tile path)
   int k12_splitk;     // split-K of K1 / K2 on the large-tile path when their outputs have too few tiles
   size_t bytes_per_entry;
+  Carve carve;     // slot offsets inside one matrix' share of the workspace
+  size_t ws_off;   // offset of the group's first matrix in the workspace (set by dion_init_state)
 };
 
 constexpr int kEventsPerGroup = DION_STAGE_COUNT + 1;
@@ -82,11 +89,6 @@ void plan_gram(Group& g) {
   }
 }
 
-// workspace floats of one matrix, in slot order
-struct Carve {
-  size_t off[NSLOTS];
-  size_t total;
-};
 Carve carve_entry(const Group& g) {
   Carve c;
   memset(&c, 0, sizeof(c));
@@ -121,6 +123,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_EPART, 256);
   take(SLOT_FAST, 1);
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
+  take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 1));
   c.total = pos;
   return c;
 }
@@ -162,7 +165,8 @@ bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r,
     g.first_row = row;
     row += g.count;
     plan_gram(g);
-    g.bytes_per_entry = carve_entry(g).total;
+    g.carve = carve_entry(g);
+    g.bytes_per_entry = g.carve.total;
   }
   std::vector<int> next(groups.size());
   for (size_t k = 0; k < groups.size(); ++k) next[k] = groups[k].first_row;
@@ -187,6 +191,8 @@ struct dion_state {
   hipStream_t last_stream;
   bool timing;
   int orth_mode;
+  unsigned chol_epoch;       // launch counter of the single-launch Cholesky kernel (its flags are tagged with it)
+  unsigned chol_spin_limit;  // polls after which a wait inside that kernel gives up
   std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
   std::vector<char> group_timed;       // which groups ran in the last call with timing on
 };
@@ -278,9 +284,37 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   const int skip = adaptive ? SLOT_FAST : -1;
   if (adaptive) HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, s));
   base.status_slot = skip;
-  // blocked right-looking Cholesky, one fused launch per 64-wide panel
-  for (int k = 0; k < rp; k += CHOL_NB)
-    HIPCHK(launch_chol_panel(tab, NSLOTS, batch, SLOT_C, SLOT_L, SLOT_W, k, rp, piv_lo, piv_hi, skip, s));
+  // blocked right-looking Cholesky, one fused launch per 64-wide panel.  The kernel gets the addresses of
+  // its buffers as arguments: a look-up in the pointer table would cost it one more memory round trip.
+  CholPanelPtrs pp;
+  {
+    char* e0 = st->ws + g.ws_off + (size_t)row0 * g.bytes_per_entry;
+    pp.C = (float*)(e0 + g.carve.off[SLOT_C]);
+    pp.L = (float*)(e0 + g.carve.off[SLOT_L]);
+    pp.W = (float*)(e0 + g.carve.off[SLOT_W]);
+    pp.skip = adaptive ? (const int*)(e0 + g.carve.off[SLOT_FAST]) : nullptr;
+    pp.stride = (long long)(g.bytes_per_entry / sizeof(float));
+    pp.status = st->status + g.first_row + row0;
+  }
+  const int nb = rp / CHOL_NB;
+  if (batch <= 4 && nb >= 4 && nb <= 128) {
+    // one or a few matrices: the whole factorisation in one launch of at most 256 co-resident workgroups
+    CholStreamArgs ca;
+    ca.C = pp.C; ca.L = pp.L; ca.W = pp.W; ca.status = pp.status; ca.skip = pp.skip;
+    ca.sync = (unsigned long long*)(st->ws + g.ws_off + (size_t)row0 * g.bytes_per_entry + g.carve.off[SLOT_SYNC]);
+    ca.stride = pp.stride;
+    ca.sync_stride = (long long)(g.bytes_per_entry / sizeof(unsigned long long));
+    ca.rp = rp;
+    ca.pr = ca.pc = (batch == 1 && nb >= 16) ? 16 : 8;
+    ca.piv_lo = piv_lo; ca.piv_hi = piv_hi;
+    if (++st->chol_epoch == 0) st->chol_epoch = 1;
+    ca.epoch = st->chol_epoch;
+    ca.spin_limit = st->chol_spin_limit;
+    HIPCHK(launch_chol_stream(ca, batch, s));
+  } else {
+    for (int k = 0; k < rp; k += CHOL_NB)
+      HIPCHK(launch_chol_panel(pp, batch, k, rp, piv_lo, piv_hi, s));
+  }
   // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]].
   // Blocks start as the 64-wide inverses left by the panel kernel; an odd block is carried to the next level,
   // so any multiple of 64 works.  Runs of equal, evenly spaced pairs go out as one launch.
@@ -538,6 +572,8 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     st->last_stream = s;
     st->timing = false;
     st->orth_mode = DION_ORTH_CHOLQR2;
+    st->chol_epoch = 0;
+    st->chol_spin_limit = 1u << 20;
     st->group_timed.assign(st->groups.size(), 0);
     // host image of the pointer table
     std::vector<void*> host((size_t)count * NSLOTS, nullptr);
@@ -545,6 +581,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     std::vector<size_t> group_base(st->groups.size());
     for (size_t k = 0; k < st->groups.size(); ++k) {
       group_base[k] = pos;
+      st->groups[k].ws_off = pos;
       pos += st->groups[k].bytes_per_entry * st->groups[k].count;
     }
     for (int i = 0; i < count; ++i) {
@@ -554,7 +591,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_KPART; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_SYNC; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];
@@ -581,6 +618,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
   for (auto& g : st->groups) {
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 1), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, g.n, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
   }

@@ -38,6 +38,7 @@ enum Slot {
   SLOT_EPART,  // 256 partial sums of the squared Gram defect ||C - I||_F^2
   SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
+  SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
   NSLOTS = 32
 };
 
@@ -98,9 +99,36 @@ hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int sl
                                long long rows, long long cols, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
                                 int first_stream, hipStream_t s);
-// skip_slot >= 0: the launch does nothing for matrices whose int32 at that slot is non-zero
-hipError_t launch_chol_panel(void* const* table, int nslots, int batch, int slotC, int slotL, int slotW, int k0, int rp,
-                             float piv_lo, float piv_hi, int skip_slot, hipStream_t s);
+// Buffers of the first matrix of a batch; matrix b has them `stride` 4-byte words further (status: b ints further).
+// skip != nullptr: the launch does nothing for matrices whose int32 there is non-zero.
+struct CholPanelPtrs {
+  float* C;
+  float* L;
+  float* W;
+  int* status;
+  const int* skip;
+  long long stride;
+};
+hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s);
+// The whole factorisation in one launch (tiles owned by pr x pc workgroups that hand results on through flags).
+// sync: per matrix 2 * rp / 64 + 1 64-bit words that were zero before the first launch; epoch: a number that
+// differs from launch to launch and is never 0; every wait inside the kernel gives up after spin_limit polls.
+// All pr * pc * batch workgroups must fit on the GPU at once.
+struct CholStreamArgs {
+  float* C;
+  float* L;
+  float* W;
+  int* status;
+  const int* skip;
+  unsigned long long* sync;
+  long long stride;        // 4-byte words between the matrices of a batch (C, L, W, skip)
+  long long sync_stride;   // 64-bit words between their flag arrays
+  int rp, pr, pc;
+  float piv_lo, piv_hi;
+  unsigned epoch;
+  unsigned spin_limit;
+};
+hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
 // identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
 // Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
