@@ -27,7 +27,7 @@ DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DE
 DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_last_status",
-           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
 
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
+        L.dion_set_wait_limit.argtypes = [C.c_void_p, C.c_uint]
         L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
         L.dion_destroy_state.argtypes = [C.c_void_p]
@@ -212,6 +213,10 @@ def dion_last_status(state: DionState) -> Tuple[int, int]:
 
 def dion_set_orth_mode(state: DionState, mode: int) -> None:
     _check(lib().dion_set_orth_mode(state.handle, int(mode)), "dion_set_orth_mode")
+
+
+def dion_set_wait_limit(state: DionState, polls: int) -> None:
+    _check(lib().dion_set_wait_limit(state.handle, int(polls)), "dion_set_wait_limit")
 
 
 def dion_set_stage_timing(state: DionState, enable: bool) -> None:

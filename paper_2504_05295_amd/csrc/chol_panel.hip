@@ -442,14 +442,15 @@ __device__ __forceinline__ bool wait_until(const StreamCtx& x, int* gave_up, boo
     unsigned n = 0;
     while (!ready()) {
       __builtin_amdgcn_s_sleep(2);
-      if ((++n & 31u) == 0) {
-        if (flag_load(x.abort_word) == x.epoch) { *(volatile int*)gave_up = 1; break; }
-        if (n > x.spin_limit) {
-          flag_store(x.abort_word, x.epoch);
-          *x.status = 1;
-          *(volatile int*)gave_up = 1;
-          break;
-        }
+      if (++n > x.spin_limit) {
+        flag_store(x.abort_word, x.epoch);
+        *x.status = 1;
+        *(volatile int*)gave_up = 1;
+        break;
+      }
+      if ((n & 31u) == 0 && flag_load(x.abort_word) == x.epoch) {
+        *(volatile int*)gave_up = 1;
+        break;
       }
     }
   }

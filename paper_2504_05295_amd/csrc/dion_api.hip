@@ -740,6 +740,12 @@ int dion_set_orth_mode(dion_state_t* st, int mode) {
   return DION_OK;
 }
 
+int dion_set_wait_limit(dion_state_t* st, unsigned polls) {
+  if (!st) return DION_EINVAL;
+  st->chol_spin_limit = polls;
+  return DION_OK;
+}
+
 int dion_set_stage_timing(dion_state_t* st, int enable) {
   if (!st) return DION_EINVAL;
   if (enable && st->events.empty()) {

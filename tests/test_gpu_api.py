@@ -342,3 +342,23 @@ def test_retry_completes_only_the_matrices_that_broke_down():
     for i in range(3):
         ref = orc.dion_step(before[i][0], grads[i], before[i][1], before[i][2], MU, ETA)
         assert relf(gp.host(i)[0], ref["X"]) < 1e-4 and relf(gp.host(i)[1], ref["M"]) < 1e-4
+
+
+def test_bounded_waits_of_the_single_launch_cholesky():
+    # r = 512 takes the single-launch Cholesky kernel, whose workgroups wait for one another.  With the wait
+    # limit at zero every wait that is not satisfied at once gives up: the kernel must still end, the step must
+    # be reported as failed with the state untouched, and the next step (normal limit) must be right again.
+    shape = (1024, 768, 512)
+    gp = GpuProblem([shape], True, "bf16")
+    grads = gp.grads_np(0)
+    gp.upload_grads(grads)
+    before = gp.host(0)
+    gp.B.dion_set_wait_limit(gp.state, 0)
+    status, bad = gp.step(MU, ETA)
+    assert (status, bad) == (gp.B.DION_NUM_BREAKDOWN, 0)
+    for u, v in zip(before, gp.host(0)):
+        assert np.array_equal(u, v)
+    gp.B.dion_set_wait_limit(gp.state, 1 << 20)
+    assert gp.step(MU, ETA) == (0, -1)
+    rep, _ = one_step_report(gp, 0, *before, gp.grad_as_f32(grads[0], True), MU, ETA)
+    assert rep["X"] < 2e-2 and rep["M"] < 2e-2 and rep["orth"] < 1e-3, rep
