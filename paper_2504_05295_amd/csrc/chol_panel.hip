@@ -374,7 +374,7 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
 // -> D(k+1), which bounds the run time, crosses workgroups once per panel, and that workgroup takes it before
 // its other work.  Every workgroup handles its tasks in an order in which a task only waits for tasks that
 // come earlier in the common order (panel, then D < T < U), so somebody can always proceed.
-// Flags carry the number of the launch (epoch) and need no clearing.  Waits are bounded: a workgroup that
+// Flags carry the number of the launch (epoch, a counter kept in device memory) and need no clearing.  Waits are bounded: a workgroup that
 // gives up raises the abort word, everybody else sees it at the next wait, and the status word reports the
 // matrix as failed; all workgroups must be resident at once, which the host guarantees by the grid size.
 namespace {
@@ -471,7 +471,7 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   x.wflag = (gu64*)(p.sync + (long long)blockIdx.y * p.sync_stride);
   x.lflag = x.wflag + nb;
   x.abort_word = x.lflag + nb;
-  x.epoch = p.epoch;
+  x.epoch = x.abort_word[1];   // launch counter, incremented by the kernel that cleared W before this launch
   x.spin_limit = p.spin_limit;
   x.ld = p.rp;
   x.piv_lo = p.piv_lo;

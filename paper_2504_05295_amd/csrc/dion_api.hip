@@ -123,7 +123,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_EPART, 256);
   take(SLOT_FAST, 1);
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
-  take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 1));
+  take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 2));
   c.total = pos;
   return c;
 }
@@ -191,7 +191,6 @@ struct dion_state {
   hipStream_t last_stream;
   bool timing;
   int orth_mode;
-  unsigned chol_epoch;       // launch counter of the single-launch Cholesky kernel (its flags are tagged with it)
   unsigned chol_spin_limit;  // polls after which a wait inside that kernel gives up
   std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
   std::vector<char> group_timed;       // which groups ran in the last call with timing on
@@ -276,7 +275,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   }
   if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
-  HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s));
+  // (the same launch advances the launch counter of the single-launch Cholesky kernel)
+  HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s, SLOT_SYNC, 2 * (rp / CHOL_NB) + 1));
   // Second pass: the input is already orthonormal to about 1e-5, so its Gram matrix is I + E with tiny E
   // and chol(I + E)^-1 = I - Phi(E) + O(E^2): no factorisation needed.  The decision is taken on the device
   // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
@@ -307,8 +307,6 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
     ca.rp = rp;
     ca.pr = ca.pc = (batch == 1 && nb >= 16) ? 16 : 8;
     ca.piv_lo = piv_lo; ca.piv_hi = piv_hi;
-    if (++st->chol_epoch == 0) st->chol_epoch = 1;
-    ca.epoch = st->chol_epoch;
     ca.spin_limit = st->chol_spin_limit;
     HIPCHK(launch_chol_stream(ca, batch, s));
   } else {
@@ -572,7 +570,6 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     st->last_stream = s;
     st->timing = false;
     st->orth_mode = DION_ORTH_CHOLQR2;
-    st->chol_epoch = 0;
     st->chol_spin_limit = 1u << 20;
     st->group_timed.assign(st->groups.size(), 0);
     // host image of the pointer table
@@ -618,7 +615,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
   for (auto& g : st->groups) {
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
-    if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 1), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 2), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, g.n, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
   }

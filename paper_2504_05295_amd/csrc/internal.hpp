@@ -76,7 +76,9 @@ hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);      
 // Small kernels (small_kernels.hip).  All take the pointer table and a batch count.
 hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
                                 void* const* M, void* const* Q, hipStream_t s);
-hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
+// count_slot >= 0: also adds one to the 64-bit word number count_index of that slot (a launch counter kept on the device)
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
+                       int count_slot = -1, int count_index = 0);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
 hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s);
@@ -111,8 +113,9 @@ struct CholPanelPtrs {
 };
 hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s);
 // The whole factorisation in one launch (tiles owned by pr x pc workgroups that hand results on through flags).
-// sync: per matrix 2 * rp / 64 + 1 64-bit words that were zero before the first launch; epoch: a number that
-// differs from launch to launch and is never 0; every wait inside the kernel gives up after spin_limit polls.
+// sync: per matrix 2 * rp / 64 + 2 64-bit words that were zero before the first launch: flags, the abort word,
+// and last a launch counter that the host has a kernel increment before every launch (on the device, so that a
+// captured graph can be replayed).  Every wait inside the kernel gives up after spin_limit polls.
 // All pr * pc * batch workgroups must fit on the GPU at once.
 struct CholStreamArgs {
   float* C;
@@ -125,7 +128,6 @@ struct CholStreamArgs {
   long long sync_stride;   // 64-bit words between their flag arrays
   int rp, pr, pc;
   float piv_lo, piv_hi;
-  unsigned epoch;
   unsigned spin_limit;
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);

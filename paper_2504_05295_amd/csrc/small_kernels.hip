@@ -34,16 +34,22 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
 }
 
 // ---------------------------------------------------------------- fills
-__global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value) {
+// count_slot >= 0: the 64-bit word at index count_index of that slot is incremented as well (once per matrix).
+__global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value, int count_slot,
+                            int count_index) {
   float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long long)gridDim.x * blockDim.x)
     p[i] = value;
+  if (count_slot >= 0 && blockIdx.x == 0 && threadIdx.x == 0)
+    ((unsigned long long*)table[(size_t)blockIdx.y * nslots + count_slot])[count_index] += 1ull;
 }
-hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s) {
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
+                       int count_slot, int count_index) {
   if (count <= 0 || batch <= 0) return hipSuccess;
   long long blocks = (count + 1023) / 1024;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value);
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value, count_slot,
+                     count_index);
   return hipGetLastError();
 }
 __global__ void fill_i32_kernel(void* const* table, int nslots, int slot, long long count, int value) {

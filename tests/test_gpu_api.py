@@ -362,3 +362,33 @@ def test_bounded_waits_of_the_single_launch_cholesky():
     assert gp.step(MU, ETA) == (0, -1)
     rep, _ = one_step_report(gp, 0, *before, gp.grad_as_f32(grads[0], True), MU, ETA)
     assert rep["X"] < 2e-2 and rep["M"] < 2e-2 and rep["orth"] < 1e-3, rep
+
+
+def test_captured_step_replays_like_eager_steps():
+    # A step only launches kernels (no allocation, no host synchronisation, no memset), so a caller may capture
+    # it into a HIP graph.  Each replay must give what the eager step gives, bit for bit, also for the
+    # single-launch Cholesky kernel whose flags are tagged with a launch counter (kept on the device).
+    import torch
+    shape = (1024, 768, 512)
+    eager = GpuProblem([shape], True, "bf16")
+    graphed = GpuProblem([shape], True, "bf16")
+    B = graphed.B
+    g0 = eager.grads_np(0)
+    eager.upload_grads(g0)
+    graphed.upload_grads(g0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.dion_step(graphed.state, graphed.X[0], graphed.G[0], graphed.M[0], graphed.Q[0], MU, ETA)
+    torch.cuda.synchronize()
+    for t in range(4):
+        eager.upload_grads(eager.grads_np(t))
+        graphed.G[0].copy_(eager.G[0])
+        assert eager.step(MU, ETA) == (0, -1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert B.dion_last_status(graphed.state) == (0, -1)
+        for u, v in zip(eager.host(0), graphed.host(0)):
+            assert np.array_equal(u, v), t
