@@ -13,6 +13,9 @@ the paper's future-work paragraph and of the library's interface:
     P = U (orthonormal left factor) R = W (right factor before ColNorm)
     mu = 1 - beta                   B = M + G (buffer after accumulation)
 
+lazy_dion_step / sym_power_iter1 follow the Lazy-Dion update rule of Section 5.1 (the
+paper's V, W, U keep their names there, since Q/R/P would clash with their roles above).
+
 Every function is pinned by tests that do not use the function itself (closed forms,
 a brute-force Jacobi SVD, LAPACK's QR, hand-computed tiny cases); nothing here is
 "parity unpinned".  Two conventions are ours because the paper is silent: the ColNorm
@@ -145,6 +148,60 @@ def dion_step(X, G, M, Q, mu, eta, method="householder"):
     O = P @ Q_new.T                                        # orthonormal update
     X_new = X - eta * np.sqrt(m / n) * O                   # scaled by sqrt(|I|/|J|)
     return dict(X=X_new, M=M_new, Q=Q_new, Z=Z, P=P, R=R, T=T, s=s, B=B, status=status)
+
+
+def sym_power_iter1(B, V, method="householder"):
+    """SymPowerIter1 of the faster-variants algorithm (Section 5.1): V <- Orthonormalize(B^T (B V)).
+    One step of orthogonal iteration on B^T B.  Returns (V_new, Y, T, status), Y = B^T B V."""
+    B = _f64(B)
+    V = _f64(V)
+    Y = B.T @ (B @ V)
+    V_new, T, status = orthonormalize(Y, method)
+    return V_new, Y, T, status
+
+
+def lazy_dion_step(X, G, M, V, mu, eta, refresh, method="householder"):
+    """One Lazy-Dion step (Section 5.1, unsharded Lazy-Dion update rule) for one m x n matrix.
+
+    B = M + G;  if refresh: V <- SymPowerIter1(B, V);  W = B V;  M_new = B - beta W V^T;
+    U = ColNorm(W);  X_new = X - eta sqrt(m/n) U V^T.   `refresh` is the caller's
+    "t mod k = 0".  Returns X, M, V (new state), the intermediates W, U, s and `status`
+    (STATUS_BREAKDOWN from the refresh leaves the state unchanged).
+    """
+    X = _f64(X)
+    m, n = X.shape
+    B = accumulate(M, G)
+    V = _f64(V)
+    status = STATUS_OK
+    if refresh:
+        V_new, _, _, status = sym_power_iter1(B, V, method)
+        if status != STATUS_OK:
+            return dict(X=X, M=_f64(M), V=V, W=None, U=None, s=None, B=B, status=status)
+        V = V_new
+    beta = 1.0 - mu
+    W = B @ V
+    M_new = B - beta * (W @ V.T)
+    U, s = col_norm(W)
+    X_new = X - eta * np.sqrt(m / n) * (U @ V.T)
+    return dict(X=X_new, M=M_new, V=V, W=W, U=U, s=s, B=B, status=status)
+
+
+def run_lazy_steps(X, grads, M, V, mu, eta, k, method="householder", store=np.float32, first_t=0):
+    """Lazy-Dion over len(grads) steps with a refresh whenever t mod k = 0 (t counts from first_t, so the
+    default refreshes at the very first step, which also makes the initial V orthonormal).  State rounded
+    to the storage dtype after each step."""
+    out = []
+    X = np.asarray(X, dtype=store)
+    M = np.asarray(M, dtype=store)
+    V = np.asarray(V, dtype=store)
+    for i, G in enumerate(grads):
+        res = lazy_dion_step(X, G, M, V, mu, eta, (first_t + i) % k == 0, method)
+        X = res["X"].astype(store)
+        M = res["M"].astype(store)
+        V = res["V"].astype(store)
+        res = dict(res, X=X, M=M, V=V)
+        out.append(res)
+    return out
 
 
 def init_state(m, n, Q_raw):
