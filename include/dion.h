@@ -91,6 +91,22 @@ int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* c
                       void* const* M, void* const* Q, const int64_t* m, const int64_t* n,
                       const int64_t* r, float mu, float eta, void* hip_stream);
 
+/* Lazy-Dion (Section 5.1, "Faster Dion with Lazy Orthonormalization", the Lazy-Dion update rule and its
+ * SymPowerIter1): the state is M and a right factor V (n x r, in the buffer the other calls name Q) that is
+ * only refreshed on the steps the caller chooses (the paper: every k-th step):
+ *     B = M + G
+ *     refresh != 0:  V <- Orthonormalize(B^T (B V))      (thin-QR factor, by Cholesky-QR on n x r)
+ *     W = B V;   M <- B - (1 - mu) W V^T;   X <- X - eta sqrt(m/n) ColNorm(W) V^T
+ * Without a refresh the step has no orthonormalisation at all (three products and a column normalisation).
+ * The update assumes V has orthonormal columns, so the first step after dion_init_state must refresh.
+ * A breakdown of the refresh is reported as for dion_step and leaves X, M, V untouched.  Arguments and
+ * conventions as for dion_step / dion_step_batched; the same state object serves both kinds of step. */
+int dion_lazy_step(dion_state_t* st, void* X, const void* G, void* M, void* V,
+                   int64_t m, int64_t n, int64_t r, float mu, float eta, int refresh, void* hip_stream);
+int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const void* const* G,
+                           void* const* M, void* const* V, const int64_t* m, const int64_t* n,
+                           const int64_t* r, float mu, float eta, int refresh, void* hip_stream);
+
 /* Waits for the stream of the last step and reports its numerical status: *status_out is
  * DION_OK or DION_NUM_BREAKDOWN; *first_bad_index is the lowest matrix index that broke
  * down (-1 if none).  Either pointer may be NULL. */
@@ -130,9 +146,9 @@ int dion_set_wait_limit(dion_state_t* st, unsigned polls);
  * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <
  * DION_STAGE_COUNT, the summed duration in milliseconds of that stage over the last call. */
 enum {
-  DION_STAGE_K1_BQ = 0,     /* Z = (M+G) Q */
-  DION_STAGE_ORTH = 1,      /* CholeskyQR2 */
-  DION_STAGE_K2_BTP = 2,    /* R = (M+G)^T P */
+  DION_STAGE_K1_BQ = 0,     /* Z = (M+G) Q          (Lazy-Dion: W = (M+G) V) */
+  DION_STAGE_ORTH = 1,      /* CholeskyQR2          (Lazy-Dion: the whole refresh, 0 without one) */
+  DION_STAGE_K2_BTP = 2,    /* R = (M+G)^T P        (Lazy-Dion: 0) */
   DION_STAGE_COLNORM = 3,   /* column norms of R and Q_new = R diag(d) */
   DION_STAGE_K5_UPDATE = 4, /* fused M and X update */
   DION_STAGE_COUNT = 5

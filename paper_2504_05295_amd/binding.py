@@ -26,7 +26,8 @@ DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DE
 
 DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 
-EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_last_status",
+EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
+           "dion_last_status",
            "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
@@ -56,6 +57,10 @@ def lib() -> C.CDLL:
                                         C.c_float, C.c_void_p]
         L.dion_retry_breakdowns.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
                                             C.c_float, C.c_void_p, C.POINTER(C.c_int)]
+        L.dion_lazy_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                     C.c_int64, C.c_float, C.c_float, C.c_int, C.c_void_p]
+        L.dion_lazy_step_batched.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
+                                             C.c_float, C.c_int, C.c_void_p]
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
@@ -192,6 +197,34 @@ def dion_step_batched(state: DionState, X: List, G: List, M: List, Q: List, mu: 
     _check(lib().dion_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(Q), _i64([s[0] for s in sh]),
                                    _i64([s[1] for s in sh]), _i64([s[2] for s in sh]), mu, eta, _stream(stream)),
            "dion_step_batched")
+
+
+def dion_lazy_step(state: DionState, X, G, M, V, mu: float, eta: float, refresh: bool, stream=None) -> None:
+    import torch
+    m, n = X.shape
+    r = V.shape[1]
+    _check_tensor(X, torch.float32, (m, n), "X")
+    _check_tensor(G, _g_dtype(state), (m, n), "G")
+    _check_tensor(M, torch.float32, (m, n), "M")
+    _check_tensor(V, torch.float32, (n, r), "V")
+    _check(lib().dion_lazy_step(state.handle, _ptr(X), _ptr(G), _ptr(M), _ptr(V), m, n, r, mu, eta, 1 if refresh else 0,
+                                _stream(stream)), "dion_lazy_step")
+
+
+def dion_lazy_step_batched(state: DionState, X: List, G: List, M: List, V: List, mu: float, eta: float, refresh: bool,
+                           stream=None) -> None:
+    import torch
+    count = len(X)
+    for i in range(count):
+        m, n, r = state.shapes[i]
+        _check_tensor(X[i], torch.float32, (m, n), "X[%d]" % i)
+        _check_tensor(G[i], _g_dtype(state), (m, n), "G[%d]" % i)
+        _check_tensor(M[i], torch.float32, (m, n), "M[%d]" % i)
+        _check_tensor(V[i], torch.float32, (n, r), "V[%d]" % i)
+    sh = state.shapes[:count]
+    _check(lib().dion_lazy_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(V),
+                                        _i64([s[0] for s in sh]), _i64([s[1] for s in sh]), _i64([s[2] for s in sh]),
+                                        mu, eta, 1 if refresh else 0, _stream(stream)), "dion_lazy_step_batched")
 
 
 def dion_retry_breakdowns(state: DionState, X: List, G: List, M: List, Q: List, mu: float, eta: float, stream=None) -> int:

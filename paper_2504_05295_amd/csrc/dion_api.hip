@@ -43,43 +43,54 @@ struct Carve {
   size_t off[NSLOTS];
   size_t total;
 };
+// How the Gram matrix of a rows x r matrix is split over the contraction (fixed at init: sizes workspace).
+struct GramPlan {
+  int variant, splitk, kps;   // fp32 path: tile variant, number of splits, rows per split
+  int splitk2;                // split-bf16 path on large tiles
+};
 struct Group {
   int64_t m, n, r;
   int rp;          // r rounded up to a multiple of CHOL_NB
   int first_row, count;
-  int gram_variant, gram_splitk, gram_kps;
-  int gram2_splitk;   // split-K of the split-bf16 Gram product (large-tile path)
+  GramPlan gram_m, gram_n;   // Gram products over the m x r matrices of a Dion step / the n x r ones of a Lazy-Dion refresh
   int k12_splitk;     // split-K of K1 / K2 on the large-tile path when their outputs have too few tiles
   size_t bytes_per_entry;
   Carve carve;     // slot offsets inside one matrix' share of the workspace
   size_t ws_off;   // offset of the group's first matrix in the workspace (set by dion_init_state)
 };
 
-constexpr int kEventsPerGroup = DION_STAGE_COUNT + 1;
+constexpr int kEventsPerGroup = 2 * DION_STAGE_COUNT;   // a start and an end event per stage
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 int padded_rank(int64_t r) { return (int)((r + CHOL_NB - 1) / CHOL_NB * CHOL_NB); }
 
-void plan_gram(Group& g) {
-  g.gram_variant = pick_variant(g.r, g.r, g.m, g.count, true);
-  const int bt = (g.gram_variant == VAR_BIG) ? 128 : 64;
-  const int bk = (g.gram_variant == VAR_BIG) ? 32 : 64;
+GramPlan plan_gram_rows(const Group& g, int64_t rows) {
+  GramPlan gp;
+  gp.variant = pick_variant(g.r, g.r, rows, g.count, true);
+  const int bt = (gp.variant == VAR_BIG) ? 128 : 64;
+  const int bk = (gp.variant == VAR_BIG) ? 32 : 64;
   const long long t1 = (g.r + bt - 1) / bt;
   const long long tiles = t1 * (t1 + 1) / 2 * g.count;
   long long want = (512 + tiles - 1) / tiles;
   if (want > 64) want = 64;
   if (want < 1) want = 1;
-  long long kps = (g.m + want - 1) / want;
+  long long kps = (rows + want - 1) / want;
   kps = (kps + 2 * bk - 1) / (2 * bk) * (2 * bk);
-  g.gram_kps = (int)kps;
-  g.gram_splitk = (int)((g.m + kps - 1) / kps);
+  gp.kps = (int)kps;
+  gp.splitk = (int)((rows + kps - 1) / kps);
   // large-tile path: 128x128 tiles, lower triangle only
   const long long t2 = (g.r + 127) / 128;
   long long want2 = (768 + t2 * (t2 + 1) / 2 * g.count - 1) / (t2 * (t2 + 1) / 2 * g.count);
   if (want2 > 32) want2 = 32;
   if (want2 < 1) want2 = 1;
-  g.gram2_splitk = (int)want2;
+  gp.splitk2 = (int)want2;
+  return gp;
+}
+
+void plan_gram(Group& g) {
+  g.gram_m = plan_gram_rows(g, g.m);
+  g.gram_n = plan_gram_rows(g, g.n);
   // K1 (m x r output) and K2 (n x r output) on 128x128 tiles: split the contraction until about 512 workgroups exist
   g.k12_splitk = 1;
   if (g.m % 256 == 0 && g.n % 256 == 0 && g.r % 128 == 0) {
@@ -98,26 +109,28 @@ Carve carve_entry(const Group& g) {
     pos += align_up(floats * sizeof(float), 256);
   };
   const size_t mr = (size_t)g.m * g.r, nr = (size_t)g.n * g.r, rr = (size_t)g.rp * g.rp;
+  // buffers of the orthonormalisation are sized for the taller of the m x r (Dion step) and n x r (Lazy-Dion refresh) inputs
+  const size_t xr = std::max(mr, nr);
   take(SLOT_Z, mr);
-  take(SLOT_P1, mr);
+  take(SLOT_P1, xr);
   take(SLOT_P, mr);
   take(SLOT_R, nr);
   take(SLOT_C, rr);
   take(SLOT_L, rr);
   take(SLOT_W, rr);
   take(SLOT_T, rr);
-  take(SLOT_CPART, rr * (size_t)std::max(g.gram_splitk, g.gram2_splitk));
-  take(SLOT_SPART, (size_t)((g.n + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
+  take(SLOT_CPART, rr * (size_t)std::max(std::max(g.gram_m.splitk, g.gram_m.splitk2), std::max(g.gram_n.splitk, g.gram_n.splitk2)));
+  take(SLOT_SPART, (size_t)((std::max(g.m, g.n) + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
   // bf16 operand copies (two bf16 values per float slot)
   take(SLOT_QT16, (nr + 1) / 2);
-  take(SLOT_P16, (mr + 1) / 2);
-  take(SLOT_PT16, (mr + 1) / 2);
+  take(SLOT_P16, (xr + 1) / 2);
+  take(SLOT_PT16, (xr + 1) / 2);
   take(SLOT_R16, (nr + 1) / 2);
   take(SLOT_Q16, (nr + 1) / 2);
-  take(SLOT_ZL16, (mr + 1) / 2);
-  take(SLOT_ZLT16, (mr + 1) / 2);
+  take(SLOT_ZL16, (xr + 1) / 2);
+  take(SLOT_ZLT16, (xr + 1) / 2);
   take(SLOT_WH16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_EPART, 256);
@@ -225,34 +238,34 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
   return o;
 }
 
-// One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices starting at
-// table row `row0` of group g.
+// One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices of `rows` x r starting at
+// table row `row0` of group g (rows = m in a Dion step, n in a Lazy-Dion refresh; gp is the matching plan).
 // With `split` the two large products run on the bf16 matrix pipe with split operands (x = hi + lo,
 // three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
 // Cholesky factorisation and the triangular inverse stay in fp32.
-int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in, int slot_out, float piv_lo, float piv_hi,
-                bool split, bool adaptive, float shift_rel, hipStream_t s) {
+int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long rows, const GramPlan& gp, int slot_in,
+                int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
   GemmArgs base = rebase(base_args(st, g), row0);
   // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
   if (split) {
-    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, g.m, r, SLOT_P16, SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
     GemmArgs a = base;
-    a.M = r; a.N = r; a.K = 3 * (int)g.m;
-    a.nseg = 3; a.kseg = (int)g.m;
+    a.M = r; a.N = r; a.K = 3 * (int)rows;
+    a.nseg = 3; a.kseg = (int)rows;
     a.segA[0] = SLOT_PT16; a.segB[0] = SLOT_PT16;
     a.segA[1] = SLOT_PT16; a.segB[1] = SLOT_ZLT16;
     a.segA[2] = SLOT_ZLT16; a.segB[2] = SLOT_PT16;
-    a.A = opnd(SLOT_PT16, 0, g.m);
-    a.B = opnd(SLOT_PT16, 0, g.m);
+    a.A = opnd(SLOT_PT16, 0, rows);
+    a.B = opnd(SLOT_PT16, 0, rows);
     a.lower_only = 1;
     // 256x256 tiles when the lower triangle of such tiles alone fills the GPU (large batches), else 128x128 + split-K
     const long long t256 = r / 256;
-    const bool gram_big = r % 256 == 0 && g.m % 64 == 0 && t256 * (t256 + 1) / 2 * batch >= 256;
+    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && t256 * (t256 + 1) / 2 * batch >= 256;
     const int gcfg = gram_big ? G2_256x256 : G2_128x128;
-    a.splitk = gram_big ? 1 : g.gram2_splitk;
+    a.splitk = gram_big ? 1 : gp.splitk2;
     const int eff = gemm2_nt_splitk(gcfg, a);
     a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
@@ -261,17 +274,17 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
     if (eff > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, eff, rr, s));
   } else {
     GemmArgs a = base;
-    a.M = r; a.N = r; a.K = (int)g.m;
+    a.M = r; a.N = r; a.K = (int)rows;
     a.A = opnd(slot_in, 0, r);
     a.B = opnd(slot_in, 0, r);
     a.lower_only = 1;
-    a.splitk = g.gram_splitk;
-    a.k_per_split = g.gram_kps;
-    a.E.slot = (g.gram_splitk > 1) ? SLOT_CPART : SLOT_C;
+    a.splitk = gp.splitk;
+    a.k_per_split = gp.kps;
+    a.E.slot = (gp.splitk > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
     a.E.split_stride = rr;
-    HIPCHK(gemm_f32_tn(g.gram_variant, a, batch, s));
-    if (g.gram_splitk > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, g.gram_splitk, rr, s));
+    HIPCHK(gemm_f32_tn(gp.variant, a, batch, s));
+    if (gp.splitk > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, gp.splitk, rr, s));
   }
   if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
@@ -362,7 +375,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   if (split) {
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
-    a.M = (int)g.m; a.N = r; a.K = 3 * r;
+    a.M = (int)rows; a.N = r; a.K = 3 * r;
     a.nseg = 3; a.kseg = r;
     a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;
     a.segA[1] = SLOT_P16; a.segB[1] = SLOT_WL16;
@@ -372,11 +385,11 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
     a.tri_k = 1;
     a.E.slot = slot_out; a.E.ld = r;
     a.xcd_remap = 1;
-    const int cfg = (g.m % 256 == 0 && r % 256 == 0 && (g.m / 256) * (r / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
+    const int cfg = (rows % 256 == 0 && r % 256 == 0 && (rows / 256) * (r / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
     HIPCHK(gemm2_nt(cfg, a, batch, s));
   } else {
     GemmArgs a = base;  // out = in W^T   (= in L^-T)
-    a.M = (int)g.m; a.N = r; a.K = r;
+    a.M = (int)rows; a.N = r; a.K = r;
     a.A = opnd(slot_in, 0, r);
     a.B = opnd(SLOT_W, 0, rp);
     a.E.slot = slot_out; a.E.ld = r;
@@ -386,126 +399,216 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, int slot_in
   return DION_OK;
 }
 
-int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
-  const Group& g = st->groups[gi];
-  void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
-  const bool bf16 = st->math == DION_MATH_BF16, gbf16 = st->g_dtype == DION_G_BF16;
+// What the stages of a step share: the matrices [row0, row0 + batch) of one shape group.
+struct RowCtx {
+  dion_state* st;
+  const Group* g;
+  int gi, row0, batch;
+  void* const* tab;
+  bool bf16, gbf16;
+  bool big;   // large-tile bf16 kernels: need tile-aligned shapes and bf16 copies of the small operands
+  GemmArgs base;
+  hipEvent_t* ev;   // start / end event per stage, or nullptr
+  hipStream_t s;
+};
+
+RowCtx make_ctx(dion_state* st, int gi, int row0, int batch, hipStream_t s) {
+  RowCtx c;
+  c.st = st; c.g = &st->groups[gi]; c.gi = gi; c.row0 = row0; c.batch = batch; c.s = s;
+  c.tab = st->table + (size_t)(c.g->first_row + row0) * NSLOTS;
+  c.bf16 = st->math == DION_MATH_BF16;
+  c.gbf16 = st->g_dtype == DION_G_BF16;
+  c.big = c.bf16 && c.g->m % 256 == 0 && c.g->n % 256 == 0 && c.g->r % 128 == 0;
+  c.base = rebase(base_args(st, *c.g), row0);
+  c.ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
+  return c;
+}
+int mark(const RowCtx& c, int stage, int end) {
+  if (c.ev) HIPCHK(hipEventRecord(c.ev[2 * stage + end], c.s));
+  return DION_OK;
+}
+int tile_cfg2(const RowCtx& c, long long Mo, long long No) {
+  return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * c.batch >= 128) ? G2_256x256 : G2_128x128;
+}
+
+// K1: Z = (M+G) Q with Q (n x r) taken from SLOT_Q
+int stage_k1(const RowCtx& c) {
+  const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
-  GemmArgs base = rebase(base_args(st, g), row0);
-  hipEvent_t* ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
-  HIPCHK(launch_fill_i32(tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
-  if (ev) { HIPCHK(hipEventRecord(ev[0], s)); st->group_timed[gi] = 1; }
-  // Large-tile bf16 kernels need tile-aligned shapes and bf16 copies of the small operands.
-  const bool big = bf16 && m % 256 == 0 && n % 256 == 0 && r % 128 == 0;
-  auto cfg2 = [&](long long Mo, long long No) {
-    return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
-  };
-  if (big) {
-    HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_Q, -1, SLOT_QT16, n, r, s));
-    GemmArgs a = base;  // K1: Z = (M+G) Q
-    a.M = m; a.N = r; a.K = n;
-    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+  GemmArgs a = c.base;
+  a.M = m; a.N = r; a.K = n;
+  a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+  a.E.slot = SLOT_Z; a.E.ld = r;
+  a.xcd_remap = 1;
+  if (c.big) {
+    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, SLOT_Q, -1, SLOT_QT16, n, r, c.s));
     a.B = opnd(SLOT_QT16, 0, n);
-    a.E.slot = SLOT_Z; a.E.ld = r;
-    a.xcd_remap = 1;
-    const int c1 = cfg2(m, r);
+    const int c1 = tile_cfg2(c, m, r);
     if (c1 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)m * r;
       const int eff = gemm2_k1_splitk(c1, a);
-      HIPCHK(gemm2_k1(c1, gbf16, a, batch, s));
-      HIPCHK(launch_sum_partials(tab, NSLOTS, batch, SLOT_KPART, SLOT_Z, (long long)m * r, eff, s));
+      HIPCHK(gemm2_k1(c1, c.gbf16, a, c.batch, c.s));
+      HIPCHK(launch_sum_partials(c.tab, NSLOTS, c.batch, SLOT_KPART, SLOT_Z, (long long)m * r, eff, c.s));
     } else {
-      HIPCHK(gemm2_k1(c1, gbf16, a, batch, s));
+      HIPCHK(gemm2_k1(c1, c.gbf16, a, c.batch, c.s));
     }
   } else {
-    GemmArgs a = base;  // K1: Z = (M+G) Q
-    a.M = m; a.N = r; a.K = n;
-    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
     a.B = opnd(SLOT_Q, 0, r);
-    a.E.slot = SLOT_Z; a.E.ld = r;
-    a.xcd_remap = 1;
-    HIPCHK(gemm_k1(pick_variant(m, r, n, batch, true), bf16, gbf16, a, batch, s));
+    HIPCHK(gemm_k1(pick_variant(m, r, n, c.batch, true), c.bf16, c.gbf16, a, c.batch, c.s));
   }
-  if (ev) HIPCHK(hipEventRecord(ev[1], s));
-  {
-    // pass 1: any positive finite pivot; pass 2: the Gram matrix of a nearly orthonormal P1 has pivots near 1
-    int rc;
-    if (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) {
-      // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
-      // leaves a factor with a condition number of a few hundred), then CholeskyQR2 on that.  The product of
-      // the three triangular factors is still the QR factor.  Z's buffer is reused for the middle result.
-      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, 1e-5f, s);
-      if (rc != DION_OK) return rc;
-      rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_Z, 0.f, 3.0e38f, big, false, 0.f, s);
-      if (rc != DION_OK) return rc;
-      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P, 0.1f, 10.f, big, true, 0.f, s);
-    } else {
-      rc = cholqr_pass(st, g, row0, batch, SLOT_Z, SLOT_P1, 0.f, 3.0e38f, big, false, 0.f, s);
-      if (rc != DION_OK) return rc;
-      rc = cholqr_pass(st, g, row0, batch, SLOT_P1, SLOT_P, 0.1f, 10.f, big, true, 0.f, s);
-    }
-    if (rc != DION_OK) return rc;
-  }
-  if (big) HIPCHK(launch_convert_bf16(tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
-  if (ev) HIPCHK(hipEventRecord(ev[2], s));
-  if (big) {
-    GemmArgs a = base;  // K2: R = (M+G)^T P
-    a.M = n; a.N = r; a.K = m;
-    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+  return DION_OK;
+}
+
+// K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile path, its bf16 transpose in SLOT_PT16
+int stage_k2(const RowCtx& c, int slot_p) {
+  const Group& g = *c.g;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  GemmArgs a = c.base;
+  a.M = n; a.N = r; a.K = m;
+  a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
+  a.E.slot = SLOT_R; a.E.ld = r;
+  a.xcd_remap = 1;
+  if (c.big) {
     a.B = opnd(SLOT_PT16, 0, m);
-    a.E.slot = SLOT_R; a.E.ld = r;
-    a.xcd_remap = 1;
-    const int c2 = cfg2(n, r);
+    const int c2 = tile_cfg2(c, n, r);
     if (c2 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)n * r;
       const int eff = gemm2_k2_splitk(c2, a);
-      HIPCHK(gemm2_k2(c2, gbf16, a, batch, s));
-      HIPCHK(launch_sum_partials(tab, NSLOTS, batch, SLOT_KPART, SLOT_R, (long long)n * r, eff, s));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s));
+      HIPCHK(launch_sum_partials(c.tab, NSLOTS, c.batch, SLOT_KPART, SLOT_R, (long long)n * r, eff, c.s));
     } else {
-      HIPCHK(gemm2_k2(c2, gbf16, a, batch, s));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s));
     }
   } else {
-    GemmArgs a = base;  // K2: R = (M+G)^T P
-    a.M = n; a.N = r; a.K = m;
-    a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
-    a.B = opnd(SLOT_P, 0, r);
-    a.E.slot = SLOT_R; a.E.ld = r;
-    a.xcd_remap = 1;
-    HIPCHK(gemm_k2(pick_variant(n, r, m, batch, true), bf16, gbf16, a, batch, s));
+    a.B = opnd(slot_p, 0, r);
+    HIPCHK(gemm_k2(pick_variant(n, r, m, c.batch, true), c.bf16, c.gbf16, a, c.batch, c.s));
   }
-  if (ev) HIPCHK(hipEventRecord(ev[3], s));
-  HIPCHK(launch_colnorm(tab, NSLOTS, batch, SLOT_R, n, r, s));
-  HIPCHK(launch_scale_cols(tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, big ? SLOT_Q16 : -1, big ? SLOT_R16 : -1, s));
-  if (ev) HIPCHK(hipEventRecord(ev[4], s));
-  if (big) {
-    GemmArgs a = base;  // K5: fused M and X update
-    a.M = m; a.N = n; a.K = r;
-    a.A = opnd(SLOT_P16, 0, r);
-    a.B = opnd(SLOT_R16, 0, r);
-    a.B2 = opnd(SLOT_Q16, 0, r);
-    a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
-    a.E.c_m = 1.0f - mu;
-    a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
-    a.status_slot = SLOT_STATUS;
+  return DION_OK;
+}
+
+// Orthonormalisation of the rows x r matrices in slot_a; slot_b is a second buffer of that size.  The result
+// ends up in slot_final (CholeskyQR2: a -> b -> final, so final may be a; shifted CholeskyQR3: a -> b -> a ->
+// final, so final must not be a).
+int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final) {
+  dion_state* st = c.st;
+  const Group& g = *c.g;
+  int rc;
+  // first pass: any positive finite pivot; last pass: the Gram matrix of a nearly orthonormal input has pivots near 1
+  if (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) {
+    // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
+    // leaves a factor with a condition number of a few hundred), then CholeskyQR2 on that.  The product of
+    // the three triangular factors is still the QR factor.
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 1e-5f, c.s);
+    if (rc != DION_OK) return rc;
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_a, 0.f, 3.0e38f, c.big, false, 0.f, c.s);
+    if (rc != DION_OK) return rc;
+    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_final, 0.1f, 10.f, c.big, true, 0.f, c.s);
+  }
+  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 0.f, c.s);
+  if (rc != DION_OK) return rc;
+  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_final, 0.1f, 10.f, c.big, true, 0.f, c.s);
+}
+
+// K5: M <- (M+G) - (1-mu) A B^T and X <- X - eta sqrt(m/n) A B2^T in one pass (A: m x r, B and B2: n x r).
+// Large-tile path: bf16 operands from the *16 slots; otherwise fp32 operands from the *32 slots.
+int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int b2_32, float mu, float eta) {
+  const Group& g = *c.g;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  GemmArgs a = c.base;
+  a.M = m; a.N = n; a.K = r;
+  a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
+  a.E.c_m = 1.0f - mu;
+  a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
+  a.status_slot = SLOT_STATUS;
+  if (c.big) {
+    a.A = opnd(a16, 0, r);
+    a.B = opnd(b16, 0, r);
+    a.B2 = opnd(b2_16, 0, r);
     a.xcd_remap = 1;
-    // keep about 2.5 MB of R / Q_new column panels (128 rows x r, two bf16 matrices) resident in an XCD's L2
+    // keep about 2.5 MB of the two n x r column panels (128 rows x r, two bf16 matrices) resident in an XCD's L2
     // (only worth it when at least four panels fit; for larger r the row-major tile order measured faster)
     a.group_n = (int)(2621440LL / (128LL * r * 4));
     if (a.group_n < 4) a.group_n = 0;
-    HIPCHK(gemm2_k5(G2_256x256, gbf16, a, batch, s));
+    HIPCHK(gemm2_k5(G2_256x256, c.gbf16, a, c.batch, c.s));
   } else {
-    GemmArgs a = base;  // K5: fused M and X update
-    a.M = m; a.N = n; a.K = r;
-    a.A = opnd(SLOT_P, 0, r);
-    a.B = opnd(SLOT_R, 0, r);
-    a.B2 = opnd(SLOT_Q, 0, r);
-    a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
-    a.E.c_m = 1.0f - mu;
-    a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
-    a.status_slot = SLOT_STATUS;
-    HIPCHK(gemm_k5(pick_variant(m, n, r, batch, true), bf16, gbf16, a, batch, s));
+    a.A = opnd(a32, 0, r);
+    a.B = opnd(b32, 0, r);
+    a.B2 = opnd(b2_32, 0, r);
+    HIPCHK(gemm_k5(pick_variant(m, n, r, c.batch, true), c.bf16, c.gbf16, a, c.batch, c.s));
   }
-  if (ev) HIPCHK(hipEventRecord(ev[5], s));
+  return DION_OK;
+}
+
+#define STAGECHK(expr)            \
+  do {                            \
+    int rc_ = (expr);             \
+    if (rc_ != DION_OK) return rc_; \
+  } while (0)
+
+// One Dion step (Algorithm 1 with the unsharded update rule) for the matrices of one shape group.
+int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
+  const RowCtx c = make_ctx(st, gi, row0, batch, s);
+  const Group& g = *c.g;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  if (c.ev) st->group_timed[gi] = 1;
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
+  STAGECHK(stage_k1(c));
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
+  STAGECHK(mark(c, DION_STAGE_ORTH, 0));
+  STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P));
+  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
+  STAGECHK(mark(c, DION_STAGE_ORTH, 1));
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
+  STAGECHK(stage_k2(c, SLOT_P));
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
+  HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_R, n, r, s));
+  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));
+  STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_P, SLOT_R, SLOT_Q, mu, eta));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 1));
+  return DION_OK;
+}
+
+// One Lazy-Dion step (Section 5.1) for the matrices of one shape group; the caller's Q buffer holds V.
+//   refresh:  V <- Orthonormalize(B^T (B V))                 (SymPowerIter1; K1, K2 and the orthonormalisation on n x r)
+//   always:   W = B V;  M <- B - (1-mu) W V^T;  X <- X - eta sqrt(m/n) ColNorm(W) V^T
+// ColNorm(W) V^T = W (V diag(d))^T with d_j = 1 / (||W_j|| + eps), so the fused update kernel of the Dion step
+// serves unchanged with A = W, B = V, B2 = V diag(d).
+int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, bool refresh, hipStream_t s) {
+  const RowCtx c = make_ctx(st, gi, row0, batch, s);
+  const Group& g = *c.g;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  if (c.ev) st->group_timed[gi] = 1;
+  // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
+  STAGECHK(mark(c, DION_STAGE_ORTH, 0));
+  if (refresh) {
+    STAGECHK(stage_k1(c));                                                        // Z = B V
+    if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, -1, SLOT_PT16, m, r, s));
+    STAGECHK(stage_k2(c, SLOT_Z));                                                // R = B^T Z
+    const int fin = (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) ? SLOT_P1 : SLOT_R;
+    STAGECHK(stage_orth(c, g.n, g.gram_n, SLOT_R, SLOT_P1, fin));
+    // V is state: it only changes when the factorisation succeeded
+    HIPCHK(launch_copy_gated(c.tab, NSLOTS, batch, fin, SLOT_Q, (long long)n * r, SLOT_STATUS, s));
+  }
+  STAGECHK(mark(c, DION_STAGE_ORTH, 1));
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
+  STAGECHK(stage_k1(c));                                                          // W = B V
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
+  HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_Z, m, r, s));                  // d from the columns of W
+  // R <- V diag(d) (fp32), with bf16 copies of it and of V for the large-tile update kernel
+  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_Q, SLOT_R, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
+  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, SLOT_P16, -1, m, r, s));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));
+  STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_Z, SLOT_Q, SLOT_R, mu, eta));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 1));
   return DION_OK;
 }
 
@@ -671,6 +774,54 @@ int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q, int64_
   return step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
 }
 
+int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M, void* const* V,
+                           const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta, int refresh,
+                           void* hip_stream) {
+  if (!st || count < 0) return DION_EINVAL;
+  if (count == 0) return DION_OK;
+  if (!batch_args_ok(st, count, X, G, M, V, m, n, r, mu, eta)) return DION_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  st->last_stream = s;
+  std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
+  try {
+    std::vector<void*> xs(count), ms(count), qs(count);
+    std::vector<const void*> gs(count);
+    for (int i = 0; i < count; ++i) {
+      const int row = st->entries[i].row;
+      xs[row] = X[i]; gs[row] = G[i]; ms[row] = M[i]; qs[row] = V[i];
+    }
+    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+  } catch (const std::bad_alloc&) {
+    return DION_ENOMEM;
+  }
+  for (size_t gi = 0; gi < st->groups.size(); ++gi) {
+    int rc = lazy_rows(st, (int)gi, 0, st->groups[gi].count, mu, eta, refresh != 0, s);
+    if (rc != DION_OK) return rc;
+  }
+  return DION_OK;
+}
+
+int dion_lazy_step(dion_state_t* st, void* X, const void* G, void* M, void* V, int64_t m, int64_t n, int64_t r, float mu,
+                   float eta, int refresh, void* hip_stream) {
+  if (!st || !coeffs_ok(mu, eta)) return DION_EINVAL;
+  if (!aligned16(X) || !aligned16(G) || !aligned16(M) || !aligned16(V)) return DION_EINVAL;
+  int idx = -1;
+  for (int i = 0; i < st->count && idx < 0; ++i)
+    if (st->entries[i].m == m && st->entries[i].n == n && st->entries[i].r == r) idx = i;
+  if (idx < 0) return DION_EINVAL;
+  const Entry& e = st->entries[idx];
+  const Group& g = st->groups[e.group];
+  hipStream_t s = (hipStream_t)hip_stream;
+  st->last_stream = s;
+  std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
+  void* xs[1] = {X};
+  const void* gs[1] = {G};
+  void* ms[1] = {M};
+  void* qs[1] = {V};
+  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
+  return lazy_rows(st, e.group, e.row - g.first_row, 1, mu, eta, refresh != 0, s);
+}
+
 int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M,
                           void* const* Q, const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta,
                           void* hip_stream, int* retried_out) {
@@ -767,7 +918,7 @@ int dion_stage_times(dion_state_t* st, float* ms_out) {
     hipEvent_t* ev = &st->events[gi * kEventsPerGroup];
     for (int sidx = 0; sidx < DION_STAGE_COUNT; ++sidx) {
       float ms = 0.f;
-      HIPCHK(hipEventElapsedTime(&ms, ev[sidx], ev[sidx + 1]));
+      HIPCHK(hipEventElapsedTime(&ms, ev[2 * sidx], ev[2 * sidx + 1]));
       ms_out[sidx] += ms;
     }
   }

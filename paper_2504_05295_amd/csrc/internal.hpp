@@ -79,6 +79,9 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
 // count_slot >= 0: also adds one to the 64-bit word number count_index of that slot (a launch counter kept on the device)
 hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
                        int count_slot = -1, int count_index = 0);
+// out <- in unless *status != 0 (both 16-byte aligned)
+hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
+                             hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
 hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s);

@@ -52,6 +52,26 @@ hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long
                      count_index);
   return hipGetLastError();
 }
+// out <- in (count floats, a multiple of 4) unless the matrix' status word says that the step has failed
+__global__ void copy_gated_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long count, int status_slot) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  if (status_slot >= 0 && *(const int*)tab[status_slot] != 0) return;
+  const f32x4_t* in = (const f32x4_t*)tab[slot_in];
+  f32x4_t* out = (f32x4_t*)tab[slot_out];
+  const long long n4 = count >> 2;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) out[i] = in[i];
+  if (blockIdx.x == 0 && threadIdx.x < (count & 3)) ((float*)out)[n4 * 4 + threadIdx.x] = ((const float*)in)[n4 * 4 + threadIdx.x];
+}
+hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
+                             hipStream_t s) {
+  if (count <= 0 || batch <= 0) return hipSuccess;
+  long long blocks = (count / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(copy_gated_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_in, slot_out, count,
+                     status_slot);
+  return hipGetLastError();
+}
 __global__ void fill_i32_kernel(void* const* table, int nslots, int slot, long long count, int value) {
   int* p = (int*)table[(size_t)blockIdx.y * nslots + slot];
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long long)gridDim.x * blockDim.x)

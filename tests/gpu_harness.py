@@ -65,6 +65,16 @@ class GpuProblem:
             B.dion_step(self.state, self.X[0], self.G[0], self.M[0], self.Q[0], mu, eta)
         return B.dion_last_status(self.state)
 
+    def lazy_step(self, mu, eta, refresh, batched=None):
+        B = self.B
+        if batched is None:
+            batched = len(self.shapes) > 1
+        if batched:
+            B.dion_lazy_step_batched(self.state, self.X, self.G, self.M, self.Q, mu, eta, refresh)
+        else:
+            B.dion_lazy_step(self.state, self.X[0], self.G[0], self.M[0], self.Q[0], mu, eta, refresh)
+        return B.dion_last_status(self.state)
+
     def host(self, i=0):
         return (self.X[i].cpu().numpy(), self.M[i].cpu().numpy(), self.Q[i].cpu().numpy())
 
