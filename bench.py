@@ -102,13 +102,20 @@ def build_problem(cfg, seed=0, n_grads=2):
 def do_step(p, t):
     B = p["B"]
     ng = len(p["G"][0])
-    if len(p["shapes"]) == 1:
+    if p.get("variant") == "lazy":
+        refresh = t % p["refresh_every"] == 0
+        if len(p["shapes"]) == 1:
+            B.dion_lazy_step(p["state"], p["X"][0], p["G"][0][t % ng], p["M"][0], p["Q"][0], inputs.MU, inputs.ETA, refresh)
+        else:
+            B.dion_lazy_step_batched(p["state"], p["X"], [g[t % ng] for g in p["G"]], p["M"], p["Q"], inputs.MU, inputs.ETA,
+                                     refresh)
+    elif len(p["shapes"]) == 1:
         B.dion_step(p["state"], p["X"][0], p["G"][0][t % ng], p["M"][0], p["Q"][0], inputs.MU, inputs.ETA)
     else:
         B.dion_step_batched(p["state"], p["X"], [g[t % ng] for g in p["G"]], p["M"], p["Q"], inputs.MU, inputs.ETA)
 
 
-def cpu_baseline(cfg, p, budget_s=30.0):
+def cpu_baseline(cfg, p, budget_s=30.0, variant="dion", refresh_every=1):
     """Times the CPU oracle (as it stands, fp64 numpy) on a bounded sample of the workload."""
     from oracle import dion_oracle as orc
     shapes = cfg["shapes"]
@@ -133,12 +140,17 @@ def cpu_baseline(cfg, p, budget_s=30.0):
     # repeat the step (state carried on) until about 10 s of CPU work have been measured
     X0, steps_done, t0 = x, 0, time.perf_counter()
     while True:
-        res = orc.dion_step(X0, g32, M0, Q0, inputs.MU, inputs.ETA, method="lapack")
-        assert res["status"] == 0
-        X0, M0, Q0 = res["X"], res["M"], res["Q"]
+        if variant == "lazy":
+            res = orc.lazy_dion_step(X0, g32, M0, Q0, inputs.MU, inputs.ETA, steps_done % refresh_every == 0, method="lapack")
+            assert res["status"] == 0
+            X0, M0, Q0 = res["X"], res["M"], res["V"]
+        else:
+            res = orc.dion_step(X0, g32, M0, Q0, inputs.MU, inputs.ETA, method="lapack")
+            assert res["status"] == 0
+            X0, M0, Q0 = res["X"], res["M"], res["Q"]
         steps_done += 1
         dt = time.perf_counter() - t0
-        if dt >= 10.0 or steps_done >= 8:
+        if (dt >= 10.0 and steps_done % refresh_every == 0) or steps_done >= 8 * refresh_every:
             break
     sample += " (%d step%s timed)" % (steps_done, "" if steps_done == 1 else "s")
     dt /= steps_done
@@ -164,6 +176,9 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3a", choices=sorted(inputs.CONFIGS))
+    ap.add_argument("--variant", default="dion", choices=["dion", "lazy"],
+                    help="dion: the Dion step (default); lazy: Lazy-Dion with a refresh every --refresh-every steps")
+    ap.add_argument("--refresh-every", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -178,6 +193,12 @@ def main():
         sys.exit(2)
     cfg = inputs.CONFIGS[args.workload]
     p = build_problem(cfg)
+    p["variant"], p["refresh_every"] = args.variant, max(1, args.refresh_every)
+    if args.variant == "lazy":
+        # the first step must refresh (V starts column-normalised, not orthonormal); time whole refresh periods
+        args.warmup = max(1, args.warmup)
+        args.warmup += (-args.warmup) % p["refresh_every"]
+        args.steps += (-args.steps) % p["refresh_every"]
     B = p["B"]
     for t in range(args.warmup):
         do_step(p, t)
@@ -229,19 +250,21 @@ def main():
                                tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
     dominant = max(rooflines, key=lambda k: rooflines[k]["ms"]) if rooflines else None
     out = {
-        "metric": "ms per Dion step per m x n matrix at rank r",
+        "metric": "ms per Dion step per m x n matrix at rank r" if args.variant == "dion"
+                  else "ms per Lazy-Dion step per m x n matrix at rank r (refresh every %d steps)" % p["refresh_every"],
         "value": ms_per_step, "unit": "ms/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["math"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.workload], "matrices": len(cfg["shapes"]),
                    "shape": list(cfg["shapes"][0]) if len(set(cfg["shapes"])) == 1 else "mixed",
-                   "mu": inputs.MU, "eta": inputs.ETA, "g_dtype": "bf16" if cfg["g_bf16"] else "f32"},
+                   "mu": inputs.MU, "eta": inputs.ETA, "g_dtype": "bf16" if cfg["g_bf16"] else "f32",
+                   "variant": args.variant},
         "stage_ms": stages,
         "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
         "rooflines": rooflines,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, p)
+        out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=p["refresh_every"])
     print(json.dumps(out))
 
 
