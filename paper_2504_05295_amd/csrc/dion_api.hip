@@ -225,6 +225,7 @@ GemmArgs base_args(const dion_state* st, const Group& g) {
   a.splitk = 1;
   a.sub_count = 1;
   a.status_slot = -1;
+  a.fast_slot = a.fast_b_slot = a.fast_addend_slot = -1;
   a.E.alpha = 1.f;
   return a;
 }
@@ -295,7 +296,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
   // factorisation, otherwise they return at once.
   const int skip = adaptive ? SLOT_FAST : -1;
-  if (adaptive) HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, s));
+  if (adaptive) HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? SLOT_WH16 : -1, s));
   base.status_slot = skip;
   // blocked right-looking Cholesky, one fused launch per 64-wide panel.  The kernel gets the addresses of
   // its buffers as arguments: a look-up in the pointer table would cost it one more memory round trip.
@@ -373,8 +374,11 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   base.status_slot = -1;
   if (split) {
-    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s));
+    // (with the first-order factor W = I - Phi the kernel above has left Phi in SLOT_WH16 and the product below
+    // shrinks to out = in - hi(in) Phi^T: Phi is below 1e-3, so its bf16 rounding costs less than 4e-6 relative)
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s, skip));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
+    if (adaptive) { a.fast_slot = SLOT_FAST; a.fast_b_slot = SLOT_WH16; a.fast_addend_slot = slot_in; }
     a.M = (int)rows; a.N = r; a.K = 3 * r;
     a.nseg = 3; a.kseg = r;
     a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;
@@ -529,7 +533,10 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
     // (only worth it when at least four panels fit; for larger r the row-major tile order measured faster)
     a.group_n = (int)(2621440LL / (128LL * r * 4));
     if (a.group_n < 4) a.group_n = 0;
-    HIPCHK(gemm2_k5(G2_256x256, c.gbf16, a, c.batch, c.s));
+    // short contractions spend a large share of the time in the epilogue, where nothing multiplies: 128x128 tiles
+    // put two workgroups on a compute unit, so that one can multiply while the other streams M, G and X
+    // (measured: 11 % faster at r = 512, 2 % at r = 1024, 5 % slower at r = 2048)
+    HIPCHK(gemm2_k5(r <= 1024 ? G2_128x128 : G2_256x256, c.gbf16, a, c.batch, c.s));
   } else {
     a.A = opnd(a32, 0, r);
     a.B = opnd(b32, 0, r);

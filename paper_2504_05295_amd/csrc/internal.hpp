@@ -99,7 +99,8 @@ hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot
 // fp32 [rows][cols] (leading dimension ld_in) -> split bf16 x = hi + lo: plain copies [rows][cols] and transposed
 // copies [cols][rows]; any output slot may be -1.  rows and cols must be multiples of 64.
 hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot_in, long long ld_in, long long rows,
-                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s);
+                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s,
+                             int skip_slot = -1);   // skip_slot >= 0: nothing happens for matrices whose int32 there is non-zero
 hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
                                long long rows, long long cols, hipStream_t s);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
@@ -137,6 +138,8 @@ hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
 // identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
 // Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
-hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, hipStream_t s);
+// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well.
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
+                                      hipStream_t s);
 
 }  // namespace dion

@@ -293,8 +293,9 @@ hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int sl
 // 16 mantissa bits on the bf16 matrix pipe.
 __global__ void __launch_bounds__(256) split_bf16_kernel(void* const* table, int nslots, int slot_in, long long ld_in,
                                                          long long rows, long long cols, int slot_hi, int slot_lo,
-                                                         int slot_hiT, int slot_loT) {
+                                                         int slot_hiT, int slot_loT, int skip_slot) {
   void* const* tab = table + (size_t)blockIdx.z * nslots;
+  if (skip_slot >= 0 && *(const int*)tab[skip_slot] != 0) return;
   const float* in = (const float*)tab[slot_in];
   uint16_t* hi = slot_hi >= 0 ? (uint16_t*)tab[slot_hi] : nullptr;
   uint16_t* lo = slot_lo >= 0 ? (uint16_t*)tab[slot_lo] : nullptr;
@@ -328,10 +329,10 @@ __global__ void __launch_bounds__(256) split_bf16_kernel(void* const* table, int
   }
 }
 hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot_in, long long ld_in, long long rows,
-                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s) {
+                             long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s, int skip_slot) {
   if (rows % 64 || cols % 64 || ld_in % 4) return hipErrorInvalidValue;
   hipLaunchKernelGGL(split_bf16_kernel, dim3((unsigned)(cols / 64), (unsigned)(rows / 64), batch), dim3(256), 0, s, table, nslots,
-                     slot_in, ld_in, rows, cols, slot_hi, slot_lo, slot_hiT, slot_loT);
+                     slot_in, ld_in, rows, cols, slot_hi, slot_lo, slot_hiT, slot_loT, skip_slot);
   return hipGetLastError();
 }
 
@@ -355,7 +356,8 @@ __global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, in
   }
   if (threadIdx.x == 0) part[blockIdx.x] = red[0];
 }
-__global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* table, int nslots, int r, int rp, float tau2) {
+__global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* table, int nslots, int r, int rp, float tau2,
+                                                                  int slot_phi16) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   const float* part = (const float*)tab[SLOT_EPART];
   // every block adds the 256 partials in the same order, so all blocks take the same decision
@@ -371,26 +373,31 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
   if (!fast) return;
   const float* C = (const float*)tab[SLOT_C];
   float* W = (float*)tab[SLOT_W];
+  uint16_t* phi16 = slot_phi16 >= 0 ? (uint16_t*)tab[slot_phi16] : nullptr;   // Phi itself, r x r bf16
   const long long n = (long long)rp * rp;
   for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (long long)gridDim.x * 256) {
     const int i = (int)(idx / rp), j = (int)(idx % rp);
-    float v = 0.f;
+    float v = 0.f, phi = 0.f;
     if (i < r && j < r) {
-      if (i == j) v = 1.f - 0.5f * (C[idx] - 1.f);
-      else if (j < i) v = -C[idx];
+      if (i == j) phi = 0.5f * (C[idx] - 1.f);
+      else if (j < i) phi = C[idx];
+      v = (i == j ? 1.f : 0.f) - phi;
+      if (phi16) phi16[(long long)i * r + j] = (uint16_t)(pack_bf16x2(phi, 0.f) & 0xffffu);
     } else if (i == j) {
       v = 1.f;
     }
     W[idx] = v;
   }
 }
-hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, hipStream_t s) {
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
+                                      hipStream_t s) {
   hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long blocks = ((long long)rp * rp + 2047) / 2048;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(first_order_inverse_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, r, rp, tau * tau);
+  hipLaunchKernelGGL(first_order_inverse_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, r, rp, tau * tau,
+                     slot_phi16);
   return hipGetLastError();
 }
 
