@@ -137,6 +137,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_FAST, 1);
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
   take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 2));
+  take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
   c.total = pos;
   return c;
 }
@@ -226,6 +227,7 @@ GemmArgs base_args(const dion_state* st, const Group& g) {
   a.sub_count = 1;
   a.status_slot = -1;
   a.fast_slot = a.fast_b_slot = a.fast_addend_slot = -1;
+  a.side_slot = -1;
   a.E.alpha = 1.f;
   return a;
 }
@@ -262,11 +264,13 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.A = opnd(SLOT_PT16, 0, rows);
     a.B = opnd(SLOT_PT16, 0, rows);
     a.lower_only = 1;
-    // 256x256 tiles when the lower triangle of such tiles alone fills the GPU (large batches), else 128x128 + split-K
-    const long long t256 = r / 256;
-    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && t256 * (t256 + 1) / 2 * batch >= 256;
+    // 256x256 tiles when the lower triangle of such tiles fills at least half of the GPU (large batches, r = 4096),
+    // split over the rows once more if need be; else 128x128 tiles with a deeper split
+    const long long t256 = r / 256, tiles256 = t256 * (t256 + 1) / 2 * batch;
+    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && tiles256 >= 128;
+    const int big_split = gram_big ? (int)std::min<long long>(gp.splitk2, (256 + tiles256 - 1) / tiles256) : 1;
     const int gcfg = gram_big ? G2_256x256 : G2_128x128;
-    a.splitk = gram_big ? 1 : gp.splitk2;
+    a.splitk = gram_big ? big_split : gp.splitk2;
     const int eff = gemm2_nt_splitk(gcfg, a);
     a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
@@ -435,8 +439,9 @@ int tile_cfg2(const RowCtx& c, long long Mo, long long No) {
   return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * c.batch >= 128) ? G2_256x256 : G2_128x128;
 }
 
-// K1: Z = (M+G) Q with Q (n x r) taken from SLOT_Q
-int stage_k1(const RowCtx& c) {
+// K1: Z = (M+G) Q with Q (n x r) taken from SLOT_Q.  keep_b16: the large-tile kernel also leaves bf16(M+G) in
+// SLOT_B16 for a K2 that follows.
+int stage_k1(const RowCtx& c, bool keep_b16) {
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs a = c.base;
@@ -447,6 +452,7 @@ int stage_k1(const RowCtx& c) {
   if (c.big) {
     HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, SLOT_Q, -1, SLOT_QT16, n, r, c.s));
     a.B = opnd(SLOT_QT16, 0, n);
+    if (keep_b16) a.side_slot = SLOT_B16;
     const int c1 = tile_cfg2(c, m, r);
     if (c1 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)m * r;
@@ -473,15 +479,17 @@ int stage_k2(const RowCtx& c, int slot_p) {
   a.E.slot = SLOT_R; a.E.ld = r;
   a.xcd_remap = 1;
   if (c.big) {
+    // M + G was rounded to bf16 once, by K1, and is read back from there (2 bytes per element instead of 6)
+    a.A = opnd(SLOT_B16, 0, n);
     a.B = opnd(SLOT_PT16, 0, m);
     const int c2 = tile_cfg2(c, n, r);
     if (c2 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)n * r;
       const int eff = gemm2_k2_splitk(c2, a);
-      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, true));
       HIPCHK(launch_sum_partials(c.tab, NSLOTS, c.batch, SLOT_KPART, SLOT_R, (long long)n * r, eff, c.s));
     } else {
-      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, true));
     }
   } else {
     a.B = opnd(slot_p, 0, r);
@@ -560,7 +568,7 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  STAGECHK(stage_k1(c));
+  STAGECHK(stage_k1(c, true));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
   STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P));
@@ -593,7 +601,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
   if (refresh) {
-    STAGECHK(stage_k1(c));                                                        // Z = B V
+    STAGECHK(stage_k1(c, true));                                                  // Z = B V
     if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, -1, SLOT_PT16, m, r, s));
     STAGECHK(stage_k2(c, SLOT_Z));                                                // R = B^T Z
     const int fin = (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) ? SLOT_P1 : SLOT_R;
@@ -605,7 +613,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  STAGECHK(stage_k1(c));                                                          // W = B V
+  STAGECHK(stage_k1(c, false));                                                   // W = B V
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
   HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_Z, m, r, s));                  // d from the columns of W
@@ -698,7 +706,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_SYNC; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_B16; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];

@@ -10,7 +10,9 @@
 
 namespace dion {
 
-enum { SRC2_BF16_KC = 0, SRC2_SUM_KC = 1, SRC2_SUM_KS = 2 };
+// Operand sources: bf16 matrix read along k; fused fp32 sum M + G read along k; the same sum read across k
+// (transposed on its way into LDS); bf16 matrix read across k.
+enum { SRC2_BF16_KC = 0, SRC2_SUM_KC = 1, SRC2_SUM_KS = 2, SRC2_BF16_KS = 3 };
 
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int STAGES_, int MINW_>
 struct TileCfg2 {
@@ -28,20 +30,22 @@ struct TileCfg2 {
 template <class Cfg, int ROWS, int SRC, bool GBF16>
 struct Mover2 {
   static constexpr int BK = Cfg::BK, NT = Cfg::NT, BKP = Cfg::BKP;
-  static constexpr bool KS = (SRC == SRC2_SUM_KS);
-  static constexpr bool SUM = (SRC != SRC2_BF16_KC);
+  static constexpr bool KS = (SRC == SRC2_SUM_KS || SRC == SRC2_BF16_KS);
+  static constexpr bool SUM = (SRC == SRC2_SUM_KC || SRC == SRC2_SUM_KS);
   // KC: item = 1 row x 8 k.   KS: item = 8 k x 4 rows.
   static constexpr int ITEMS = KS ? (ROWS / 4) * (BK / 8) : ROWS * (BK / 8);
   static constexpr int PER = ITEMS / NT;
   static_assert(ITEMS % NT == 0 && PER >= 1, "tile does not divide over the workgroup");
-  static constexpr int AW = !SUM ? 4 : (KS ? 32 : 8);                 // 32-bit words of the main operand per item
+  static constexpr int AW = SUM ? (KS ? 32 : 8) : (KS ? 16 : 4);      // 32-bit words of the main operand per item
   static constexpr int GW = !SUM ? 1 : (GBF16 ? AW / 2 : AW);         // words of G per item
 
   uint32_t a[PER][AW];
   uint32_t g[PER][GW];
+  int k0_;   // k offset of the slab in the registers (for the side copy)
 
   __device__ __forceinline__ void load(const void* __restrict__ p0, const void* __restrict__ p1, long long ld, int row0, int k0) {
     const int t = threadIdx.x;
+    k0_ = k0;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int item = t + i * NT;
@@ -71,6 +75,11 @@ struct Mover2 {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
           const long long idx = (long long)(k0 + kc * 8 + kk) * ld + (row0 + rg * 4);
+          if constexpr (!SUM) {
+            const u32x2_t x = gload<u32x2_t>((const uint16_t*)p0 + idx);
+            a[i][2 * kk + 0] = x[0]; a[i][2 * kk + 1] = x[1];
+            continue;
+          }
           const u32x4_t x = gload<u32x4_t>((const float*)p0 + idx);
           a[i][4 * kk + 0] = x[0]; a[i][4 * kk + 1] = x[1]; a[i][4 * kk + 2] = x[2]; a[i][4 * kk + 3] = x[3];
           if constexpr (GBF16) {
@@ -93,7 +102,9 @@ struct Mover2 {
     return x;
   }
 
-  __device__ __forceinline__ void store(uint16_t* __restrict__ lds) const {
+  // side != nullptr (fused sum read along k only): the bf16 values also go to side[row][k], leading dimension ld
+  __device__ __forceinline__ void store(uint16_t* __restrict__ lds, uint16_t* __restrict__ side = nullptr, long long ld = 0,
+                                        int row0 = 0) const {
     const int t = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
@@ -106,6 +117,7 @@ struct Mover2 {
         } else {
           w[0] = pack_bf16x2(sum(i, 0), sum(i, 1)); w[1] = pack_bf16x2(sum(i, 2), sum(i, 3));
           w[2] = pack_bf16x2(sum(i, 4), sum(i, 5)); w[3] = pack_bf16x2(sum(i, 6), sum(i, 7));
+          if (side) gstore<u32x4_t>(side + (long long)(row0 + row) * ld + (k0_ + kc * 8), w);
         }
         *(u32x4_t*)(lds + row * BKP + kc * 8) = w;
       } else {
@@ -113,6 +125,15 @@ struct Mover2 {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           u32x4_t w;
+          if constexpr (!SUM) {
+            // element (k, row rr) is the (rr & 1) half of word a[2 k + rr / 2]: gather the halves of two k per word
+            constexpr unsigned SEL_LO = 0x05040100u, SEL_HI = 0x07060302u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              w[j] = __builtin_amdgcn_perm(a[i][2 * (2 * j + 1) + rr / 2], a[i][2 * (2 * j) + rr / 2], (rr & 1) ? SEL_HI : SEL_LO);
+            *(u32x4_t*)(lds + (rg * 4 + rr) * BKP + kc * 8) = w;
+            continue;
+          }
           w[0] = pack_bf16x2(sum(i, 0 * 4 + rr), sum(i, 1 * 4 + rr));
           w[1] = pack_bf16x2(sum(i, 2 * 4 + rr), sum(i, 3 * 4 + rr));
           w[2] = pack_bf16x2(sum(i, 4 * 4 + rr), sum(i, 5 * 4 + rr));
@@ -164,7 +185,11 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   void* const* tab = g.table + (size_t)b * g.nslots;
   if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
 
-  const void* A1 = (ASRC != SRC2_BF16_KC) ? tab[g.A.slot1] : nullptr;
+  const void* A1 = (ASRC == SRC2_SUM_KC || ASRC == SRC2_SUM_KS) ? tab[g.A.slot1] : nullptr;
+  // the bf16 values of the fused sum are also left in memory: the workgroups of one tile row all hold the same
+  // k-slabs of it, so they take turns (slab s is written by tile column s mod tiles_n)
+  uint16_t* sideA = nullptr;
+  if constexpr (ASRC == SRC2_SUM_KC) sideA = g.side_slot >= 0 ? (uint16_t*)tab[g.side_slot] : nullptr;
   const void* B20 = DUAL ? tab[g.B2.slot0] : nullptr;
 
   const int row0 = tm * BM, col0 = tn * BN;
@@ -210,7 +235,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
     if constexpr (DUAL) xb2.load(B20, nullptr, g.B2.ld, col0, k0);
   };
   auto stash = [&](int stage, const auto& xa, const auto& xb, const auto& xb2) __attribute__((always_inline)) {
-    xa.store(As + stage * BM * BKP);
+    xa.store(As + stage * BM * BKP, (sideA && (xa.k0_ / BK) % g.tiles_n == tn) ? sideA : nullptr, g.A.ld, row0);
     xb.store(Bs + stage * BN * BKP);
     if constexpr (DUAL) xb2.store(B2s + stage * BN * BKP);
   };

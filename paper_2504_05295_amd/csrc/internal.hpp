@@ -39,6 +39,7 @@ enum Slot {
   SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
+  SLOT_B16,    // bf16(M + G), m x n: written by K1 on its way, read by K2 (large-tile path)
   NSLOTS = 32
 };
 
@@ -63,7 +64,7 @@ hipError_t gemm_k5(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hi
 // hipErrorInvalidValue when the shape is not a multiple of the tile.
 enum { G2_256x256 = 0, G2_128x128 = 1 };
 hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
-hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
+hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s, bool from_bf16 = false);   // from_bf16: A = bf16 [K][M]
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 int gemm2_k1_splitk(int cfg, const GemmArgs& g);   // number of split-K partials the launch will write
 int gemm2_k2_splitk(int cfg, const GemmArgs& g);
