@@ -157,9 +157,10 @@ int dion_set_stage_timing(dion_state_t* st, int enable);
 int dion_stage_times(dion_state_t* st, float* ms_out /* [DION_STAGE_COUNT] */);
 
 /* Test access to the intermediates of matrix `index` left in the workspace by the last step:
- * which = 0: Z of the first pass' input (m x r, overwritten by P), 1: P (m x r), 2: R (n x r),
- * 3: column norms s (r), 4: status word (int32).  Writes the device pointer and the leading
- * dimension (elements). */
+ * which = 0: Z (m x r; after a Lazy-Dion step: W), 1: P (m x r), 2: R (n x r), 3: column norms s (r),
+ * 4: status word (int32), 5: the output of the first Cholesky-QR pass, 6 / 7 / 8: Gram matrix, its Cholesky
+ * factor and that factor's inverse of the last pass (rp x rp, rp = r rounded up to 64), 9: 1 / (s + eps).
+ * Writes the device pointer and the leading dimension (elements). */
 int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, int64_t* ld_out);
 
 int dion_destroy_state(dion_state_t* st);

@@ -250,11 +250,6 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
   __shared__ volatile int scaled;                               // set when rsv is complete
   __shared__ volatile int raw_done;                             // number of eliminated (raw) columns
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-#ifdef CHOL_TIMING
-  long long* tlog = (long long*)(L + 64) + (size_t)(k0 / CB) * 8;
-  const bool tl = blockIdx.x == 0 && mode != 2;
-  if (tl && t == 0) tlog[0] = wall_clock64();
-#endif
   const int wm = wave & 1, wn = wave >> 1, lr = lane & 31, lk = lane >> 5;
 
   // tile (i, j), 1 <= j <= i, in units of 64 rows/columns below/right of the diagonal block
@@ -299,24 +294,12 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
       if (j != i) *(f32x4_t*)(S2 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowj + rr) * ld + k0 + cc);
     }
   } else if (wave == 0) {
-#ifdef CHOL_TIMING
-    if (tl && lane == 0) { tlog[1] = wall_clock64(); }
-#endif
     eliminate_wave((lds_float*)S0, (lds_counter*)&raw_done, lane);
-#ifdef CHOL_TIMING
-    if (tl && lane == 0) { tlog[2] = wall_clock64(); }
-#endif
   } else if (wave == 2) {
     scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, piv_lo, piv_hi,
                writer ? L + (long long)k0 * ld + k0 : nullptr, ld, status);
-#ifdef CHOL_TIMING
-    if (tl && lane == 0) tlog[6] = wall_clock64();
-#endif
   } else if (wave == 1) {
     invert_wave((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane);
-#ifdef CHOL_TIMING
-    if (tl && lane == 0) tlog[3] = wall_clock64();
-#endif
   } else if (!writer) {
     for (int idx = lane; idx < CB * CB / 4; idx += 64) {
       const int rr = idx >> 4, cc = (idx & 15) * 4;
@@ -326,16 +309,10 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
   }
   __syncthreads();
   if (writer) {
-#ifdef CHOL_TIMING
-    if (tl && t == 0) tlog[4] = wall_clock64();
-#endif
     for (int idx = t; idx < CB * CB / 4; idx += 256) {
       const int rr = idx >> 4, cc = (idx & 15) * 4;
       *(f32x4_t*)(W + (long long)(k0 + rr) * ld + k0 + cc) = *(const f32x4_t*)(S0 + rr * CBP + cc);
     }
-#ifdef CHOL_TIMING
-    if (tl && t == 0) tlog[5] = wall_clock64();
-#endif
     return;
   }
   const f32x16_t li = mma_64(S1, S0, wm, wn, lr, lk);   // L21_i = C21_i W11^T
@@ -602,24 +579,11 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   for (int k = -1; k + 1 < nb; ++k) {
     // the chain: T(k+1, k), U(k+1, k+1, k), D(k+1)
     if (((k + 1) % pr) * pc + ((k + 1) % pc) == wg) {
-#ifdef CHOL_TIMING
-      long long* tlog = (long long*)(x.L + 64) + (size_t)(k < 0 ? 31 : k) * 8;
-      if (t == 0) tlog[0] = wall_clock64();
-#endif
       if (k >= 0) {
         if (!do_column_tile(k + 1, k, true)) return;
-#ifdef CHOL_TIMING
-        if (t == 0) tlog[1] = wall_clock64();
-#endif
         do_update_to_diag(k + 1);
       }
-#ifdef CHOL_TIMING
-      if (t == 0) tlog[2] = wall_clock64();
-#endif
       do_diag(k + 1, k >= 0);
-#ifdef CHOL_TIMING
-      if (t == 0) tlog[3] = wall_clock64();
-#endif
     }
     if (k < 0) continue;
     // the other tiles of column k
