@@ -122,18 +122,35 @@ struct Mover2 {
         *(u32x4_t*)(lds + row * BKP + kc * 8) = w;
       } else {
         const int rg = item % (ROWS / 4), kc = item / (ROWS / 4);
+        if constexpr (!SUM) {
+          // element (k, row rr) is the (rr & 1) half of word a[2 k + rr / 2]: gather the halves of two k per word
+          constexpr unsigned SEL_LO = 0x05040100u, SEL_HI = 0x07060302u;
+          u32x4_t wr[4];
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              wr[rr][j] = __builtin_amdgcn_perm(a[i][2 * (2 * j + 1) + rr / 2], a[i][2 * (2 * j) + rr / 2], (rr & 1) ? SEL_HI : SEL_LO);
+          // Lanes that are neighbours hold rows 4 apart, which with this row stride fall on the same banks four at
+          // a time; so in each of the four rounds a lane writes a different one of its rows, chosen so that any 16
+          // consecutive lanes hit 16 different residues of the row number modulo 16.
+          const int rot = (rg >> 2) & 3;
+#pragma unroll
+          for (int rnd = 0; rnd < 4; ++rnd) {
+            const int rr = (rnd + rot) & 3;
+            u32x4_t w;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const uint32_t lo = (rr & 1) ? wr[1][j] : wr[0][j], hi = (rr & 1) ? wr[3][j] : wr[2][j];
+              w[j] = (rr & 2) ? hi : lo;
+            }
+            *(u32x4_t*)(lds + (rg * 4 + rr) * BKP + kc * 8) = w;
+          }
+          continue;
+        }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           u32x4_t w;
-          if constexpr (!SUM) {
-            // element (k, row rr) is the (rr & 1) half of word a[2 k + rr / 2]: gather the halves of two k per word
-            constexpr unsigned SEL_LO = 0x05040100u, SEL_HI = 0x07060302u;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              w[j] = __builtin_amdgcn_perm(a[i][2 * (2 * j + 1) + rr / 2], a[i][2 * (2 * j) + rr / 2], (rr & 1) ? SEL_HI : SEL_LO);
-            *(u32x4_t*)(lds + (rg * 4 + rr) * BKP + kc * 8) = w;
-            continue;
-          }
           w[0] = pack_bf16x2(sum(i, 0 * 4 + rr), sum(i, 1 * 4 + rr));
           w[1] = pack_bf16x2(sum(i, 2 * 4 + rr), sum(i, 3 * 4 + rr));
           w[2] = pack_bf16x2(sum(i, 4 * 4 + rr), sum(i, 5 * 4 + rr));
