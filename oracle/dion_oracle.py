@@ -150,6 +150,33 @@ def dion_step(X, G, M, Q, mu, eta, method="householder"):
     return dict(X=X_new, M=M_new, Q=Q_new, Z=Z, P=P, R=R, T=T, s=s, B=B, status=status)
 
 
+def dion_step_transposed(X, G, M, Vt, mu, eta, method="householder"):
+    """One Dion step in the transposed form (Section 4.3, "Other variants": the power iteration runs on the
+    transpose of the buffer).  The state factor Vt is m x r and lives on the row side:
+
+        B = M + G;   Z' = B^T Vt (n x r);   P' = Orthonormalize(Z');   R' = B P' (m x r)
+        M_new = B - beta R' P'^T;   Vt_new = ColNorm(R');   X_new = X - eta sqrt(m/n) Vt_new P'^T
+
+    This is the unsharded update rule applied to the n x m matrix X^T with the roles of the axes swapped;
+    the scale factor stays sqrt(d_out/d_in) = sqrt(m/n) of the parameter itself (the paper says the forms are
+    equivalent up to renaming and gives no separate factor).  Orthonormalisation acts on n x r.
+    Returns X, M, Vt (new state), the intermediates Zt, Pt, Rt, s and `status`."""
+    X = _f64(X)
+    m, n = X.shape
+    B = accumulate(M, G)
+    Vt = _f64(Vt)
+    Zt = B.T @ Vt
+    Pt, T, status = orthonormalize(Zt, method)
+    if status != STATUS_OK:
+        return dict(X=X, M=_f64(M), Vt=Vt, Zt=Zt, Pt=Pt, Rt=None, s=None, B=B, status=status)
+    Rt = B @ Pt
+    beta = 1.0 - mu
+    M_new = B - beta * (Rt @ Pt.T)
+    Vt_new, s = col_norm(Rt)
+    X_new = X - eta * np.sqrt(m / n) * (Vt_new @ Pt.T)
+    return dict(X=X_new, M=M_new, Vt=Vt_new, Zt=Zt, Pt=Pt, Rt=Rt, s=s, B=B, status=status)
+
+
 def sym_power_iter1(B, V, method="householder"):
     """SymPowerIter1 of the faster-variants algorithm (Section 5.1): V <- Orthonormalize(B^T (B V)).
     One step of orthogonal iteration on B^T B.  Returns (V_new, Y, T, status), Y = B^T B V."""
