@@ -74,13 +74,15 @@ def kernel_models(shapes, g_bytes, math):
     return out
 
 
-def build_problem(cfg, seed=0, n_grads=2):
+def build_problem(cfg, seed=0, n_grads=2, form="standard"):
     import torch
     from paper_2504_05295_amd import binding as B
     shapes = cfg["shapes"]
     dev = "cuda"
     X, M, Q, G = [], [], [], []
     uniq = {}
+    forms = [B.DION_FORM_TRANSPOSED if (form == "transposed" or (form == "short-side" and n < m)) else B.DION_FORM_STANDARD
+             for (m, n, r) in shapes]
     for i, (m, n, r) in enumerate(shapes):
         # one host draw per distinct shape is enough for timing; every matrix still gets its own buffers
         if (m, n, r) not in uniq:
@@ -89,13 +91,16 @@ def build_problem(cfg, seed=0, n_grads=2):
         x, q, gs = uniq[(m, n, r)]
         X.append(torch.from_numpy(x).to(dev))
         M.append(torch.empty((m, n), dtype=torch.float32, device=dev))
+        if forms[i] == B.DION_FORM_TRANSPOSED:
+            q = inputs.right_factor_raw(m, r, seed + 2, 0)
         Q.append(torch.from_numpy(q).to(dev))
         if cfg["g_bf16"]:
             G.append([torch.from_numpy(g.view(np.int16)).view(torch.bfloat16).to(dev) for g in gs])
         else:
             G.append([torch.from_numpy(g).to(dev) for g in gs])
     state = B.dion_init_state(shapes, B.DION_G_BF16 if cfg["g_bf16"] else B.DION_G_F32,
-                              B.DION_MATH_BF16 if cfg["math"] == "bf16" else B.DION_MATH_F32, M, Q, q_is_filled=True)
+                              B.DION_MATH_BF16 if cfg["math"] == "bf16" else B.DION_MATH_F32, M, Q, q_is_filled=True,
+                              forms=None if form == "standard" else forms)
     return dict(B=B, shapes=shapes, X=X, M=M, Q=Q, G=G, state=state, uniq=uniq)
 
 
@@ -179,6 +184,9 @@ def main():
     ap.add_argument("--variant", default="dion", choices=["dion", "lazy"],
                     help="dion: the Dion step (default); lazy: Lazy-Dion with a refresh every --refresh-every steps")
     ap.add_argument("--refresh-every", type=int, default=8)
+    ap.add_argument("--form", default="standard", choices=["standard", "transposed", "short-side"],
+                    help="power iteration on M (standard), on M^T (transposed), or per matrix on whichever side makes the "
+                         "orthonormalised factor shorter (transposed where n < m)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -192,7 +200,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     cfg = inputs.CONFIGS[args.workload]
-    p = build_problem(cfg)
+    if args.form != "standard" and (args.variant != "dion"):
+        print("--form applies to the Dion step only", file=sys.stderr)
+        sys.exit(2)
+    p = build_problem(cfg, form=args.form)
     p["variant"], p["refresh_every"] = args.variant, max(1, args.refresh_every)
     if args.variant == "lazy":
         # the first step must refresh (V starts column-normalised, not orthonormal); time whole refresh periods
@@ -258,12 +269,12 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[args.workload], "matrices": len(cfg["shapes"]),
                    "shape": list(cfg["shapes"][0]) if len(set(cfg["shapes"])) == 1 else "mixed",
                    "mu": inputs.MU, "eta": inputs.ETA, "g_dtype": "bf16" if cfg["g_bf16"] else "f32",
-                   "variant": args.variant},
+                   "variant": args.variant, "form": args.form},
         "stage_ms": stages,
         "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
         "rooflines": rooflines,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.form == "standard":
         out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=p["refresh_every"])
     print(json.dumps(out))
 

@@ -77,6 +77,24 @@ int dion_init_state(dion_state_t** st, int count, const int64_t* m, const int64_
                     void* const* M_dev, void* const* Q_dev, int q_is_filled, uint64_t seed,
                     void* hip_stream);
 
+/* As dion_init_state, with the form of the power iteration chosen per matrix (Section 4.3, "Other variants":
+ * it can run on M or on M^T).  form: host array of `count` DION_FORM_* values, or NULL for all standard.
+ *   DION_FORM_STANDARD    the factor Q is n x r; Z = B Q (m x r) is orthonormalised     (as described above)
+ *   DION_FORM_TRANSPOSED  the factor is m x r (call it Vt; it lives in the Q argument of every call):
+ *                           Z' = B^T Vt (n x r);  P' = Orthonormalize(Z');  R' = B P' (m x r)
+ *                           M_new = B - (1 - mu) R' P'^T;  Vt_new = ColNorm(R');
+ *                           X_new = X - eta sqrt(m/n) Vt_new P'^T
+ *                         the same rule applied to X^T, with the parameter's own scale factor sqrt(m/n) kept;
+ *                         the orthonormalisation then acts on n x r, which is the cheaper side when n < m.
+ * dion_step / dion_step_batched / dion_retry_breakdowns follow the form declared here; dion_step looks a
+ * matrix up by its shape and takes the first declared entry of that shape.  The Lazy-Dion calls accept the
+ * standard form only. */
+enum { DION_FORM_STANDARD = 0, DION_FORM_TRANSPOSED = 1 };
+int dion_init_state_ex(dion_state_t** st, int count, const int64_t* m, const int64_t* n, const int64_t* r,
+                       const int* form, int g_dtype, int math, void* workspace_dev, size_t workspace_bytes,
+                       void* const* M_dev, void* const* Q_dev, int q_is_filled, uint64_t seed,
+                       void* hip_stream);
+
 /* One Dion step for one matrix (Algorithm 1 with the unsharded update rule).  The shape
  * (m, n, r) must be one declared to dion_init_state.  mu in [0,1] (the paper's 1 - beta),
  * eta = learning rate. */

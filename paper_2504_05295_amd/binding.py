@@ -25,8 +25,9 @@ STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
 DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D = range(10)
 
 DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
+DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
-EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
+EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
            "dion_last_status",
            "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
@@ -51,6 +52,8 @@ def lib() -> C.CDLL:
         L.dion_workspace_bytes.argtypes = [C.c_int, i64p, i64p, i64p, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
         L.dion_init_state.argtypes = [C.POINTER(C.c_void_p), C.c_int, i64p, i64p, i64p, C.c_int, C.c_int, C.c_void_p,
                                       C.c_size_t, vpp, vpp, C.c_int, C.c_uint64, C.c_void_p]
+        L.dion_init_state_ex.argtypes = [C.POINTER(C.c_void_p), C.c_int, i64p, i64p, i64p, C.POINTER(C.c_int), C.c_int, C.c_int,
+                                         C.c_void_p, C.c_size_t, vpp, vpp, C.c_int, C.c_uint64, C.c_void_p]
         L.dion_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
                                 C.c_int64, C.c_float, C.c_float, C.c_void_p]
         L.dion_step_batched.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
@@ -147,9 +150,10 @@ def dion_workspace_bytes(shapes: Sequence[Tuple[int, int, int]], g_dtype: int, m
 
 
 def dion_init_state(shapes, g_dtype, math, M: List, Q: List, q_is_filled: bool = True, seed: int = 0,
-                    workspace=None, stream=None) -> DionState:
+                    workspace=None, stream=None, forms=None) -> DionState:
     """Creates the state for matrices of `shapes` = [(m, n, r), ...]; zero-fills M, column-normalises Q
-    (drawing it first when q_is_filled is False).  `workspace`: a uint8 device tensor, allocated here if None."""
+    (drawing it first when q_is_filled is False).  `workspace`: a uint8 device tensor, allocated here if None.
+    `forms`: per-matrix DION_FORM_* (dion_init_state_ex); a transposed-form matrix has an m x r factor."""
     import torch
     need = dion_workspace_bytes(shapes, g_dtype, math)
     if workspace is None:
@@ -159,13 +163,22 @@ def dion_init_state(shapes, g_dtype, math, M: List, Q: List, q_is_filled: bool =
     avail = workspace.numel() - (aligned - base)
     for i, (m, n, r) in enumerate(shapes):
         _check_tensor(M[i], torch.float32, (m, n), "M[%d]" % i)
-        _check_tensor(Q[i], torch.float32, (n, r), "Q[%d]" % i)
+        frows = m if (forms is not None and forms[i] == DION_FORM_TRANSPOSED) else n
+        _check_tensor(Q[i], torch.float32, (frows, r), "Q[%d]" % i)
     handle = C.c_void_p(None)
     m, n, r = _i64([s[0] for s in shapes]), _i64([s[1] for s in shapes]), _i64([s[2] for s in shapes])
-    _check(lib().dion_init_state(C.byref(handle), len(shapes), m, n, r, g_dtype, math, C.c_void_p(aligned), avail,
-                                 _ptrs(M), _ptrs(Q), 1 if q_is_filled else 0, int(seed), _stream(stream)),
-           "dion_init_state")
-    return DionState(handle, shapes, g_dtype, math, workspace)
+    if forms is None:
+        _check(lib().dion_init_state(C.byref(handle), len(shapes), m, n, r, g_dtype, math, C.c_void_p(aligned), avail,
+                                     _ptrs(M), _ptrs(Q), 1 if q_is_filled else 0, int(seed), _stream(stream)),
+               "dion_init_state")
+    else:
+        farr = (C.c_int * len(shapes))(*[int(f) for f in forms])
+        _check(lib().dion_init_state_ex(C.byref(handle), len(shapes), m, n, r, farr, g_dtype, math, C.c_void_p(aligned),
+                                        avail, _ptrs(M), _ptrs(Q), 1 if q_is_filled else 0, int(seed), _stream(stream)),
+               "dion_init_state_ex")
+    st = DionState(handle, shapes, g_dtype, math, workspace)
+    st.forms = list(forms) if forms is not None else [DION_FORM_STANDARD] * len(shapes)
+    return st
 
 
 def _g_dtype(state):
@@ -180,7 +193,9 @@ def dion_step(state: DionState, X, G, M, Q, mu: float, eta: float, stream=None) 
     _check_tensor(X, torch.float32, (m, n), "X")
     _check_tensor(G, _g_dtype(state), (m, n), "G")
     _check_tensor(M, torch.float32, (m, n), "M")
-    _check_tensor(Q, torch.float32, (n, r), "Q")
+    if tuple(Q.shape) != (n, r) and tuple(Q.shape) != (m, r):
+        raise ValueError("Q must be n x r (standard form) or m x r (transposed form)")
+    _check_tensor(Q, torch.float32, tuple(Q.shape), "Q")
     _check(lib().dion_step(state.handle, _ptr(X), _ptr(G), _ptr(M), _ptr(Q), m, n, r, mu, eta, _stream(stream)), "dion_step")
 
 
@@ -192,7 +207,8 @@ def dion_step_batched(state: DionState, X: List, G: List, M: List, Q: List, mu: 
         _check_tensor(X[i], torch.float32, (m, n), "X[%d]" % i)
         _check_tensor(G[i], _g_dtype(state), (m, n), "G[%d]" % i)
         _check_tensor(M[i], torch.float32, (m, n), "M[%d]" % i)
-        _check_tensor(Q[i], torch.float32, (n, r), "Q[%d]" % i)
+        frows = m if getattr(state, "forms", None) and state.forms[i] == DION_FORM_TRANSPOSED else n
+        _check_tensor(Q[i], torch.float32, (frows, r), "Q[%d]" % i)
     sh = state.shapes[:count]
     _check(lib().dion_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(Q), _i64([s[0] for s in sh]),
                                    _i64([s[1] for s in sh]), _i64([s[2] for s in sh]), mu, eta, _stream(stream)),

@@ -35,6 +35,7 @@ namespace {
 
 struct Entry {
   int64_t m, n, r;
+  int form;   // DION_FORM_*
   int group;
   int row;  // row of the pointer table (group-sorted order)
 };
@@ -50,6 +51,7 @@ struct GramPlan {
 };
 struct Group {
   int64_t m, n, r;
+  int form;        // DION_FORM_*: all matrices of a group share it
   int rp;          // r rounded up to a multiple of CHOL_NB
   int first_row, count;
   GramPlan gram_m, gram_n;   // Gram products over the m x r matrices of a Dion step / the n x r ones of a Lazy-Dion refresh
@@ -154,23 +156,26 @@ bool shapes_ok(int count, const int64_t* m, const int64_t* n, const int64_t* r) 
   return true;
 }
 
-bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r, std::vector<Entry>& entries,
+bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r, const int* form, std::vector<Entry>& entries,
                 std::vector<Group>& groups) {
   entries.resize(count);
   groups.clear();
   for (int i = 0; i < count; ++i) {
     int gi = -1;
+    const int f = form ? form[i] : DION_FORM_STANDARD;
     for (size_t k = 0; k < groups.size(); ++k)
-      if (groups[k].m == m[i] && groups[k].n == n[i] && groups[k].r == r[i]) gi = (int)k;
+      if (groups[k].m == m[i] && groups[k].n == n[i] && groups[k].r == r[i] && groups[k].form == f) gi = (int)k;
     if (gi < 0) {
       Group g;
       memset(&g, 0, sizeof(g));
       g.m = m[i]; g.n = n[i]; g.r = r[i];
+      g.form = f;
       g.rp = padded_rank(r[i]);
       groups.push_back(g);
       gi = (int)groups.size() - 1;
     }
     entries[i].m = m[i]; entries[i].n = n[i]; entries[i].r = r[i];
+    entries[i].form = f;
     entries[i].group = gi;
     groups[gi].count++;
   }
@@ -439,9 +444,9 @@ int tile_cfg2(const RowCtx& c, long long Mo, long long No) {
   return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * c.batch >= 128) ? G2_256x256 : G2_128x128;
 }
 
-// K1: Z = (M+G) Q with Q (n x r) taken from SLOT_Q.  keep_b16: the large-tile kernel also leaves bf16(M+G) in
+// K1: Z = (M+G) Q with Q (n x r, fp32) taken from slot_q.  keep_b16: the large-tile kernel also leaves bf16(M+G) in
 // SLOT_B16 for a K2 that follows.
-int stage_k1(const RowCtx& c, bool keep_b16) {
+int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs a = c.base;
@@ -450,7 +455,7 @@ int stage_k1(const RowCtx& c, bool keep_b16) {
   a.E.slot = SLOT_Z; a.E.ld = r;
   a.xcd_remap = 1;
   if (c.big) {
-    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, SLOT_Q, -1, SLOT_QT16, n, r, c.s));
+    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, -1, SLOT_QT16, n, r, c.s));
     a.B = opnd(SLOT_QT16, 0, n);
     if (keep_b16) a.side_slot = SLOT_B16;
     const int c1 = tile_cfg2(c, m, r);
@@ -463,14 +468,15 @@ int stage_k1(const RowCtx& c, bool keep_b16) {
       HIPCHK(gemm2_k1(c1, c.gbf16, a, c.batch, c.s));
     }
   } else {
-    a.B = opnd(SLOT_Q, 0, r);
+    a.B = opnd(slot_q, 0, r);
     HIPCHK(gemm_k1(pick_variant(m, r, n, c.batch, true), c.bf16, c.gbf16, a, c.batch, c.s));
   }
   return DION_OK;
 }
 
-// K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile path, its bf16 transpose in SLOT_PT16
-int stage_k2(const RowCtx& c, int slot_p) {
+// K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile path, its bf16 transpose in SLOT_PT16.
+// from_b16: a K1 of this step has left bf16(M+G) in SLOT_B16 (large-tile path only).
+int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true) {
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs a = c.base;
@@ -480,16 +486,16 @@ int stage_k2(const RowCtx& c, int slot_p) {
   a.xcd_remap = 1;
   if (c.big) {
     // M + G was rounded to bf16 once, by K1, and is read back from there (2 bytes per element instead of 6)
-    a.A = opnd(SLOT_B16, 0, n);
+    if (from_b16) a.A = opnd(SLOT_B16, 0, n);
     a.B = opnd(SLOT_PT16, 0, m);
     const int c2 = tile_cfg2(c, n, r);
     if (c2 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)n * r;
       const int eff = gemm2_k2_splitk(c2, a);
-      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, true));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, from_b16));
       HIPCHK(launch_sum_partials(c.tab, NSLOTS, c.batch, SLOT_KPART, SLOT_R, (long long)n * r, eff, c.s));
     } else {
-      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, true));
+      HIPCHK(gemm2_k2(c2, c.gbf16, a, c.batch, c.s, from_b16));
     }
   } else {
     a.B = opnd(slot_p, 0, r);
@@ -627,6 +633,48 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   return DION_OK;
 }
 
+// One Dion step in the transposed form (Section 4.3, other variants) for the matrices of one shape group; the
+// caller's factor buffer holds Vt (m x r):
+//   Z' = B^T Vt (n x r);  P' = orth(Z');  R' = B P' (m x r);  M <- B - (1-mu) R' P'^T;  Vt <- ColNorm(R');
+//   X <- X - eta sqrt(m/n) Vt_new P'^T = X - eta sqrt(m/n) R' (P' diag(d))^T
+// i.e. the products of the standard step in the other order, the orthonormalisation on n x r, and the fused
+// update kernel with A = R', B = P', B2 = P' diag(d).
+int transposed_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
+  const RowCtx c = make_ctx(st, gi, row0, batch, s);
+  const Group& g = *c.g;
+  const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  if (c.ev) st->group_timed[gi] = 1;
+  // stage names as in the standard step: "K2" is the product with B^T, "K1" the one with B
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
+  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Q, -1, SLOT_PT16, m, r, s));
+  STAGECHK(stage_k2(c, SLOT_Q, false));                                           // R = B^T Vt   (n x r)
+  STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
+  STAGECHK(mark(c, DION_STAGE_ORTH, 0));
+  const int pt = (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) ? SLOT_P1 : SLOT_R;   // where P' ends up
+  const int scratch = (pt == SLOT_R) ? SLOT_P1 : SLOT_R;                            // the other n x r buffer
+  STAGECHK(stage_orth(c, g.n, g.gram_n, SLOT_R, SLOT_P1, pt));
+  STAGECHK(mark(c, DION_STAGE_ORTH, 1));
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
+  STAGECHK(stage_k1(c, false, pt));                                               // Z = B P'     (m x r)
+  STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
+  HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_Z, m, r, s));
+  // scratch <- P' diag(d) with bf16 copies of it and of P'; Vt <- R' diag(d) with a bf16 copy of R'
+  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, pt, scratch, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
+  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_Z, SLOT_Q, m, r, SLOT_STATUS, -1, c.big ? SLOT_P16 : -1, s));
+  STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));
+  STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_Z, pt, scratch, mu, eta));
+  STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 1));
+  return DION_OK;
+}
+
+int any_step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
+  return st->groups[gi].form == DION_FORM_TRANSPOSED ? transposed_rows(st, gi, row0, batch, mu, eta, s)
+                                                     : step_rows(st, gi, row0, batch, mu, eta, s);
+}
+
 bool aligned16(const void* p) { return p && ((uintptr_t)p & 15u) == 0; }
 bool coeffs_ok(float mu, float eta) { return mu >= 0.f && mu <= 1.f && isfinite(eta) && isfinite(mu); }
 
@@ -652,7 +700,7 @@ int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const in
   try {
     std::vector<Entry> entries;
     std::vector<Group> groups;
-    build_plan(count, m, n, r, entries, groups);
+    build_plan(count, m, n, r, nullptr, entries, groups);   // the form does not change any size
     size_t total = header_bytes(count);
     for (auto& g : groups) total += g.bytes_per_entry * g.count;
     *bytes_out = total + 256;
@@ -665,7 +713,17 @@ int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const in
 int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64_t* n, const int64_t* r, int g_dtype,
                     int math, void* workspace_dev, size_t workspace_bytes, void* const* M_dev, void* const* Q_dev,
                     int q_is_filled, uint64_t seed, void* hip_stream) {
+  return dion_init_state_ex(out, count, m, n, r, nullptr, g_dtype, math, workspace_dev, workspace_bytes, M_dev, Q_dev,
+                            q_is_filled, seed, hip_stream);
+}
+
+int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const int64_t* n, const int64_t* r, const int* form,
+                       int g_dtype, int math, void* workspace_dev, size_t workspace_bytes, void* const* M_dev,
+                       void* const* Q_dev, int q_is_filled, uint64_t seed, void* hip_stream) {
   if (!out) return DION_EINVAL;
+  if (form)
+    for (int i = 0; i < count; ++i)
+      if (form[i] != DION_FORM_STANDARD && form[i] != DION_FORM_TRANSPOSED) return DION_EINVAL;
   *out = nullptr;
   size_t need = 0;
   int rc = dion_workspace_bytes(count, m, n, r, g_dtype, math, &need);
@@ -680,7 +738,7 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
   try {
     st = new dion_state();
     st->count = count; st->g_dtype = g_dtype; st->math = math;
-    build_plan(count, m, n, r, st->entries, st->groups);
+    build_plan(count, m, n, r, form, st->entries, st->groups);
     st->ws = (char*)workspace_dev;
     st->ws_bytes = workspace_bytes;
     st->table = (void**)st->ws;
@@ -728,14 +786,15 @@ int dion_init_state(dion_state_t** out, int count, const int64_t* m, const int64
     void* const* rowtab = st->table + (size_t)e.row * NSLOTS;
     if (launch_fill(rowtab, NSLOTS, 1, SLOT_M, (long long)e.m * e.n, 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (!q_is_filled)
-      if (launch_gaussian_fill(rowtab, NSLOTS, 1, SLOT_Q, (long long)e.n * e.r, seed, i, s) != hipSuccess) return fail(DION_ELAUNCH);
+      if (launch_gaussian_fill(rowtab, NSLOTS, 1, SLOT_Q, (e.form == DION_FORM_TRANSPOSED ? e.m : e.n) * e.r, seed, i, s) != hipSuccess) return fail(DION_ELAUNCH);
   }
   for (auto& g : st->groups) {
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 2), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
-    if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, g.n, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
-    if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, g.n, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
+    const long long frows = g.form == DION_FORM_TRANSPOSED ? g.m : g.n;   // the factor is n x r, or m x r in the transposed form
+    if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, frows, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, frows, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
   }
   *out = st;
   return DION_OK;
@@ -762,7 +821,7 @@ int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* c
     return DION_ENOMEM;
   }
   for (size_t gi = 0; gi < st->groups.size(); ++gi) {
-    int rc = step_rows(st, (int)gi, 0, st->groups[gi].count, mu, eta, s);
+    int rc = any_step_rows(st, (int)gi, 0, st->groups[gi].count, mu, eta, s);
     if (rc != DION_OK) return rc;
   }
   return DION_OK;
@@ -786,7 +845,7 @@ int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q, int64_
   void* ms[1] = {M};
   void* qs[1] = {Q};
   HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
-  return step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
+  return any_step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
 }
 
 int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M, void* const* V,
@@ -795,6 +854,8 @@ int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const vo
   if (!st || count < 0) return DION_EINVAL;
   if (count == 0) return DION_OK;
   if (!batch_args_ok(st, count, X, G, M, V, m, n, r, mu, eta)) return DION_EINVAL;
+  for (const Group& g : st->groups)
+    if (g.form != DION_FORM_STANDARD) return DION_EINVAL;   // Lazy-Dion is built for the standard form only
   hipStream_t s = (hipStream_t)hip_stream;
   st->last_stream = s;
   std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
@@ -823,7 +884,7 @@ int dion_lazy_step(dion_state_t* st, void* X, const void* G, void* M, void* V, i
   int idx = -1;
   for (int i = 0; i < st->count && idx < 0; ++i)
     if (st->entries[i].m == m && st->entries[i].n == n && st->entries[i].r == r) idx = i;
-  if (idx < 0) return DION_EINVAL;
+  if (idx < 0 || st->entries[idx].form != DION_FORM_STANDARD) return DION_EINVAL;
   const Entry& e = st->entries[idx];
   const Group& g = st->groups[e.group];
   hipStream_t s = (hipStream_t)hip_stream;
@@ -867,7 +928,7 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
     void* ms[1] = {M[i]};
     void* qs[1] = {Q[i]};
     if (launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s) != hipSuccess) { rc = DION_ELAUNCH; break; }
-    rc = step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
+    rc = any_step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
     ++retried;
   }
   st->orth_mode = saved_mode;

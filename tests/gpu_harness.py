@@ -15,7 +15,7 @@ def relf(a, b):
 class GpuProblem:
     """One batch of matrices living on the GPU, stepped through the library."""
 
-    def __init__(self, shapes, g_bf16, math, seed=0, q_raw=None, x0=None, q_is_filled=True, init_seed=0):
+    def __init__(self, shapes, g_bf16, math, seed=0, q_raw=None, x0=None, q_is_filled=True, init_seed=0, forms=None):
         import torch
         from paper_2504_05295_amd import binding as B
         self.B = B
@@ -25,14 +25,16 @@ class GpuProblem:
         self.seed = seed
         dev = "cuda"
         self.x0 = x0 if x0 is not None else [inputs.weight(m, n, seed + 1, i) for i, (m, n, r) in enumerate(shapes)]
-        self.q_raw = q_raw if q_raw is not None else [inputs.right_factor_raw(n, r, seed + 2, i)
+        self.forms = forms
+        tr = [forms is not None and forms[i] == B.DION_FORM_TRANSPOSED for i in range(len(shapes))]
+        self.q_raw = q_raw if q_raw is not None else [inputs.right_factor_raw(m if tr[i] else n, r, seed + 2, i)
                                                         for i, (m, n, r) in enumerate(shapes)]
         self.X = [torch.from_numpy(x.copy()).to(dev) for x in self.x0]
         self.M = [torch.full((m, n), 7.0, dtype=torch.float32, device=dev) for (m, n, r) in shapes]  # init must zero it
         self.Q = [torch.from_numpy(q.copy()).to(dev) for q in self.q_raw]
         self.state = B.dion_init_state(self.shapes, B.DION_G_BF16 if g_bf16 else B.DION_G_F32,
                                        B.DION_MATH_BF16 if math == "bf16" else B.DION_MATH_F32,
-                                       self.M, self.Q, q_is_filled=q_is_filled, seed=init_seed)
+                                       self.M, self.Q, q_is_filled=q_is_filled, seed=init_seed, forms=forms)
         self.G = [None] * len(shapes)
 
     def grads_np(self, step, kind="gaussian"):
