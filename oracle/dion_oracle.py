@@ -177,6 +177,36 @@ def dion_step_transposed(X, G, M, Vt, mu, eta, method="householder"):
     return dict(X=X_new, M=M_new, Vt=Vt_new, Zt=Zt, Pt=Pt, Rt=Rt, s=s, B=B, status=status)
 
 
+def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
+    """One Double Dion step (Section 5.2 and the Double Dion algorithm, without the sharding and the
+    data-parallel synchronisation of stage 1) for one m x n matrix, beta_i = 1 - mu_i:
+
+        stage 1 (rank r1):  B1 = M1 + G;  U1, W1 = PowerIter1(B1, V1);  M1 <- B1 - beta1 U1 W1^T;  V1 <- ColNorm(W1)
+        stage 2 (rank r2):  B2 = M2 + U1 W1^T;  U2, W2 = PowerIter1(B2, V2);  M2 <- B2 - beta2 U2 W2^T;  V2 <- ColNorm(W2)
+        X <- X - eta sqrt(m/n) U2 V2_new^T
+
+    Returns the new state (X, M1, V1, M2, V2), the stage-1 sketch D = U1 W1^T and `status`; a breakdown in either
+    stage leaves the whole state unchanged."""
+    X = _f64(X)
+    m, n = X.shape
+    same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None)
+    B1 = accumulate(M1, G)
+    U1, W1, _, _, status = power_iter1(B1, V1, method)
+    if status != STATUS_OK:
+        return dict(same, status=status)
+    D = U1 @ W1.T
+    M1_new = B1 - (1.0 - mu1) * D
+    V1_new, _ = col_norm(W1)
+    B2 = accumulate(M2, D)
+    U2, W2, _, _, status = power_iter1(B2, V2, method)
+    if status != STATUS_OK:
+        return dict(same, status=status)
+    M2_new = B2 - (1.0 - mu2) * (U2 @ W2.T)
+    V2_new, _ = col_norm(W2)
+    X_new = X - eta * np.sqrt(m / n) * (U2 @ V2_new.T)
+    return dict(X=X_new, M1=M1_new, V1=V1_new, M2=M2_new, V2=V2_new, D=D, status=status)
+
+
 def sym_power_iter1(B, V, method="householder"):
     """SymPowerIter1 of the faster-variants algorithm (Section 5.1): V <- Orthonormalize(B^T (B V)).
     One step of orthogonal iteration on B^T B.  Returns (V_new, Y, T, status), Y = B^T B V."""
