@@ -125,6 +125,24 @@ int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const vo
                            void* const* M, void* const* V, const int64_t* m, const int64_t* n,
                            const int64_t* r, float mu, float eta, int refresh, void* hip_stream);
 
+/* Double Dion (Section 5.2 and the Double Dion algorithm; here without sharding, so that the data-parallel
+ * synchronisation of its first stage has nothing to do): two chained Dion steps per matrix,
+ *     stage 1 (rank r1):  B1 = M1 + G;  U1, W1 = PowerIter1(B1, V1);  M1 <- B1 - (1 - mu1) U1 W1^T;  V1 <- ColNorm(W1)
+ *     stage 2 (rank r2):  B2 = M2 + U1 W1^T;  U2, W2 = PowerIter1(B2, V2);  M2 <- B2 - (1 - mu2) U2 W2^T;
+ *                         V2 <- ColNorm(W2);   X <- X - eta sqrt(m/n) U2 V2^T
+ * st1 / st2: states created for the shapes (m, n, r1) / (m, n, r2) in this order, standard form, on separate
+ * workspaces; st1 with the storage type of G, st2 with DION_G_F32.  D: host array of `count` device buffers of
+ * m x n floats (caller-owned scratch) that receive the sketch U1 W1^T between the stages.  A matrix whose stage 1
+ * breaks down is skipped in stage 2 as well, so its X, M1, V1, M2, V2 all stay untouched; when only stage 2 breaks
+ * down (it must while M2, a sum of rank-r1 sketches, has rank below r2: the first r2/r1 steps from M2 = 0), X and
+ * V2 stay untouched, stage 1 has taken its step and M2 only accumulates the sketch, M2 <- M2 + U1 W1^T.  dion_last_status(st2) reports breakdowns of
+ * either stage (dion_last_status(st1) those of stage 1).  Other conventions as for
+ * dion_step_batched; both states must be used on the same stream. */
+int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* const* X, const void* const* G,
+                     void* const* M1, void* const* V1, void* const* M2, void* const* V2, void* const* D,
+                     const int64_t* m, const int64_t* n, const int64_t* r1, const int64_t* r2,
+                     float mu1, float mu2, float eta, void* hip_stream);
+
 /* Waits for the stream of the last step and reports its numerical status: *status_out is
  * DION_OK or DION_NUM_BREAKDOWN; *first_bad_index is the lowest matrix index that broke
  * down (-1 if none).  Either pointer may be NULL. */

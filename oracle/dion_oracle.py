@@ -185,8 +185,11 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
         stage 2 (rank r2):  B2 = M2 + U1 W1^T;  U2, W2 = PowerIter1(B2, V2);  M2 <- B2 - beta2 U2 W2^T;  V2 <- ColNorm(W2)
         X <- X - eta sqrt(m/n) U2 V2_new^T
 
-    Returns the new state (X, M1, V1, M2, V2), the stage-1 sketch D = U1 W1^T and `status`; a breakdown in either
-    stage leaves the whole state unchanged."""
+    Returns the new state (X, M1, V1, M2, V2), the stage-1 sketch D = U1 W1^T and `status`.  The paper says nothing
+    about failures; the convention here: a breakdown in stage 1 leaves the whole state unchanged; a breakdown in
+    stage 2 (which is what happens while M2, a sum of rank-r1 sketches, still has rank below r2, e.g. on the
+    first r2/r1 steps from M2 = 0) leaves X and V2 unchanged, stage 1 (M1, V1) has taken its step, and M2 only
+    accumulates the sketch, M2 <- M2 + D, so that it can grow into full rank."""
     X = _f64(X)
     m, n = X.shape
     same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None)
@@ -200,7 +203,7 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
     B2 = accumulate(M2, D)
     U2, W2, _, _, status = power_iter1(B2, V2, method)
     if status != STATUS_OK:
-        return dict(same, status=status)
+        return dict(same, M1=M1_new, V1=V1_new, M2=B2, D=D, status=status)
     M2_new = B2 - (1.0 - mu2) * (U2 @ W2.T)
     V2_new, _ = col_norm(W2)
     X_new = X - eta * np.sqrt(m / n) * (U2 @ V2_new.T)

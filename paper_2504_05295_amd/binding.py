@@ -28,7 +28,7 @@ DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
-           "dion_last_status",
+           "dion_double_step", "dion_last_status",
            "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
                                      C.c_int64, C.c_float, C.c_float, C.c_int, C.c_void_p]
         L.dion_lazy_step_batched.argtypes = [C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, i64p, i64p, i64p, C.c_float,
                                              C.c_float, C.c_int, C.c_void_p]
+        L.dion_double_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, vpp, vpp, vpp, i64p, i64p, i64p, i64p,
+                                       C.c_float, C.c_float, C.c_float, C.c_void_p]
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
@@ -241,6 +243,29 @@ def dion_lazy_step_batched(state: DionState, X: List, G: List, M: List, V: List,
     _check(lib().dion_lazy_step_batched(state.handle, count, _ptrs(X), _ptrs(G), _ptrs(M), _ptrs(V),
                                         _i64([s[0] for s in sh]), _i64([s[1] for s in sh]), _i64([s[2] for s in sh]),
                                         mu, eta, 1 if refresh else 0, _stream(stream)), "dion_lazy_step_batched")
+
+
+def dion_double_step(state1: DionState, state2: DionState, X: List, G: List, M1: List, V1: List, M2: List, V2: List, D: List,
+                     mu1: float, mu2: float, eta: float, stream=None) -> None:
+    """One Double Dion step: state1 holds the rank-r1 stage (M1, V1), state2 the rank-r2 stage (M2, V2);
+    D are m x n fp32 scratch tensors for the stage-1 sketch."""
+    import torch
+    count = len(X)
+    for i in range(count):
+        m, n, r1 = state1.shapes[i]
+        r2 = state2.shapes[i][2]
+        _check_tensor(X[i], torch.float32, (m, n), "X[%d]" % i)
+        _check_tensor(G[i], _g_dtype(state1), (m, n), "G[%d]" % i)
+        _check_tensor(D[i], torch.float32, (m, n), "D[%d]" % i)
+        _check_tensor(M1[i], torch.float32, (m, n), "M1[%d]" % i)
+        _check_tensor(M2[i], torch.float32, (m, n), "M2[%d]" % i)
+        _check_tensor(V1[i], torch.float32, (n, r1), "V1[%d]" % i)
+        _check_tensor(V2[i], torch.float32, (n, r2), "V2[%d]" % i)
+    sh1, sh2 = state1.shapes[:count], state2.shapes[:count]
+    _check(lib().dion_double_step(state1.handle, state2.handle, count, _ptrs(X), _ptrs(G), _ptrs(M1), _ptrs(V1), _ptrs(M2),
+                                  _ptrs(V2), _ptrs(D), _i64([s[0] for s in sh1]), _i64([s[1] for s in sh1]),
+                                  _i64([s[2] for s in sh1]), _i64([s[2] for s in sh2]), mu1, mu2, eta, _stream(stream)),
+           "dion_double_step")
 
 
 def dion_retry_breakdowns(state: DionState, X: List, G: List, M: List, Q: List, mu: float, eta: float, stream=None) -> int:

@@ -162,7 +162,7 @@ __device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw
         constexpr int k = decltype(kc)::value;
         Lout[(long long)lane * ld + k] = (k <= lane) ? l[k] : 0.f;
       });
-      if (bad && lane == 0) *status = 1;
+      if (bad && lane == 0 && *status == 0) *status = 1;   // a code that is already there (an earlier stage failed) stays
     }
 }
 
@@ -421,7 +421,7 @@ __device__ __forceinline__ bool wait_until(const StreamCtx& x, int* gave_up, boo
       __builtin_amdgcn_s_sleep(2);
       if (++n > x.spin_limit) {
         flag_store(x.abort_word, x.epoch);
-        *x.status = 1;
+        if (*x.status == 0) *x.status = 1;
         *(volatile int*)gave_up = 1;
         break;
       }

@@ -529,7 +529,9 @@ int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, 
 
 // K5: M <- (M+G) - (1-mu) A B^T and X <- X - eta sqrt(m/n) A B2^T in one pass (A: m x r, B and B2: n x r).
 // Large-tile path: bf16 operands from the *16 slots; otherwise fp32 operands from the *32 slots.
-int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int b2_32, float mu, float eta) {
+// sketch: instead of the weight update, X (which then is a scratch buffer) receives A B^T itself.
+int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int b2_32, float mu, float eta,
+             bool sketch = false) {
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs a = c.base;
@@ -537,6 +539,12 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
   a.E.slotX = SLOT_X; a.E.slotG = SLOT_G; a.E.slotM = SLOT_M; a.E.ld = n;
   a.E.c_m = 1.0f - mu;
   a.E.c_x = (float)((double)eta * sqrt((double)g.m / (double)g.n));
+  if (sketch) {
+    a.E.c_x = -1.f;
+    a.E.x_overwrite = 1;
+    b2_16 = b16;
+    b2_32 = b32;
+  }
   a.status_slot = SLOT_STATUS;
   if (c.big) {
     a.A = opnd(a16, 0, r);
@@ -567,11 +575,15 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
   } while (0)
 
 // One Dion step (Algorithm 1 with the unsharded update rule) for the matrices of one shape group.
-int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s) {
+// The two stages of a Double Dion step (Section 5.2) are such steps with a twist each:
+//   STEP_SKETCH     the X buffer is a scratch matrix that receives P R^T instead of a weight update (stage 1)
+//   STEP_KEEP_STATUS the status words are not cleared: they hold the outcome of stage 1 (stage 2)
+enum { STEP_PLAIN = 0, STEP_SKETCH = 1, STEP_KEEP_STATUS = 2 };
+int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s, int mode = STEP_PLAIN) {
   const RowCtx c = make_ctx(st, gi, row0, batch, s);
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
-  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
+  if (mode != STEP_KEEP_STATUS) HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
   STAGECHK(stage_k1(c, true));
@@ -588,7 +600,10 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
   STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));
-  STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_P, SLOT_R, SLOT_Q, mu, eta));
+  STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_P, SLOT_R, SLOT_Q, mu, eta, mode == STEP_SKETCH));
+  // a second stage that could not orthonormalise (its buffer is a sum of a few low-rank sketches at first) still
+  // takes the sketch into its momentum
+  if (mode == STEP_KEEP_STATUS) HIPCHK(launch_accumulate_failed(c.tab, NSLOTS, batch, (long long)m * n, s));
   STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 1));
   return DION_OK;
 }
@@ -896,6 +911,53 @@ int dion_lazy_step(dion_state_t* st, void* X, const void* G, void* M, void* V, i
   void* qs[1] = {V};
   HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
   return lazy_rows(st, e.group, e.row - g.first_row, 1, mu, eta, refresh != 0, s);
+}
+
+int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* const* X, const void* const* G, void* const* M1,
+                     void* const* V1, void* const* M2, void* const* V2, void* const* D, const int64_t* m, const int64_t* n,
+                     const int64_t* r1, const int64_t* r2, float mu1, float mu2, float eta, void* hip_stream) {
+  if (!st1 || !st2 || count < 0) return DION_EINVAL;
+  if (count == 0) return DION_OK;
+  if (!D || st2->g_dtype != DION_G_F32) return DION_EINVAL;   // the sketch is an fp32 matrix
+  if (!batch_args_ok(st1, count, D, G, M1, V1, m, n, r1, mu1, eta)) return DION_EINVAL;
+  if (!batch_args_ok(st2, count, X, (const void* const*)D, M2, V2, m, n, r2, mu2, eta)) return DION_EINVAL;
+  for (const Group& g : st1->groups) if (g.form != DION_FORM_STANDARD) return DION_EINVAL;
+  for (const Group& g : st2->groups) if (g.form != DION_FORM_STANDARD) return DION_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  st1->last_stream = st2->last_stream = s;
+  std::fill(st1->group_timed.begin(), st1->group_timed.end(), 0);
+  std::fill(st2->group_timed.begin(), st2->group_timed.end(), 0);
+  try {
+    std::vector<void*> xs(count), ms(count), qs(count);
+    std::vector<const void*> gs(count);
+    std::vector<int> rows1(count), rows2(count);
+    // stage 1: a Dion step of rank r1 on (M1, V1) whose "weights" are the sketch buffer D
+    for (int i = 0; i < count; ++i) {
+      const int row = st1->entries[i].row;
+      xs[row] = D[i]; gs[row] = G[i]; ms[row] = M1[i]; qs[row] = V1[i];
+      rows1[i] = row;
+      rows2[i] = st2->entries[i].row;
+    }
+    HIPCHK(launch_set_user_ptrs(st1->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    for (size_t gi = 0; gi < st1->groups.size(); ++gi) {
+      int rc = step_rows(st1, (int)gi, 0, st1->groups[gi].count, mu1, 0.f, s, STEP_SKETCH);
+      if (rc != DION_OK) return rc;
+    }
+    // stage 2: a Dion step of rank r2 on (X, M2, V2) with D as its gradient, skipped where stage 1 failed
+    HIPCHK(launch_copy_status_rows(st1->status, st2->status, count, rows1.data(), rows2.data(), s));
+    for (int i = 0; i < count; ++i) {
+      const int row = st2->entries[i].row;
+      xs[row] = X[i]; gs[row] = D[i]; ms[row] = M2[i]; qs[row] = V2[i];
+    }
+    HIPCHK(launch_set_user_ptrs(st2->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    for (size_t gi = 0; gi < st2->groups.size(); ++gi) {
+      int rc = step_rows(st2, (int)gi, 0, st2->groups[gi].count, mu2, eta, s, STEP_KEEP_STATUS);
+      if (rc != DION_OK) return rc;
+    }
+  } catch (const std::bad_alloc&) {
+    return DION_ENOMEM;
+  }
+  return DION_OK;
 }
 
 int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const void* const* G, void* const* M,

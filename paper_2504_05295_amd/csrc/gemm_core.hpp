@@ -44,6 +44,7 @@ struct EpilogueDesc {
   // EPI_UPDATE: M = (M+G) - c_m*acc ; X = X - c_x*acc2      (ld is the leading dimension n)
   int slotX, slotG, slotM;
   float c_m, c_x;
+  int x_overwrite;      // EPI_UPDATE: X = -c_x*acc2, the old contents of X are not read
 };
 
 struct GemmArgs {
@@ -422,7 +423,7 @@ __global__ void __launch_bounds__(Cfg::NT) gemm_kernel(const GemmArgs g) {
           const float gv = GBF16 ? bf16_to_f32(gload<uint16_t>((const uint16_t*)Gp + idx)) : gload<float>((const float*)Gp + idx);
           const float bv = gload<float>(Mp + idx) + gv;
           gstore<float>(Mp + idx, bv - g.E.c_m * acc[i][j][v]);
-          if constexpr (DUAL) gstore<float>(Xp + idx, gload<float>(Xp + idx) - g.E.c_x * acc2[i][j][v]);
+          if constexpr (DUAL) gstore<float>(Xp + idx, (g.E.x_overwrite ? 0.f : gload<float>(Xp + idx)) - g.E.c_x * acc2[i][j][v]);
         }
   }
 }

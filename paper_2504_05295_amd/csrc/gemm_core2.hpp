@@ -369,7 +369,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
           idx[p] = (long long)row * g.E.ld + col;
           mv[p] = gload<f32x4_t>(Mp + idx[p]);
-          if constexpr (DUAL) xv[p] = gload<f32x4_t>(Xp + idx[p]);
+          if constexpr (DUAL) xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : gload<f32x4_t>(Xp + idx[p]);
           if constexpr (GBF16) {
             const u32x2_t w = gload<u32x2_t>((const uint16_t*)Gp + idx[p]);
             gv[p] = f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};

@@ -78,6 +78,11 @@ hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);      
 hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
                                 void* const* M, void* const* Q, hipStream_t s);
 // count_slot >= 0: also adds one to the 64-bit word number count_index of that slot (a launch counter kept on the device)
+// dst_status[dst_rows[i]] = 2 where src_status[src_rows[i]] != 0, else 0, for i < count (row lists are host arrays)
+hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,
+                                   hipStream_t s);
+// M += G (fp32 G) for the matrices whose status word is exactly 1
+hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, long long count, hipStream_t s);
 hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
                        int count_slot = -1, int count_index = 0);
 // out <- in unless *status != 0 (both 16-byte aligned)

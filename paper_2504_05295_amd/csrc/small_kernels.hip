@@ -33,6 +33,49 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
   return hipSuccess;
 }
 
+// status[dst_row[i]] = other_status[src_row[i]]: the second stage of a Double Dion step starts from the outcome of the
+// first (a matrix that failed there is skipped here as well)
+struct RowPairChunk {
+  int src[96], dst[96];
+  int count;
+};
+__global__ void copy_status_rows_kernel(const int* src_status, int* dst_status, const RowPairChunk c) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < c.count) dst_status[c.dst[t]] = src_status[c.src[t]] != 0 ? 2 : 0;   // 2: failed before this stage began
+}
+hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,
+                                   hipStream_t s) {
+  for (int done = 0; done < count; done += 96) {
+    RowPairChunk c;
+    c.count = (count - done < 96) ? count - done : 96;
+    for (int i = 0; i < c.count; ++i) { c.src[i] = src_rows[done + i]; c.dst[i] = dst_rows[done + i]; }
+    hipLaunchKernelGGL(copy_status_rows_kernel, dim3(1), dim3(128), 0, s, src_status, dst_status, c);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// Second stage of a Double Dion step that broke down in its own orthonormalisation (status 1, not the 2 inherited
+// from the first stage): the momentum still takes in the sketch, M += G (G is the fp32 sketch), nothing else moves.
+__global__ void accumulate_failed_kernel(void* const* table, int nslots, long long count) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  if (*(const int*)tab[SLOT_STATUS] != 1) return;
+  f32x4_t* M = (f32x4_t*)tab[SLOT_M];
+  const f32x4_t* G = (const f32x4_t*)tab[SLOT_G];
+  const long long n4 = count >> 2;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) M[i] = M[i] + G[i];
+  if (blockIdx.x == 0 && threadIdx.x < (count & 3)) ((float*)M)[n4 * 4 + threadIdx.x] += ((const float*)G)[n4 * 4 + threadIdx.x];
+}
+hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, long long count, hipStream_t s) {
+  if (count <= 0 || batch <= 0) return hipSuccess;
+  long long blocks = (count / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(accumulate_failed_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, count);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- fills
 // count_slot >= 0: the 64-bit word at index count_index of that slot is incremented as well (once per matrix).
 __global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value, int count_slot,

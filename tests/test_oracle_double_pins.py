@@ -53,13 +53,37 @@ def test_full_rank_stage_one_passes_the_whole_buffer_on():
     assert np.abs(res["X"] - s2["X"]).max() < 1e-11
 
 
-def test_breakdown_in_either_stage_leaves_everything_untouched():
+def test_breakdown_handling():
     m, n, r1, r2 = 12, 10, 3, 4
     X, G, M1, V1, M2, V2 = problem(m, n, r1, r2, 5)
     bad1 = V1.copy(); bad1[:, 2] = bad1[:, 0]
     bad2 = V2.copy(); bad2[:, 3] = bad2[:, 1]
-    for a, b in ((bad1, V2), (V1, bad2)):
-        res = orc.double_dion_step(X, G, M1, a, M2, b, 0.99, 0.95, 0.01)
-        assert res["status"] == orc.STATUS_BREAKDOWN
-        assert np.array_equal(res["X"], X) and np.array_equal(res["M1"], M1) and np.array_equal(res["M2"], M2)
-        assert np.array_equal(res["V1"], a) and np.array_equal(res["V2"], b)
+    # stage 1 fails: nothing moves
+    res = orc.double_dion_step(X, G, M1, bad1, M2, V2, 0.99, 0.95, 0.01)
+    assert res["status"] == orc.STATUS_BREAKDOWN
+    assert np.array_equal(res["X"], X) and np.array_equal(res["M1"], M1) and np.array_equal(res["M2"], M2)
+    assert np.array_equal(res["V1"], bad1) and np.array_equal(res["V2"], V2)
+    # stage 2 fails: stage 1 has taken its (ordinary) step, M2 only accumulates the sketch, X and V2 are untouched
+    res = orc.double_dion_step(X, G, M1, V1, M2, bad2, 0.99, 0.95, 0.01)
+    assert res["status"] == orc.STATUS_BREAKDOWN
+    s1 = orc.dion_step(np.zeros((m, n)), G, M1, V1, 0.99, 0.0)
+    assert np.array_equal(res["M1"], s1["M"]) and np.array_equal(res["V1"], s1["Q"])
+    assert np.array_equal(res["X"], X) and np.array_equal(res["V2"], bad2)
+    assert np.array_equal(res["M2"], M2 + s1["P"] @ s1["R"].T)
+
+
+def test_cold_start_grows_m2_into_full_rank():
+    # from M2 = 0 the second stage sees a buffer of rank r1, 2 r1, ... and can only start once that reaches r2
+    m, n, r1, r2 = 20, 16, 2, 6
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((m, n))
+    M1, M2 = np.zeros((m, n)), np.zeros((m, n))
+    V1, _ = orc.col_norm(rng.standard_normal((n, r1)))
+    V2, _ = orc.col_norm(rng.standard_normal((n, r2)))
+    statuses = []
+    for t in range(5):
+        res = orc.double_dion_step(X, rng.standard_normal((m, n)), M1, V1, M2, V2, 0.9, 0.95, 0.01)
+        statuses.append(res["status"])
+        X, M1, V1, M2, V2 = res["X"], res["M1"], res["V1"], res["M2"], res["V2"]
+        assert np.linalg.matrix_rank(M2) == min((t + 1) * r1, n) or res["status"] == orc.STATUS_OK
+    assert statuses[:2] == [orc.STATUS_BREAKDOWN] * 2 and statuses[2:] == [orc.STATUS_OK] * 3
