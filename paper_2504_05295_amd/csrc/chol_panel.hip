@@ -1,6 +1,9 @@
-// One panel step of the blocked right-looking Cholesky factorisation used by Cholesky-QR (Appendix A),
-// fused into a single launch with no dependency between workgroups.
+// The r x r Cholesky factorisation of Cholesky-QR (Appendix A), blocked right-looking with 64-wide panels.
+// Two drivers share the code for the 64 x 64 diagonal block: one launch per panel with no dependency between
+// workgroups (below; large batches), and the whole factorisation in one launch with workgroups that hand
+// results on through flags (chol_stream_kernel further down; one to four matrices).
 //
+// One panel step as a single launch:
 // For the 64-wide panel starting at row/column k0 of the rp x rp Gram matrix C (lower triangle):
 //   L11 = chol(C11),  W11 = L11^-1                       (64 x 64)
 //   L21 = C21 W11^T                                       (rows below the diagonal block)

@@ -7,6 +7,8 @@
 //   K2  R = (M+G)^T P                    MFMA GEMM, transposing operand load
 //   K6  s_j = ||R_j||, d_j = 1/(s_j + eps);   K7  Q = R diag(d)
 //   K5  M = (M+G) - (1-mu) P R^T ;  X = X - eta sqrt(m/n) P Q^T     one fused pass
+// The stages are functions of their own (stage_k1, stage_orth, ...); the Dion step, its transposed form, the
+// Lazy-Dion step and the two stages of Double Dion are different sequences of them.
 #include <math.h>
 #include <string.h>
 

@@ -1,5 +1,5 @@
-// R = (M + G)^T P with bf16 operands on large tiles: A = fused sum transposed on its way into LDS (the
-// big matrices are still read along their rows), B = P^T (bf16).
+// R = (M + G)^T P with bf16 operands on large tiles: A = the fused sum, or the bf16 copy of it that K1 left in
+// memory, transposed on its way into LDS (the big matrices are still read along their rows), B = P^T (bf16).
 #include "gemm_core2.hpp"
 #include "internal.hpp"
 namespace dion {

@@ -1,7 +1,9 @@
 // Large-tile bf16 MFMA GEMM core for gfx950 (v_mfma_f32_32x32x16_bf16), used by the three big
 // products of the Dion step when the shapes are multiples of the tile:
-//   K1  Z = (M+G) Q          A = fused sum read along k,           B = Q^T  (bf16 copy, k contiguous)
-//   K2  R = (M+G)^T P        A = fused sum transposed into LDS,    B = P^T  (bf16 copy, k contiguous)
+//   K1  Z = (M+G) Q          A = fused sum read along k (its bf16 values can be kept in memory on the way),
+//                            B = Q^T  (bf16 copy, k contiguous)
+//   K2  R = (M+G)^T P        A = that bf16 copy (or the fused sum itself) transposed into LDS,
+//                            B = P^T  (bf16 copy, k contiguous)
 //   K5  M, X updates         A = P (bf16 copy), B = R, B2 = Q_new (bf16 copies), fused epilogue
 // Same conventions as gemm_core.hpp: C[i,j] = sum_k A(i,k) B(j,k), LDS tiles [row][k] with 16 bytes
 // of padding per row, register prefetch of the next k-slab while the MFMAs of the current one run.
