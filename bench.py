@@ -274,8 +274,28 @@ def main():
         "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
         "rooflines": rooflines,
     }
+    if args.workload == "C3a" and args.variant == "dion" and args.form == "standard" and not args.calibration_copy:
+        # the second configuration of the benchmark list (2048 x 2048, r = 512, 20 steps) lives in the Infinity Cache and
+        # is bound by launch latencies, so it is not the headline workload; its step times are reported alongside
+        also = {}
+        p = dict(uniq=p["uniq"], refresh_every=p["refresh_every"])   # drop the device buffers, keep the host inputs for the oracle
+        torch.cuda.empty_cache()
+        for tag in ("C2", "C2b"):
+            q = build_problem(inputs.CONFIGS[tag])
+            q["variant"], q["refresh_every"] = "dion", 1
+            for t in range(3):
+                do_step(q, t)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for t in range(20):
+                do_step(q, 3 + t)
+            torch.cuda.synchronize()
+            also[WORKLOAD_NAMES[tag]] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / 20, "steps": 20}
+            assert q["B"].dion_last_status(q["state"])[0] == 0
+            del q
+        out["also"] = also
     if not args.no_cpu_baseline and args.form == "standard":
-        out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=p["refresh_every"])
+        out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=max(1, args.refresh_every) if args.variant == "lazy" else 1)
     print(json.dumps(out))
 
 
