@@ -46,7 +46,7 @@ def build(verbose: bool = True, jobs: int | None = None) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(one, zip(srcs, objs)))
-    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB] + objs)
     if verbose:
         print("built", LIB)
     return LIB

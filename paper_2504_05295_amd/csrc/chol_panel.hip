@@ -451,7 +451,7 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   x.wflag = (gu64*)(p.sync + (long long)blockIdx.y * p.sync_stride);
   x.lflag = x.wflag + nb;
   x.abort_word = x.lflag + nb;
-  x.epoch = x.abort_word[1];   // launch counter, incremented by the kernel that cleared W before this launch
+  x.epoch = *p.step_counter * 8ull + (u64)p.pass;   // unique per launch: step counter kept on the device, pass within the step
   x.spin_limit = p.spin_limit;
   x.ld = p.rp;
   x.piv_lo = p.piv_lo;

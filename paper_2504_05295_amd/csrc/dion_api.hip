@@ -195,8 +195,8 @@ bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r,
   return true;
 }
 
-size_t header_bytes(int count) {
-  return align_up((size_t)count * NSLOTS * sizeof(void*), 256) + align_up((size_t)count * sizeof(int), 256);
+size_t header_bytes(int count) {   // pointer table, status words, step counter
+  return align_up((size_t)count * NSLOTS * sizeof(void*), 256) + align_up((size_t)count * sizeof(int), 256) + 256;
 }
 
 }  // namespace
@@ -209,6 +209,7 @@ struct dion_state {
   size_t ws_bytes;
   void** table;   // device, count * NSLOTS
   int* status;    // device, count ints (table-row order)
+  unsigned long long* step_counter;   // device: number of steps enqueued so far (tags the flags of the Cholesky kernel)
   hipStream_t last_stream;
   bool timing;
   int orth_mode;
@@ -254,7 +255,7 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 // three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
 // Cholesky factorisation and the triangular inverse stay in fp32.
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long rows, const GramPlan& gp, int slot_in,
-                int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, hipStream_t s) {
+                int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, int pass, hipStream_t s) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -300,8 +301,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
-  // (the same launch advances the launch counter of the single-launch Cholesky kernel)
-  HIPCHK(launch_fill(tab, NSLOTS, batch, SLOT_W, rr, 0.f, s, SLOT_SYNC, 2 * (rp / CHOL_NB) + 1));
+  // (W needs no clearing: its part above the block diagonal was zeroed at init and nothing ever writes there; the
+  // rest is overwritten in full by the factorisation kernels, the merges below or the first-order factor)
   // Second pass: the input is already orthonormal to about 1e-5, so its Gram matrix is I + E with tiny E
   // and chol(I + E)^-1 = I - Phi(E) + O(E^2): no factorisation needed.  The decision is taken on the device
   // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
@@ -332,6 +333,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ca.rp = rp;
     ca.pr = ca.pc = (batch == 1 && nb >= 16) ? 16 : 8;
     ca.piv_lo = piv_lo; ca.piv_hi = piv_hi;
+    ca.step_counter = st->step_counter;
+    ca.pass = pass;
     ca.spin_limit = st->chol_spin_limit;
     HIPCHK(launch_chol_stream(ca, batch, s));
   } else {
@@ -518,15 +521,15 @@ int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, 
     // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
     // leaves a factor with a condition number of a few hundred), then CholeskyQR2 on that.  The product of
     // the three triangular factors is still the QR factor.
-    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 1e-5f, c.s);
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 1e-5f, 1, c.s);
     if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_a, 0.f, 3.0e38f, c.big, false, 0.f, c.s);
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_a, 0.f, 3.0e38f, c.big, false, 0.f, 2, c.s);
     if (rc != DION_OK) return rc;
-    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_final, 0.1f, 10.f, c.big, true, 0.f, c.s);
+    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_final, 0.1f, 10.f, c.big, true, 0.f, 3, c.s);
   }
-  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 0.f, c.s);
+  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s);
   if (rc != DION_OK) return rc;
-  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_final, 0.1f, 10.f, c.big, true, 0.f, c.s);
+  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_final, 0.1f, 10.f, c.big, true, 0.f, 2, c.s);
 }
 
 // K5: M <- (M+G) - (1-mu) A B^T and X <- X - eta sqrt(m/n) A B2^T in one pass (A: m x r, B and B2: n x r).
@@ -579,13 +582,14 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
 // One Dion step (Algorithm 1 with the unsharded update rule) for the matrices of one shape group.
 // The two stages of a Double Dion step (Section 5.2) are such steps with a twist each:
 //   STEP_SKETCH     the X buffer is a scratch matrix that receives P R^T instead of a weight update (stage 1)
-//   STEP_KEEP_STATUS the status words are not cleared: they hold the outcome of stage 1 (stage 2)
+//   STEP_KEEP_STATUS the status words hold the outcome of stage 1; a breakdown of this stage's own still lets the
+//                    momentum take in the gradient (stage 2)
+// The status words are cleared by the kernel that refreshes the pointer table before the step.
 enum { STEP_PLAIN = 0, STEP_SKETCH = 1, STEP_KEEP_STATUS = 2 };
 int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s, int mode = STEP_PLAIN) {
   const RowCtx c = make_ctx(st, gi, row0, batch, s);
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
-  if (mode != STEP_KEEP_STATUS) HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
   STAGECHK(stage_k1(c, true));
@@ -619,7 +623,6 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   const RowCtx c = make_ctx(st, gi, row0, batch, s);
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
-  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (c.ev) st->group_timed[gi] = 1;
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
@@ -660,7 +663,6 @@ int transposed_rows(dion_state* st, int gi, int row0, int batch, float mu, float
   const RowCtx c = make_ctx(st, gi, row0, batch, s);
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
-  HIPCHK(launch_fill_i32(c.tab, NSLOTS, batch, SLOT_STATUS, 1, 0, s));
   if (c.ev) st->group_timed[gi] = 1;
   // stage names as in the standard step: "K2" is the product with B^T, "K1" the one with B
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
@@ -760,6 +762,7 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
     st->ws_bytes = workspace_bytes;
     st->table = (void**)st->ws;
     st->status = (int*)(st->ws + align_up((size_t)count * NSLOTS * sizeof(void*), 256));
+    st->step_counter = (unsigned long long*)((char*)st->status + align_up((size_t)count * sizeof(int), 256));
     st->last_stream = s;
     st->timing = false;
     st->orth_mode = DION_ORTH_CHOLQR2;
@@ -786,11 +789,11 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];
     }
-    if (count > 0) {
-      if (hipMemcpy(st->table, host.data(), host.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess) {
-        delete st;
-        return DION_ELAUNCH;
-      }
+    const unsigned long long zero = 0;
+    if (hipMemcpy(st->step_counter, &zero, sizeof(zero), hipMemcpyHostToDevice) != hipSuccess ||
+        (count > 0 && hipMemcpy(st->table, host.data(), host.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)) {
+      delete st;
+      return DION_ELAUNCH;
     }
   } catch (const std::bad_alloc&) {
     delete st;
@@ -809,6 +812,7 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 2), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_fill(tab, NSLOTS, g.count, SLOT_W, (long long)g.rp * g.rp, 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     const long long frows = g.form == DION_FORM_TRANSPOSED ? g.m : g.n;   // the factor is n x r, or m x r in the transposed form
     if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, frows, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_scale_cols(tab, NSLOTS, g.count, SLOT_Q, SLOT_Q, frows, (int)g.r, -1, -1, -1, s) != hipSuccess) return fail(DION_ELAUNCH);
@@ -833,7 +837,7 @@ int dion_step_batched(dion_state_t* st, int count, void* const* X, const void* c
       const int row = st->entries[i].row;
       xs[row] = X[i]; gs[row] = G[i]; ms[row] = M[i]; qs[row] = Q[i];
     }
-    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s, st->status, st->step_counter));
   } catch (const std::bad_alloc&) {
     return DION_ENOMEM;
   }
@@ -861,7 +865,7 @@ int dion_step(dion_state_t* st, void* X, const void* G, void* M, void* Q, int64_
   const void* gs[1] = {G};
   void* ms[1] = {M};
   void* qs[1] = {Q};
-  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
+  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s, st->status, st->step_counter));
   return any_step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
 }
 
@@ -883,7 +887,7 @@ int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const vo
       const int row = st->entries[i].row;
       xs[row] = X[i]; gs[row] = G[i]; ms[row] = M[i]; qs[row] = V[i];
     }
-    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s, st->status, st->step_counter));
   } catch (const std::bad_alloc&) {
     return DION_ENOMEM;
   }
@@ -911,7 +915,7 @@ int dion_lazy_step(dion_state_t* st, void* X, const void* G, void* M, void* V, i
   const void* gs[1] = {G};
   void* ms[1] = {M};
   void* qs[1] = {V};
-  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s));
+  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s, st->status, st->step_counter));
   return lazy_rows(st, e.group, e.row - g.first_row, 1, mu, eta, refresh != 0, s);
 }
 
@@ -940,7 +944,7 @@ int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* cons
       rows1[i] = row;
       rows2[i] = st2->entries[i].row;
     }
-    HIPCHK(launch_set_user_ptrs(st1->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    HIPCHK(launch_set_user_ptrs(st1->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s, st1->status, st1->step_counter));
     for (size_t gi = 0; gi < st1->groups.size(); ++gi) {
       int rc = step_rows(st1, (int)gi, 0, st1->groups[gi].count, mu1, 0.f, s, STEP_SKETCH);
       if (rc != DION_OK) return rc;
@@ -951,7 +955,7 @@ int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* cons
       const int row = st2->entries[i].row;
       xs[row] = X[i]; gs[row] = D[i]; ms[row] = M2[i]; qs[row] = V2[i];
     }
-    HIPCHK(launch_set_user_ptrs(st2->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s));
+    HIPCHK(launch_set_user_ptrs(st2->table, NSLOTS, 0, count, xs.data(), gs.data(), ms.data(), qs.data(), s, nullptr, st2->step_counter));
     for (size_t gi = 0; gi < st2->groups.size(); ++gi) {
       int rc = step_rows(st2, (int)gi, 0, st2->groups[gi].count, mu2, eta, s, STEP_KEEP_STATUS);
       if (rc != DION_OK) return rc;
@@ -991,7 +995,7 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
     const void* gs[1] = {G[i]};
     void* ms[1] = {M[i]};
     void* qs[1] = {Q[i]};
-    if (launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s) != hipSuccess) { rc = DION_ELAUNCH; break; }
+    if (launch_set_user_ptrs(st->table, NSLOTS, e.row, 1, xs, gs, ms, qs, s, st->status, st->step_counter) != hipSuccess) { rc = DION_ELAUNCH; break; }
     rc = any_step_rows(st, e.group, e.row - g.first_row, 1, mu, eta, s);
     ++retried;
   }

@@ -75,16 +75,16 @@ hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);      
 hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KS, B KS
 
 // Small kernels (small_kernels.hip).  All take the pointer table and a batch count.
+// status != nullptr: clears status[first_row .. first_row + count) as well; counter != nullptr: increments that word
 hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
-                                void* const* M, void* const* Q, hipStream_t s);
+                                void* const* M, void* const* Q, hipStream_t s, int* status, unsigned long long* counter);
 // count_slot >= 0: also adds one to the 64-bit word number count_index of that slot (a launch counter kept on the device)
 // dst_status[dst_rows[i]] = 2 where src_status[src_rows[i]] != 0, else 0, for i < count (row lists are host arrays)
 hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,
                                    hipStream_t s);
 // M += G (fp32 G) for the matrices whose status word is exactly 1
 hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, long long count, hipStream_t s);
-hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
-                       int count_slot = -1, int count_index = 0);
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
 // out <- in unless *status != 0 (both 16-byte aligned)
 hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
                              hipStream_t s);
@@ -123,9 +123,10 @@ struct CholPanelPtrs {
 };
 hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s);
 // The whole factorisation in one launch (tiles owned by pr x pc workgroups that hand results on through flags).
-// sync: per matrix 2 * rp / 64 + 2 64-bit words that were zero before the first launch: flags, the abort word,
-// and last a launch counter that the host has a kernel increment before every launch (on the device, so that a
-// captured graph can be replayed).  Every wait inside the kernel gives up after spin_limit polls.
+// sync: per matrix 2 * rp / 64 + 2 64-bit words that were zero before the first launch: flags and the abort word.
+// Flags are tagged with *step_counter * 8 + pass: the counter is a device word that a kernel increments once per
+// step (on the device, so that a captured graph can be replayed), pass (1..7) tells the launches of one step
+// apart.  Every wait inside the kernel gives up after spin_limit polls.
 // All pr * pc * batch workgroups must fit on the GPU at once.
 struct CholStreamArgs {
   float* C;
@@ -138,6 +139,8 @@ struct CholStreamArgs {
   long long sync_stride;   // 64-bit words between their flag arrays
   int rp, pr, pc;
   float piv_lo, piv_hi;
+  const unsigned long long* step_counter;
+  int pass;
   unsigned spin_limit;
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);

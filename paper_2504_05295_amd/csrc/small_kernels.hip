@@ -8,13 +8,17 @@ struct UserPtrChunk {
   void* p[48][4];
   int first_row, count, nslots;
 };
-__global__ void set_user_ptrs_kernel(void** table, const UserPtrChunk c) {
+// status != nullptr: the status words of these rows are cleared as well.  counter != nullptr: that 64-bit word is
+// incremented (once per step: the single-launch Cholesky kernel tags its flags with it).
+__global__ void set_user_ptrs_kernel(void** table, const UserPtrChunk c, int* status, unsigned long long* counter) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t == 0 && counter) *counter += 1ull;
+  if (status && t < c.count) status[c.first_row + t] = 0;
   if (t >= c.count * 4) return;
   table[(size_t)(c.first_row + t / 4) * c.nslots + (t % 4)] = c.p[t / 4][t % 4];
 }
 hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
-                                void* const* M, void* const* Q, hipStream_t s) {
+                                void* const* M, void* const* Q, hipStream_t s, int* status, unsigned long long* counter) {
   for (int done = 0; done < count; done += 48) {
     UserPtrChunk c;
     c.first_row = first_row + done;
@@ -26,7 +30,7 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
       c.p[i][SLOT_M] = M[done + i];
       c.p[i][SLOT_Q] = Q[done + i];
     }
-    hipLaunchKernelGGL(set_user_ptrs_kernel, dim3(1), dim3(256), 0, s, table, c);
+    hipLaunchKernelGGL(set_user_ptrs_kernel, dim3(1), dim3(256), 0, s, table, c, status, done == 0 ? counter : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -77,22 +81,16 @@ hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, l
 }
 
 // ---------------------------------------------------------------- fills
-// count_slot >= 0: the 64-bit word at index count_index of that slot is incremented as well (once per matrix).
-__global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value, int count_slot,
-                            int count_index) {
+__global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value) {
   float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (long long)gridDim.x * blockDim.x)
     p[i] = value;
-  if (count_slot >= 0 && blockIdx.x == 0 && threadIdx.x == 0)
-    ((unsigned long long*)table[(size_t)blockIdx.y * nslots + count_slot])[count_index] += 1ull;
 }
-hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s,
-                       int count_slot, int count_index) {
+hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s) {
   if (count <= 0 || batch <= 0) return hipSuccess;
   long long blocks = (count + 1023) / 1024;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value, count_slot,
-                     count_index);
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, count, value);
   return hipGetLastError();
 }
 // out <- in (count floats, a multiple of 4) unless the matrix' status word says that the step has failed
