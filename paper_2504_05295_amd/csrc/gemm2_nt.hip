@@ -2,12 +2,17 @@
 // (hi,hi), (hi,lo), (lo,hi) of split-bf16 operands this evaluates an fp32-grade product on the bf16
 // matrix pipe; used for the Gram matrix and the triangular multiply of Cholesky-QR (Appendix A).
 #include "gemm_core2.hpp"
+#include "gemm_core3.hpp"
 #include "internal.hpp"
 namespace dion {
 using NtBig = TileCfg2<256, 256, 64, 2, 4, 2, 1>;
 using NtMid = TileCfg2<128, 128, 64, 2, 2, 1, 2>;
 hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
-  if (cfg == G2_256x256) return launch_gemm2<NtBig, SRC2_BF16_KC, false, EPI_STORE, false>(g, batch, s);
+  if (cfg == G2_256x256) {
+    using Direct = TileCfg3<256, 256, 2, 4>;   // same tile, operands loaded straight into LDS
+    if (gemm3_fits<Direct>(g)) return launch_gemm3<Direct, false, EPI_STORE, false>(g, batch, s);
+    return launch_gemm2<NtBig, SRC2_BF16_KC, false, EPI_STORE, false>(g, batch, s);
+  }
   return launch_gemm2<NtMid, SRC2_BF16_KC, false, EPI_STORE, false>(g, batch, s);
 }
 int gemm2_nt_splitk(int cfg, const GemmArgs& g) {

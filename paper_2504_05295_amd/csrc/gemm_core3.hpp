@@ -1,0 +1,381 @@
+// bf16 x bf16 MFMA GEMM core for gfx950 whose operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions), for the products of the Dion
+// step whose operands are both bf16 matrices with k contiguous:
+//   the Gram matrix and the triangular multiply of Cholesky-QR (up to three split-bf16 operand pairs),
+//   the fused rank-r updates of M and X (A = P, B = R, B2 = Q_new).
+// Conventions as in gemm_core2.hpp: C[i,j] = sum_k A(i,k) B(j,k), same GemmArgs, same epilogues.
+//
+// LDS tile layout.  A direct load writes the 64 lanes' 16-byte chunks to 1 KB of consecutive LDS, so rows cannot
+// be padded; instead chunk kc of row r sits at chunk position kc ^ ((r >> 1) & 7) of its 128-byte row (BK = 64).
+// The lane decides which global chunk it fetches, so the permutation costs nothing on the way in, and on the way
+// out the 16 lanes that read one chunk column of 16 consecutive rows hit 16 different 16-byte bank groups.
+//
+// Pipeline: two LDS stages.  The loads of slab s+1 are issued when slab s starts; each wave waits for its own
+// loads before the one barrier per slab, which sits before the last k-step's MFMAs so that these and the first
+// fragment reads of the next slab cover it.  The waits on the loads are written by hand (s_waitcnt vmcnt): left
+// to the compiler, every LDS read would wait for all loads in flight, since it cannot tell their LDS
+// destinations apart.
+#pragma once
+#include "gemm_core.hpp"
+
+namespace dion {
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+struct TileCfg3 {
+  static constexpr int BM = BM_, BN = BN_, BK = 64;
+  static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NW = WAVES_M_ * WAVES_N_;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM_ / WAVES_M_, WTN = BN_ / WAVES_N_;
+  static constexpr int MI = WTM / 32, NI = WTN / 32;
+  static constexpr int A_BYTES = BM_ * BK * 2, B_BYTES = BN_ * BK * 2;
+  static constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW;   // 1 KB loads per wave and slab
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile does not divide over the waves");
+};
+
+// 64 lanes x 16 bytes: global (one address per lane) -> LDS [lds_addr, lds_addr + 1024).  The instruction takes
+// its LDS address from M0; lds_addr has to be in a scalar register when it gets here (the build fails otherwise).
+// Nothing in the statement writes a register that code outside it reads: the compiler does not look into an asm
+// statement, so it could not keep a dependent instruction the required number of wait states away.  (A
+// v_readfirstlane_b32 written here right after the compiler's own v_mov_b32 into its source read the old value.)
+__device__ __forceinline__ void load_to_lds_16_raw(unsigned lds_addr, const void* lane_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off"
+      :
+      : "s"(lds_addr), "v"(lane_addr)
+      : "memory");
+}
+#ifdef DION_GEMM3_BOUNDS
+// Checking build (test harness only): a lane whose 16 bytes do not lie inside [lo, hi) is counted and loads
+// nothing.
+__device__ unsigned long long dion_gemm3_bounds[2];
+__device__ unsigned int dion_gemm3_violations;
+__device__ unsigned long long dion_gemm3_first[64];
+__device__ __forceinline__ void load_to_lds_16(unsigned lds_addr, const void* lane_addr) {
+  const unsigned long long a = (unsigned long long)lane_addr;
+  const bool ok = a >= dion_gemm3_bounds[0] && a + 16 <= dion_gemm3_bounds[1] && lds_addr + 1024 <= 160 * 1024;
+  if (!ok) {
+    const unsigned n = atomicAdd(&dion_gemm3_violations, 1u);
+    if (n < 16) {
+      dion_gemm3_first[4 * n + 0] = a;
+      dion_gemm3_first[4 * n + 1] = 0;
+      dion_gemm3_first[4 * n + 2] = lds_addr;
+      dion_gemm3_first[4 * n + 3] = blockIdx.x * 1024ull + threadIdx.x;
+    }
+  }
+  if (ok) load_to_lds_16_raw(lds_addr, lane_addr);
+}
+#else
+__device__ __forceinline__ void load_to_lds_16(unsigned lds_addr, const void* lane_addr) { load_to_lds_16_raw(lds_addr, lane_addr); }
+#endif
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 1) & 7; }
+
+template <class Cfg, bool GBF16, int EPI, bool DUAL>
+__global__ void __launch_bounds__(Cfg::NT, 1) gemm3_kernel(const GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW;
+  constexpr int MI = Cfg::MI, NI = Cfg::NI, KSTEPS = BK / 16;
+  constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES;
+  constexpr int STAGE_BYTES = A_BYTES + B_BYTES * (DUAL ? 2 : 1);
+  constexpr int SP = 36;   // epilogue patch row stride in floats
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  int bid = blockIdx.x;
+  if (g.xcd_remap) {
+    const int per = gridDim.x >> 3;
+    bid = (bid & 7) * per + (bid >> 3);
+  }
+  const int ntile = g.tiles_m * g.tiles_n;
+  const int tile = bid % ntile;
+  int rest = bid / ntile;
+  const int ks = rest % g.splitk;
+  const int b = rest / g.splitk;
+  int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+  if (g.group_n > 0) {
+    const int gw = g.group_n * g.tiles_m;
+    const int cg = tile / gw;
+    const int first = cg * g.group_n;
+    const int width = min(g.group_n, g.tiles_n - first);
+    const int rem = tile - cg * gw;
+    tm = rem / width;
+    tn = first + rem % width;
+  }
+  if (g.lower_only && tn * BN > tm * BM + BM - 1) return;
+
+  void* const* tab = g.table + (size_t)b * g.nslots;
+  if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
+
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave % Cfg::WAVES_M, wn = wave / Cfg::WAVES_M;
+  const int lr = lane & 31, lk = lane >> 5;
+
+  // byte offset, inside its matrix, of the chunk this lane fetches in each of the wave's loads of a slab
+  unsigned aoff[Cfg::A_LOADS], boff[Cfg::B_LOADS];
+#pragma unroll
+  for (int q = 0; q < Cfg::A_LOADS; ++q) {
+    const int pos = (q * NW + wave) * 64 + lane;
+    const int row = pos >> 3, kc = (pos & 7) ^ lds_swizzle(row);
+    aoff[q] = (unsigned)(((long long)(row0 + row) * g.A.ld + kc * 8) * 2);
+  }
+#pragma unroll
+  for (int q = 0; q < Cfg::B_LOADS; ++q) {
+    const int pos = (q * NW + wave) * 64 + lane;
+    const int row = pos >> 3, kc = (pos & 7) ^ lds_swizzle(row);
+    boff[q] = (unsigned)(((long long)(col0 + row) * g.B.ld + kc * 8) * 2);
+  }
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
+  // The contraction is a list of k-slabs: nseg operand pairs, each contributing kseg_eff / BK slabs.
+  bool fast = false;
+  if constexpr (EPI == EPI_STORE && !DUAL) fast = g.fast_slot >= 0 && __builtin_amdgcn_readfirstlane(*(const int*)tab[g.fast_slot]) != 0;
+  const int nseg = fast ? 1 : (g.nseg > 0 ? g.nseg : 1);
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
+  const int slabs_per_seg = kseg_eff / BK;
+  const int total = nseg * slabs_per_seg;
+  const int s_begin = ks * g.k_per_split;
+  const int s_end = min(total, s_begin + g.k_per_split);
+  // Operand base addresses of the (up to three) operand pairs, read once and kept in scalar registers: a look-up
+  // in the pointer table inside the loop is a memory load, and the wait for it would also wait for every tile
+  // load in flight.  (Separate variables: an array indexed by the pair number would live in scratch memory.)
+  const int b_fixed = fast ? g.fast_b_slot : (g.nseg > 0 ? -1 : g.B.slot0);
+  const unsigned char* const A0 = (const unsigned char*)(tab[g.nseg > 0 ? g.segA[0] : g.A.slot0]);
+  const unsigned char* const A1 = nseg > 1 ? (const unsigned char*)(tab[g.segA[1]]) : A0;
+  const unsigned char* const A2 = nseg > 2 ? (const unsigned char*)(tab[g.segA[2]]) : A0;
+  const unsigned char* const B0 = (const unsigned char*)(tab[b_fixed >= 0 ? b_fixed : g.segB[0]]);
+  const unsigned char* const B1 = nseg > 1 ? (const unsigned char*)(tab[g.segB[1]]) : B0;
+  const unsigned char* const B2 = nseg > 2 ? (const unsigned char*)(tab[g.segB[2]]) : B0;
+  // running addresses of the next slab to be loaded, advanced by one slab per load
+  int ld_seg = slabs_per_seg > 0 ? s_begin / slabs_per_seg : 0;
+  int ld_k0 = (s_begin - ld_seg * slabs_per_seg) * BK;
+  const unsigned char* a_run = (ld_seg <= 0 ? A0 : ld_seg == 1 ? A1 : A2) + (size_t)ld_k0 * 2;
+  const unsigned char* b_run = (ld_seg <= 0 ? B0 : ld_seg == 1 ? B1 : B2) + (size_t)ld_k0 * 2;
+  const unsigned char* b2_run = DUAL ? (const unsigned char*)(tab[g.B2.slot0]) + (size_t)ld_k0 * 2 : nullptr;
+
+  auto issue = [&](int stage, const unsigned char* Ap, const unsigned char* Bp, const unsigned char* B2k) __attribute__((always_inline)) {
+    const unsigned la = lds0 + stage * STAGE_BYTES + wave_s * 1024;
+#pragma unroll
+    for (int q = 0; q < Cfg::A_LOADS; ++q) load_to_lds_16(la + q * NW * 1024, Ap + aoff[q]);
+#pragma unroll
+    for (int q = 0; q < Cfg::B_LOADS; ++q) load_to_lds_16(la + A_BYTES + q * NW * 1024, Bp + boff[q]);
+    if constexpr (DUAL) {
+#pragma unroll
+      for (int q = 0; q < Cfg::B_LOADS; ++q) load_to_lds_16(la + A_BYTES + B_BYTES + q * NW * 1024, B2k + boff[q]);
+    }
+  };
+
+  f32x16_t acc[MI][NI];
+  f32x16_t acc2[DUAL ? MI : 1][DUAL ? NI : 1];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      if constexpr (DUAL) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0.f;
+      }
+    }
+
+  // fragment of k-step kk: row r, chunk 2 kk + lk, at r * 128 + ((2 kk + lk) ^ swizzle(r)) * 16; the rows
+  // i * 32 + lr of one lane all have the swizzle of lr
+  const int sw = lds_swizzle(lr);
+  const int a_row_off = (wm * Cfg::WTM + lr) * 128, b_row_off = A_BYTES + (wn * Cfg::WTN + lr) * 128;
+  bf16x8_t af[2][MI], bf[2][NI], bf2[2][DUAL ? NI : 1];
+  auto fetch = [&](int stage, int set, int kk) __attribute__((always_inline)) {
+    const unsigned char* sa = smem + stage * STAGE_BYTES + a_row_off;
+    const unsigned char* sb = smem + stage * STAGE_BYTES + b_row_off;
+    const int co = ((kk * 2 + lk) ^ sw) * 16;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[set][i] = *(const bf16x8_t*)(sa + i * 32 * 128 + co);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      bf[set][j] = *(const bf16x8_t*)(sb + j * 32 * 128 + co);
+      if constexpr (DUAL) bf2[set][j] = *(const bf16x8_t*)(sb + B_BYTES + j * 32 * 128 + co);
+    }
+  };
+  auto mma = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bf[set][j], acc[i][j], 0, 0, 0);
+        if constexpr (DUAL) acc2[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bf2[set][j], acc2[i][j], 0, 0, 0);
+      }
+  };
+  // schedule of one k-step: MFMA, LDS read, MFMA, LDS read, ... so that the fragments of the next k-step trickle
+  // in behind the MFMAs of this one
+  auto interleave = [&]() __attribute__((always_inline)) {
+    constexpr int READS = MI + NI * (DUAL ? 2 : 1), MMAS = MI * NI * (DUAL ? 2 : 1);
+    static_assert(MMAS >= READS, "fewer MFMAs than fragment reads");
+#pragma unroll
+    for (int q = 0; q < READS; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    if constexpr (MMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MMAS - READS, 0);
+  };
+
+  // loads of the next slab into the given stage; then the running addresses move on
+#define DION_GEMM3_ISSUE(stage)                                                                        \
+  do {                                                                                                 \
+    issue((stage), a_run, b_run, b2_run);                                                              \
+    a_run += BK * 2;                                                                                   \
+    b_run += BK * 2;                                                                                   \
+    if constexpr (DUAL) b2_run += BK * 2;                                                              \
+    ld_k0 += BK;                                                                                       \
+    if (ld_k0 == kseg_eff && ld_seg + 1 < nseg) {                                                      \
+      ld_k0 = 0;                                                                                       \
+      ++ld_seg;                                                                                        \
+      a_run = ld_seg == 1 ? A1 : A2;                                                                   \
+      b_run = ld_seg == 1 ? B1 : B2;                                                                   \
+    }                                                                                                  \
+  } while (0)
+  if (s_begin < s_end) {
+    DION_GEMM3_ISSUE(0);
+    wait_all_loads();
+  }
+  __syncthreads();
+  if (s_begin < s_end) {
+    fetch(0, 0, 0);
+    int cur = 0;
+    for (int sl = s_begin; sl < s_end; ++sl) {
+      if (sl + 1 < s_end) DION_GEMM3_ISSUE(cur ^ 1);
+#pragma unroll
+      for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
+        fetch(cur, (kk + 1) & 1, kk + 1);
+        mma(kk & 1);
+        interleave();
+      }
+      wait_all_loads();        // this wave's part of the next slab has landed
+      __syncthreads();         // ... everybody's has, and everybody has read the last fragments of this slab
+      fetch(cur ^ 1, KSTEPS & 1, 0);   // (after the last slab this reads stale data that nobody uses)
+      mma((KSTEPS - 1) & 1);
+      interleave();
+      cur ^= 1;
+    }
+  }
+#undef DION_GEMM3_ISSUE
+  __syncthreads();   // the operand tiles are dead from here on: the epilogue reuses their LDS
+
+  // ---- epilogue (as in gemm_core2.hpp): each 32x32 accumulator tile goes through a wave-private LDS patch so
+  // that a lane ends up with four consecutive columns of one row.
+  float* patch = (float*)smem + wave * 32 * SP;
+  const int prow = lane >> 3, pcol = (lane & 7) * 4;
+  auto to_patch = [&](const f32x16_t& t) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) patch[(8 * (v / 4) + 4 * lk + (v % 4)) * SP + lr] = t[v];
+  };
+  if constexpr (EPI == EPI_STORE) {
+    float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        to_patch(acc[i][j]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+          f32x4_t v = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          if (fast) v = gload<f32x4_t>((const float*)tab[g.fast_addend_slot] + (long long)row * g.E.ld + col) - v;
+          gstore<f32x4_t>(C + (long long)row * g.E.ld + col, v);
+        }
+      }
+  } else {
+    // M <- (M + G) - (1-mu) (P R^T);   X <- X - eta sqrt(m/n) (P Q_new^T)
+    float* Xp = (float*)tab[g.E.slotX];
+    float* Mp = (float*)tab[g.E.slotM];
+    const void* Gp = tab[g.E.slotG];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        long long idx[4];
+        f32x4_t mv[4], xv[4], gv[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+          idx[p] = (long long)row * g.E.ld + col;
+          mv[p] = gload<f32x4_t>(Mp + idx[p]);
+          if constexpr (DUAL) xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : gload<f32x4_t>(Xp + idx[p]);
+          if constexpr (GBF16) {
+            const u32x2_t w = gload<u32x2_t>((const uint16_t*)Gp + idx[p]);
+            gv[p] = f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
+          } else {
+            gv[p] = gload<f32x4_t>((const float*)Gp + idx[p]);
+          }
+        }
+        to_patch(acc[i][j]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          gstore<f32x4_t>(Mp + idx[p], (mv[p] + gv[p]) - g.E.c_m * a4);
+        }
+        if constexpr (DUAL) {
+          to_patch(acc2[i][j]);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+            gstore<f32x4_t>(Xp + idx[p], xv[p] - g.E.c_x * a4);
+          }
+        }
+      }
+  }
+}
+
+// True when launch_gemm3 can take these arguments: tile-aligned shapes and operands small enough for the
+// 32-bit byte offsets of the direct loads.
+template <class Cfg>
+inline bool gemm3_fits(const GemmArgs& g) {
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  if (g.M % Cfg::BM || g.N % Cfg::BN || kseg % Cfg::BK || kseg <= 0) return false;
+  if (g.tri_k && Cfg::BN % Cfg::BK) return false;
+  if (g.A.ld % 8 || g.B.ld % 8) return false;                         // 16-byte aligned chunks
+  const long long lim = 1ll << 32;
+  return (long long)g.M * g.A.ld * 2 < lim && (long long)g.N * g.B.ld * 2 < lim;
+}
+
+template <class Cfg, bool GBF16, int EPI, bool DUAL>
+inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
+  if (!gemm3_fits<Cfg>(g)) return hipErrorInvalidValue;
+  if (DUAL && g.B2.ld != g.B.ld) return hipErrorInvalidValue;          // B2 is fetched with B's offsets
+  const int kseg = g.nseg > 0 ? g.kseg : g.K;
+  g.tiles_m = g.M / Cfg::BM;
+  g.tiles_n = g.N / Cfg::BN;
+  if (g.splitk < 1) g.splitk = 1;
+  const int total = (g.nseg > 0 ? g.nseg : 1) * (kseg / Cfg::BK);
+  if (g.splitk > total) g.splitk = total;
+  g.k_per_split = (total + g.splitk - 1) / g.splitk;
+  g.splitk = (total + g.k_per_split - 1) / g.k_per_split;
+  const long long blocks = (long long)g.tiles_m * g.tiles_n * g.splitk * batch;
+  if (blocks <= 0) return hipSuccess;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
+  constexpr int STAGE_BYTES = Cfg::A_BYTES + Cfg::B_BYTES * (DUAL ? 2 : 1);
+  constexpr int PATCH_BYTES = Cfg::NW * 32 * 36 * (int)sizeof(float);
+  constexpr int LDS_BYTES = 2 * STAGE_BYTES > PATCH_BYTES ? 2 * STAGE_BYTES : PATCH_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the LDS");
+  // more than 64 KB of dynamic LDS has to be allowed once per kernel and device
+  static bool allowed[16] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  if (!allowed[dev]) {
+    e = hipFuncSetAttribute((const void*)gemm3_kernel<Cfg, GBF16, EPI, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    allowed[dev] = true;
+  }
+  hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL>), dim3((unsigned)blocks), dim3(Cfg::NT), LDS_BYTES, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace dion
