@@ -58,6 +58,8 @@ struct Group {
   int first_row, count;
   GramPlan gram_m, gram_n;   // Gram products over the m x r matrices of a Dion step / the n x r ones of a Lazy-Dion refresh
   int k12_splitk;     // split-K of K1 / K2 on the large-tile path when their outputs have too few tiles
+  bool direct12;      // K1 / K2 may read bf16(M + G) and its transpose from memory (direct-load kernels): the shape
+                      // fills the GPU with 256 x 256 tiles and the copies fit the kernels' 32-bit offsets
   size_t bytes_per_entry;
   Carve carve;     // slot offsets inside one matrix' share of the workspace
   size_t ws_off;   // offset of the group's first matrix in the workspace (set by dion_init_state)
@@ -97,10 +99,12 @@ void plan_gram(Group& g) {
   g.gram_n = plan_gram_rows(g, g.n);
   // K1 (m x r output) and K2 (n x r output) on 128x128 tiles: split the contraction until about 512 workgroups exist
   g.k12_splitk = 1;
+  g.direct12 = false;
   if (g.m % 256 == 0 && g.n % 256 == 0 && g.r % 128 == 0) {
     const long long tiles = std::min(g.m, g.n) / 128 * (g.r / 128) * g.count;
     const bool big_tiles = g.r % 256 == 0 && (std::min(g.m, g.n) / 256) * (g.r / 256) * g.count >= 128;
     if (!big_tiles && tiles < 512) g.k12_splitk = (int)std::min<long long>(8, (512 + tiles - 1) / tiles);
+    g.direct12 = big_tiles && g.m * g.n * 2 < (1ll << 32);
   }
 }
 
@@ -142,6 +146,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
   take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 2));
   take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
+  take(SLOT_B16T, g.direct12 ? ((size_t)g.m * g.n + 1) / 2 : 0);
   c.total = pos;
   return c;
 }
@@ -449,6 +454,22 @@ int tile_cfg2(const RowCtx& c, long long Mo, long long No) {
   return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * c.batch >= 128) ? G2_256x256 : G2_128x128;
 }
 
+// Direct-load path of K1 and K2: both read bf16(M + G) from memory, K1 as m x n, K2 its transpose, so that both are
+// plain bf16 products with the contraction index contiguous in either operand.  Taken when the plan has the two
+// buffers and this call's batch still fills the GPU with 256 x 256 tiles.
+bool direct12(const RowCtx& c) {
+  const Group& g = *c.g;
+  return c.big && g.direct12 && tile_cfg2(c, g.m, g.r) == G2_256x256 && tile_cfg2(c, g.n, g.r) == G2_256x256;
+}
+// The bf16 copies of M + G for the K1 / K2 of this call (a no-op off the direct-load path); the transposed one only
+// when a K2 will run.
+int stage_b16(const RowCtx& c, bool with_transpose = true) {
+  if (!direct12(c)) return DION_OK;
+  HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, with_transpose ? SLOT_B16T : -1, c.g->m, c.g->n,
+                         c.s));
+  return DION_OK;
+}
+
 // K1: Z = (M+G) Q with Q (n x r, fp32) taken from slot_q.  keep_b16: the large-tile kernel also leaves bf16(M+G) in
 // SLOT_B16 for a K2 that follows.
 int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
@@ -462,6 +483,11 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
   if (c.big) {
     HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, -1, SLOT_QT16, n, r, c.s));
     a.B = opnd(SLOT_QT16, 0, n);
+    if (direct12(c)) {
+      a.A = opnd(SLOT_B16, 0, n);
+      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
+      return DION_OK;
+    }
     if (keep_b16) a.side_slot = SLOT_B16;
     const int c1 = tile_cfg2(c, m, r);
     if (c1 == G2_128x128 && g.k12_splitk > 1) {
@@ -491,8 +517,13 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true) {
   a.xcd_remap = 1;
   if (c.big) {
     // M + G was rounded to bf16 once, by K1, and is read back from there (2 bytes per element instead of 6)
-    if (from_b16) a.A = opnd(SLOT_B16, 0, n);
     a.B = opnd(SLOT_PT16, 0, m);
+    if (direct12(c)) {
+      a.A = opnd(SLOT_B16T, 0, m);
+      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
+      return DION_OK;
+    }
+    if (from_b16) a.A = opnd(SLOT_B16, 0, n);
     const int c2 = tile_cfg2(c, n, r);
     if (c2 == G2_128x128 && g.k12_splitk > 1) {
       a.splitk = g.k12_splitk; a.E.slot = SLOT_KPART; a.E.split_stride = (long long)n * r;
@@ -592,6 +623,7 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
+  STAGECHK(stage_b16(c));
   STAGECHK(stage_k1(c, true));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
@@ -626,6 +658,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (c.ev) st->group_timed[gi] = 1;
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
+  STAGECHK(stage_b16(c, refresh));
   if (refresh) {
     STAGECHK(stage_k1(c, true));                                                  // Z = B V
     if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, -1, SLOT_PT16, m, r, s));
@@ -666,6 +699,7 @@ int transposed_rows(dion_state* st, int gi, int row0, int batch, float mu, float
   if (c.ev) st->group_timed[gi] = 1;
   // stage names as in the standard step: "K2" is the product with B^T, "K1" the one with B
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
+  STAGECHK(stage_b16(c));
   if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Q, -1, SLOT_PT16, m, r, s));
   STAGECHK(stage_k2(c, SLOT_Q, false));                                           // R = B^T Vt   (n x r)
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
@@ -784,7 +818,7 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
       char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
       void** rowp = &host[(size_t)e.row * NSLOTS];
       for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_B16; ++sl) rowp[sl] = base + c.off[sl];
+      for (int sl = SLOT_QT16; sl <= SLOT_B16T; ++sl) rowp[sl] = base + c.off[sl];
       rowp[SLOT_STATUS] = st->status + e.row;
       rowp[SLOT_M] = M_dev[i];
       rowp[SLOT_Q] = Q_dev[i];

@@ -39,7 +39,8 @@ enum Slot {
   SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
-  SLOT_B16,    // bf16(M + G), m x n: written by K1 on its way, read by K2 (large-tile path)
+  SLOT_B16,    // bf16(M + G), m x n: A operand of K1 on the direct-load path; else written by K1 on its way for K2
+  SLOT_B16T,   // its transpose, n x m: A operand of K2 on the direct-load path
   NSLOTS = 32
 };
 
@@ -88,6 +89,9 @@ hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long
 // out <- in unless *status != 0 (both 16-byte aligned)
 hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
                              hipStream_t s);
+// out16 = bf16(M + G) as [rows][cols]; outT16 (if >= 0) = the same as [cols][rows]  (rows, cols multiples of 64)
+hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
+                           int slot_outT16, long long rows, long long cols, hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
 hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s);
