@@ -277,13 +277,17 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.A = opnd(SLOT_PT16, 0, rows);
     a.B = opnd(SLOT_PT16, 0, rows);
     a.lower_only = 1;
-    // 256x256 tiles when the lower triangle of such tiles fills at least half of the GPU (large batches, r = 4096),
-    // split over the rows once more if need be; else 128x128 tiles with a deeper split
+    // 256x256 tiles (direct-load kernel) when the lower triangle of such tiles, split over the rows as far as the
+    // partial-result buffer allows, fills at least half of the GPU and every split still has a contraction worth
+    // starting a pipeline for; else 128x128 tiles with a deeper split
     const long long t256 = r / 256, tiles256 = t256 * (t256 + 1) / 2 * batch;
-    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && tiles256 >= 128;
-    const int big_split = gram_big ? (int)std::min<long long>(gp.splitk2, (256 + tiles256 - 1) / tiles256) : 1;
+    const int big_split = tiles256 > 0 ? (int)std::min<long long>(gp.splitk2, (256 + tiles256 - 1) / tiles256) : 1;
+    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && tiles256 * big_split >= 128 && 3 * (rows / 64) / big_split >= 16;
     const int gcfg = gram_big ? G2_256x256 : G2_128x128;
     a.splitk = gram_big ? big_split : gp.splitk2;
+    // consecutive tiles of one split on one XCD: they share the rows of the split and many operand panels, so an
+    // XCD's L2 fetches a fraction of what a round-robin placement makes it fetch
+    a.xcd_remap = gram_big ? 1 : 0;
     const int eff = gemm2_nt_splitk(gcfg, a);
     a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;

@@ -67,6 +67,7 @@ struct GemmArgs {
   // shape and leading dimension as C) from fast_addend_slot.  Used for out = in - in Phi^T when the triangular
   // factor is I - Phi with a tiny Phi: one bf16 product is then as good as the three-term split product.
   int fast_slot, fast_b_slot, fast_addend_slot;
+  int tri_grid;         // set by the direct-load launcher: lower_only grids hold the lower-triangle tiles only
   int side_slot;        // large-tile K1 only, >= 0: bf16(M + G) is also written there ([M][K] row-major, bf16)
   Operand A, B, B2;
   EpilogueDesc E;

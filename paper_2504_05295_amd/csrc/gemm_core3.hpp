@@ -88,13 +88,20 @@ __global__ void __launch_bounds__(Cfg::NT, 1) gemm3_kernel(const GemmArgs g) {
     const int per = gridDim.x >> 3;
     bid = (bid & 7) * per + (bid >> 3);
   }
-  const int ntile = g.tiles_m * g.tiles_n;
+  // tri_grid: the grid holds the tiles on and below the diagonal only (tile t -> row tm, column tn <= tm), so that
+  // no workgroup is launched just to return and the live ones spread evenly over the XCDs
+  const int ntile = g.tri_grid ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
   const int tile = bid % ntile;
   int rest = bid / ntile;
   const int ks = rest % g.splitk;
   const int b = rest / g.splitk;
   int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
-  if (g.group_n > 0) {
+  if (g.tri_grid) {
+    tm = (int)((__builtin_sqrtf(8.f * (float)tile + 1.f) - 1.f) * 0.5f);
+    while (tm * (tm + 1) / 2 > tile) --tm;
+    while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
+    tn = tile - tm * (tm + 1) / 2;
+  } else if (g.group_n > 0) {
     const int gw = g.group_n * g.tiles_m;
     const int cg = tile / gw;
     const int first = cg * g.group_n;
@@ -355,7 +362,9 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   if (g.splitk > total) g.splitk = total;
   g.k_per_split = (total + g.splitk - 1) / g.splitk;
   g.splitk = (total + g.k_per_split - 1) / g.k_per_split;
-  const long long blocks = (long long)g.tiles_m * g.tiles_n * g.splitk * batch;
+  g.tri_grid = (g.lower_only && Cfg::BM == Cfg::BN && g.tiles_m == g.tiles_n && g.group_n == 0) ? 1 : 0;
+  const long long ntile = g.tri_grid ? (long long)g.tiles_m * (g.tiles_m + 1) / 2 : (long long)g.tiles_m * g.tiles_n;
+  const long long blocks = ntile * g.splitk * batch;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
