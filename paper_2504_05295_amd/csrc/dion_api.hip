@@ -598,7 +598,7 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
     // short contractions spend a large share of the time in the epilogue, where nothing multiplies: 128x128 tiles
     // put two workgroups on a compute unit, so that one can multiply while the other streams M, G and X
     // (measured: 11 % faster at r = 512, 2 % at r = 1024, 5 % slower at r = 2048)
-    HIPCHK(gemm2_k5(r <= 1024 ? G2_128x128 : G2_256x256, c.gbf16, a, c.batch, c.s));
+    HIPCHK(gemm2_k5(r <= 512 ? G2_128x128 : G2_256x256, c.gbf16, a, c.batch, c.s));
   } else {
     a.A = opnd(a32, 0, r);
     a.B = opnd(b32, 0, r);

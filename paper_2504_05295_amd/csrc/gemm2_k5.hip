@@ -10,6 +10,11 @@ hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
   if (cfg == G2_256x256 && gemm3_fits<Direct>(g) && g.B2.ld == g.B.ld)
     return gbf16 ? launch_gemm3<Direct, true, EPI_UPDATE, true>(g, batch, s)
                  : launch_gemm3<Direct, false, EPI_UPDATE, true>(g, batch, s);
+  // small tiles: two four-wave workgroups per compute unit, so that one multiplies while the other streams M, G, X
+  using DirectMid = TileCfg3<128, 128, 2, 2, 32, 2>;
+  if (cfg == G2_128x128 && gemm3_fits<DirectMid>(g) && g.B2.ld == g.B.ld)
+    return gbf16 ? launch_gemm3<DirectMid, true, EPI_UPDATE, true>(g, batch, s)
+                 : launch_gemm3<DirectMid, false, EPI_UPDATE, true>(g, batch, s);
   if (cfg == G2_256x256)
     return gbf16 ? launch_gemm2<Big, SRC2_BF16_KC, true, EPI_UPDATE, true>(g, batch, s)
                  : launch_gemm2<Big, SRC2_BF16_KC, false, EPI_UPDATE, true>(g, batch, s);

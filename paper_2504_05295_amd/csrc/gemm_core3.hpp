@@ -6,7 +6,8 @@
 // Conventions as in gemm_core2.hpp: C[i,j] = sum_k A(i,k) B(j,k), same GemmArgs, same epilogues.
 //
 // LDS tile layout.  A direct load writes the 64 lanes' 16-byte chunks to 1 KB of consecutive LDS, so rows cannot
-// be padded; instead chunk kc of row r sits at chunk position kc ^ ((r >> 1) & 7) of its 128-byte row (BK = 64).
+// be padded; instead chunk kc of row r sits at chunk position kc ^ ((r >> 1) & 7) of its 128-byte row (BK = 64;
+// with BK = 32 a row has 64 bytes and the position is kc ^ ((r >> 2) & 3)).
 // The lane decides which global chunk it fetches, so the permutation costs nothing on the way in, and on the way
 // out the 16 lanes that read one chunk column of 16 consecutive rows hit 16 different 16-byte bank groups.
 //
@@ -20,9 +21,14 @@
 
 namespace dion {
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+// BK_: 64, or 32 for tiles small enough that two workgroups share a compute unit (MINW_ = waves per SIMD the
+// register budget is cut for: 2 means two four-wave workgroups per compute unit).
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int BK_ = 64, int MINW_ = 1>
 struct TileCfg3 {
-  static constexpr int BM = BM_, BN = BN_, BK = 64;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, MINW = MINW_;
+  static constexpr int CPR = BK_ / 8;     // 16-byte chunks per LDS row
+  static constexpr int ROWB = BK_ * 2;    // bytes per LDS row
+  static_assert(BK_ == 64 || BK_ == 32, "slab depth");
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NW = WAVES_M_ * WAVES_N_;
   static constexpr int NT = 64 * NW;
   static constexpr int WTM = BM_ / WAVES_M_, WTN = BN_ / WAVES_N_;
@@ -72,11 +78,14 @@ __device__ __forceinline__ void load_to_lds_16(unsigned lds_addr, const void* la
 #endif
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-__device__ __forceinline__ int lds_swizzle(int row) { return (row >> 1) & 7; }
+template <int CPR>
+__device__ __forceinline__ int lds_swizzle(int row) {
+  return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3;
+}
 
 template <class Cfg, bool GBF16, int EPI, bool DUAL>
-__global__ void __launch_bounds__(Cfg::NT, 1) gemm3_kernel(const GemmArgs g) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW;
+__global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, CPR = Cfg::CPR, ROWB = Cfg::ROWB;
   constexpr int MI = Cfg::MI, NI = Cfg::NI, KSTEPS = BK / 16;
   constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES * (DUAL ? 2 : 1);
@@ -125,13 +134,13 @@ __global__ void __launch_bounds__(Cfg::NT, 1) gemm3_kernel(const GemmArgs g) {
 #pragma unroll
   for (int q = 0; q < Cfg::A_LOADS; ++q) {
     const int pos = (q * NW + wave) * 64 + lane;
-    const int row = pos >> 3, kc = (pos & 7) ^ lds_swizzle(row);
+    const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
     aoff[q] = (unsigned)(((long long)(row0 + row) * g.A.ld + kc * 8) * 2);
   }
 #pragma unroll
   for (int q = 0; q < Cfg::B_LOADS; ++q) {
     const int pos = (q * NW + wave) * 64 + lane;
-    const int row = pos >> 3, kc = (pos & 7) ^ lds_swizzle(row);
+    const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
     boff[q] = (unsigned)(((long long)(col0 + row) * g.B.ld + kc * 8) * 2);
   }
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem);
@@ -190,21 +199,21 @@ __global__ void __launch_bounds__(Cfg::NT, 1) gemm3_kernel(const GemmArgs g) {
       }
     }
 
-  // fragment of k-step kk: row r, chunk 2 kk + lk, at r * 128 + ((2 kk + lk) ^ swizzle(r)) * 16; the rows
+  // fragment of k-step kk: row r, chunk 2 kk + lk, at r * ROWB + ((2 kk + lk) ^ swizzle(r)) * 16; the rows
   // i * 32 + lr of one lane all have the swizzle of lr
-  const int sw = lds_swizzle(lr);
-  const int a_row_off = (wm * Cfg::WTM + lr) * 128, b_row_off = A_BYTES + (wn * Cfg::WTN + lr) * 128;
+  const int sw = lds_swizzle<CPR>(lr);
+  const int a_row_off = (wm * Cfg::WTM + lr) * ROWB, b_row_off = A_BYTES + (wn * Cfg::WTN + lr) * ROWB;
   bf16x8_t af[2][MI], bf[2][NI], bf2[2][DUAL ? NI : 1];
   auto fetch = [&](int stage, int set, int kk) __attribute__((always_inline)) {
     const unsigned char* sa = smem + stage * STAGE_BYTES + a_row_off;
     const unsigned char* sb = smem + stage * STAGE_BYTES + b_row_off;
     const int co = ((kk * 2 + lk) ^ sw) * 16;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[set][i] = *(const bf16x8_t*)(sa + i * 32 * 128 + co);
+    for (int i = 0; i < MI; ++i) af[set][i] = *(const bf16x8_t*)(sa + i * 32 * ROWB + co);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      bf[set][j] = *(const bf16x8_t*)(sb + j * 32 * 128 + co);
-      if constexpr (DUAL) bf2[set][j] = *(const bf16x8_t*)(sb + B_BYTES + j * 32 * 128 + co);
+      bf[set][j] = *(const bf16x8_t*)(sb + j * 32 * ROWB + co);
+      if constexpr (DUAL) bf2[set][j] = *(const bf16x8_t*)(sb + B_BYTES + j * 32 * ROWB + co);
     }
   };
   auto mma = [&](int set) __attribute__((always_inline)) {
