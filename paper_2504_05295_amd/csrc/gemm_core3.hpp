@@ -306,44 +306,61 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
       }
   } else {
     // M <- (M + G) - (1-mu) (P R^T);   X <- X - eta sqrt(m/n) (P Q_new^T)
+    // The old M, X and G of the next 32x32 block are requested before the current block is written, so that a
+    // wave always has loads in flight: with one block at a time the pass is a chain of load latencies.
     float* Xp = (float*)tab[g.E.slotX];
     float* Mp = (float*)tab[g.E.slotM];
     const void* Gp = tab[g.E.slotG];
+    struct BlockIn {
+      f32x4_t mv[4], xv[4];
+      u32x4_t gw[4];   // G as loaded: four fp32 values, or four bf16 values in the first two words
+    };
+    auto block_index = [&](int t, int p) __attribute__((always_inline)) {
+      const int i = t / NI, j = t % NI;
+      const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+      const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+      return (long long)row * g.E.ld + col;
+    };
+    auto load_block = [&](int t, BlockIn& in) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        long long idx[4];
-        f32x4_t mv[4], xv[4], gv[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
-          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
-          idx[p] = (long long)row * g.E.ld + col;
-          mv[p] = gload<f32x4_t>(Mp + idx[p]);
-          if constexpr (DUAL) xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : gload<f32x4_t>(Xp + idx[p]);
-          if constexpr (GBF16) {
-            const u32x2_t w = gload<u32x2_t>((const uint16_t*)Gp + idx[p]);
-            gv[p] = f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
-          } else {
-            gv[p] = gload<f32x4_t>((const float*)Gp + idx[p]);
-          }
+      for (int p = 0; p < 4; ++p) {
+        const long long idx = block_index(t, p);
+        in.mv[p] = gload<f32x4_t>(Mp + idx);
+        if constexpr (DUAL) in.xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : gload<f32x4_t>(Xp + idx);
+        if constexpr (GBF16) {
+          const u32x2_t w = gload<u32x2_t>((const uint16_t*)Gp + idx);
+          in.gw[p] = u32x4_t{w[0], w[1], 0u, 0u};
+        } else {
+          in.gw[p] = gload<u32x4_t>((const float*)Gp + idx);
         }
-        to_patch(acc[i][j]);
+      }
+    };
+    auto g_value = [&](const u32x4_t& w) __attribute__((always_inline)) {
+      if constexpr (GBF16) return f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
+      else return __builtin_bit_cast(f32x4_t, w);
+    };
+    constexpr int NBLK = MI * NI;
+    BlockIn in[2];
+    load_block(0, in[0]);
+#pragma unroll
+    for (int t = 0; t < NBLK; ++t) {
+      if (t + 1 < NBLK) load_block(t + 1, in[(t + 1) & 1]);
+      const BlockIn& c = in[t & 1];
+      to_patch(acc[t / NI][t % NI]);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+        gstore<f32x4_t>(Mp + block_index(t, p), (c.mv[p] + g_value(c.gw[p])) - g.E.c_m * a4);
+      }
+      if constexpr (DUAL) {
+        to_patch(acc2[t / NI][t % NI]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          gstore<f32x4_t>(Mp + idx[p], (mv[p] + gv[p]) - g.E.c_m * a4);
-        }
-        if constexpr (DUAL) {
-          to_patch(acc2[i][j]);
-#pragma unroll
-          for (int p = 0; p < 4; ++p) {
-            const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-            gstore<f32x4_t>(Xp + idx[p], xv[p] - g.E.c_x * a4);
-          }
+          gstore<f32x4_t>(Xp + block_index(t, p), c.xv[p] - g.E.c_x * a4);
         }
       }
+    }
   }
 }
 
