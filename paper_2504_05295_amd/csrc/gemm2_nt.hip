@@ -1,6 +1,7 @@
 // Plain bf16 x bf16 products C = sum over operand pairs of A_s B_s^T on large tiles.  With the pairs
 // (hi,hi), (hi,lo), (lo,hi) of split-bf16 operands this evaluates an fp32-grade product on the bf16
-// matrix pipe; used for the Gram matrix and the triangular multiply of Cholesky-QR (Appendix A).
+// matrix pipe; used for the Gram matrix and the triangular multiply of Cholesky-QR (Appendix A).  With one
+// pair it is also K1 and K2 of the step on the direct-load path (A = bf16(M+G) or its transpose).
 #include "gemm_core2.hpp"
 #include "gemm_core3.hpp"
 #include "internal.hpp"

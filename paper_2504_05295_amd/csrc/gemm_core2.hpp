@@ -1,5 +1,8 @@
-// Large-tile bf16 MFMA GEMM core for gfx950 (v_mfma_f32_32x32x16_bf16), used by the three big
-// products of the Dion step when the shapes are multiples of the tile:
+// Register-staged bf16 MFMA GEMM core for gfx950 (v_mfma_f32_32x32x16_bf16): operand tiles go global ->
+// registers -> LDS, which lets an operand be transformed on the way (the fused sum M + G, a transposition).
+// Serves the big products of the Dion step when the shapes are multiples of the tile but the output has too few
+// 256-wide tiles to fill the GPU (128 x 128 tiles, split-K), and any shape the direct-load core
+// (gemm_core3.hpp) cannot take:
 //   K1  Z = (M+G) Q          A = fused sum read along k (its bf16 values can be kept in memory on the way),
 //                            B = Q^T  (bf16 copy, k contiguous)
 //   K2  R = (M+G)^T P        A = that bf16 copy (or the fused sum itself) transposed into LDS,
