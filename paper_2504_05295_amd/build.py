@@ -3,7 +3,8 @@
     python -m paper_2504_05295_amd.build
 
 Every .hip file under csrc/ is compiled to an object under _build/ (in parallel) and the objects
-are linked into paper_2504_05295_amd/libdion.so.
+are linked into paper_2504_05295_amd/libdion.so.  The checking program of the direct-load GEMM core
+(tests/native/gemm3_check.hip, run by a GPU test) is built next to its source.
 """
 from __future__ import annotations
 
@@ -17,6 +18,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libdion.so")
+CHECK_SRC = os.path.join(ROOT, "tests", "native", "gemm3_check.hip")
+CHECK_BIN = os.path.join(ROOT, "tests", "native", "gemm3_check")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -44,8 +47,14 @@ def build(verbose: bool = True, jobs: int | None = None) -> str:
             print(out)
         return obj
 
+    def check_program(_):
+        if os.path.exists(CHECK_SRC):
+            _run([HIPCC] + [f for f in FLAGS if f != "-fPIC"] + [CHECK_SRC, "-o", CHECK_BIN])
+
     with ThreadPoolExecutor(max_workers=jobs) as ex:
+        extra = ex.submit(check_program, None)
         list(ex.map(one, zip(srcs, objs)))
+        extra.result()
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB] + objs)
     if verbose:
         print("built", LIB)

@@ -55,8 +55,8 @@ __device__ __forceinline__ void load_to_lds_16_raw(unsigned lds_addr, const void
       : "memory");
 }
 #ifdef DION_GEMM3_BOUNDS
-// Checking build (test harness only): a lane whose 16 bytes do not lie inside [lo, hi) is counted and loads
-// nothing.
+// Checking build (the program tests/native/gemm3_check.hip only): a lane whose 16 bytes do not lie inside
+// [lo, hi) is counted and loads nothing.
 __device__ unsigned long long dion_gemm3_bounds[2];
 __device__ unsigned int dion_gemm3_violations;
 __device__ unsigned long long dion_gemm3_first[64];

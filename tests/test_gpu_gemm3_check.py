@@ -1,0 +1,35 @@
+"""The direct-load GEMM core in its bounds-checking build (tests/native/gemm3_check.hip): every direct load is
+tested against the address range of the operands, and the results against fp64 sums of small-integer inputs.
+Shapes: the triangular multiply and the fused update at the sizes of the benchmark configurations whose kernels
+these are (C3, C4 r=1024, C5 classes), plus small ones that exercise one and two operand pairs."""
+import os
+import subprocess
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+EXE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "native", "gemm3_check")
+
+CASES = [
+    ("nt", 16384, 1024, 1, 3),     # C4 r=1024: rows of Z, rank, triangular factor, three split-bf16 pairs
+    ("nt", 8192, 2048, 1, 3),      # C3
+    ("nt", 4096, 512, 0, 1),
+    ("nt", 4096, 512, 0, 2),
+    ("k5", 2048, 4096, 2048, 0, 1),
+    ("k5", 3072, 8192, 768, 4, 1),  # a C5 class, column groups of 4 tiles
+    ("k5", 8192, 3072, 2048, 2, 1),
+    ("k5", 3072, 8192, 512, 4, 0),  # 128-wide tiles, two workgroups per compute unit
+    ("k5", 1024, 1024, 512, 2, 0),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_direct_loads_stay_in_bounds_and_results_match(case):
+    if not os.path.exists(EXE):
+        pytest.fail("tests/native/gemm3_check is not built: run python -m paper_2504_05295_amd.build")
+    print("running", case, flush=True)
+    p = subprocess.run([EXE] + [str(x) for x in case], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=110)
+    print(p.stdout, flush=True)
+    assert "violations 0" in p.stdout
+    assert " bad 0" in p.stdout
+    assert p.returncode == 0
