@@ -791,6 +791,9 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
   for (int i = 0; i < count; ++i)
     if (!aligned16(M_dev[i]) || !aligned16(Q_dev[i])) return DION_EINVAL;
   hipStream_t s = (hipStream_t)hip_stream;
+  // kernels that use more than 64 KB of LDS are given leave to do so now, not at their first launch, which may
+  // be inside a stream capture
+  if (gemm2_nt_prepare() != hipSuccess || gemm2_k5_prepare() != hipSuccess) return DION_ELAUNCH;
   dion_state* st = nullptr;
   try {
     st = new dion_state();

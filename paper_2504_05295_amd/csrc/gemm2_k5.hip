@@ -21,4 +21,13 @@ hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
   return gbf16 ? launch_gemm2<Mid, SRC2_BF16_KC, true, EPI_UPDATE, true>(g, batch, s)
                : launch_gemm2<Mid, SRC2_BF16_KC, false, EPI_UPDATE, true>(g, batch, s);
 }
+hipError_t gemm2_k5_prepare() {
+  using Direct = TileCfg3<256, 128, 2, 4>;
+  using DirectMid = TileCfg3<128, 128, 2, 2, 32, 2>;
+  hipError_t e = gemm3_prepare<Direct, true, EPI_UPDATE, true>();
+  if (e == hipSuccess) e = gemm3_prepare<Direct, false, EPI_UPDATE, true>();
+  if (e == hipSuccess) e = gemm3_prepare<DirectMid, true, EPI_UPDATE, true>();
+  if (e == hipSuccess) e = gemm3_prepare<DirectMid, false, EPI_UPDATE, true>();
+  return e;
+}
 }  // namespace dion

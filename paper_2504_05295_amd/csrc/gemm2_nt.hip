@@ -16,6 +16,7 @@ hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
   }
   return launch_gemm2<NtMid, SRC2_BF16_KC, false, EPI_STORE, false>(g, batch, s);
 }
+hipError_t gemm2_nt_prepare() { return gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false>(); }
 int gemm2_nt_splitk(int cfg, const GemmArgs& g) {
   return cfg == G2_256x256 ? gemm2_effective_splitk<NtBig>(g) : gemm2_effective_splitk<NtMid>(g);
 }

@@ -377,6 +377,34 @@ inline bool gemm3_fits(const GemmArgs& g) {
   return (long long)g.M * g.A.ld * 2 < lim && (long long)g.N * g.B.ld * 2 < lim;
 }
 
+template <class Cfg, bool DUAL>
+constexpr int gemm3_lds_bytes() {
+  constexpr int STAGE_BYTES = Cfg::A_BYTES + Cfg::B_BYTES * (DUAL ? 2 : 1);
+  constexpr int PATCH_BYTES = Cfg::NW * 32 * 36 * (int)sizeof(float);
+  constexpr int LDS_BYTES = 2 * STAGE_BYTES > PATCH_BYTES ? 2 * STAGE_BYTES : PATCH_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the LDS");
+  return LDS_BYTES;
+}
+
+// More than 64 KB of dynamic LDS has to be allowed once per kernel and device.  The library does it for all its
+// instantiations when a state is created (that call must not end up inside a stream capture); the launcher
+// repeats it for a device it has not seen.
+template <class Cfg, bool GBF16, int EPI, bool DUAL>
+inline hipError_t gemm3_prepare() {
+  static bool allowed[16] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+  if (!allowed[dev]) {
+    e = hipFuncSetAttribute((const void*)gemm3_kernel<Cfg, GBF16, EPI, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            gemm3_lds_bytes<Cfg, DUAL>());
+    if (e != hipSuccess) return e;
+    allowed[dev] = true;
+  }
+  return hipSuccess;
+}
+
 template <class Cfg, bool GBF16, int EPI, bool DUAL>
 inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   if (!gemm3_fits<Cfg>(g)) return hipErrorInvalidValue;
@@ -395,21 +423,9 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
-  constexpr int STAGE_BYTES = Cfg::A_BYTES + Cfg::B_BYTES * (DUAL ? 2 : 1);
-  constexpr int PATCH_BYTES = Cfg::NW * 32 * 36 * (int)sizeof(float);
-  constexpr int LDS_BYTES = 2 * STAGE_BYTES > PATCH_BYTES ? 2 * STAGE_BYTES : PATCH_BYTES;
-  static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit the LDS");
-  // more than 64 KB of dynamic LDS has to be allowed once per kernel and device
-  static bool allowed[16] = {};
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
+  constexpr int LDS_BYTES = gemm3_lds_bytes<Cfg, DUAL>();
+  hipError_t e = gemm3_prepare<Cfg, GBF16, EPI, DUAL>();
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
-  if (!allowed[dev]) {
-    e = hipFuncSetAttribute((const void*)gemm3_kernel<Cfg, GBF16, EPI, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    allowed[dev] = true;
-  }
   hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL>), dim3((unsigned)blocks), dim3(Cfg::NT), LDS_BYTES, stream, g);
   return hipGetLastError();
 }

@@ -69,6 +69,9 @@ hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s, b
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 int gemm2_k1_splitk(int cfg, const GemmArgs& g);   // number of split-K partials the launch will write
 int gemm2_k2_splitk(int cfg, const GemmArgs& g);
+// dynamic-LDS permissions of the direct-load kernels on the current device (once per device; not inside a capture)
+hipError_t gemm2_nt_prepare();
+hipError_t gemm2_k5_prepare();
 hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s);   // bf16 A (KC) x bf16 B (KC), up to 3 operand pairs
 int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
