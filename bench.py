@@ -189,6 +189,7 @@ def main():
                          "orthonormalised factor shorter (transposed where n < m)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the two micro-kernels that measure this GPU's MFMA and streaming ceilings")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
@@ -259,6 +260,15 @@ def main():
         rooflines[name] = dict(bound=mdl["bound"], achieved=ach / div, peak=mdl["peak"] / div, unit=unit,
                                frac=ach / mdl["peak"], traffic=traffic.get(name), ms=ms,
                                tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
+    # measured ceilings of this GPU, in the same run: bf16 MFMA issue loop, 18-byte-per-element streaming pass
+    ceilings = None
+    if not args.no_ceilings:
+        scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        ceilings = B.dion_measure_ceilings(scratch)
+        del scratch
+        for name, rf in rooflines.items():
+            top = ceilings["mfma_tflops"] if rf["bound"] == "mfma" else ceilings["stream_gbps"]
+            rf["frac_of_measured"] = rf["achieved"] / top
     dominant = max(rooflines, key=lambda k: rooflines[k]["ms"]) if rooflines else None
     out = {
         "metric": "ms per Dion step per m x n matrix at rank r" if args.variant == "dion"
@@ -273,6 +283,7 @@ def main():
         "stage_ms": stages,
         "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
         "rooflines": rooflines,
+        "ceilings": ceilings,
     }
     if args.workload == "C3a" and args.variant == "dion" and args.form == "standard" and not args.calibration_copy:
         # the second configuration of the benchmark list (2048 x 2048, r = 512, 20 steps) lives in the Infinity Cache and

@@ -192,6 +192,19 @@ enum {
 int dion_set_stage_timing(dion_state_t* st, int enable);
 int dion_stage_times(dion_state_t* st, float* ms_out /* [DION_STAGE_COUNT] */);
 
+/* Measured ceilings of the GPU the calling thread has current, for quoting achieved rates against (the hot path's
+ * bounds are the bf16 matrix pipe for the products at r >= 1024 and HBM for the fused update at smaller r; see the
+ * step-time analysis around Figure 1 of the paper for the same split on its hardware):
+ *   *mfma_tflops  an issue-only loop of the bf16 matrix instruction the products use (no memory traffic),
+ *   *stream_gbps  a streaming pass with the traffic of the fused update: per element it reads fp32, bf16, fp32
+ *                 and writes fp32, fp32 (18 bytes), with 16-byte accesses.
+ * scratch_dev: device memory, 256-byte aligned, owned by the caller and overwritten; at least 10 MiB, and the
+ * streaming pass covers scratch_bytes / 10 elements, so give it more than the 256 MB Infinity Cache holds (1 GiB
+ * is what bench.py uses).  The call enqueues on hip_stream and waits for the result (host outputs).
+ * Errors: DION_EINVAL (null or misaligned arguments), DION_EWORKSPACE (scratch too small), DION_ELAUNCH. */
+int dion_measure_ceilings(void* scratch_dev, size_t scratch_bytes, double* mfma_tflops, double* stream_gbps,
+                          void* hip_stream);
+
 /* Test access to the intermediates of matrix `index` left in the workspace by the last step:
  * which = 0: Z (m x r; after a Lazy-Dion step: W), 1: P (m x r), 2: R (n x r), 3: column norms s (r),
  * 4: status word (int32), 5: the output of the first Cholesky-QR pass, 6 / 7 / 8: Gram matrix, its Cholesky

@@ -29,7 +29,7 @@ DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
            "dion_double_step", "dion_last_status",
-           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_measure_ceilings", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_wait_limit.argtypes = [C.c_void_p, C.c_uint]
         L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+        L.dion_measure_ceilings.argtypes = [C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
         L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
         L.dion_destroy_state.argtypes = [C.c_void_p]
         L.dion_strerror.argtypes = [C.c_int]
@@ -301,6 +302,17 @@ def dion_stage_times(state: DionState) -> dict:
     arr = (C.c_float * len(STAGES))()
     _check(lib().dion_stage_times(state.handle, arr), "dion_stage_times")
     return {k: float(arr[i]) for i, k in enumerate(STAGES)}
+
+
+def dion_measure_ceilings(scratch, stream=None) -> dict:
+    """Measured bf16 MFMA issue rate (TFLOP/s) and 18-byte-per-element streaming rate (GB/s) of the current GPU.
+    `scratch`: a uint8 device tensor (overwritten), 1 GiB or so."""
+    import torch
+    mf, st = C.c_double(0.0), C.c_double(0.0)
+    s = stream if stream is not None else torch.cuda.current_stream()
+    _check(lib().dion_measure_ceilings(C.c_void_p(scratch.data_ptr()), scratch.numel() * scratch.element_size(), C.byref(mf),
+                                       C.byref(st), C.c_void_p(s.cuda_stream)), "dion_measure_ceilings")
+    return {"mfma_tflops": float(mf.value), "stream_gbps": float(st.value)}
 
 
 def dion_debug_buffer(state: DionState, index: int, which: int):

@@ -1079,6 +1079,14 @@ int dion_set_wait_limit(dion_state_t* st, unsigned polls) {
   return DION_OK;
 }
 
+int dion_measure_ceilings(void* scratch_dev, size_t scratch_bytes, double* mfma_tflops, double* stream_gbps, void* hip_stream) {
+  if (!scratch_dev || ((uintptr_t)scratch_dev & 255u) || !mfma_tflops || !stream_gbps) return DION_EINVAL;
+  if (scratch_bytes < (size_t)10 * (1u << 20)) return DION_EWORKSPACE;
+  const long long elems = (long long)(scratch_bytes / 10);
+  if (run_ceiling_probes(scratch_dev, elems, mfma_tflops, stream_gbps, (hipStream_t)hip_stream) != hipSuccess) return DION_ELAUNCH;
+  return DION_OK;
+}
+
 int dion_set_stage_timing(dion_state_t* st, int enable) {
   if (!st) return DION_EINVAL;
   if (enable && st->events.empty()) {

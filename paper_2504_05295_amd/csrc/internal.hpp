@@ -69,6 +69,8 @@ hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s, b
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 int gemm2_k1_splitk(int cfg, const GemmArgs& g);   // number of split-K partials the launch will write
 int gemm2_k2_splitk(int cfg, const GemmArgs& g);
+// measured ceilings: bf16 MFMA issue loop (TFLOP/s) and an 18-byte-per-element streaming pass (GB/s); synchronises
+hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflops, double* stream_gbps, hipStream_t s);
 // dynamic-LDS permissions of the direct-load kernels on the current device (once per device; not inside a capture)
 hipError_t gemm2_nt_prepare();
 hipError_t gemm2_k5_prepare();

@@ -392,3 +392,16 @@ def test_captured_step_replays_like_eager_steps():
         assert B.dion_last_status(graphed.state) == (0, -1)
         for u, v in zip(eager.host(0), graphed.host(0)):
             assert np.array_equal(u, v), t
+
+
+def test_measured_ceilings_are_plausible():
+    import torch
+    from paper_2504_05295_amd import binding as B
+    scratch = torch.empty(1 << 29, dtype=torch.uint8, device="cuda")
+    c = B.dion_measure_ceilings(scratch)
+    print(c, flush=True)
+    # published peaks: 2500 TFLOP/s dense bf16, 8000 GB/s; a working MI355X delivers a good part of both
+    assert 500.0 < c["mfma_tflops"] < 2600.0
+    assert 1500.0 < c["stream_gbps"] < 8100.0
+    with pytest.raises(B.DionError):
+        B.dion_measure_ceilings(scratch[: 1 << 20])
