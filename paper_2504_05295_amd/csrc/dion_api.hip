@@ -412,7 +412,14 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.tri_k = 1;
     a.E.slot = slot_out; a.E.ld = r;
     a.xcd_remap = 1;
-    const int cfg = (rows % 256 == 0 && r % 256 == 0 && (rows / 256) * (r / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
+    int cfg = (rows % 256 == 0 && r % 256 == 0 && (rows / 256) * (r / 256) * batch >= 128) ? G2_256x256 : G2_128x128;
+    // One matrix whose 256-wide tiles make a single round of workgroups: the triangular factor makes the last
+    // column tile cost r / 256 times the first, and that one sets the time.  128-wide column tiles give two
+    // rounds, costliest first.
+    if (cfg == G2_256x256 && batch == 1 && (rows / 256) * (r / 256) <= 256 && (rows / 256) % 8 == 0) {
+      cfg = G2_256x128;
+      a.heavy_first = 1;
+    }
     HIPCHK(gemm2_nt(cfg, a, batch, s));
   } else {
     GemmArgs a = base;  // out = in W^T   (= in L^-T)

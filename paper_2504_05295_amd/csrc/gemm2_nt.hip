@@ -9,6 +9,13 @@ namespace dion {
 using NtBig = TileCfg2<256, 256, 64, 2, 4, 2, 1>;
 using NtMid = TileCfg2<128, 128, 64, 2, 2, 1, 2>;
 hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
+  if (cfg == G2_256x128) {
+    // narrower column tiles for the triangular multiply of a single matrix: twice as many workgroups as compute
+    // units, costliest first (GemmArgs::heavy_first), instead of one round in which the last column tile sets the time
+    using Narrow = TileCfg3<256, 128, 4, 2>;   // wave tiles of 64 x 64
+    if (gemm3_fits<Narrow>(g)) return launch_gemm3<Narrow, false, EPI_STORE, false>(g, batch, s);
+    cfg = G2_256x256;
+  }
   if (cfg == G2_256x256) {
     using Direct = TileCfg3<256, 256, 2, 4>;   // same tile, operands loaded straight into LDS
     if (gemm3_fits<Direct>(g)) return launch_gemm3<Direct, false, EPI_STORE, false>(g, batch, s);
@@ -16,7 +23,11 @@ hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
   }
   return launch_gemm2<NtMid, SRC2_BF16_KC, false, EPI_STORE, false>(g, batch, s);
 }
-hipError_t gemm2_nt_prepare() { return gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false>(); }
+hipError_t gemm2_nt_prepare() {
+  hipError_t e = gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false>();
+  if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 128, 4, 2>, false, EPI_STORE, false>();
+  return e;
+}
 int gemm2_nt_splitk(int cfg, const GemmArgs& g) {
   return cfg == G2_256x256 ? gemm2_effective_splitk<NtBig>(g) : gemm2_effective_splitk<NtMid>(g);
 }

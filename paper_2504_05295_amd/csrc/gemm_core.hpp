@@ -67,6 +67,9 @@ struct GemmArgs {
   // shape and leading dimension as C) from fast_addend_slot.  Used for out = in - in Phi^T when the triangular
   // factor is I - Phi with a tiny Phi: one bf16 product is then as good as the three-term split product.
   int fast_slot, fast_b_slot, fast_addend_slot;
+  int heavy_first;      // direct-load core, triangular B (tri_k): column tiles cost (tn + 1) units each; every XCD gets
+                        // tiles_m / 8 tile rows and visits their column tiles from the costliest down, so that the
+                        // second round of workgroups fills in behind the first (needs xcd_remap, one matrix, split-K 1)
   int tri_grid;         // set by the direct-load launcher: lower_only grids hold the lower-triangle tiles only
   int side_slot;        // large-tile K1 only, >= 0: bf16(M + G) is also written there ([M][K] row-major, bf16)
   Operand A, B, B2;

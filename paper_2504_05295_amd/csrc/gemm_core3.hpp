@@ -111,6 +111,11 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
     while (tm * (tm + 1) / 2 > tile) --tm;
     while ((tm + 1) * (tm + 2) / 2 <= tile) ++tm;
     tn = tile - tm * (tm + 1) / 2;
+  } else if (g.heavy_first) {
+    const int rows_per_xcd = g.tiles_m >> 3, per = rows_per_xcd * g.tiles_n;   // bid = xcd * per + position in the XCD
+    const int xcd = tile / per, pos = tile - xcd * per;
+    tm = xcd * rows_per_xcd + pos % rows_per_xcd;
+    tn = g.tiles_n - 1 - pos / rows_per_xcd;
   } else if (g.group_n > 0) {
     const int gw = g.group_n * g.tiles_m;
     const int cg = tile / gw;
@@ -423,6 +428,7 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
+  g.heavy_first = (g.heavy_first && g.xcd_remap && !g.tri_grid && g.group_n == 0 && g.splitk == 1 && batch == 1 && g.tiles_m % 8 == 0) ? 1 : 0;
   constexpr int LDS_BYTES = gemm3_lds_bytes<Cfg, DUAL>();
   hipError_t e = gemm3_prepare<Cfg, GBF16, EPI, DUAL>();
   if (e != hipSuccess) return e;

@@ -63,7 +63,7 @@ hipError_t gemm_k2(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hi
 hipError_t gemm_k5(int variant, bool bf16, bool gbf16, GemmArgs g, int batch, hipStream_t s);   // dual B, fused update
 // Large-tile bf16 versions (gemm_core2.hpp); `cfg` selects the tile, see gemm2_*.hip.  They return
 // hipErrorInvalidValue when the shape is not a multiple of the tile.
-enum { G2_256x256 = 0, G2_128x128 = 1 };
+enum { G2_256x256 = 0, G2_128x128 = 1, G2_256x128 = 2 };   // (the last one: gemm2_nt only)
 hipError_t gemm2_k1(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);
 hipError_t gemm2_k2(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s, bool from_bf16 = false);   // from_bf16: A = bf16 [K][M]
 hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s);

@@ -1,7 +1,8 @@
 // Checking program for the direct-load GEMM core (gemm_core3.hpp built with DION_GEMM3_BOUNDS): every direct
 // load is tested against the address range of an arena that holds all operands; a lane outside it is counted
 // and loads nothing.  Results are compared with fp64 sums on the host (small integer inputs: exact in bf16).
-//   gemm3_check nt  M r tri_k nseg        the triangular multiply / Gram form, 256x256 tiles, up to 3 operand pairs
+//   gemm3_check nt  M r tri_k nseg narrow the triangular multiply / Gram form, 256x256 tiles (or 256x128, costliest
+//                                         column tiles first, with narrow = 1), up to 3 operand pairs
 //   gemm3_check k5  m n r group_n big     the fused update, 256x128 tiles (big = 1) or 128x128 tiles (big = 0)
 // Prints "violations V" and "checked C bad B"; exit status 0 only when V = B = 0.
 #define DION_GEMM3_BOUNDS 1
@@ -73,10 +74,14 @@ static int run_nt(int argc, char** argv) {
   a.tri_k = tri;
   a.E.slot = S_OUT; a.E.ld = r;
   a.xcd_remap = 1;
+  const int narrow = argc > 5 ? atoi(argv[5]) : 0;   // 256x128 tiles, costliest column tiles first
   using Cfg = TileCfg3<256, 256, 2, 4>;
-  if (!gemm3_fits<Cfg>(a)) { printf("does not fit\n"); return 1; }
+  using Narrow = TileCfg3<256, 128, 4, 2>;
+  a.heavy_first = narrow;
+  if (narrow ? !gemm3_fits<Narrow>(a) : !gemm3_fits<Cfg>(a)) { printf("does not fit\n"); return 1; }
   printf("launching\n"); fflush(stdout);
-  CK((launch_gemm3<Cfg, false, EPI_STORE, false>(a, 1, 0)));
+  if (narrow) CK((launch_gemm3<Narrow, false, EPI_STORE, false>(a, 1, 0)));
+  else CK((launch_gemm3<Cfg, false, EPI_STORE, false>(a, 1, 0)));
   CK(hipDeviceSynchronize());
   unsigned viol = 0;
   CK(hipMemcpyFromSymbol(&viol, HIP_SYMBOL(dion_gemm3_violations), sizeof(viol)));

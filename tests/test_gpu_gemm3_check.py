@@ -15,6 +15,8 @@ CASES = [
     ("nt", 8192, 2048, 1, 3),      # C3
     ("nt", 4096, 512, 0, 1),
     ("nt", 4096, 512, 0, 2),
+    ("nt", 8192, 2048, 1, 3, 1),   # C3 again, 128-wide column tiles visited from the costliest down
+    ("nt", 16384, 1024, 1, 1, 1),
     ("k5", 2048, 4096, 2048, 0, 1),
     ("k5", 3072, 8192, 768, 4, 1),  # a C5 class, column groups of 4 tiles
     ("k5", 8192, 3072, 2048, 2, 1),
