@@ -296,18 +296,28 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   };
   if constexpr (EPI == EPI_STORE) {
     float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
+    // fast path (C = D - acc): D's address is looked up once, and a block's four row groups of D are requested
+    // before the block goes through the patch, so that the epilogue is not a chain of dependent loads
+    const float* D = fast ? (const float*)tab[g.fast_addend_slot] : nullptr;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        to_patch(acc[i][j]);
+        long long idx[4];
+        f32x4_t dv[4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
+          idx[p] = (long long)row * g.E.ld + col;
+          if (fast) dv[p] = gload<f32x4_t>(D + idx[p]);
+        }
+        to_patch(acc[i][j]);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
           f32x4_t v = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          if (fast) v = gload<f32x4_t>((const float*)tab[g.fast_addend_slot] + (long long)row * g.E.ld + col) - v;
-          gstore<f32x4_t>(C + (long long)row * g.E.ld + col, v);
+          if (fast) v = dv[p] - v;
+          gstore<f32x4_t>(C + idx[p], v);
         }
       }
   } else {
