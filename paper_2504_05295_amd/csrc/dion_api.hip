@@ -332,15 +332,28 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     pp.status = st->status + g.first_row + row0;
   }
   const int nb = rp / CHOL_NB;
-  if (batch <= 4 && nb >= 4 && nb <= 128) {
-    // one or a few matrices: the whole factorisation in one launch of at most 256 co-resident workgroups
+  // Workgroups per matrix for the single-launch driver: all of a launch must be resident at once (one per compute
+  // unit), so a batch shares the 256 compute units; from two workgroups per matrix on it still beats a launch per
+  // panel, in which every workgroup redoes the diagonal block and the second pass costs a launch per panel to skip.
+  int spr = 0, spc = 0;
+  {
+    const int per = 256 / (batch > 0 ? batch : 1);
+    if (per >= 256 && nb >= 16) { spr = 16; spc = 16; }
+    else if (per >= 64) { spr = 8; spc = 8; }
+    else if (per >= 16) { spr = 4; spc = 4; }
+    else if (per >= 8) { spr = 4; spc = 2; }
+    else if (per >= 4) { spr = 2; spc = 2; }
+    else if (per >= 2) { spr = 2; spc = 1; }
+  }
+  if (spr > 0 && nb >= 4 && nb <= 128) {
+    // the whole factorisation in one launch of at most 256 co-resident workgroups
     CholStreamArgs ca;
     ca.C = pp.C; ca.L = pp.L; ca.W = pp.W; ca.status = pp.status; ca.skip = pp.skip;
     ca.sync = (unsigned long long*)(st->ws + g.ws_off + (size_t)row0 * g.bytes_per_entry + g.carve.off[SLOT_SYNC]);
     ca.stride = pp.stride;
     ca.sync_stride = (long long)(g.bytes_per_entry / sizeof(unsigned long long));
     ca.rp = rp;
-    ca.pr = ca.pc = (batch == 1 && nb >= 16) ? 16 : 8;
+    ca.pr = spr; ca.pc = spc;
     ca.piv_lo = piv_lo; ca.piv_hi = piv_hi;
     ca.step_counter = st->step_counter;
     ca.pass = pass;
