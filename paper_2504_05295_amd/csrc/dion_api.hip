@@ -144,7 +144,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_EPART, 256);
   take(SLOT_FAST, 1);
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
-  take(SLOT_SYNC, 2 * (size_t)(2 * (g.rp / CHOL_NB) + 2));
+  take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
   take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
   take(SLOT_B16T, g.direct12 ? ((size_t)g.m * g.n + 1) / 2 : 0);
   c.total = pos;
@@ -265,6 +265,26 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
   GemmArgs base = rebase(base_args(st, g), row0);
+  const int nb = rp / CHOL_NB;
+  // Workgroups per matrix for the single-launch driver: all of a launch must be resident at once (one per compute
+  // unit), so a batch shares the 256 compute units; from two workgroups per matrix on it still beats a launch per
+  // panel, in which every workgroup redoes the diagonal block and the second pass costs a launch per panel to skip.
+  int spr = 0, spc = 0;
+  {
+    const int per = 256 / (batch > 0 ? batch : 1);
+    if (per >= 256 && nb >= 16) { spr = 16; spc = 16; }
+    else if (per >= 64) { spr = 8; spc = 8; }
+    else if (per >= 16) { spr = 4; spc = 4; }
+    else if (per >= 8) { spr = 4; spc = 2; }
+    else if (per >= 4) { spr = 2; spc = 2; }
+    else if (per >= 2) { spr = 2; spc = 1; }
+  }
+  const bool use_stream = spr > 0 && nb >= 4 && nb <= 128;
+  // The split-K partial Gram matrices of an adaptive pass are added up by its defect kernel, which reads the whole
+  // Gram matrix anyway (and stores the sum); other passes run a reduction kernel.  (Adding them up inside the
+  // single-launch factorisation, every workgroup its own tiles, was measured slower than that kernel.)
+  const bool sum_in_defect = adaptive && shift_rel == 0.f;
+  int c_nsplit = 1;
   // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
   if (split) {
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
@@ -293,7 +313,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.E.ld = rp;
     a.E.split_stride = rr;
     HIPCHK(gemm2_nt(gcfg, a, batch, s));
-    if (eff > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, eff, rr, s));
+    c_nsplit = eff;
   } else {
     GemmArgs a = base;
     a.M = r; a.N = r; a.K = (int)rows;
@@ -306,7 +326,11 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.E.ld = rp;
     a.E.split_stride = rr;
     HIPCHK(gemm_f32_tn(gp.variant, a, batch, s));
-    if (gp.splitk > 1) HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, gp.splitk, rr, s));
+    c_nsplit = gp.splitk;
+  }
+  if (c_nsplit > 1 && !sum_in_defect) {
+    HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, c_nsplit, rr, s));
+    c_nsplit = 1;
   }
   if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
@@ -317,7 +341,10 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
   // factorisation, otherwise they return at once.
   const int skip = adaptive ? SLOT_FAST : -1;
-  if (adaptive) HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? SLOT_WH16 : -1, s));
+  if (adaptive) {
+    HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? SLOT_WH16 : -1, c_nsplit, rr, s));
+    c_nsplit = 1;
+  }
   base.status_slot = skip;
   // blocked right-looking Cholesky, one fused launch per 64-wide panel.  The kernel gets the addresses of
   // its buffers as arguments: a look-up in the pointer table would cost it one more memory round trip.
@@ -331,21 +358,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     pp.stride = (long long)(g.bytes_per_entry / sizeof(float));
     pp.status = st->status + g.first_row + row0;
   }
-  const int nb = rp / CHOL_NB;
-  // Workgroups per matrix for the single-launch driver: all of a launch must be resident at once (one per compute
-  // unit), so a batch shares the 256 compute units; from two workgroups per matrix on it still beats a launch per
-  // panel, in which every workgroup redoes the diagonal block and the second pass costs a launch per panel to skip.
-  int spr = 0, spc = 0;
-  {
-    const int per = 256 / (batch > 0 ? batch : 1);
-    if (per >= 256 && nb >= 16) { spr = 16; spc = 16; }
-    else if (per >= 64) { spr = 8; spc = 8; }
-    else if (per >= 16) { spr = 4; spc = 4; }
-    else if (per >= 8) { spr = 4; spc = 2; }
-    else if (per >= 4) { spr = 2; spc = 2; }
-    else if (per >= 2) { spr = 2; spc = 1; }
-  }
-  if (spr > 0 && nb >= 4 && nb <= 128) {
+  if (use_stream) {
     // the whole factorisation in one launch of at most 256 co-resident workgroups
     CholStreamArgs ca;
     ca.C = pp.C; ca.L = pp.L; ca.W = pp.W; ca.status = pp.status; ca.skip = pp.skip;
@@ -364,9 +377,24 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
       HIPCHK(launch_chol_panel(pp, batch, k, rp, piv_lo, piv_hi, s));
   }
   // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]].
-  // Blocks start as the 64-wide inverses left by the panel kernel; an odd block is carried to the next level,
-  // so any multiple of 64 works.  Runs of equal, evenly spaced pairs go out as one launch.
-  {
+  // Blocks start as the 64-wide inverses left by the factorisation.
+  if (use_stream) {
+    // all levels in one launch, by the same number of co-resident workgroups as the factorisation had
+    InvTreeArgs ta;
+    char* e0 = st->ws + g.ws_off + (size_t)row0 * g.bytes_per_entry;
+    ta.L = pp.L; ta.W = pp.W; ta.T = (float*)(e0 + g.carve.off[SLOT_T]);
+    ta.status = pp.status; ta.skip = pp.skip;
+    ta.sync = (unsigned long long*)(e0 + g.carve.off[SLOT_SYNC]) + chol_sync_words(nb);
+    ta.stride = pp.stride;
+    ta.sync_stride = (long long)(g.bytes_per_entry / sizeof(unsigned long long));
+    ta.rp = rp;
+    ta.step_counter = st->step_counter;
+    ta.pass = pass;
+    ta.spin_limit = st->chol_spin_limit;
+    HIPCHK(launch_inv_tree(ta, spr * spc, batch, s));
+  } else {
+    // one launch per product: an odd block is carried to the next level, so any multiple of 64 works; runs of equal,
+    // evenly spaced pairs go out as one launch
     struct Blk { int off, size; };
     static_assert(32768 / CHOL_NB <= 512, "block list size");
     Blk cur[512], nxt[512];
@@ -872,7 +900,7 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
   for (auto& g : st->groups) {
     void* const* tab = st->table + (size_t)g.first_row * NSLOTS;
     if (launch_fill_i32(tab, NSLOTS, g.count, SLOT_STATUS, 1, 0, s) != hipSuccess) return fail(DION_ELAUNCH);
-    if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * (2 * (g.rp / CHOL_NB) + 2), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
+    if (launch_fill(tab, NSLOTS, g.count, SLOT_SYNC, 2 * sync_words(g.rp / CHOL_NB), 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     if (launch_fill(tab, NSLOTS, g.count, SLOT_W, (long long)g.rp * g.rp, 0.f, s) != hipSuccess) return fail(DION_ELAUNCH);
     const long long frows = g.form == DION_FORM_TRANSPOSED ? g.m : g.n;   // the factor is n x r, or m x r in the transposed form
     if (launch_colnorm(tab, NSLOTS, g.count, SLOT_Q, frows, (int)g.r, s) != hipSuccess) return fail(DION_ELAUNCH);

@@ -153,11 +153,33 @@ struct CholStreamArgs {
   unsigned spin_limit;
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
+// W = L^-1 from L and the inverses of its 64 x 64 diagonal blocks (both as the factorisation leaves them), one launch
+// for `batch` matrices with `groups` workgroups each; groups * batch must not exceed the number of compute units.
+constexpr int INV_TREE_MAX_GROUPS = 256;
+struct InvTreeArgs {
+  const float* L;
+  float* W;
+  float* T;                // scratch, rp x rp
+  int* status;
+  const int* skip;         // per matrix: non-zero = nothing to do (or nullptr)
+  unsigned long long* sync;   // per matrix INV_TREE_MAX_GROUPS arrival words + 1 abort word
+  long long stride;        // 4-byte words between the matrices of a batch (L, W, T, skip)
+  long long sync_stride;   // 64-bit words between their arrival words
+  int rp;
+  const unsigned long long* step_counter;
+  int pass;
+  unsigned spin_limit;
+};
+hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, hipStream_t s);
+// 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
+constexpr int chol_sync_words(int nb) { return 2 * nb + 2; }
+constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
 // identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
 // Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
-// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well.
+// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well.  nsplit > 1: C still is nsplit split-K partial
+// results in SLOT_CPART, split_stride words apart; their sum is formed (and stored to SLOT_C) here.
 hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
-                                      hipStream_t s);
+                                      int nsplit, long long split_stride, hipStream_t s);
 
 }  // namespace dion

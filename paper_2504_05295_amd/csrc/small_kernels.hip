@@ -427,15 +427,28 @@ hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot
 }
 
 // ---------------------------------------------------------------- first-order inverse Cholesky factor near the identity
-__global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, int nslots, int r, long long ld) {
+// nsplit > 1: the Gram matrix arrives as split-K partial results (SLOT_CPART, split_stride apart); their sum, taken in the
+// fixed order, is stored to SLOT_C on the way.
+__global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, int nslots, int r, long long ld, int nsplit,
+                                                          long long split_stride) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
-  const float* C = (const float*)tab[SLOT_C];
+  float* C = (float*)tab[SLOT_C];
+  const float* cpart = (const float*)tab[SLOT_CPART];
   float* part = (float*)tab[SLOT_EPART];
   __shared__ float red[256];
   float acc = 0.f;
   for (int i = blockIdx.x; i < r; i += gridDim.x)
     for (int j = threadIdx.x; j <= i; j += 256) {
-      const float e = C[(long long)i * ld + j] - (i == j ? 1.f : 0.f);
+      const long long idx = (long long)i * ld + j;
+      float c;
+      if (nsplit > 1) {
+        c = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) c += cpart[sp * split_stride + idx];
+        C[idx] = c;
+      } else {
+        c = C[idx];
+      }
+      const float e = c - (i == j ? 1.f : 0.f);
       acc += (i == j ? 1.f : 2.f) * e * e;
     }
   red[threadIdx.x] = acc;
@@ -480,8 +493,8 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
   }
 }
 hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
-                                      hipStream_t s) {
-  hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp);
+                                      int nsplit, long long split_stride, hipStream_t s) {
+  hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp, nsplit, split_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long blocks = ((long long)rp * rp + 2047) / 2048;
