@@ -342,7 +342,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   // factorisation, otherwise they return at once.
   const int skip = adaptive ? SLOT_FAST : -1;
   if (adaptive) {
-    HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? SLOT_WH16 : -1, c_nsplit, rr, s));
+    // (bf16 mode: decision only, see the product at the end)
+    HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? FIRST_ORDER_DECISION_ONLY : -1, c_nsplit, rr, s));
     c_nsplit = 1;
   }
   base.status_slot = skip;
@@ -438,11 +439,12 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   base.status_slot = -1;
   if (split) {
-    // (with the first-order factor W = I - Phi the kernel above has left Phi in SLOT_WH16 and the product below
-    // shrinks to out = in - hi(in) Phi^T: Phi is below 1e-3, so its bf16 rounding costs less than 4e-6 relative)
+    // (Adaptive pass whose input was found orthonormal to 1e-3: out = in, a plain copy by the same launch.  Both
+    // consumers of the result round it to bf16, whose unit roundoff is 2e-3 per entry, so not even the first-order
+    // correction in - in Phi^T, itself below 1e-3, would survive.)
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s, skip));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
-    if (adaptive) { a.fast_slot = SLOT_FAST; a.fast_b_slot = SLOT_WH16; a.fast_addend_slot = slot_in; }
+    if (adaptive) { a.fast_slot = SLOT_FAST; a.fast_b_slot = SLOT_WH16; a.fast_addend_slot = slot_in; a.fast_copy = 1; }
     a.M = (int)rows; a.N = r; a.K = 3 * r;
     a.nseg = 3; a.kseg = r;
     a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;

@@ -67,6 +67,7 @@ struct GemmArgs {
   // shape and leading dimension as C) from fast_addend_slot.  Used for out = in - in Phi^T when the triangular
   // factor is I - Phi with a tiny Phi: one bf16 product is then as good as the three-term split product.
   int fast_slot, fast_b_slot, fast_addend_slot;
+  int fast_copy;        // with the fast path taken: no product at all, C = D (the first-order term is dropped too)
   int heavy_first;      // direct-load core, triangular B (tri_k): column tiles cost (tn + 1) units each; every XCD gets
                         // tiles_m / 8 tile rows and visits their column tiles from the costliest down, so that the
                         // second round of workgroups fills in behind the first (needs xcd_remap, one matrix, split-K 1)

@@ -245,7 +245,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
   const int slabs_per_seg = kseg_eff / BK;
-  const int total = nseg * slabs_per_seg;
+  const int total = (fast && g.fast_copy) ? 0 : nseg * slabs_per_seg;
   const int s_begin = ks * g.k_per_split;                     // k_per_split counts slabs here
   const int s_end = min(total, s_begin + g.k_per_split);
   auto issue = [&](int sl, auto& xa, auto& xb, auto& xb2) __attribute__((always_inline)) {

@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
   const int slabs_per_seg = kseg_eff / BK;
-  const int total = nseg * slabs_per_seg;
+  const int total = (fast && g.fast_copy) ? 0 : nseg * slabs_per_seg;
   const int s_begin = ks * g.k_per_split;
   const int s_end = min(total, s_begin + g.k_per_split);
   // Operand base addresses of the (up to three) operand pairs, read once and kept in scalar registers: a look-up

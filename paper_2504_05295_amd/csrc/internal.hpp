@@ -177,8 +177,10 @@ constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GRO
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
 // identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
 // Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
-// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well.  nsplit > 1: C still is nsplit split-K partial
+// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well; FIRST_ORDER_DECISION_ONLY: only SLOT_FAST is
+// set, W is left alone either way.  nsplit > 1: C still is nsplit split-K partial
 // results in SLOT_CPART, split_stride words apart; their sum is formed (and stored to SLOT_C) here.
+constexpr int FIRST_ORDER_DECISION_ONLY = -2;
 hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
                                       int nsplit, long long split_stride, hipStream_t s);
 

@@ -473,7 +473,7 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
   __syncthreads();
   const bool fast = total <= tau2;   // false for NaN
   if (blockIdx.x == 0 && threadIdx.x == 0) *(int*)tab[SLOT_FAST] = fast ? 1 : 0;
-  if (!fast) return;
+  if (!fast || slot_phi16 == FIRST_ORDER_DECISION_ONLY) return;
   const float* C = (const float*)tab[SLOT_C];
   float* W = (float*)tab[SLOT_W];
   uint16_t* phi16 = slot_phi16 >= 0 ? (uint16_t*)tab[slot_phi16] : nullptr;   // Phi itself, r x r bf16
@@ -499,6 +499,7 @@ hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch,
   if (e != hipSuccess) return e;
   long long blocks = ((long long)rp * rp + 2047) / 2048;
   if (blocks > 1024) blocks = 1024;
+  if (slot_phi16 == FIRST_ORDER_DECISION_ONLY) blocks = 1;
   hipLaunchKernelGGL(first_order_inverse_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, r, rp, tau * tau,
                      slot_phi16);
   return hipGetLastError();
