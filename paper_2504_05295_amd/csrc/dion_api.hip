@@ -239,7 +239,7 @@ GemmArgs base_args(const dion_state* st, const Group& g) {
   a.splitk = 1;
   a.sub_count = 1;
   a.status_slot = -1;
-  a.fast_slot = a.fast_b_slot = a.fast_addend_slot = -1;
+  a.noop_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   return a;
@@ -439,12 +439,16 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   base.status_slot = -1;
   if (split) {
-    // (Adaptive pass whose input was found orthonormal to 1e-3: out = in, a plain copy by the same launch.  Both
-    // consumers of the result round it to bf16, whose unit roundoff is 2e-3 per entry, so not even the first-order
-    // correction in - in Phi^T, itself below 1e-3, would survive.)
+    // (Adaptive pass whose input was found orthonormal to 1e-3: the input is the result.  Both consumers of it round
+    // it to bf16, whose unit roundoff is 2e-3 per entry, so not even the first-order correction in - in Phi^T, itself
+    // below 1e-3, would survive.  Such a pass runs in place, slot_out == slot_in: the product reads the bf16 copies
+    // of its input, never the fp32 original, so it may overwrite that; and when the flag is set it has nothing to do.)
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s, skip));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
-    if (adaptive) { a.fast_slot = SLOT_FAST; a.fast_b_slot = SLOT_WH16; a.fast_addend_slot = slot_in; a.fast_copy = 1; }
+    if (adaptive) {
+      if (slot_out != slot_in) return DION_EINVAL;
+      a.noop_slot = SLOT_FAST;
+    }
     a.M = (int)rows; a.N = r; a.K = 3 * r;
     a.nseg = 3; a.kseg = r;
     a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;
@@ -596,25 +600,30 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true) {
 
 // Orthonormalisation of the rows x r matrices in slot_a; slot_b is a second buffer of that size.  The result
 // ends up in slot_final (CholeskyQR2: a -> b -> final, so final may be a; shifted CholeskyQR3: a -> b -> a ->
-// final, so final must not be a).
+// final, so final must not be a).  On the split-bf16 path the products read bf16 copies of their input, never the
+// fp32 original, so a pass may write where it reads: the first pass already writes to slot_final and the last,
+// adaptive one runs there in place, which leaves it nothing to do when it finds its input orthonormal enough.
 int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final) {
   dion_state* st = c.st;
   const Group& g = *c.g;
+  const bool in_place = c.big;
   int rc;
   // first pass: any positive finite pivot; last pass: the Gram matrix of a nearly orthonormal input has pivots near 1
   if (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) {
     // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
     // leaves a factor with a condition number of a few hundred), then CholeskyQR2 on that.  The product of
     // the three triangular factors is still the QR factor.
+    const int mid = in_place ? slot_final : slot_a;
     rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 1e-5f, 1, c.s);
     if (rc != DION_OK) return rc;
-    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_a, 0.f, 3.0e38f, c.big, false, 0.f, 2, c.s);
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, mid, 0.f, 3.0e38f, c.big, false, 0.f, 2, c.s);
     if (rc != DION_OK) return rc;
-    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_final, 0.1f, 10.f, c.big, true, 0.f, 3, c.s);
+    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 3, c.s);
   }
-  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s);
+  const int mid = in_place ? slot_final : slot_b;
+  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, mid, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s);
   if (rc != DION_OK) return rc;
-  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_final, 0.1f, 10.f, c.big, true, 0.f, 2, c.s);
+  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 2, c.s);
 }
 
 // K5: M <- (M+G) - (1-mu) A B^T and X <- X - eta sqrt(m/n) A B2^T in one pass (A: m x r, B and B2: n x r).

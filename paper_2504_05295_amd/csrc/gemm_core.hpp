@@ -62,12 +62,7 @@ struct GemmArgs {
   int tri_k;            // B is lower triangular: column tile tn only needs k < (tn+1)*BN of every segment
   int group_n;          // > 0: tiles are visited column group by column group (group_n column tiles wide, all row
                         // tiles inside a group before the next group), so the B panels of a group stay in L2
-  // Large-tile EPI_STORE kernels only.  fast_slot >= 0 and the int32 there non-zero: the product shrinks to the
-  // first operand pair with B taken from fast_b_slot, and the result is stored as C = D - acc with D (same
-  // shape and leading dimension as C) from fast_addend_slot.  Used for out = in - in Phi^T when the triangular
-  // factor is I - Phi with a tiny Phi: one bf16 product is then as good as the three-term split product.
-  int fast_slot, fast_b_slot, fast_addend_slot;
-  int fast_copy;        // with the fast path taken: no product at all, C = D (the first-order term is dropped too)
+  int noop_slot;        // large-tile kernels: >= 0 and the int32 there non-zero: the launch does nothing (like status_slot)
   int heavy_first;      // direct-load core, triangular B (tri_k): column tiles cost (tn + 1) units each; every XCD gets
                         // tiles_m / 8 tile rows and visits their column tiles from the costliest down, so that the
                         // second round of workgroups fills in behind the first (needs xcd_remap, one matrix, split-K 1)

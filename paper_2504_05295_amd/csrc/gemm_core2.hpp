@@ -239,19 +239,18 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
   const int lr = lane & 31, lk = lane >> 5;
 
   // The contraction is a list of k-slabs: nseg operand pairs, each contributing kseg_eff / BK slabs.
-  bool fast = false;
-  if constexpr (EPI == EPI_STORE && !DUAL) fast = g.fast_slot >= 0 && *(const int*)tab[g.fast_slot] != 0;   // uniform
-  const int nseg = fast ? 1 : (g.nseg > 0 ? g.nseg : 1);
+  if (g.noop_slot >= 0 && *(const int*)tab[g.noop_slot] != 0) return;   // uniform, before any barrier
+  const int nseg = g.nseg > 0 ? g.nseg : 1;
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
   const int slabs_per_seg = kseg_eff / BK;
-  const int total = (fast && g.fast_copy) ? 0 : nseg * slabs_per_seg;
+  const int total = nseg * slabs_per_seg;
   const int s_begin = ks * g.k_per_split;                     // k_per_split counts slabs here
   const int s_end = min(total, s_begin + g.k_per_split);
   auto issue = [&](int sl, auto& xa, auto& xb, auto& xb2) __attribute__((always_inline)) {
     const int seg = sl / slabs_per_seg, k0 = (sl - seg * slabs_per_seg) * BK;
     const void* Ap = tab[g.nseg > 0 ? g.segA[seg] : g.A.slot0];
-    const void* Bp = tab[fast ? g.fast_b_slot : (g.nseg > 0 ? g.segB[seg] : g.B.slot0)];
+    const void* Bp = tab[g.nseg > 0 ? g.segB[seg] : g.B.slot0];
     xa.load(Ap, A1, g.A.ld, row0, k0);
     xb.load(Bp, nullptr, g.B.ld, col0, k0);
     if constexpr (DUAL) xb2.load(B20, nullptr, g.B2.ld, col0, k0);
@@ -353,7 +352,6 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm2_kernel(const GemmArg
           const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
           f32x4_t v = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          if (fast) v = gload<f32x4_t>((const float*)tab[g.fast_addend_slot] + (long long)row * g.E.ld + col) - v;
           gstore<f32x4_t>(C + (long long)row * g.E.ld + col, v);
         }
       }

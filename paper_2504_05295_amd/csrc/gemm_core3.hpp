@@ -153,19 +153,18 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
   // The contraction is a list of k-slabs: nseg operand pairs, each contributing kseg_eff / BK slabs.
-  bool fast = false;
-  if constexpr (EPI == EPI_STORE && !DUAL) fast = g.fast_slot >= 0 && __builtin_amdgcn_readfirstlane(*(const int*)tab[g.fast_slot]) != 0;
-  const int nseg = fast ? 1 : (g.nseg > 0 ? g.nseg : 1);
+  if (g.noop_slot >= 0 && __builtin_amdgcn_readfirstlane(*(const int*)tab[g.noop_slot]) != 0) return;   // uniform, before any barrier
+  const int nseg = g.nseg > 0 ? g.nseg : 1;
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
   const int slabs_per_seg = kseg_eff / BK;
-  const int total = (fast && g.fast_copy) ? 0 : nseg * slabs_per_seg;
+  const int total = nseg * slabs_per_seg;
   const int s_begin = ks * g.k_per_split;
   const int s_end = min(total, s_begin + g.k_per_split);
   // Operand base addresses of the (up to three) operand pairs, read once and kept in scalar registers: a look-up
   // in the pointer table inside the loop is a memory load, and the wait for it would also wait for every tile
   // load in flight.  (Separate variables: an array indexed by the pair number would live in scratch memory.)
-  const int b_fixed = fast ? g.fast_b_slot : (g.nseg > 0 ? -1 : g.B.slot0);
+  const int b_fixed = g.nseg > 0 ? -1 : g.B.slot0;
   const unsigned char* const A0 = (const unsigned char*)(tab[g.nseg > 0 ? g.segA[0] : g.A.slot0]);
   const unsigned char* const A1 = nseg > 1 ? (const unsigned char*)(tab[g.segA[1]]) : A0;
   const unsigned char* const A2 = nseg > 2 ? (const unsigned char*)(tab[g.segA[2]]) : A0;
@@ -296,28 +295,16 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   };
   if constexpr (EPI == EPI_STORE) {
     float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
-    // fast path (C = D - acc): D's address is looked up once, and a block's four row groups of D are requested
-    // before the block goes through the patch, so that the epilogue is not a chain of dependent loads
-    const float* D = fast ? (const float*)tab[g.fast_addend_slot] : nullptr;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        long long idx[4];
-        f32x4_t dv[4];
+        to_patch(acc[i][j]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
-          idx[p] = (long long)row * g.E.ld + col;
-          if (fast) dv[p] = gload<f32x4_t>(D + idx[p]);
-        }
-        to_patch(acc[i][j]);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          f32x4_t v = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          if (fast) v = dv[p] - v;
-          gstore<f32x4_t>(C + idx[p], v);
+          gstore<f32x4_t>(C + (long long)row * g.E.ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
         }
       }
   } else {

@@ -61,7 +61,7 @@ static int run_nt(int argc, char** argv) {
   a.table = (void* const*)(arena + tab_off);
   a.nslots = NS;
   a.splitk = 1; a.sub_count = 1; a.status_slot = -1;
-  a.fast_slot = a.fast_b_slot = a.fast_addend_slot = -1;
+  a.noop_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   a.M = M; a.N = r; a.K = nseg * r;
@@ -165,7 +165,7 @@ static int run_k5(int argc, char** argv) {
   a.table = (void* const*)(arena + tab_off);
   a.nslots = NS;
   a.splitk = 1; a.sub_count = 1; a.status_slot = S_STATUS;
-  a.fast_slot = a.fast_b_slot = a.fast_addend_slot = -1;
+  a.noop_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   a.M = m; a.N = n; a.K = r;
