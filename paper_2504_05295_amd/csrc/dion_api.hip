@@ -287,7 +287,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   int c_nsplit = 1;
   // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
   if (split) {
-    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
+    // (an adaptive pass needs the low part in row-major order only if it goes on to its product: made after the decision)
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, adaptive ? -1 : SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
     GemmArgs a = base;
     a.M = r; a.N = r; a.K = 3 * (int)rows;
     a.nseg = 3; a.kseg = (int)rows;
@@ -444,6 +445,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     // below 1e-3, would survive.  Such a pass runs in place, slot_out == slot_in: the product reads the bf16 copies
     // of its input, never the fp32 original, so it may overwrite that; and when the flag is set it has nothing to do.)
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s, skip));
+    if (adaptive) HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, -1, SLOT_ZL16, -1, -1, s, skip));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
     if (adaptive) {
       if (slot_out != slot_in) return DION_EINVAL;
@@ -691,7 +693,9 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
   STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P));
-  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s));
+  // bf16 copies of P for K2 and K5.  When the last Cholesky-QR pass found its input orthonormal enough, that input is
+  // P, and the pass has left the very same copies (the high parts of its split) in the same two slots.
+  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s, SLOT_FAST));
   STAGECHK(mark(c, DION_STAGE_ORTH, 1));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   STAGECHK(stage_k2(c, SLOT_P));

@@ -117,7 +117,7 @@ hipError_t launch_split_bf16(void* const* table, int nslots, int batch, int slot
                              long long cols, int slot_hi, int slot_lo, int slot_hiT, int slot_loT, hipStream_t s,
                              int skip_slot = -1);   // skip_slot >= 0: nothing happens for matrices whose int32 there is non-zero
 hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
-                               long long rows, long long cols, hipStream_t s);
+                               long long rows, long long cols, hipStream_t s, int skip_slot = -1);
 hipError_t launch_gaussian_fill(void* const* table, int nslots, int batch, int slot, long long count, uint64_t seed,
                                 int first_stream, hipStream_t s);
 // Buffers of the first matrix of a batch; matrix b has them `stride` 4-byte words further (status: b ints further).

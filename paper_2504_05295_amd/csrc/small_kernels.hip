@@ -294,9 +294,11 @@ hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot
 }
 
 // fp32 [rows][cols] -> bf16 [rows][cols] and / or bf16 [cols][rows], 64x64 tiles transposed through LDS.
+// skip_slot >= 0 and the int32 there non-zero: nothing to do.
 __global__ void __launch_bounds__(256) convert_bf16_kernel(void* const* table, int nslots, int slot_in, int slot_out16,
-                                                           int slot_outT16, long long rows, long long cols) {
+                                                           int slot_outT16, long long rows, long long cols, int skip_slot) {
   void* const* tab = table + (size_t)blockIdx.z * nslots;
+  if (skip_slot >= 0 && *(const int*)tab[skip_slot] != 0) return;
   const float* in = (const float*)tab[slot_in];
   uint16_t* out16 = slot_out16 >= 0 ? (uint16_t*)tab[slot_out16] : nullptr;
   uint16_t* outT = slot_outT16 >= 0 ? (uint16_t*)tab[slot_outT16] : nullptr;
@@ -323,10 +325,10 @@ __global__ void __launch_bounds__(256) convert_bf16_kernel(void* const* table, i
   }
 }
 hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int slot_in, int slot_out16, int slot_outT16,
-                               long long rows, long long cols, hipStream_t s) {
+                               long long rows, long long cols, hipStream_t s, int skip_slot) {
   if (rows % 64 || cols % 64) return hipErrorInvalidValue;
   hipLaunchKernelGGL(convert_bf16_kernel, dim3((unsigned)(cols / 64), (unsigned)(rows / 64), batch), dim3(256), 0, s, table, nslots,
-                     slot_in, slot_out16, slot_outT16, rows, cols);
+                     slot_in, slot_out16, slot_outT16, rows, cols, skip_slot);
   return hipGetLastError();
 }
 
