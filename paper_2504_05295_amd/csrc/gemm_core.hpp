@@ -94,6 +94,18 @@ __device__ __forceinline__ void gstore(void* p, T v) {
   *(__attribute__((address_space(1))) T*)(p) = v;
 }
 
+// The same with the non-temporal hint, for data that is read or written once per step and is far too large to be
+// found in a cache the next time: a pass that updates M and X in place streams about 10 % faster with the hint on both
+// its loads and its stores (5.5-5.8 against 4.9-5.2 TB/s for the 18-byte-per-element update; either alone gains nothing).
+template <class T>
+__device__ __forceinline__ T gload_nt(const void* p) {
+  return __builtin_nontemporal_load((const __attribute__((address_space(1))) T*)(p));
+}
+template <class T>
+__device__ __forceinline__ void gstore_nt(void* p, T v) {
+  __builtin_nontemporal_store(v, (__attribute__((address_space(1))) T*)(p));
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2_t f = {lo, hi};
   bf16x2_t v = __builtin_convertvector(f, bf16x2_t);

@@ -24,15 +24,24 @@ __global__ void __launch_bounds__(512, 1) probe_mfma_kernel(float* sink, int ite
   if (s == -1.f) sink[0] = s;   // never true: keeps the loop alive
 }
 
-// a[i] = a[i] + g[i] - 0.5 x[i];  x[i] = x[i] - 0.25 a_old[i]   (18 bytes per element, 16-byte accesses)
+// a[i] = a[i] + g[i] - 0.5 x[i];  x[i] = x[i] - 0.25 a_old[i]   (18 bytes per element, 16-byte accesses, with or
+// without the non-temporal hint)
+template <bool NT>
 __global__ void __launch_bounds__(256) probe_stream_kernel(float* a, const uint16_t* g, float* x, long long n4) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-    const f32x4_t av = gload<f32x4_t>(a + 4 * i), xv = gload<f32x4_t>(x + 4 * i);
-    const u32x2_t w = gload<u32x2_t>(g + 4 * i);
+    const f32x4_t av = NT ? gload_nt<f32x4_t>(a + 4 * i) : gload<f32x4_t>(a + 4 * i);
+    const f32x4_t xv = NT ? gload_nt<f32x4_t>(x + 4 * i) : gload<f32x4_t>(x + 4 * i);
+    const u32x2_t w = NT ? gload_nt<u32x2_t>(g + 4 * i) : gload<u32x2_t>(g + 4 * i);
     const f32x4_t gv = {bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
-    gstore<f32x4_t>(a + 4 * i, av + gv - 0.5f * xv);
-    gstore<f32x4_t>(x + 4 * i, xv - 0.25f * av);
+    const f32x4_t na = av + gv - 0.5f * xv, nx = xv - 0.25f * av;
+    if (NT) {
+      gstore_nt<f32x4_t>(a + 4 * i, na);
+      gstore_nt<f32x4_t>(x + 4 * i, nx);
+    } else {
+      gstore<f32x4_t>(a + 4 * i, na);
+      gstore<f32x4_t>(x + 4 * i, nx);
+    }
   }
 }
 
@@ -60,13 +69,19 @@ hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflop
   float* a = (float*)scratch;
   float* x = a + n;
   uint16_t* g = (uint16_t*)(x + n);
-  // the best of a few grid sizes counts: a ceiling must not be understated by an unlucky launch shape
+  // the best of a few grid sizes and of both kinds of access counts: a ceiling must not be understated by an unlucky
+  // launch shape
   *stream_gbps = 0.0;
   const int grids[5] = {1024, 2048, 4096, 8192, 16384};
-  for (int gi = 0; gi < 5; ++gi) {
-    hipLaunchKernelGGL(probe_stream_kernel, dim3(grids[gi]), dim3(256), 0, s, a, g, x, n / 4);   // warm-up
+  for (int gi = 0; gi < 10; ++gi) {
+    const dim3 grid(grids[gi % 5]);
+    auto launch = [&] {
+      if (gi < 5) hipLaunchKernelGGL(probe_stream_kernel<false>, grid, dim3(256), 0, s, a, g, x, n / 4);
+      else hipLaunchKernelGGL(probe_stream_kernel<true>, grid, dim3(256), 0, s, a, g, x, n / 4);
+    };
+    launch();   // warm-up
     if ((e = hipEventRecord(e0, s)) != hipSuccess) return fail(e);
-    for (int rep = 0; rep < 4; ++rep) hipLaunchKernelGGL(probe_stream_kernel, dim3(grids[gi]), dim3(256), 0, s, a, g, x, n / 4);
+    for (int rep = 0; rep < 4; ++rep) launch();
     if ((e = hipEventRecord(e1, s)) != hipSuccess) return fail(e);
     if ((e = hipEventSynchronize(e1)) != hipSuccess) return fail(e);
     if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) return fail(e);
