@@ -652,6 +652,8 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
     a.B = opnd(b16, 0, r);
     a.B2 = opnd(b2_16, 0, r);
     a.xcd_remap = 1;
+    // M, X and G of this call beyond what the 256 MB last-level cache can hold from one step to the next: stream them
+    a.E.stream_hint = (double)c.batch * (double)m * (double)n * 18.0 > 192e6 ? 1 : 0;
     // keep about 2.5 MB of the two n x r column panels (128 rows x r, two bf16 matrices) resident in an XCD's L2
     // (only worth it when at least four panels fit; for larger r the row-major tile order measured faster)
     a.group_n = (int)(2621440LL / (128LL * r * 4));

@@ -45,6 +45,8 @@ struct EpilogueDesc {
   int slotX, slotG, slotM;
   float c_m, c_x;
   int x_overwrite;      // EPI_UPDATE: X = -c_x*acc2, the old contents of X are not read
+  int stream_hint;      // EPI_UPDATE of the direct-load core: M, X and G are loaded and stored with the non-temporal hint
+                        // (for working sets far beyond the last-level cache)
 };
 
 struct GemmArgs {

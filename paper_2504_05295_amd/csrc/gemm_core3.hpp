@@ -314,6 +314,7 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
     float* Xp = (float*)tab[g.E.slotX];
     float* Mp = (float*)tab[g.E.slotM];
     const void* Gp = tab[g.E.slotG];
+    const bool nt = g.E.stream_hint != 0;
     struct BlockIn {
       f32x4_t mv[4], xv[4];
       u32x4_t gw[4];   // G as loaded: four fp32 values, or four bf16 values in the first two words
@@ -328,13 +329,14 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const long long idx = block_index(t, p);
-        in.mv[p] = gload_nt<f32x4_t>(Mp + idx);
-        if constexpr (DUAL) in.xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : gload_nt<f32x4_t>(Xp + idx);
+        in.mv[p] = nt ? gload_nt<f32x4_t>(Mp + idx) : gload<f32x4_t>(Mp + idx);
+        if constexpr (DUAL)
+          in.xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : nt ? gload_nt<f32x4_t>(Xp + idx) : gload<f32x4_t>(Xp + idx);
         if constexpr (GBF16) {
-          const u32x2_t w = gload_nt<u32x2_t>((const uint16_t*)Gp + idx);
+          const u32x2_t w = nt ? gload_nt<u32x2_t>((const uint16_t*)Gp + idx) : gload<u32x2_t>((const uint16_t*)Gp + idx);
           in.gw[p] = u32x4_t{w[0], w[1], 0u, 0u};
         } else {
-          in.gw[p] = gload_nt<u32x4_t>((const float*)Gp + idx);
+          in.gw[p] = nt ? gload_nt<u32x4_t>((const float*)Gp + idx) : gload<u32x4_t>((const float*)Gp + idx);
         }
       }
     };
@@ -353,14 +355,18 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-        gstore_nt<f32x4_t>(Mp + block_index(t, p), (c.mv[p] + g_value(c.gw[p])) - g.E.c_m * a4);
+        const f32x4_t mn = (c.mv[p] + g_value(c.gw[p])) - g.E.c_m * a4;
+        if (nt) gstore_nt<f32x4_t>(Mp + block_index(t, p), mn);
+        else gstore<f32x4_t>(Mp + block_index(t, p), mn);
       }
       if constexpr (DUAL) {
         to_patch(acc2[t / NI][t % NI]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          gstore_nt<f32x4_t>(Xp + block_index(t, p), c.xv[p] - g.E.c_x * a4);
+          const f32x4_t xn = c.xv[p] - g.E.c_x * a4;
+          if (nt) gstore_nt<f32x4_t>(Xp + block_index(t, p), xn);
+          else gstore<f32x4_t>(Xp + block_index(t, p), xn);
         }
       }
     }
