@@ -27,7 +27,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 // Operand sources.  KC: element (row,k) at p[row*ld + k].  KS: element (row,k) at p[k*ld + row].
 enum { SRC_F32_KC = 0, SRC_F32_KS = 1, SRC_SUM_KC = 2, SRC_SUM_KS = 3 };
 // Epilogues.
-enum { EPI_STORE = 0, EPI_UPDATE = 1 };
+enum { EPI_STORE = 0, EPI_UPDATE = 1, EPI_UPDATE_STREAM = 2 };   // the last: direct-load core only, non-temporal M, X, G
 
 struct Operand {
   int slot0;            // pointer-table slot of the fp32 matrix
@@ -45,8 +45,8 @@ struct EpilogueDesc {
   int slotX, slotG, slotM;
   float c_m, c_x;
   int x_overwrite;      // EPI_UPDATE: X = -c_x*acc2, the old contents of X are not read
-  int stream_hint;      // EPI_UPDATE of the direct-load core: M, X and G are loaded and stored with the non-temporal hint
-                        // (for working sets far beyond the last-level cache)
+  int stream_hint;      // host side: take the EPI_UPDATE_STREAM kernel (M, X and G loaded and stored with the
+                        // non-temporal hint; for working sets far beyond the last-level cache)
 };
 
 struct GemmArgs {

@@ -314,7 +314,6 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
     float* Xp = (float*)tab[g.E.slotX];
     float* Mp = (float*)tab[g.E.slotM];
     const void* Gp = tab[g.E.slotG];
-    const bool nt = g.E.stream_hint != 0;
     struct BlockIn {
       f32x4_t mv[4], xv[4];
       u32x4_t gw[4];   // G as loaded: four fp32 values, or four bf16 values in the first two words
@@ -325,48 +324,55 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
       const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
       return (long long)row * g.E.ld + col;
     };
-    auto load_block = [&](int t, BlockIn& in) __attribute__((always_inline)) {
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const long long idx = block_index(t, p);
-        in.mv[p] = nt ? gload_nt<f32x4_t>(Mp + idx) : gload<f32x4_t>(Mp + idx);
-        if constexpr (DUAL)
-          in.xv[p] = g.E.x_overwrite ? f32x4_t{0.f, 0.f, 0.f, 0.f} : nt ? gload_nt<f32x4_t>(Xp + idx) : gload<f32x4_t>(Xp + idx);
-        if constexpr (GBF16) {
-          const u32x2_t w = nt ? gload_nt<u32x2_t>((const uint16_t*)Gp + idx) : gload<u32x2_t>((const uint16_t*)Gp + idx);
-          in.gw[p] = u32x4_t{w[0], w[1], 0u, 0u};
-        } else {
-          in.gw[p] = nt ? gload_nt<u32x4_t>((const float*)Gp + idx) : gload<u32x4_t>((const float*)Gp + idx);
-        }
-      }
-    };
     auto g_value = [&](const u32x4_t& w) __attribute__((always_inline)) {
       if constexpr (GBF16) return f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
       else return __builtin_bit_cast(f32x4_t, w);
     };
-    constexpr int NBLK = MI * NI;
-    BlockIn in[2];
-    load_block(0, in[0]);
+    // (the hint is a compile-time choice: a select between a hinted and a plain load would issue both, and two copies
+    // of the pass inside one kernel cost registers)
+    {
+      constexpr bool NTH = EPI == EPI_UPDATE_STREAM;
+      auto load_block = [&](int t, BlockIn& in) __attribute__((always_inline)) {
 #pragma unroll
-    for (int t = 0; t < NBLK; ++t) {
-      if (t + 1 < NBLK) load_block(t + 1, in[(t + 1) & 1]);
-      const BlockIn& c = in[t & 1];
-      to_patch(acc[t / NI][t % NI]);
+        for (int p = 0; p < 4; ++p) {
+          const long long idx = block_index(t, p);
+          in.mv[p] = NTH ? gload_nt<f32x4_t>(Mp + idx) : gload<f32x4_t>(Mp + idx);
+          if constexpr (DUAL) {
+            if (g.E.x_overwrite) in.xv[p] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            else in.xv[p] = NTH ? gload_nt<f32x4_t>(Xp + idx) : gload<f32x4_t>(Xp + idx);
+          }
+          if constexpr (GBF16) {
+            const u32x2_t w = NTH ? gload_nt<u32x2_t>((const uint16_t*)Gp + idx) : gload<u32x2_t>((const uint16_t*)Gp + idx);
+            in.gw[p] = u32x4_t{w[0], w[1], 0u, 0u};
+          } else {
+            in.gw[p] = NTH ? gload_nt<u32x4_t>((const float*)Gp + idx) : gload<u32x4_t>((const float*)Gp + idx);
+          }
+        }
+      };
+      constexpr int NBLK = MI * NI;
+      BlockIn in[2];
+      load_block(0, in[0]);
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-        const f32x4_t mn = (c.mv[p] + g_value(c.gw[p])) - g.E.c_m * a4;
-        if (nt) gstore_nt<f32x4_t>(Mp + block_index(t, p), mn);
-        else gstore<f32x4_t>(Mp + block_index(t, p), mn);
-      }
-      if constexpr (DUAL) {
-        to_patch(acc2[t / NI][t % NI]);
+      for (int t = 0; t < NBLK; ++t) {
+        if (t + 1 < NBLK) load_block(t + 1, in[(t + 1) & 1]);
+        const BlockIn& c = in[t & 1];
+        to_patch(acc[t / NI][t % NI]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
-          const f32x4_t xn = c.xv[p] - g.E.c_x * a4;
-          if (nt) gstore_nt<f32x4_t>(Xp + block_index(t, p), xn);
-          else gstore<f32x4_t>(Xp + block_index(t, p), xn);
+          const f32x4_t mn = (c.mv[p] + g_value(c.gw[p])) - g.E.c_m * a4;
+          if constexpr (NTH) gstore_nt<f32x4_t>(Mp + block_index(t, p), mn);
+          else gstore<f32x4_t>(Mp + block_index(t, p), mn);
+        }
+        if constexpr (DUAL) {
+          to_patch(acc2[t / NI][t % NI]);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const f32x4_t a4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+            const f32x4_t xn = c.xv[p] - g.E.c_x * a4;
+            if constexpr (NTH) gstore_nt<f32x4_t>(Xp + block_index(t, p), xn);
+            else gstore<f32x4_t>(Xp + block_index(t, p), xn);
+          }
         }
       }
     }
