@@ -64,6 +64,14 @@ def test_ragged_shapes(shape, g_bf16, math):
     run_trajectory(shape, g_bf16, math, 3, "householder")
 
 
+@pytest.mark.parametrize("shape", [(640, 400, 300), (704, 960, 448)])
+@pytest.mark.parametrize("g_bf16,math", [(False, "f32"), (True, "bf16")])
+def test_ragged_rank_on_the_single_launch_factorisation(shape, g_bf16, math):
+    # r = 300 is padded to 5 panels of 64 (an odd count: one block of the triangular inverse waits a level for its
+    # neighbour), r = 448 makes 7; both are factored and inverted by the single-launch kernels
+    run_trajectory(shape, g_bf16, math, 2, "lapack")
+
+
 @pytest.mark.parametrize("math", ["f32", "bf16"])
 def test_c2_2048_twenty_steps(math):
     run_trajectory((2048, 2048, 512), True, math, 20, "lapack", check_every=5)
