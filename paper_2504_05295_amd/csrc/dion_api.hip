@@ -128,7 +128,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_W, rr);
   take(SLOT_T, rr);
   take(SLOT_CPART, rr * (size_t)std::max(std::max(g.gram_m.splitk, g.gram_m.splitk2), std::max(g.gram_n.splitk, g.gram_n.splitk2)));
-  take(SLOT_SPART, (size_t)((std::max(g.m, g.n) + COLNORM_ROWS - 1) / COLNORM_ROWS) * g.r);
+  take(SLOT_SPART, (size_t)((std::max(g.m, g.n) + COLNORM_CHUNK_MIN - 1) / COLNORM_CHUNK_MIN) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
   // bf16 operand copies (two bf16 values per float slot)
@@ -240,6 +240,7 @@ GemmArgs base_args(const dion_state* st, const Group& g) {
   a.sub_count = 1;
   a.status_slot = -1;
   a.noop_slot = -1;
+  a.E.colsq_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   return a;
@@ -567,9 +568,12 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
 
 // K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile path, its bf16 transpose in SLOT_PT16.
 // from_b16: a K1 of this step has left bf16(M+G) in SLOT_B16 (large-tile path only).
-int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true) {
+// colsq_chunks: if given, the product may leave per-column partial sums of squares of R in SLOT_SPART (it does on the
+// direct-load path); *colsq_chunks then is their number of chunks, else 0.
+int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunks = nullptr) {
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
+  if (colsq_chunks) *colsq_chunks = 0;
   GemmArgs a = c.base;
   a.M = n; a.N = r; a.K = m;
   a.A = opnd(SLOT_M, 0, n, 0, SLOT_G);
@@ -580,6 +584,10 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true) {
     a.B = opnd(SLOT_PT16, 0, m);
     if (direct12(c)) {
       a.A = opnd(SLOT_B16T, 0, m);
+      if (colsq_chunks) {
+        *colsq_chunks = gemm2_nt_colsq_chunks(G2_256x256, a);
+        if (*colsq_chunks > 0) a.E.colsq_slot = SLOT_SPART;
+      }
       HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
       return DION_OK;
     }
@@ -700,10 +708,12 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s, SLOT_FAST));
   STAGECHK(mark(c, DION_STAGE_ORTH, 1));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
-  STAGECHK(stage_k2(c, SLOT_P));
+  int colsq_chunks = 0;
+  STAGECHK(stage_k2(c, SLOT_P, true, &colsq_chunks));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
-  HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_R, n, r, s));
+  if (colsq_chunks > 0) HIPCHK(launch_colnorm_final(c.tab, NSLOTS, batch, colsq_chunks, r, s));   // K2 has left the partial sums
+  else HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_R, n, r, s));
   HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
   STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));

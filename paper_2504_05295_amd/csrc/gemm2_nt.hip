@@ -28,6 +28,11 @@ hipError_t gemm2_nt_prepare() {
   if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 128, 4, 2>, false, EPI_STORE, false>();
   return e;
 }
+int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g) {
+  using Direct = TileCfg3<256, 256, 2, 4>;
+  if (cfg != G2_256x256 || !gemm3_fits<Direct>(g) || g.splitk > 1) return 0;
+  return g.M / Direct::WTM;
+}
 int gemm2_nt_splitk(int cfg, const GemmArgs& g) {
   return cfg == G2_256x256 ? gemm2_effective_splitk<NtBig>(g) : gemm2_effective_splitk<NtMid>(g);
 }

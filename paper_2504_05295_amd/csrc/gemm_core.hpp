@@ -45,6 +45,8 @@ struct EpilogueDesc {
   int slotX, slotG, slotM;
   float c_m, c_x;
   int x_overwrite;      // EPI_UPDATE: X = -c_x*acc2, the old contents of X are not read
+  int colsq_slot;       // EPI_STORE of the direct-load core, whole products only: >= 0: per-column partial sums of squares
+                        // of the result go there, one row of N floats per block of Cfg::WTM result rows
   int stream_hint;      // host side: take the EPI_UPDATE_STREAM kernel (M, X and G loaded and stored with the
                         // non-temporal hint; for working sets far beyond the last-level cache)
 };

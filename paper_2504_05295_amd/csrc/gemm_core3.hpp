@@ -295,10 +295,15 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   };
   if constexpr (EPI == EPI_STORE) {
     float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
+    float colsq[NI];   // sums of squares of this wave's WTM rows, per column (lane & 31) of each column block
+#pragma unroll
+    for (int j = 0; j < NI; ++j) colsq[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) colsq[j] += acc[i][j][v] * acc[i][j][v];
         to_patch(acc[i][j]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -307,6 +312,17 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
           gstore<f32x4_t>(C + (long long)row * g.E.ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
         }
       }
+    // Column norms of the result (ColNorm of the update rule) without another pass over it: one partial sum of
+    // squares per column and block of WTM rows, chunk (tile row, wave row) at part[chunk * N + column]; whoever
+    // finishes adds the chunks up in their order.  Only for whole products (no split over k).
+    if (g.E.colsq_slot >= 0) {
+      float* part = (float*)tab[g.E.colsq_slot] + (long long)(tm * Cfg::WAVES_M + wm) * g.N + col0 + wn * Cfg::WTN;
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const float both = colsq[j] + __shfl_xor(colsq[j], 32);   // the lane halves hold different rows
+        if (lk == 0) part[j * 32 + lr] = both;
+      }
+    }
   } else {
     // M <- (M + G) - (1-mu) (P R^T);   X <- X - eta sqrt(m/n) (P Q_new^T)
     // The old M, X and G of the next 32x32 block are requested before the current block is written, so that a

@@ -46,7 +46,8 @@ enum Slot {
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
 constexpr float COLNORM_EPS = 1e-8f;
-constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares
+constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares (colnorm_partial_kernel)
+constexpr int COLNORM_CHUNK_MIN = 128;   // fewest rows per partial sum that any producer uses (sizes SLOT_SPART)
 
 // Tile configurations of the MFMA GEMM core.
 using CfgBig = TileCfg<128, 128, 32, 2, 2>;
@@ -75,6 +76,9 @@ hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflop
 hipError_t gemm2_nt_prepare();
 hipError_t gemm2_k5_prepare();
 hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s);   // bf16 A (KC) x bf16 B (KC), up to 3 operand pairs
+// rows of per-column partial sums of squares that gemm2_nt writes for these arguments when GemmArgs::E.colsq_slot is set
+// (0: this product cannot, leave the slot at -1)
+int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g);
 int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
 hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
@@ -107,6 +111,8 @@ hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int
 hipError_t launch_sum_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, long long count,
                                int nsplit, hipStream_t s);
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s);
+// second stage alone: s, d from nchunks rows of partial sums of squares already in SLOT_SPART
+hipError_t launch_colnorm_final(void* const* table, int nslots, int batch, int nchunks, int r, hipStream_t s);
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
                              int status_slot, int slot_out16, int slot_in16, hipStream_t s);
 // fp32 [rows][cols] -> bf16 copy [rows][cols] (slot_out16 >= 0) and bf16 transpose [cols][rows] (slot_outT16 >= 0);

@@ -240,6 +240,10 @@ __global__ void colnorm_final_kernel(void* const* table, int nslots, int nchunks
   sn[col] = nrm;
   d[col] = 1.0f / (nrm + COLNORM_EPS);
 }
+hipError_t launch_colnorm_final(void* const* table, int nslots, int batch, int nchunks, int r, hipStream_t s) {
+  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, s, table, nslots, nchunks, r);
+  return hipGetLastError();
+}
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s) {
   const int nchunks = (int)((rows + COLNORM_ROWS - 1) / COLNORM_ROWS);
   hipLaunchKernelGGL(colnorm_partial_kernel, dim3((r + 63) / 64, nchunks, batch), dim3(256), 0, s, table, nslots, slot_in, rows, r);

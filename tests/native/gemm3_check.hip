@@ -62,6 +62,7 @@ static int run_nt(int argc, char** argv) {
   a.nslots = NS;
   a.splitk = 1; a.sub_count = 1; a.status_slot = -1;
   a.noop_slot = -1;
+  a.E.colsq_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   a.M = M; a.N = r; a.K = nseg * r;
@@ -166,6 +167,7 @@ static int run_k5(int argc, char** argv) {
   a.nslots = NS;
   a.splitk = 1; a.sub_count = 1; a.status_slot = S_STATUS;
   a.noop_slot = -1;
+  a.E.colsq_slot = -1;
   a.side_slot = -1;
   a.E.alpha = 1.f;
   a.M = m; a.N = n; a.K = r;
