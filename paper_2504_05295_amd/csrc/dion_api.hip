@@ -345,7 +345,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   const int skip = adaptive ? SLOT_FAST : -1;
   if (adaptive) {
     // (bf16 mode: decision only, see the product at the end)
-    HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split ? FIRST_ORDER_DECISION_ONLY : -1, c_nsplit, rr, s));
+    HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split, c_nsplit, rr, s));
     c_nsplit = 1;
   }
   base.status_slot = skip;

@@ -36,7 +36,7 @@ enum Slot {
   SLOT_WH16,   // hi part of L^-1              r x r
   SLOT_WL16,   // lo part of L^-1              r x r
   SLOT_EPART,  // 256 partial sums of the squared Gram defect ||C - I||_F^2
-  SLOT_FAST,   // int32: 1 when the second Cholesky-QR pass may use the first-order inverse factor
+  SLOT_FAST,   // int32: 1 when the last Cholesky-QR pass found its input orthonormal to the tolerance
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
   SLOT_B16,    // bf16(M + G), m x n: A operand of K1 on the direct-load path; else written by K1 on its way for K2
@@ -180,14 +180,11 @@ hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, hipStream_t s);
 // 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
 constexpr int chol_sync_words(int nb) { return 2 * nb + 2; }
 constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
-// Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the
-// identity in Frobenius norm, chol(C)^-1 = I - Phi(C - I) up to O(tau^2), Phi = strict lower part + half the diagonal.
-// Writes that factor into W and sets SLOT_FAST = 1; otherwise sets SLOT_FAST = 0 and leaves W alone.
-// slot_phi16 >= 0: Phi(C - I) itself goes there as r x r bf16 as well; FIRST_ORDER_DECISION_ONLY: only SLOT_FAST is
-// set, W is left alone either way.  nsplit > 1: C still is nsplit split-K partial
-// results in SLOT_CPART, split_stride words apart; their sum is formed (and stored to SLOT_C) here.
-constexpr int FIRST_ORDER_DECISION_ONLY = -2;
-hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
+// Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the identity in
+// Frobenius norm, SLOT_FAST is set to 1 (else 0) and, unless decision_only, W receives chol(C)^-1 = I - Phi(C - I) up to
+// O(tau^2), Phi = strict lower part + half the diagonal.  nsplit > 1: C still is nsplit split-K partial results in
+// SLOT_CPART, split_stride words apart; their sum is formed (and stored to SLOT_C) here.
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, bool decision_only,
                                       int nsplit, long long split_stride, hipStream_t s);
 
 }  // namespace dion

@@ -466,7 +466,7 @@ __global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, in
   if (threadIdx.x == 0) part[blockIdx.x] = red[0];
 }
 __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* table, int nslots, int r, int rp, float tau2,
-                                                                  int slot_phi16) {
+                                                                  int decision_only) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   const float* part = (const float*)tab[SLOT_EPART];
   // every block adds the 256 partials in the same order, so all blocks take the same decision
@@ -479,10 +479,9 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
   __syncthreads();
   const bool fast = total <= tau2;   // false for NaN
   if (blockIdx.x == 0 && threadIdx.x == 0) *(int*)tab[SLOT_FAST] = fast ? 1 : 0;
-  if (!fast || slot_phi16 == FIRST_ORDER_DECISION_ONLY) return;
+  if (!fast || decision_only) return;
   const float* C = (const float*)tab[SLOT_C];
   float* W = (float*)tab[SLOT_W];
-  uint16_t* phi16 = slot_phi16 >= 0 ? (uint16_t*)tab[slot_phi16] : nullptr;   // Phi itself, r x r bf16
   const long long n = (long long)rp * rp;
   for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (long long)gridDim.x * 256) {
     const int i = (int)(idx / rp), j = (int)(idx % rp);
@@ -491,23 +490,22 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
       if (i == j) phi = 0.5f * (C[idx] - 1.f);
       else if (j < i) phi = C[idx];
       v = (i == j ? 1.f : 0.f) - phi;
-      if (phi16) phi16[(long long)i * r + j] = (uint16_t)(pack_bf16x2(phi, 0.f) & 0xffffu);
     } else if (i == j) {
       v = 1.f;
     }
     W[idx] = v;
   }
 }
-hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, int slot_phi16,
+hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, bool decision_only,
                                       int nsplit, long long split_stride, hipStream_t s) {
   hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp, nsplit, split_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long blocks = ((long long)rp * rp + 2047) / 2048;
   if (blocks > 1024) blocks = 1024;
-  if (slot_phi16 == FIRST_ORDER_DECISION_ONLY) blocks = 1;
+  if (decision_only) blocks = 1;
   hipLaunchKernelGGL(first_order_inverse_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, r, rp, tau * tau,
-                     slot_phi16);
+                     decision_only ? 1 : 0);
   return hipGetLastError();
 }
 
