@@ -50,6 +50,7 @@ struct Carve {
 struct GramPlan {
   int variant, splitk, kps;   // fp32 path: tile variant, number of splits, rows per split
   int splitk2;                // split-bf16 path on large tiles
+  int split_cap256;           // most partial results the 256 x 256-tile kernel may be asked for (sizes their buffer)
 };
 struct Group {
   int64_t m, n, r;
@@ -91,6 +92,10 @@ GramPlan plan_gram_rows(const Group& g, int64_t rows) {
   if (want2 > 32) want2 = 32;
   if (want2 < 1) want2 = 1;
   gp.splitk2 = (int)want2;
+  // 256 x 256 tiles: a single matrix (or a few) has fewer lower tiles than the GPU has compute units and is split over
+  // the rows by up to 8; a batch that fills the GPU anyway is not
+  const long long t3 = g.r / 256;
+  gp.split_cap256 = (t3 * (t3 + 1) / 2 * g.count < 256) ? std::max(8, gp.splitk2) : gp.splitk2;
   return gp;
 }
 
@@ -127,7 +132,8 @@ Carve carve_entry(const Group& g) {
   take(SLOT_L, rr);
   take(SLOT_W, rr);
   take(SLOT_T, rr);
-  take(SLOT_CPART, rr * (size_t)std::max(std::max(g.gram_m.splitk, g.gram_m.splitk2), std::max(g.gram_n.splitk, g.gram_n.splitk2)));
+  take(SLOT_CPART, rr * (size_t)std::max(std::max(std::max(g.gram_m.splitk, g.gram_m.splitk2), std::max(g.gram_n.splitk, g.gram_n.splitk2)),
+                                         std::max(g.gram_m.split_cap256, g.gram_n.split_cap256)));
   take(SLOT_SPART, (size_t)((std::max(g.m, g.n) + COLNORM_CHUNK_MIN - 1) / COLNORM_CHUNK_MIN) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
@@ -303,7 +309,28 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     // partial-result buffer allows, fills at least half of the GPU and every split still has a contraction worth
     // starting a pipeline for; else 128x128 tiles with a deeper split
     const long long t256 = r / 256, tiles256 = t256 * (t256 + 1) / 2 * batch;
-    const int big_split = tiles256 > 0 ? (int)std::min<long long>(gp.splitk2, (256 + tiles256 - 1) / tiles256) : 1;
+    // Split over the rows.  The plain choice: as many workgroups per tile as it takes to reach the number of compute
+    // units.  With s workgroups per tile the kernel runs in ceil(tiles s / 256) rounds of 1/s of the contraction each,
+    // and the partial results cost a pass over s of them afterwards (about 0.06 us per tile and partial): where that
+    // estimate finds a split at least a fifth cheaper (136 tiles at r = 4096: two per tile make a second round for 16
+    // workgroups, seven make four full rounds), it is taken; smaller predicted gains did not show up in measurements
+    // (r = 2048: seven per tile slower than six).  Every split must keep a contraction worth starting a pipeline for.
+    int big_split = 1;
+    if (tiles256 > 0) {
+      const double t_full = 3.0 * (double)(rows / 64) * 1.8, t_red = 0.06 * (double)tiles256;
+      auto cost = [&](int sp) {
+        const double rounds = (double)((tiles256 * sp + 255) / 256);
+        return rounds / sp * t_full + (sp > 1 ? sp * t_red + 5.0 : 0.0);
+      };
+      big_split = (int)std::min<long long>(std::min(gp.splitk2, gp.split_cap256), (256 + tiles256 - 1) / tiles256);
+      if (big_split < 1) big_split = 1;
+      int best = big_split;
+      for (int sp = 1; sp <= gp.split_cap256; ++sp) {
+        if (sp > 1 && 3 * (rows / 64) / sp < 16) break;
+        if (cost(sp) < cost(best)) best = sp;
+      }
+      if (cost(best) < 0.8 * cost(big_split)) big_split = best;
+    }
     const bool gram_big = r % 256 == 0 && rows % 64 == 0 && tiles256 * big_split >= 128 && 3 * (rows / 64) / big_split >= 16;
     const int gcfg = gram_big ? G2_256x256 : G2_128x128;
     a.splitk = gram_big ? big_split : gp.splitk2;
