@@ -147,7 +147,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_ZLT16, (xr + 1) / 2);
   take(SLOT_WH16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
-  take(SLOT_EPART, 256);
+  take(SLOT_EPART, GRAM_DEFECT_PARTS);
   take(SLOT_FAST, 1);
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));

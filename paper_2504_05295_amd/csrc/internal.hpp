@@ -35,7 +35,7 @@ enum Slot {
   SLOT_ZLT16,  // lo part, transposed          r x m
   SLOT_WH16,   // hi part of L^-1              r x r
   SLOT_WL16,   // lo part of L^-1              r x r
-  SLOT_EPART,  // 256 partial sums of the squared Gram defect ||C - I||_F^2
+  SLOT_EPART,  // GRAM_DEFECT_PARTS partial sums of the squared Gram defect ||C - I||_F^2
   SLOT_FAST,   // int32: 1 when the last Cholesky-QR pass found its input orthonormal to the tolerance
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
@@ -46,6 +46,7 @@ enum Slot {
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
 constexpr float COLNORM_EPS = 1e-8f;
+constexpr int GRAM_DEFECT_PARTS = 1024;   // workgroups (and partial sums) of the kernel that measures ||C - I||_F
 constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares (colnorm_partial_kernel)
 constexpr int COLNORM_CHUNK_MIN = 128;   // fewest rows per partial sum that any producer uses (sizes SLOT_SPART)
 

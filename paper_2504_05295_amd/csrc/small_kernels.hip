@@ -164,23 +164,31 @@ hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int 
 }
 
 // ---------------------------------------------------------------- split-K reduction (fixed order => deterministic)
-__global__ void reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r, long long ld,
-                                       int nsplit, long long split_stride) {
+// Lower triangle only (that is what is produced and consumed); a block takes rows, a thread four columns at a time.
+__global__ void __launch_bounds__(256) reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r,
+                                                              long long ld, int nsplit, long long split_stride) {
   const float* part = (const float*)table[(size_t)blockIdx.y * nslots + slot_part];
   float* out = (float*)table[(size_t)blockIdx.y * nslots + slot_out];
-  const long long total = (long long)r * r;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-    if ((i % r) > (i / r)) continue;  // only the lower triangle is produced and consumed
-    const long long idx = (i / r) * ld + (i % r);
-    float acc = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp) acc += part[sp * split_stride + idx];
-    out[idx] = acc;
-  }
+  for (int i = blockIdx.x; i < r; i += gridDim.x)
+    for (int j0 = threadIdx.x * 4; j0 <= i; j0 += 1024) {
+      const long long idx = (long long)i * ld + j0;
+      if (j0 + 3 <= i) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < nsplit; ++sp) acc += gload<f32x4_t>(part + sp * split_stride + idx);
+        gstore<f32x4_t>(out + idx, acc);
+      } else {
+        for (int j = j0; j <= i; ++j) {
+          float acc = 0.f;
+          for (int sp = 0; sp < nsplit; ++sp) acc += part[sp * split_stride + idx + (j - j0)];
+          out[idx + (j - j0)] = acc;
+        }
+      }
+    }
 }
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
                                   int nsplit, long long split_stride, hipStream_t s) {
-  long long blocks = ((long long)r * r + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
+  if (ld % 4 || split_stride % 4) return hipErrorInvalidValue;
+  const int blocks = r < 2048 ? r : 2048;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_part, slot_out, r,
                      ld, nsplit, split_stride);
   return hipGetLastError();
@@ -443,19 +451,39 @@ __global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, in
   float* part = (float*)tab[SLOT_EPART];
   __shared__ float red[256];
   float acc = 0.f;
+  // a block takes rows, a thread four columns of the lower triangle at a time
   for (int i = blockIdx.x; i < r; i += gridDim.x)
-    for (int j = threadIdx.x; j <= i; j += 256) {
-      const long long idx = (long long)i * ld + j;
-      float c;
-      if (nsplit > 1) {
-        c = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) c += cpart[sp * split_stride + idx];
-        C[idx] = c;
+    for (int j0 = threadIdx.x * 4; j0 <= i; j0 += 1024) {
+      const long long idx = (long long)i * ld + j0;
+      if (j0 + 3 <= i) {
+        f32x4_t c;
+        if (nsplit > 1) {
+          c = f32x4_t{0.f, 0.f, 0.f, 0.f};
+          for (int sp = 0; sp < nsplit; ++sp) c += gload<f32x4_t>(cpart + sp * split_stride + idx);
+          gstore<f32x4_t>(C + idx, c);
+        } else {
+          c = gload<f32x4_t>(C + idx);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool diag = j0 + e == i;
+          const float d = c[e] - (diag ? 1.f : 0.f);
+          acc += (diag ? 1.f : 2.f) * d * d;
+        }
       } else {
-        c = C[idx];
+        for (int j = j0; j <= i; ++j) {
+          float c;
+          if (nsplit > 1) {
+            c = 0.f;
+            for (int sp = 0; sp < nsplit; ++sp) c += cpart[sp * split_stride + idx + (j - j0)];
+            C[idx + (j - j0)] = c;
+          } else {
+            c = C[idx + (j - j0)];
+          }
+          const float d = c - (i == j ? 1.f : 0.f);
+          acc += (i == j ? 1.f : 2.f) * d * d;
+        }
       }
-      const float e = c - (i == j ? 1.f : 0.f);
-      acc += (i == j ? 1.f : 2.f) * e * e;
     }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -469,14 +497,19 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
                                                                   int decision_only) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   const float* part = (const float*)tab[SLOT_EPART];
-  // every block adds the 256 partials in the same order, so all blocks take the same decision
-  __shared__ float total;
-  if (threadIdx.x == 0) {
+  // every block adds the partials in the same order, so all blocks take the same decision
+  __shared__ float red[256];
+  {
     float acc = 0.f;
-    for (int k = 0; k < 256; ++k) acc += part[k];
-    total = acc;
+    for (int k = threadIdx.x; k < GRAM_DEFECT_PARTS; k += 256) acc += part[k];
+    red[threadIdx.x] = acc;
   }
   __syncthreads();
+  for (int sft = 128; sft > 0; sft >>= 1) {
+    if ((int)threadIdx.x < sft) red[threadIdx.x] += red[threadIdx.x + sft];
+    __syncthreads();
+  }
+  const float total = red[0];
   const bool fast = total <= tau2;   // false for NaN
   if (blockIdx.x == 0 && threadIdx.x == 0) *(int*)tab[SLOT_FAST] = fast ? 1 : 0;
   if (!fast || decision_only) return;
@@ -498,7 +531,9 @@ __global__ void __launch_bounds__(256) first_order_inverse_kernel(void* const* t
 }
 hipError_t launch_first_order_inverse(void* const* table, int nslots, int batch, int r, int rp, float tau, bool decision_only,
                                       int nsplit, long long split_stride, hipStream_t s) {
-  hipLaunchKernelGGL(gram_defect_kernel, dim3(256, batch), dim3(256), 0, s, table, nslots, r, (long long)rp, nsplit, split_stride);
+  if (rp % 4 || split_stride % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gram_defect_kernel, dim3(GRAM_DEFECT_PARTS, batch), dim3(256), 0, s, table, nslots, r, (long long)rp, nsplit,
+                     split_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long blocks = ((long long)rp * rp + 2047) / 2048;
