@@ -235,21 +235,28 @@ __global__ void __launch_bounds__(256) colnorm_partial_kernel(void* const* table
   __syncthreads();
   if (ry == 0 && col < r) part[(long long)blockIdx.y * r + col] = (red[0][cx] + red[1][cx]) + (red[2][cx] + red[3][cx]);
 }
-// Stage 2: s = sqrt(sum of partials), d = 1/(s + eps).
-__global__ void colnorm_final_kernel(void* const* table, int nslots, int nchunks, int r) {
+// Stage 2: s = sqrt(sum of partials), d = 1/(s + eps).  A block takes 64 columns; four threads share a column's
+// chunks (chunk c goes to thread c mod 4) and their four sums are added in a fixed order.
+__global__ void __launch_bounds__(256) colnorm_final_kernel(void* const* table, int nslots, int nchunks, int r) {
   const float* part = (const float*)table[(size_t)blockIdx.y * nslots + SLOT_SPART];
   float* sn = (float*)table[(size_t)blockIdx.y * nslots + SLOT_S];
   float* d = (float*)table[(size_t)blockIdx.y * nslots + SLOT_D];
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= r) return;
+  __shared__ float red[4][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cx;
   float acc = 0.f;
-  for (int c = 0; c < nchunks; ++c) acc += part[(long long)c * r + col];
-  const float nrm = sqrtf(acc);
-  sn[col] = nrm;
-  d[col] = 1.0f / (nrm + COLNORM_EPS);
+  if (col < r)
+    for (int c = ry; c < nchunks; c += 4) acc += part[(long long)c * r + col];
+  red[ry][cx] = acc;
+  __syncthreads();
+  if (ry == 0 && col < r) {
+    const float nrm = sqrtf((red[0][cx] + red[1][cx]) + (red[2][cx] + red[3][cx]));
+    sn[col] = nrm;
+    d[col] = 1.0f / (nrm + COLNORM_EPS);
+  }
 }
 hipError_t launch_colnorm_final(void* const* table, int nslots, int batch, int nchunks, int r, hipStream_t s) {
-  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, s, table, nslots, nchunks, r);
+  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 63) / 64, batch), dim3(256), 0, s, table, nslots, nchunks, r);
   return hipGetLastError();
 }
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s) {
@@ -257,7 +264,7 @@ hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in
   hipLaunchKernelGGL(colnorm_partial_kernel, dim3((r + 63) / 64, nchunks, batch), dim3(256), 0, s, table, nslots, slot_in, rows, r);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 255) / 256, batch), dim3(256), 0, s, table, nslots, nchunks, r);
+  hipLaunchKernelGGL(colnorm_final_kernel, dim3((r + 63) / 64, batch), dim3(256), 0, s, table, nslots, nchunks, r);
   return hipGetLastError();
 }
 
