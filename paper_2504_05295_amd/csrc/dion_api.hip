@@ -689,10 +689,13 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
     a.xcd_remap = 1;
     // M, X and G of this call beyond what the 256 MB last-level cache can hold from one step to the next: stream them
     a.E.stream_hint = (double)c.batch * (double)m * (double)n * 18.0 > 192e6 ? 1 : 0;
-    // keep about 2.5 MB of the two n x r column panels (128 rows x r, two bf16 matrices) resident in an XCD's L2
-    // (only worth it when at least four panels fit; for larger r the row-major tile order measured faster)
+    // Tiles are visited column group by column group, all row tiles of a group before the next group: the n x r column
+    // panels of a group (128 rows x r, two bf16 matrices per tile column) are shared by the tiles that run at the same
+    // time on an XCD and stay in its L2 from one row of tiles to the next.  About 2.5 MB of panels per group, and at
+    // least three tile columns: measured at r = 768 (6 wide), 1024 (5), 2048 and 4096 (3), each against narrower and
+    // wider groups and against the plain row-major order, which costs 10 % at r >= 2048.
     a.group_n = (int)(2621440LL / (128LL * r * 4));
-    if (a.group_n < 4) a.group_n = 0;
+    if (a.group_n < 3) a.group_n = 3;
     // short contractions spend a large share of the time in the epilogue, where nothing multiplies: 128x128 tiles
     // put two workgroups on a compute unit, so that one can multiply while the other streams M, G and X
     // (measured: 11 % faster at r = 512, 2 % at r = 1024, 5 % slower at r = 2048)
