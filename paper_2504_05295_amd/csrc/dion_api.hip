@@ -696,10 +696,10 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
     // wider groups and against the plain row-major order, which costs 10 % at r >= 2048.
     a.group_n = (int)(2621440LL / (128LL * r * 4));
     if (a.group_n < 3) a.group_n = 3;
-    // short contractions spend a large share of the time in the epilogue, where nothing multiplies: 128x128 tiles
-    // put two workgroups on a compute unit, so that one can multiply while the other streams M, G and X
-    // (measured: 11 % faster at r = 512, 2 % at r = 1024, 5 % slower at r = 2048)
-    HIPCHK(gemm2_k5(r <= 512 ? G2_128x128 : G2_256x256, c.gbf16, a, c.batch, c.s));
+    // (128x128 tiles, two workgroups per compute unit so that one multiplies while the other streams M, G and X, cost
+    // twice the operand traffic of the 256x128 tile and lose or tie at every shape measured: 2 % at 8192 x 8192 r = 512,
+    // 10 % at r = 768 and 1024, 20 % at r = 2048, even at 2048 x 2048 r = 512)
+    HIPCHK(gemm2_k5(G2_256x256, c.gbf16, a, c.batch, c.s));
   } else {
     a.A = opnd(a32, 0, r);
     a.B = opnd(b32, 0, r);

@@ -14,15 +14,6 @@ hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
     return gbf16 ? launch_gemm3<Direct, true, EPI_UPDATE, true>(g, batch, s)
                  : launch_gemm3<Direct, false, EPI_UPDATE, true>(g, batch, s);
   }
-  // small tiles: two four-wave workgroups per compute unit, so that one multiplies while the other streams M, G, X
-  using DirectMid = TileCfg3<128, 128, 2, 2, 32, 2>;
-  if (cfg == G2_128x128 && gemm3_fits<DirectMid>(g) && g.B2.ld == g.B.ld) {
-    if (g.E.stream_hint)
-      return gbf16 ? launch_gemm3<DirectMid, true, EPI_UPDATE_STREAM, true>(g, batch, s)
-                   : launch_gemm3<DirectMid, false, EPI_UPDATE_STREAM, true>(g, batch, s);
-    return gbf16 ? launch_gemm3<DirectMid, true, EPI_UPDATE, true>(g, batch, s)
-                 : launch_gemm3<DirectMid, false, EPI_UPDATE, true>(g, batch, s);
-  }
   if (cfg == G2_256x256)
     return gbf16 ? launch_gemm2<Big, SRC2_BF16_KC, true, EPI_UPDATE, true>(g, batch, s)
                  : launch_gemm2<Big, SRC2_BF16_KC, false, EPI_UPDATE, true>(g, batch, s);
@@ -31,15 +22,10 @@ hipError_t gemm2_k5(int cfg, bool gbf16, GemmArgs g, int batch, hipStream_t s) {
 }
 hipError_t gemm2_k5_prepare() {
   using Direct = TileCfg3<256, 128, 2, 4>;
-  using DirectMid = TileCfg3<128, 128, 2, 2, 32, 2>;
   hipError_t e = gemm3_prepare<Direct, true, EPI_UPDATE, true>();
   if (e == hipSuccess) e = gemm3_prepare<Direct, false, EPI_UPDATE, true>();
-  if (e == hipSuccess) e = gemm3_prepare<DirectMid, true, EPI_UPDATE, true>();
-  if (e == hipSuccess) e = gemm3_prepare<DirectMid, false, EPI_UPDATE, true>();
   if (e == hipSuccess) e = gemm3_prepare<Direct, true, EPI_UPDATE_STREAM, true>();
   if (e == hipSuccess) e = gemm3_prepare<Direct, false, EPI_UPDATE_STREAM, true>();
-  if (e == hipSuccess) e = gemm3_prepare<DirectMid, true, EPI_UPDATE_STREAM, true>();
-  if (e == hipSuccess) e = gemm3_prepare<DirectMid, false, EPI_UPDATE_STREAM, true>();
   return e;
 }
 }  // namespace dion

@@ -3,7 +3,7 @@
 // and loads nothing.  Results are compared with fp64 sums on the host (small integer inputs: exact in bf16).
 //   gemm3_check nt  M r tri_k nseg narrow the triangular multiply / Gram form, 256x256 tiles (or 256x128, costliest
 //                                         column tiles first, with narrow = 1), up to 3 operand pairs
-//   gemm3_check k5  m n r group_n big     the fused update, 256x128 tiles (big = 1) or 128x128 tiles (big = 0)
+//   gemm3_check k5  m n r group_n stream  the fused update on 256x128 tiles; stream = 1: the epilogue with the non-temporal hint
 // Prints "violations V" and "checked C bad B"; exit status 0 only when V = B = 0.
 #define DION_GEMM3_BOUNDS 1
 #include "../../paper_2504_05295_amd/csrc/gemm_core3.hpp"
@@ -178,13 +178,12 @@ static int run_k5(int argc, char** argv) {
   a.E.c_m = 0.5f; a.E.c_x = 0.25f;
   a.xcd_remap = 1;
   a.group_n = group_n;
-  const int big = argc > 5 ? atoi(argv[5]) : 1;
+  const int stream = argc > 5 ? atoi(argv[5]) : 0;
   using Big = TileCfg3<256, 128, 2, 4>;
-  using Mid = TileCfg3<128, 128, 2, 2, 32, 2>;
-  if (big ? !gemm3_fits<Big>(a) : !gemm3_fits<Mid>(a)) { printf("does not fit\n"); return 1; }
+  if (!gemm3_fits<Big>(a)) { printf("does not fit\n"); return 1; }
   printf("launching\n"); fflush(stdout);
-  if (big) CK((launch_gemm3<Big, true, EPI_UPDATE, true>(a, 1, 0)));
-  else CK((launch_gemm3<Mid, true, EPI_UPDATE, true>(a, 1, 0)));
+  if (stream) CK((launch_gemm3<Big, true, EPI_UPDATE_STREAM, true>(a, 1, 0)));
+  else CK((launch_gemm3<Big, true, EPI_UPDATE, true>(a, 1, 0)));
   CK(hipDeviceSynchronize());
   unsigned viol = 0;
   CK(hipMemcpyFromSymbol(&viol, HIP_SYMBOL(dion_gemm3_violations), sizeof(viol)));

@@ -17,12 +17,12 @@ CASES = [
     ("nt", 4096, 512, 0, 2),
     ("nt", 8192, 2048, 1, 3, 1),   # C3 again, 128-wide column tiles visited from the costliest down
     ("nt", 16384, 1024, 1, 1, 1),
-    ("k5", 2048, 4096, 2048, 0, 1),
-    ("k5", 3072, 8192, 768, 4, 1),  # a C5 class, column groups of 4 tiles
-    ("k5", 8192, 3072, 2048, 2, 1),
+    ("k5", 2048, 4096, 2048, 0, 0),
+    ("k5", 3072, 8192, 768, 6, 1),  # a C5 class, column groups of 6 tiles, streaming epilogue
+    ("k5", 8192, 3072, 2048, 2, 0),
     ("k5", 2048, 4096, 2048, 3, 1),  # groups of 3 tile columns: 32 columns leave a ragged last group
-    ("k5", 3072, 8192, 512, 4, 0),  # 128-wide tiles, two workgroups per compute unit
-    ("k5", 1024, 1024, 512, 2, 0),
+    ("k5", 3072, 8192, 512, 10, 1),
+    ("k5", 1024, 1024, 512, 3, 0),
 ]
 
 
