@@ -170,11 +170,11 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
                           void* const* Q, const int64_t* m, const int64_t* n, const int64_t* r, float mu, float eta,
                           void* hip_stream, int* retried_out);
 
-/* Bound on the waits inside the single-launch Cholesky kernel, which factors one to four large matrices with
- * workgroups that wait for one another's results (Appendix A names the factorisation; how it is scheduled is
- * this library's business).  A workgroup that has polled `polls` times without success gives up, all others
- * follow, the kernel ends, and the matrix is reported as DION_NUM_BREAKDOWN with X, M, Q untouched; a later step
- * is not affected.  The default (about a million polls, on the order of a second) is only ever reached when
+/* Bound on the waits inside the single-launch Cholesky kernel and the single-launch triangular inverse that
+ * follows it, which factor and invert up to 128 matrices of rank 256 and more with workgroups that wait for one
+ * another's results (Appendix A names the factorisation; how it is scheduled is this library's business).  A
+ * workgroup that has polled `polls` times without success gives up, all others follow, the kernel ends, and the
+ * matrix is reported as DION_NUM_BREAKDOWN with X, M, Q untouched; a later step is not affected.  The default (about a million polls, on the order of a second) is only ever reached when
  * the GPU cannot keep all workgroups of the kernel resident; 0 makes every wait fail, for tests of this path. */
 int dion_set_wait_limit(dion_state_t* st, unsigned polls);
 
