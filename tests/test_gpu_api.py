@@ -303,6 +303,10 @@ def test_shifted_cholqr3_handles_what_cholqr2_reports():
 def test_shifted_cholqr3_matches_oracle_on_regular_inputs():
     check_batch([(256, 256, 64), (200, 136, 24)], False, "f32", orth_mode=1)
     check_batch([(512, 256, 128)] * 2 + [(192, 320, 48)], True, "bf16", orth_mode=1)
+    # ranks of four and six panels: the three passes run on the single-launch factorisation and inverse, the split-bf16
+    # ones in place
+    check_batch([(1024, 768, 256)] * 2 + [(768, 512, 384)], True, "bf16", orth_mode=1)
+    check_batch([(512, 512, 256)], False, "f32", orth_mode=1)
 
 
 def test_orth_mode_validation():
