@@ -199,8 +199,8 @@ int dion_stage_times(dion_state_t* st, float* ms_out /* [DION_STAGE_COUNT] */);
  *   *stream_gbps  a streaming pass with the traffic of the fused update: per element it reads fp32, bf16, fp32
  *                 and writes fp32, fp32 (18 bytes), with 16-byte accesses.
  * scratch_dev: device memory, 256-byte aligned, owned by the caller and overwritten; at least 10 MiB, and the
- * streaming pass covers scratch_bytes / 10 elements, so give it more than the 256 MB Infinity Cache holds (1 GiB
- * is what bench.py uses).  The call enqueues on hip_stream and waits for the result (host outputs).
+ * streaming pass covers scratch_bytes / 10 elements rounded down to a multiple of 2^20 (at most 2^26 of them), so
+ * give it more than the 256 MB Infinity Cache holds (1 GiB is what bench.py uses).  The call enqueues on hip_stream and waits for the result (host outputs).
  * Errors: DION_EINVAL (null or misaligned arguments), DION_EWORKSPACE (scratch too small), DION_ELAUNCH. */
 int dion_measure_ceilings(void* scratch_dev, size_t scratch_bytes, double* mfma_tflops, double* stream_gbps,
                           void* hip_stream);

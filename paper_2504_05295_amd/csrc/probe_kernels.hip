@@ -65,7 +65,12 @@ hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflop
   if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) return fail(e);
   *mfma_tflops = (double)groups * 8 * 8 * iters * (2.0 * 32 * 32 * 16) / (ms * 1e-3) * 1e-12;
   // stream: a (fp32), x (fp32), g (bf16) carved from scratch
-  const long long n = elems / 4 * 4;
+  // whole multiples of 2^20 elements, so that the three arrays start on the same alignment as the first (an odd size
+  // that leaves the second array 16 bytes into a 256-byte line measured 10 % lower), and no more than 2^26: larger
+  // arrays did not stream faster
+  long long n = elems / (1 << 20) * (1 << 20);
+  if (n > (1ll << 26)) n = 1ll << 26;
+  if (n <= 0) return hipErrorInvalidValue;
   float* a = (float*)scratch;
   float* x = a + n;
   uint16_t* g = (uint16_t*)(x + n);
