@@ -66,8 +66,10 @@ hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflop
   *mfma_tflops = (double)groups * 8 * 8 * iters * (2.0 * 32 * 32 * 16) / (ms * 1e-3) * 1e-12;
   // stream: a (fp32), x (fp32), g (bf16) carved from scratch
   // whole multiples of 2^20 elements, so that the three arrays start on the same alignment as the first (an odd size
-  // that leaves the second array 16 bytes into a 256-byte line measured 10 % lower), and no more than 2^26: larger
-  // arrays did not stream faster
+  // that leaves the second array 16 bytes into a 256-byte line measured 10 % lower), and no more than 2^26, the
+  // matrix size of the 8192 x 8192 workload: the rate is the best case for footprints of that size and more (0.67 GB
+  // keeps a larger share of itself in the 256 MB last-level cache between passes than 1 GB does, which streams
+  // about 10 % slower)
   long long n = elems / (1 << 20) * (1 << 20);
   if (n > (1ll << 26)) n = 1ll << 26;
   if (n <= 0) return hipErrorInvalidValue;
