@@ -238,6 +238,30 @@ def test_second_pass_takes_full_factorisation_when_needed():
     assert rep["dX"] < 1e-3 and rep["dM"] < 1e-3, rep
 
 
+@pytest.mark.parametrize("shape", [(1024, 768, 512), (8192, 2048, 1024)])
+def test_bf16_second_pass_takes_full_factorisation_when_needed(shape):
+    # The same on the split-bf16 path, where a second pass that finds its input orthonormal enough does nothing at
+    # all: a power-law gradient (cond(B Q) about 2000) must send it through the full factorisation, the triangular
+    # inverse, the late split of the low parts and the three-term product written in place (on the register-staged
+    # kernel for the first shape, on the direct-load kernel for the second).  Which way a step went shows in W, the
+    # inverse factor of the last factorisation that ran: that of a nearly orthonormal input is close to the identity.
+    m, n, r = shape
+    eye = np.eye(r)
+    control = GpuProblem([shape], True, "bf16")
+    control.upload_grads(control.grads_np(0))
+    assert control.step(MU, ETA) == (0, -1)
+    assert np.abs(control.debug(0, control.B.DEBUG_W)[:r, :r] - eye).max() > 0.5      # Gaussian input: first-pass factor
+    del control
+    gp = GpuProblem([shape], True, "bf16")
+    g = inputs.structured_gradient(m, n, 0, k=r, noise=1e-2, decay=0.5, bf16=True)
+    gp.upload_grads([g])
+    x_in, m_in, q_in = gp.host()
+    assert gp.step(MU, ETA) == (0, -1)
+    assert np.abs(gp.debug(0, gp.B.DEBUG_W)[:r, :r] - eye).max() < 0.2                # second-pass factor
+    rep, _ = one_step_report(gp, 0, x_in, m_in, q_in, inputs.bf16_bits_to_f32(g), MU, ETA, "lapack")
+    assert rep["X"] < 2e-2 and rep["M"] < 2e-2 and rep["orth"] < 1e-4, rep
+
+
 def qr_properties(gp, i, m_in, q_in, g32):
     """What defines P = thin-QR factor of Z = (M+G) Q with positive diagonal, measured without a reference P."""
     B = gp.B
