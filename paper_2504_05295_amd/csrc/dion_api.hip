@@ -496,6 +496,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     if (cfg == G2_256x256 && batch == 1 && (rows / 256) * (r / 256) <= 256 && (rows / 256) % 8 == 0) {
       cfg = G2_256x128;
       a.heavy_first = 1;
+    } else if (cfg == G2_256x256 && batch == 1 && (rows / 256) % 8 == 0) {
+      a.heavy_first = 1;   // several rounds of 256-wide tiles: still the costliest columns first, so that the cheap ones fill the tail
     }
     HIPCHK(gemm2_nt(cfg, a, batch, s));
   } else {

@@ -1,8 +1,8 @@
 // Checking program for the direct-load GEMM core (gemm_core3.hpp built with DION_GEMM3_BOUNDS): every direct
 // load is tested against the address range of an arena that holds all operands; a lane outside it is counted
 // and loads nothing.  Results are compared with fp64 sums on the host (small integer inputs: exact in bf16).
-//   gemm3_check nt  M r tri_k nseg narrow the triangular multiply / Gram form, 256x256 tiles (or 256x128, costliest
-//                                         column tiles first, with narrow = 1), up to 3 operand pairs
+//   gemm3_check nt  M r tri_k nseg order  the triangular multiply / Gram form, 256x256 tiles (order = 1: 256x128 tiles,
+//                                         costliest column tiles first; 2: that order on 256x256 tiles), up to 3 operand pairs
 //   gemm3_check k5  m n r group_n stream  the fused update on 256x128 tiles; stream = 1: the epilogue with the non-temporal hint
 // Prints "violations V" and "checked C bad B"; exit status 0 only when V = B = 0.
 #define DION_GEMM3_BOUNDS 1
@@ -75,10 +75,11 @@ static int run_nt(int argc, char** argv) {
   a.tri_k = tri;
   a.E.slot = S_OUT; a.E.ld = r;
   a.xcd_remap = 1;
-  const int narrow = argc > 5 ? atoi(argv[5]) : 0;   // 256x128 tiles, costliest column tiles first
+  const int order = argc > 5 ? atoi(argv[5]) : 0;   // 1: 256x128 tiles, costliest column tiles first; 2: that order on 256x256 tiles
+  const int narrow = order == 1;
   using Cfg = TileCfg3<256, 256, 2, 4>;
   using Narrow = TileCfg3<256, 128, 4, 2>;
-  a.heavy_first = narrow;
+  a.heavy_first = order != 0;
   if (narrow ? !gemm3_fits<Narrow>(a) : !gemm3_fits<Cfg>(a)) { printf("does not fit\n"); return 1; }
   printf("launching\n"); fflush(stdout);
   if (narrow) CK((launch_gemm3<Narrow, false, EPI_STORE, false>(a, 1, 0)));

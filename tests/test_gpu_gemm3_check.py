@@ -17,6 +17,7 @@ CASES = [
     ("nt", 4096, 512, 0, 2),
     ("nt", 8192, 2048, 1, 3, 1),   # C3 again, 128-wide column tiles visited from the costliest down
     ("nt", 16384, 1024, 1, 1, 1),
+    ("nt", 16384, 2048, 1, 3, 2),  # 512 tiles of 256 x 256 (two rounds), costliest column tiles first
     ("k5", 2048, 4096, 2048, 0, 0),
     ("k5", 3072, 8192, 768, 6, 1),  # a C5 class, column groups of 6 tiles, streaming epilogue
     ("k5", 8192, 3072, 2048, 2, 0),
