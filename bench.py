@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Dion step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3a] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4a] [--no-cpu-baseline]
 
 A "step" is one full Dion step (Z = (M+G)Q, CholeskyQR2, R = (M+G)^T P, ColNorm, fused M and X
 update) of the workload's matrices, inputs resident in HBM.  Prints ONE JSON line: ms per step as
@@ -71,7 +71,22 @@ def kernel_models(shapes, g_bytes, math):
     for name, fl, by in (("k1_BQ", k1f, k1b), ("k2_BtP", k2f, k2b), ("k5_update", k5f, k5b)):
         bound = "mfma" if fl / peak > by / PEAK_HBM else "hbm"
         out[name] = dict(flops=fl, bytes=by, bound=bound, peak=peak if bound == "mfma" else PEAK_HBM)
+    # Orthonormalisation (CholeskyQR2): two Gram matrices without symmetry (4 m r^2), two triangular solves
+    # (2 m r^2), two Cholesky factorisations (2/3 r^3); about five passes over the m x r factor.  Its products want
+    # fp32 accuracy.  In fp32 mode they run on the fp32 matrix pipe and are priced against its peak; in bf16 mode the
+    # library runs each as three bf16 products of split operands (x = hi + lo), so the same FLOP count is priced
+    # against a third of the bf16 peak, with the fraction of the fp32 peak stated beside it (`vs_fp32_mfma`: it can
+    # exceed 1, the split products being faster than the fp32 pipe, and the second pass being cut short when the
+    # first one's result is orthonormal to 1e-3).
+    of = ob = 0.0
+    for (m, n, r) in shapes:
+        of += 6.0 * m * r * r + 2.0 / 3.0 * float(r) ** 3
+        ob += 20.0 * m * r
+    out["orth"] = dict(flops=of, bytes=ob, bound="mfma", peak=PEAK_BF16 / 3.0 if math == "bf16" else PEAK_F32, f32_peak=PEAK_F32)
     return out
+
+
+_HOST_CACHE = {}   # (m, n, g_bf16, n_grads) -> (X, [G_t]) host draws of the last shape built
 
 
 def build_problem(cfg, seed=0, n_grads=2, form="standard"):
@@ -81,13 +96,18 @@ def build_problem(cfg, seed=0, n_grads=2, form="standard"):
     dev = "cuda"
     X, M, Q, G = [], [], [], []
     uniq = {}
+    cache = _HOST_CACHE if seed == 0 else {}
     forms = [B.DION_FORM_TRANSPOSED if (form == "transposed" or (form == "short-side" and n < m)) else B.DION_FORM_STANDARD
              for (m, n, r) in shapes]
     for i, (m, n, r) in enumerate(shapes):
         # one host draw per distinct shape is enough for timing; every matrix still gets its own buffers
         if (m, n, r) not in uniq:
-            gs = [inputs.gradient(m, n, t, seed, 0, bf16=cfg["g_bf16"]) for t in range(n_grads)]
-            uniq[(m, n, r)] = (inputs.weight(m, n, seed + 1, 0), inputs.right_factor_raw(n, r, seed + 2, 0), gs)
+            key = (m, n, cfg["g_bf16"], n_grads)
+            if key not in cache:
+                cache.clear()      # one shape's draws at a time: the large ones take gigabytes of host memory
+                cache[key] = (inputs.weight(m, n, seed + 1, 0),
+                              [inputs.gradient(m, n, t, seed, 0, bf16=cfg["g_bf16"]) for t in range(n_grads)])
+            uniq[(m, n, r)] = (cache[key][0], inputs.right_factor_raw(n, r, seed + 2, 0), cache[key][1])
         x, q, gs = uniq[(m, n, r)]
         X.append(torch.from_numpy(x).to(dev))
         M.append(torch.empty((m, n), dtype=torch.float32, device=dev))
@@ -155,7 +175,7 @@ def cpu_baseline(cfg, p, budget_s=30.0, variant="dion", refresh_every=1):
             X0, M0, Q0 = res["X"], res["M"], res["Q"]
         steps_done += 1
         dt = time.perf_counter() - t0
-        if (dt >= 10.0 and steps_done % refresh_every == 0) or steps_done >= 8 * refresh_every:
+        if (dt >= 10.0 and steps_done % refresh_every == 0) or steps_done >= 400 * refresh_every:
             break
     sample += " (%d step%s timed)" % (steps_done, "" if steps_done == 1 else "s")
     dt /= steps_done
@@ -175,12 +195,83 @@ def cpu_baseline(cfg, p, budget_s=30.0, variant="dion", refresh_every=1):
     return dict(value=total, unit="ms/step", cores=cores, kind="oracle", sample=sample, measured_s=dt * steps_done)
 
 
+def run_workload(tag, steps, warmup, stage_timing=True, variant="dion", refresh_every=1, form="standard",
+                 calibration_copy=False):
+    """Builds the workload, runs `warmup` untimed and exactly `steps` timed steps (inputs resident in HBM, host clock
+    bracketed by device synchronisations).  Returns the problem, ms per step and the per-stage ms."""
+    import torch
+    cfg = inputs.CONFIGS[tag]
+    p = build_problem(cfg, form=form)
+    p["variant"], p["refresh_every"] = variant, max(1, refresh_every)
+    B = p["B"]
+    for t in range(warmup):
+        do_step(p, t)
+    status, bad = B.dion_last_status(p["state"])
+    assert status == 0, "warm-up step of %s reported numerical status %d" % (tag, status)
+    if calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    B.dion_set_stage_timing(p["state"], stage_timing)
+    stage_sum = {k: 0.0 for k in B.STAGES}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if not stage_timing:
+        for t in range(steps):
+            do_step(p, warmup + t)
+    else:
+        # stage events are read back after each step (a host wait, also inside the timed region)
+        for t in range(steps):
+            do_step(p, warmup + t)
+            for k, v in B.dion_stage_times(p["state"]).items():
+                stage_sum[k] += v
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    status, bad = B.dion_last_status(p["state"])
+    assert status == 0, "timed step of %s reported numerical status %d" % (tag, status)
+    return p, (t1 - t0) * 1e3 / steps, {k: v / steps for k, v in stage_sum.items()}
+
+
+def stage_rooflines(tag, stages, ceilings):
+    """Achieved rate of every stage against its bound, from the algorithmic FLOPs / bytes of kernel_models."""
+    cfg = inputs.CONFIGS[tag]
+    models = kernel_models(cfg["shapes"], 2 if cfg["g_bf16"] else 4, cfg["math"])
+    traffic = measured_traffic(tag)
+    tsrc = "profiles/hbm_traffic_%s.txt" % PROFILE_TAGS[tag] if traffic else None
+    out = {}
+    for name, mdl in models.items():
+        ms = stages.get(name, 0.0)
+        if ms <= 0:
+            continue
+        work = mdl["flops"] if mdl["bound"] == "mfma" else mdl["bytes"]
+        ach = work / (ms * 1e-3)
+        unit = "TFLOP/s" if mdl["bound"] == "mfma" else "GB/s"
+        div = 1e12 if mdl["bound"] == "mfma" else 1e9
+        rf = dict(bound=mdl["bound"], achieved=ach / div, peak=mdl["peak"] / div, unit=unit, frac=ach / mdl["peak"],
+                  traffic=traffic.get(name), traffic_source=tsrc if traffic.get(name) is not None else None, ms=ms,
+                  tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
+        if name == "orth":
+            rf["peak_of"] = "fp32 MFMA" if mdl["peak"] == mdl["f32_peak"] else "bf16 MFMA / 3 (three split-bf16 products per fp32 product)"
+            rf["vs_fp32_mfma"] = dict(peak=mdl["f32_peak"] / 1e12, unit="TFLOP/s", frac=ach / mdl["f32_peak"])
+        elif ceilings:
+            top = ceilings["mfma_tflops"] if rf["bound"] == "mfma" else ceilings["stream_gbps"]
+            rf["frac_of_measured"] = rf["achieved"] / top
+        out[name] = rf
+    return out
+
+
+# workloads reported next to the headline one: (tag, timed steps, warm-up steps)
+ALSO = (("C4b", 3, 2), ("C3a", 10, 3), ("C3b", 10, 3), ("C5", 2, 1), ("C2", 20, 3), ("C2b", 20, 3))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C3a", choices=sorted(inputs.CONFIGS))
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4a", choices=sorted(inputs.CONFIGS))
     ap.add_argument("--variant", default="dion", choices=["dion", "lazy"],
                     help="dion: the Dion step (default); lazy: Lazy-Dion with a refresh every --refresh-every steps")
     ap.add_argument("--refresh-every", type=int, default=8)
@@ -190,6 +281,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the two micro-kernels that measure this GPU's MFMA and streaming ceilings")
+    ap.add_argument("--no-also", action="store_true", help="time the headline workload only")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
@@ -204,75 +296,26 @@ def main():
     if args.form != "standard" and (args.variant != "dion"):
         print("--form applies to the Dion step only", file=sys.stderr)
         sys.exit(2)
-    p = build_problem(cfg, form=args.form)
-    p["variant"], p["refresh_every"] = args.variant, max(1, args.refresh_every)
+    refresh_every = max(1, args.refresh_every) if args.variant == "lazy" else 1
     if args.variant == "lazy":
         # the first step must refresh (V starts column-normalised, not orthonormal); time whole refresh periods
         args.warmup = max(1, args.warmup)
-        args.warmup += (-args.warmup) % p["refresh_every"]
-        args.steps += (-args.steps) % p["refresh_every"]
+        args.warmup += (-args.warmup) % refresh_every
+        args.steps += (-args.steps) % refresh_every
+    p, ms_per_step, stages = run_workload(args.workload, args.steps, args.warmup, not args.no_stage_timing, args.variant,
+                                          refresh_every, args.form, args.calibration_copy)
     B = p["B"]
-    for t in range(args.warmup):
-        do_step(p, t)
-    status, bad = B.dion_last_status(p["state"])
-    assert status == 0, "warm-up step reported numerical breakdown"
-    if args.calibration_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
-    # timed region: exactly K steps, inputs resident in HBM
-    B.dion_set_stage_timing(p["state"], not args.no_stage_timing)
-    stage_sum = {k: 0.0 for k in B.STAGES}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if args.no_stage_timing:
-        for t in range(args.steps):
-            do_step(p, args.warmup + t)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    else:
-        # stage events are read back after each step (a host wait, also inside the timed region)
-        for t in range(args.steps):
-            do_step(p, args.warmup + t)
-            for k, v in B.dion_stage_times(p["state"]).items():
-                stage_sum[k] += v
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    status, bad = B.dion_last_status(p["state"])
-    assert status == 0, "timed step reported numerical breakdown"
-
-    g_bytes = 2 if cfg["g_bf16"] else 4
-    models = kernel_models(cfg["shapes"], g_bytes, cfg["math"])
-    stages = {k: v / args.steps for k, v in stage_sum.items()}
-    rooflines = {}
-    traffic = measured_traffic(args.workload)
-    for name, mdl in models.items():
-        ms = stages.get(name, 0.0)
-        if ms <= 0:
-            continue
-        work = mdl["flops"] if mdl["bound"] == "mfma" else mdl["bytes"]
-        ach = work / (ms * 1e-3)
-        unit = "TFLOP/s" if mdl["bound"] == "mfma" else "GB/s"
-        div = 1e12 if mdl["bound"] == "mfma" else 1e9
-        rooflines[name] = dict(bound=mdl["bound"], achieved=ach / div, peak=mdl["peak"] / div, unit=unit,
-                               frac=ach / mdl["peak"], traffic=traffic.get(name), ms=ms,
-                               tflops=mdl["flops"] / (ms * 1e-3) / 1e12, gbps=mdl["bytes"] / (ms * 1e-3) / 1e9)
     # measured ceilings of this GPU, in the same run: bf16 MFMA issue loop, 18-byte-per-element streaming pass
     ceilings = None
     if not args.no_ceilings:
         scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         ceilings = B.dion_measure_ceilings(scratch)
         del scratch
-        for name, rf in rooflines.items():
-            top = ceilings["mfma_tflops"] if rf["bound"] == "mfma" else ceilings["stream_gbps"]
-            rf["frac_of_measured"] = rf["achieved"] / top
+    rooflines = stage_rooflines(args.workload, stages, ceilings)
     dominant = max(rooflines, key=lambda k: rooflines[k]["ms"]) if rooflines else None
     out = {
         "metric": "ms per Dion step per m x n matrix at rank r" if args.variant == "dion"
-                  else "ms per Lazy-Dion step per m x n matrix at rank r (refresh every %d steps)" % p["refresh_every"],
+                  else "ms per Lazy-Dion step per m x n matrix at rank r (refresh every %d steps)" % refresh_every,
         "value": ms_per_step, "unit": "ms/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["math"] == "bf16" else "f32", "data": "synthetic",
@@ -285,28 +328,24 @@ def main():
         "rooflines": rooflines,
         "ceilings": ceilings,
     }
-    if args.workload == "C3a" and args.variant == "dion" and args.form == "standard" and not args.calibration_copy:
-        # the second configuration of the benchmark list (2048 x 2048, r = 512, 20 steps) lives in the Infinity Cache and
-        # is bound by launch latencies, so it is not the headline workload; its step times are reported alongside
+    p = dict(uniq=p["uniq"], refresh_every=refresh_every)   # drop the device buffers, keep the host inputs for the oracle
+    torch.cuda.empty_cache()
+    if args.variant == "dion" and args.form == "standard" and not args.calibration_copy and not args.no_also:
+        # the other configurations of the benchmark list, each timed the same way (fewer steps), in the same run
         also = {}
-        p = dict(uniq=p["uniq"], refresh_every=p["refresh_every"])   # drop the device buffers, keep the host inputs for the oracle
-        torch.cuda.empty_cache()
-        for tag in ("C2", "C2b"):
-            q = build_problem(inputs.CONFIGS[tag])
-            q["variant"], q["refresh_every"] = "dion", 1
-            for t in range(3):
-                do_step(q, t)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for t in range(20):
-                do_step(q, 3 + t)
-            torch.cuda.synchronize()
-            also[WORKLOAD_NAMES[tag]] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / 20, "steps": 20}
-            assert q["B"].dion_last_status(q["state"])[0] == 0
+        for tag, k, w in ALSO:
+            if tag == args.workload:
+                continue
+            q, ms, st = run_workload(tag, k, w, not args.no_stage_timing)
             del q
+            torch.cuda.empty_cache()
+            rf = stage_rooflines(tag, st, ceilings)
+            also[WORKLOAD_NAMES[tag]] = {"ms_per_step": ms, "steps": k, "warmup": w, "stage_ms": st,
+                                         "rooflines": {k2: {f: v[f] for f in ("bound", "achieved", "peak", "unit", "frac", "ms")}
+                                                       for k2, v in rf.items()}}
         out["also"] = also
     if not args.no_cpu_baseline and args.form == "standard":
-        out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=max(1, args.refresh_every) if args.variant == "lazy" else 1)
+        out["cpu_baseline"] = cpu_baseline(cfg, p, variant=args.variant, refresh_every=refresh_every)
     print(json.dumps(out))
 
 

@@ -327,6 +327,65 @@ def entry_update(X, G, M, P, R, mu, eta, rows, cols):
     return xs, ms
 
 
+# ---- block forms: whole rows / columns of one stage's output from that stage's inputs, for checks at sizes
+# ---- where a full fp64 step is too slow.  Each is the defining formula restricted to the listed rows or columns.
+
+def rows_Z(M, G, Q, rows):
+    """Z[rows, :] = (M + G)[rows, :] Q   (PowerIter1, first product)."""
+    rows = np.asarray(rows)
+    return (_f64(M[rows, :]) + _f64(G[rows, :])) @ _f64(Q)
+
+
+def cols_Z(M, G, Q, cols, chunk=2048):
+    """Z[:, cols] = (M + G) Q[:, cols], accumulated over blocks of `chunk` rows of M + G (memory only)."""
+    cols = np.asarray(cols)
+    Qc = _f64(Q[:, cols])
+    m = M.shape[0]
+    out = np.empty((m, len(cols)))
+    for i0 in range(0, m, chunk):
+        out[i0:i0 + chunk, :] = (_f64(M[i0:i0 + chunk, :]) + _f64(G[i0:i0 + chunk, :])) @ Qc
+    return out
+
+
+def rows_R(M, G, P, rows):
+    """R[rows, :] = ((M + G)[:, rows])^T P   (PowerIter1, second product; `rows` index the n side)."""
+    rows = np.asarray(rows)
+    return (_f64(M[:, rows]) + _f64(G[:, rows])).T @ _f64(P)
+
+
+def cols_R(M, G, P, cols, chunk=2048):
+    """R[:, cols] = (M + G)^T P[:, cols], accumulated over blocks of `chunk` rows of M + G."""
+    cols = np.asarray(cols)
+    m, n = M.shape
+    out = np.zeros((n, len(cols)))
+    for i0 in range(0, m, chunk):
+        out += (_f64(M[i0:i0 + chunk, :]) + _f64(G[i0:i0 + chunk, :])).T @ _f64(P[i0:i0 + chunk, :][:, cols])
+    return out
+
+
+def rows_update(X, G, M, P, R, mu, eta, rows):
+    """(X_new[rows, :], M_new[rows, :]) given the factors P and R:
+    M_new = B - (1-mu) P R^T;  X_new = X - eta sqrt(m/n) P ColNorm(R)^T."""
+    rows = np.asarray(rows)
+    m, n = X.shape
+    Qn, _ = col_norm(R)
+    Pr = _f64(P[rows, :])
+    Mn = (_f64(M[rows, :]) + _f64(G[rows, :])) - (1.0 - mu) * (Pr @ _f64(R).T)
+    Xn = _f64(X[rows, :]) - eta * np.sqrt(m / n) * (Pr @ Qn.T)
+    return Xn, Mn
+
+
+def cols_update(X, G, M, P, R, mu, eta, cols):
+    """(X_new[:, cols], M_new[:, cols]) given the factors P and R (ColNorm needs all of R's rows)."""
+    cols = np.asarray(cols)
+    m, n = X.shape
+    Qn, _ = col_norm(R)
+    Pd = _f64(P)
+    Mn = (_f64(M[:, cols]) + _f64(G[:, cols])) - (1.0 - mu) * (Pd @ _f64(R[cols, :]).T)
+    Xn = _f64(X[:, cols]) - eta * np.sqrt(m / n) * (Pd @ Qn[cols, :].T)
+    return Xn, Mn
+
+
 # ---- counter-based Gaussian fill used by the library's init call when it draws Q itself ----
 
 _PHILOX_M0 = 0xD2511F53

@@ -12,8 +12,8 @@ pytestmark = pytest.mark.gpu
 MU, ETA = inputs.MU, inputs.ETA
 
 
-def lazy_report(gp, i, x_in, m_in, v_in, g32, refresh):
-    ref = orc.lazy_dion_step(x_in, g32, m_in, v_in, MU, ETA, refresh)
+def lazy_report(gp, i, x_in, m_in, v_in, g32, refresh, method="householder"):
+    ref = orc.lazy_dion_step(x_in, g32, m_in, v_in, MU, ETA, refresh, method)
     X, M, V = gp.host(i)
     V64 = V.astype(np.float64)
     r = V.shape[1]
@@ -25,7 +25,7 @@ def lazy_report(gp, i, x_in, m_in, v_in, g32, refresh):
                 orth=float(np.abs(V64.T @ V64 - np.eye(r)).max())), ref
 
 
-def run_lazy(shapes, g_bf16, math, steps, k, tol, otol):
+def run_lazy(shapes, g_bf16, math, steps, k, tol, otol, method="householder"):
     # tol: state and the refreshed V (both products of a refresh round their operands to bf16 in bf16 mode);
     # otol: orthonormality of V, which comes from the fp32 / split-bf16 orthonormalisation in either mode
     gp = GpuProblem(shapes, g_bf16, math)
@@ -37,7 +37,8 @@ def run_lazy(shapes, g_bf16, math, steps, k, tol, otol):
         assert gp.lazy_step(MU, ETA, refresh) == (0, -1)
         for i in range(len(shapes)):
             g32 = gp.grad_as_f32(grads[i], g_bf16)
-            rep, _ = lazy_report(gp, i, *before[i], g32, refresh)
+            rep, _ = lazy_report(gp, i, *before[i], g32, refresh, method)
+            print("lazy step", t, shapes[i], "refresh" if refresh else "no refresh", {k_: "%.2e" % v for k_, v in rep.items()}, flush=True)
             assert rep["X"] <= tol and rep["M"] <= tol, (t, i, shapes[i], rep)
             assert rep["dX"] <= 3 * tol and rep["dM"] <= 3 * tol, (t, i, shapes[i], rep)
             assert rep["V"] <= tol and rep["orth"] <= otol, (t, i, shapes[i], rep)
@@ -60,6 +61,12 @@ def test_lazy_bf16_large_tile_path_tall_wide_and_batched():
     run_lazy([(512, 256, 128)], True, "bf16", 5, 2, 2e-2, 2e-4)
     run_lazy([(256, 768, 128)] * 2 + [(768, 256, 128)], True, "bf16", 4, 3, 2e-2, 2e-4)
     run_lazy([(1024, 1024, 512)], True, "bf16", 3, 2, 2e-2, 2e-4)                # single-launch Cholesky on n x r
+
+
+def test_lazy_bf16_full_size_direct_load_path():
+    # 8192 x 8192, r = 1024: the shape class whose K1 / K2 read the stored bf16 copies of M + G (the refresh writes
+    # both orientations, a step without refresh only the plain one); one step of each kind against the full oracle step
+    run_lazy([(8192, 8192, 1024)], True, "bf16", 2, 2, 2e-2, 2e-4, method="lapack")
 
 
 def test_lazy_step_without_refresh_is_defined_for_any_v():

@@ -13,8 +13,8 @@ MU, ETA = inputs.MU, inputs.ETA
 T, S = B.DION_FORM_TRANSPOSED, B.DION_FORM_STANDARD
 
 
-def transposed_report(gp, i, x_in, m_in, v_in, g32):
-    ref = orc.dion_step_transposed(x_in, g32, m_in, v_in, MU, ETA)
+def transposed_report(gp, i, x_in, m_in, v_in, g32, method="householder"):
+    ref = orc.dion_step_transposed(x_in, g32, m_in, v_in, MU, ETA, method)
     X, M, V = gp.host(i)
     V64 = V.astype(np.float64)
     return dict(status=ref["status"], X=relf(X, ref["X"]), M=relf(M, ref["M"]),
@@ -24,7 +24,7 @@ def transposed_report(gp, i, x_in, m_in, v_in, g32):
                 vnorm=float(np.abs(np.linalg.norm(V64, axis=0) - 1).max()))
 
 
-def run(shapes, forms, g_bf16, math, steps, tol):
+def run(shapes, forms, g_bf16, math, steps, tol, method="householder"):
     gp = GpuProblem(shapes, g_bf16, math, forms=forms)
     for t in range(steps):
         grads = gp.grads_np(t)
@@ -34,10 +34,11 @@ def run(shapes, forms, g_bf16, math, steps, tol):
         for i in range(len(shapes)):
             g32 = gp.grad_as_f32(grads[i], g_bf16)
             if forms[i] == T:
-                rep = transposed_report(gp, i, *before[i], g32)
+                rep = transposed_report(gp, i, *before[i], g32, method)
                 assert rep["vdot"] > 1 - 10 * tol and rep["vnorm"] < 1e-5, (t, i, shapes[i], rep)
             else:
-                rep, _ = one_step_report(gp, i, *before[i], g32, MU, ETA)
+                rep, _ = one_step_report(gp, i, *before[i], g32, MU, ETA, method)
+            print("step", t, shapes[i], "transposed" if forms[i] == T else "standard", {k_: "%.2e" % v for k_, v in rep.items()}, flush=True)
             assert rep["X"] <= tol and rep["M"] <= tol, (t, i, shapes[i], rep)
             assert rep["dX"] <= 3 * tol and rep["dM"] <= 3 * tol, (t, i, shapes[i], rep)
     return gp
@@ -53,6 +54,13 @@ def test_transposed_bf16_large_tile_path():
     run([(768, 256, 128)], [T], True, "bf16", 3, 2e-2)          # tall: the orthonormalisation runs on 256 x 128
     run([(256, 768, 128)], [T], True, "bf16", 3, 2e-2)
     run([(1024, 1024, 512)], [T], True, "bf16", 2, 2e-2)        # single-launch Cholesky
+
+
+def test_transposed_bf16_full_size_direct_load_path():
+    # shapes whose two products read the stored bf16 copies of M + G: square, and tall so that the
+    # orthonormalisation runs on the shorter side (8192 x 3072 is the W_down shape of the 3B decoder, batched by four)
+    run([(8192, 8192, 1024)], [T], True, "bf16", 2, 2e-2, method="lapack")
+    run([(8192, 3072, 768)] * 4, [T, T, T, T], True, "bf16", 1, 2e-2, method="lapack")
 
 
 def test_mixed_forms_in_one_batch():

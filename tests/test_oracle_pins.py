@@ -306,6 +306,36 @@ def test_entry_forms_match_full_step():
     assert np.abs(ms - res["M"][rows, jr]).max() < 1e-14
 
 
+def test_block_forms_match_full_step_and_explicit_loops():
+    m, n, r = 19, 13, 4
+    X, G, M, Q = rand_problem(m, n, r, seed=23)
+    mu, eta = 0.9, 0.03
+    res = orc.dion_step(X, G, M, Q, mu, eta)
+    rows, cols_r, rows_n, cols_n = [0, 18, 7], [3, 0], [12, 0, 5], [1, 12]
+    assert np.abs(orc.rows_Z(M, G, Q, rows) - res["Z"][rows, :]).max() < 1e-13
+    assert np.abs(orc.cols_Z(M, G, Q, cols_r, chunk=5) - res["Z"][:, cols_r]).max() < 1e-13
+    assert np.abs(orc.rows_R(M, G, res["P"], rows_n) - res["R"][rows_n, :]).max() < 1e-13
+    assert np.abs(orc.cols_R(M, G, res["P"], cols_r, chunk=5) - res["R"][:, cols_r]).max() < 1e-13
+    xr, mr = orc.rows_update(X, G, M, res["P"], res["R"], mu, eta, rows)
+    assert np.abs(xr - res["X"][rows, :]).max() < 1e-13 and np.abs(mr - res["M"][rows, :]).max() < 1e-13
+    xc, mc = orc.cols_update(X, G, M, res["P"], res["R"], mu, eta, cols_n)
+    assert np.abs(xc - res["X"][:, cols_n]).max() < 1e-13 and np.abs(mc - res["M"][:, cols_n]).max() < 1e-13
+    # one entry of each by explicit loops over the defining sums (catches a transposed operand in a block form)
+    i, a, j = 7, 3, 12
+    B = [[float(M[p, q]) + float(G[p, q]) for q in range(n)] for p in range(m)]
+    z = sum(B[i][q] * float(Q[q, a]) for q in range(n))
+    assert abs(orc.rows_Z(M, G, Q, [i])[0, a] - z) < 1e-13 and abs(orc.cols_Z(M, G, Q, [a])[i, 0] - z) < 1e-13
+    rr = sum(B[p][j] * res["P"][p, a] for p in range(m))
+    assert abs(orc.rows_R(M, G, res["P"], [j])[0, a] - rr) < 1e-13 and abs(orc.cols_R(M, G, res["P"], [a])[j, 0] - rr) < 1e-13
+    s = [np.sqrt(sum(res["R"][q, c] ** 2 for q in range(n))) for c in range(r)]
+    mn = B[i][j] - (1 - mu) * sum(res["P"][i, c] * res["R"][j, c] for c in range(r))
+    xn = float(X[i, j]) - eta * np.sqrt(m / n) * sum(res["P"][i, c] * res["R"][j, c] / (s[c] + orc.COLNORM_EPS) for c in range(r))
+    xr, mr = orc.rows_update(X, G, M, res["P"], res["R"], mu, eta, [i])
+    xc, mc = orc.cols_update(X, G, M, res["P"], res["R"], mu, eta, [j])
+    assert abs(xr[0, j] - xn) < 1e-13 and abs(mr[0, j] - mn) < 1e-13
+    assert abs(xc[i, 0] - xn) < 1e-13 and abs(mc[i, 0] - mn) < 1e-13
+
+
 # ---------------------------------------------------------------- counter-based generator
 def test_philox_known_answers():
     with open(os.path.join(GOLD, "philox4x32_10_kat.txt")) as f:
