@@ -6,7 +6,7 @@
  * rule and its PowerIter1 sub-routine (Section 3), the error-feedback equation of
  * Section 3.1, and Cholesky-QR orthonormalisation (Section 3.2, Appendix A):
  *
- *     B     = M + G                        (never stored; fused into operand loads)
+ *     B     = M + G                        (never stored in fp32; see "How M + G reaches the products" below)
  *     Z     = B Q                          (m x r)
  *     P     = Orthonormalize(Z)            (thin-QR factor, by CholeskyQR2)
  *     R     = B^T P                        (n x r)
@@ -15,6 +15,13 @@
  *     X_new = X - eta sqrt(m/n) P Q_new^T  (m = "out" rows, n = "in" columns)
  *
  * Names: the paper's V, P, U, W, beta are Q, Z, P, R, 1 - mu here.
+ *
+ * How M + G reaches the products.  The fused update adds M + G in fp32 in its epilogue.  The two products Z and R
+ * take it as an operand: in DION_MATH_F32, and in DION_MATH_BF16 for shapes whose outputs cannot fill the GPU with
+ * 256 x 256 tiles, the sum is formed in registers on the way into the matrix cores; for the large shapes of
+ * DION_MATH_BF16 (m, n multiples of 256, r a multiple of 256, at least 128 output tiles of 256 x 256 per group of
+ * equal shapes) one pass first stores bf16(M + G) and its transpose in the workspace (4 bytes per element) and
+ * the products read those.
  *
  * Conventions
  *   - All matrices are row-major and contiguous: X, G, M have leading dimension n, Q has r.
@@ -28,8 +35,16 @@
  *   - Return value: 0 on success, < 0 for a usage or runtime error found on the host (then
  *     nothing was launched by that call and no state was touched).  Numerical trouble is
  *     found on the device and reported later by dion_last_status.
- *   - No function throws; the library keeps no global state; one dion_state_t must not be
- *     used from two threads at once, and steps sharing a state must run on one stream.
+ *   - No function throws.  The only process-wide data are per-device caches of "this kernel may use more than
+ *     64 KB of LDS" (set once per device and kernel).  One dion_state_t must not be used from two threads at once,
+ *     and steps sharing a state must run on one stream.
+ *   - Ranks of 256 and more (up to 128 matrices per group of equal shapes) are factored by single-launch kernels
+ *     whose workgroups wait for one another and therefore must all be resident at once: one per compute unit,
+ *     sized from the device's compute-unit count read at dion_init_state.  Steps of two states that run
+ *     concurrently on two streams, or any other kernels that occupy compute units for long, can keep them from
+ *     becoming resident; the waits then give up after dion_set_wait_limit polls and the matrix is reported as
+ *     DION_WAIT_TIMEOUT (state untouched; dion_retry_breakdowns repeats it without those kernels).  Run steps of
+ *     different states one after another on one stream, or make the later one wait on an event of the earlier.
  *   - Precondition 1 <= r <= min(m, n).
  */
 #ifndef DION_H
@@ -49,14 +64,26 @@ enum {
   DION_EWORKSPACE = -2,  /* workspace too small */
   DION_ELAUNCH = -3,     /* a HIP runtime call failed */
   DION_ENOMEM = -4,      /* host allocation failed */
-  DION_NUM_BREAKDOWN = 1 /* Cholesky met a non-positive or non-finite pivot: Z is rank deficient or too ill
-                            conditioned for Cholesky-QR (Appendix A); X, M, Q of that matrix were left untouched */
+  DION_NUM_BREAKDOWN = 1, /* Cholesky met a non-positive or non-finite pivot: Z is rank deficient or too ill
+                             conditioned for Cholesky-QR (Appendix A); X, M, Q of that matrix were left untouched */
+  DION_WAIT_TIMEOUT = 2   /* a bounded wait between the workgroups of a single-launch factorisation or inverse gave
+                             up (the GPU could not keep the whole launch resident); says nothing about the matrix;
+                             X, M, Q of that matrix were left untouched */
 };
 
 enum { DION_G_F32 = 0, DION_G_BF16 = 1 };       /* storage type of the gradient G */
 enum { DION_MATH_F32 = 0, DION_MATH_BF16 = 1 }; /* operand type of the four large products (Z, R and the two
-                                                   rank-r updates); accumulation, the orthonormalisation and all
-                                                   state are fp32 in both modes */
+                                                   rank-r updates); accumulation and all state are fp32 in both
+                                                   modes.  Orthonormalisation: DION_MATH_F32 runs CholeskyQR2 on
+                                                   the fp32 matrix pipe (||P^T P - I||_max <= 1e-5).  DION_MATH_BF16
+                                                   runs its Gram matrix and triangular multiply as three bf16
+                                                   products of split operands (x = hi + lo, about 16 mantissa
+                                                   bits), the r x r factorisation and inverse in fp32, and cuts the
+                                                   second pass short: when the first pass' result P1 has
+                                                   ||P1^T P1 - I||_F <= 1e-3 it is taken as P (both consumers of P
+                                                   round it to bf16 anyway), so the usual step is one Cholesky-QR
+                                                   pass plus that check; ||P^T P - I||_max <= 1e-3 is what this
+                                                   mode guarantees */
 
 typedef struct dion_state dion_state_t; /* opaque host object: declared shapes, flags, carved workspace */
 
@@ -67,7 +94,7 @@ int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const in
 
 /* Creates the optimizer state for `count` matrices (Algorithm 1: the state of a matrix is its
  * momentum M and right factor Q) and initialises it on the device:
- *   M[i] <- 0;   Q[i] <- ColNorm(Q[i]) if q_is_filled, else ColNorm of an m x r draw of N(0,1)
+ *   M[i] <- 0;   Q[i] <- ColNorm(Q[i]) if q_is_filled, else ColNorm of an n x r draw of N(0,1)
  *   (Philox-4x32-10 keyed by `seed`, stream = i, Box-Muller).
  * workspace_dev: device buffer of at least dion_workspace_bytes(...) bytes, 256-byte aligned,
  * owned by the caller and kept alive until dion_destroy_state.  M_dev / Q_dev: host arrays of
@@ -143,9 +170,9 @@ int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* cons
                      const int64_t* m, const int64_t* n, const int64_t* r1, const int64_t* r2,
                      float mu1, float mu2, float eta, void* hip_stream);
 
-/* Waits for the stream of the last step and reports its numerical status: *status_out is
- * DION_OK or DION_NUM_BREAKDOWN; *first_bad_index is the lowest matrix index that broke
- * down (-1 if none).  Either pointer may be NULL. */
+/* Waits for the stream of the last step and reports its status: *first_bad_index is the lowest matrix index
+ * whose step did not complete (-1 if none), *status_out what happened to that matrix (DION_OK,
+ * DION_NUM_BREAKDOWN or DION_WAIT_TIMEOUT).  Either pointer may be NULL. */
 int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
 
 /* Orthonormalisation variant used by later steps (Section 3.2 and Appendix A: Cholesky-QR is the fast
@@ -159,10 +186,12 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
 enum { DION_ORTH_CHOLQR2 = 0, DION_ORTH_SHIFTED_CHOLQR3 = 1 };
 int dion_set_orth_mode(dion_state_t* st, int mode);
 
-/* Fallback for matrices whose last step reported DION_NUM_BREAKDOWN (Appendix A: when Cholesky-QR fails the
- * step falls back to a more robust orthonormalisation).  Waits for the last step, reads the per-matrix status
- * words and repeats the step, with DION_ORTH_SHIFTED_CHOLQR3, for exactly the matrices that broke down (their
- * X, M, Q were left untouched, so this completes the step; matrices that succeeded are not stepped again).
+/* Fallback for matrices whose last step did not complete (Appendix A: when Cholesky-QR fails the step falls
+ * back to a more robust orthonormalisation).  Waits for the last step, reads the per-matrix status words and
+ * repeats the step for exactly the matrices concerned (their X, M, Q were left untouched, so this completes the
+ * step; matrices that succeeded are not stepped again): with DION_ORTH_SHIFTED_CHOLQR3 after a
+ * DION_NUM_BREAKDOWN; in the state's own mode but with one launch per panel, i.e. without the kernels that
+ * wait, after a DION_WAIT_TIMEOUT.
  * Arguments as for the dion_step_batched call being completed, G unchanged since then.  *retried_out (may be
  * NULL) receives the number of matrices repeated.  The state's orthonormalisation mode is left as it was;
  * dion_last_status afterwards reports the outcome of the repeated steps. */
@@ -174,9 +203,15 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
  * follows it, which factor and invert up to 128 matrices of rank 256 and more with workgroups that wait for one
  * another's results (Appendix A names the factorisation; how it is scheduled is this library's business).  A
  * workgroup that has polled `polls` times without success gives up, all others follow, the kernel ends, and the
- * matrix is reported as DION_NUM_BREAKDOWN with X, M, Q untouched; a later step is not affected.  The default (about a million polls, on the order of a second) is only ever reached when
+ * matrix is reported as DION_WAIT_TIMEOUT with X, M, Q untouched; a later step is not affected.  The default (about a million polls, on the order of a second) is only ever reached when
  * the GPU cannot keep all workgroups of the kernel resident; 0 makes every wait fail, for tests of this path. */
 int dion_set_wait_limit(dion_state_t* st, unsigned polls);
+
+/* How the r x r factorisation of Cholesky-QR (Appendix A) would be scheduled for `batch` matrices of rank r on a
+ * GPU with `compute_units` compute units: *pr_out x *pc_out workgroups per matrix in one launch whose
+ * pr * pc * batch workgroups all have to be resident at once (never more than compute_units), or 0 x 0 for one
+ * launch per 64-column panel with no waits between workgroups.  Host only: touches no GPU. */
+int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* pr_out, int* pc_out);
 
 /* Stage timing.  With enable != 0 every later step brackets its stages with HIP events on
  * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <

@@ -19,6 +19,7 @@ DION_EWORKSPACE = -2
 DION_ELAUNCH = -3
 DION_ENOMEM = -4
 DION_NUM_BREAKDOWN = 1
+DION_WAIT_TIMEOUT = 2
 DION_G_F32, DION_G_BF16 = 0, 1
 DION_MATH_F32, DION_MATH_BF16 = 0, 1
 STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
@@ -29,7 +30,7 @@ DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
            "dion_double_step", "dion_last_status",
-           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_set_stage_timing", "dion_stage_times", "dion_measure_ceilings", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
+           "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_cholesky_grid", "dion_set_stage_timing", "dion_stage_times", "dion_measure_ceilings", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
 
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_wait_limit.argtypes = [C.c_void_p, C.c_uint]
+        L.dion_cholesky_grid.argtypes = [C.c_int, C.c_int, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dion_measure_ceilings.argtypes = [C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
         L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
@@ -292,6 +294,13 @@ def dion_set_orth_mode(state: DionState, mode: int) -> None:
 
 def dion_set_wait_limit(state: DionState, polls: int) -> None:
     _check(lib().dion_set_wait_limit(state.handle, int(polls)), "dion_set_wait_limit")
+
+
+def dion_cholesky_grid(compute_units: int, batch: int, r: int) -> Tuple[int, int]:
+    """(pr, pc): workgroups per matrix of the single-launch factorisation, or (0, 0) for a launch per panel.  Host only."""
+    pr, pc = C.c_int(0), C.c_int(0)
+    _check(lib().dion_cholesky_grid(int(compute_units), int(batch), int(r), C.byref(pr), C.byref(pc)), "dion_cholesky_grid")
+    return int(pr.value), int(pc.value)
 
 
 def dion_set_stage_timing(state: DionState, enable: bool) -> None:

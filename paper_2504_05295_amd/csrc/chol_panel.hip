@@ -165,7 +165,7 @@ __device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw
         constexpr int k = decltype(kc)::value;
         Lout[(long long)lane * ld + k] = (k <= lane) ? l[k] : 0.f;
       });
-      if (bad && lane == 0 && *status == 0) *status = 1;   // a code that is already there (an earlier stage failed) stays
+      if (bad && lane == 0 && *status == 0) *status = ST_BREAKDOWN;   // a code that is already there (an earlier stage failed) stays
     }
 }
 
@@ -355,8 +355,8 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
 // its other work.  Every workgroup handles its tasks in an order in which a task only waits for tasks that
 // come earlier in the common order (panel, then D < T < U), so somebody can always proceed.
 // Flags carry the number of the launch (epoch, a counter kept in device memory) and need no clearing.  Waits are bounded: a workgroup that
-// gives up raises the abort word, everybody else sees it at the next wait, and the status word reports the
-// matrix as failed; all workgroups must be resident at once, which the host guarantees by the grid size.
+// gives up raises the abort word, everybody else sees it at the next wait, and the status word reports a wait
+// timeout for the matrix (not a breakdown: nothing is known about its numerics); all workgroups must be resident at once, which the host guarantees by the grid size.
 namespace {
 typedef unsigned long long u64;
 typedef __attribute__((address_space(1))) float gfloat;
@@ -424,7 +424,7 @@ __device__ __forceinline__ bool wait_until(const StreamCtx& x, int* gave_up, boo
       __builtin_amdgcn_s_sleep(2);
       if (++n > x.spin_limit) {
         flag_store(x.abort_word, x.epoch);
-        if (*x.status == 0) *x.status = 1;
+        if (*x.status == 0) *x.status = ST_TIMEOUT;
         *(volatile int*)gave_up = 1;
         break;
       }
@@ -605,7 +605,7 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
       }
       if (!wait_until(x, &gave_up, need, [&] {
             const u64 v = flag_load(x.lflag + t);
-            return (v >> 32) == x.epoch && (unsigned)v >= (unsigned)(k + 1);
+            return (unsigned)(v >> 32) == (unsigned)x.epoch && (unsigned)v >= (unsigned)(k + 1);   // (the tag holds the epoch's low 32 bits)
           }))
         return;
     }

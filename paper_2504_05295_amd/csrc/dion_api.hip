@@ -2,9 +2,10 @@
 //
 // Sequence per shape group (Algorithm 1 + unsharded update rule + PowerIter1 of the paper; the
 // data-parallel all-reduces of PowerIter1 are absent because everything runs on one GPU):
-//   K1  Z = (M+G) Q                      MFMA GEMM, M+G fused into the operand load
+//   K1  Z = (M+G) Q                      MFMA GEMM; M+G fused into the operand load, or (shapes that fill the GPU with
+//                                        256-wide tiles) read from bf16 copies of M+G that one pass writes first
 //   orth: CholeskyQR2 (Appendix A applied twice): Gram, blocked Cholesky, triangular inverse, Z L^-T
-//   K2  R = (M+G)^T P                    MFMA GEMM, transposing operand load
+//   K2  R = (M+G)^T P                    MFMA GEMM, transposing operand load or the transposed bf16 copy
 //   K6  s_j = ||R_j||, d_j = 1/(s_j + eps);   K7  Q = R diag(d)
 //   K5  M = (M+G) - (1-mu) P R^T ;  X = X - eta sqrt(m/n) P Q^T     one fused pass
 // The stages are functions of their own (stage_k1, stage_orth, ...); the Dion step, its transposed form, the
@@ -30,6 +31,20 @@ int pick_variant(long long M, long long N, long long K, long long batch, bool al
     return (tiles >= 256 || !small_ok) ? VAR_BIG : VAR_SMALL;
   }
   return small_ok ? VAR_SMALL : VAR_SMALL_CHECKED;
+}
+void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc) {
+  *pr = 0; *pc = 0;
+  if (cus < 1 || batch < 1 || nb < 4 || nb > 128) return;
+  // From two workgroups per matrix on the single launch still beats a launch per panel, in which every workgroup redoes
+  // the diagonal block and the second pass costs a launch per panel to skip.
+  const int per = cus / batch;
+  if (per >= 256 && nb >= 16) { *pr = 16; *pc = 16; }
+  else if (per >= 64) { *pr = 8; *pc = 8; }
+  else if (per >= 16) { *pr = 4; *pc = 4; }
+  else if (per >= 8) { *pr = 4; *pc = 2; }
+  else if (per >= 4) { *pr = 2; *pc = 2; }
+  else if (per >= 2) { *pr = 2; *pc = 1; }
+  if ((long long)*pr * *pc * batch > cus || *pr * *pc > INV_TREE_MAX_GROUPS) { *pr = 0; *pc = 0; }
 }
 }  // namespace dion
 
@@ -223,6 +238,8 @@ struct dion_state {
   unsigned long long* step_counter;   // device: number of steps enqueued so far (tags the flags of the Cholesky kernel)
   hipStream_t last_stream;
   bool timing;
+  int cus;            // compute units of the device the state was created on
+  bool force_panel;   // factor with a launch per panel even where the single-launch kernels would serve
   int orth_mode;
   unsigned chol_spin_limit;  // polls after which a wait inside that kernel gives up
   std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
@@ -236,6 +253,54 @@ struct dion_state {
   } while (0)
 
 namespace {
+
+// Host part of creating a state: the plan, the carving of the workspace and the host image of the pointer table
+// (M_dev / Q_dev may be null: those two slots are refreshed by every step anyway).  Touches no device memory.
+int plan_state(dion_state* st, int count, const int64_t* m, const int64_t* n, const int64_t* r, const int* form, int g_dtype,
+               int math, void* workspace_dev, size_t workspace_bytes, void* const* M_dev, void* const* Q_dev,
+               std::vector<void*>& host) {
+  st->count = count; st->g_dtype = g_dtype; st->math = math;
+  build_plan(count, m, n, r, form, st->entries, st->groups);
+  st->ws = (char*)workspace_dev;
+  st->ws_bytes = workspace_bytes;
+  st->table = (void**)st->ws;
+  st->status = (int*)(st->ws + align_up((size_t)count * NSLOTS * sizeof(void*), 256));
+  st->step_counter = (unsigned long long*)((char*)st->status + align_up((size_t)count * sizeof(int), 256));
+  st->last_stream = nullptr;
+  st->timing = false;
+  st->force_panel = false;
+  st->cus = 0;
+  {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&st->cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || st->cus < 1)
+      return DION_ELAUNCH;
+  }
+  st->orth_mode = DION_ORTH_CHOLQR2;
+  st->chol_spin_limit = 1u << 20;
+  st->group_timed.assign(st->groups.size(), 0);
+  host.assign((size_t)count * NSLOTS, nullptr);
+  size_t pos = header_bytes(count);
+  std::vector<size_t> group_base(st->groups.size());
+  for (size_t k = 0; k < st->groups.size(); ++k) {
+    group_base[k] = pos;
+    st->groups[k].ws_off = pos;
+    pos += st->groups[k].bytes_per_entry * st->groups[k].count;
+  }
+  for (int i = 0; i < count; ++i) {
+    const Entry& e = st->entries[i];
+    const Group& g = st->groups[e.group];
+    const Carve c = carve_entry(g);
+    char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
+    void** rowp = &host[(size_t)e.row * NSLOTS];
+    for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
+    for (int sl = SLOT_QT16; sl <= SLOT_B16T; ++sl) rowp[sl] = base + c.off[sl];
+    rowp[SLOT_STATUS] = st->status + e.row;
+    rowp[SLOT_M] = M_dev ? M_dev[i] : nullptr;
+    rowp[SLOT_Q] = Q_dev ? Q_dev[i] : nullptr;
+  }
+  return DION_OK;
+}
 
 GemmArgs base_args(const dion_state* st, const Group& g) {
   GemmArgs a;
@@ -274,19 +339,10 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   GemmArgs base = rebase(base_args(st, g), row0);
   const int nb = rp / CHOL_NB;
   // Workgroups per matrix for the single-launch driver: all of a launch must be resident at once (one per compute
-  // unit), so a batch shares the 256 compute units; from two workgroups per matrix on it still beats a launch per
-  // panel, in which every workgroup redoes the diagonal block and the second pass costs a launch per panel to skip.
+  // unit), so a batch shares the compute units this GPU has (read once, when the state was created).
   int spr = 0, spc = 0;
-  {
-    const int per = 256 / (batch > 0 ? batch : 1);
-    if (per >= 256 && nb >= 16) { spr = 16; spc = 16; }
-    else if (per >= 64) { spr = 8; spc = 8; }
-    else if (per >= 16) { spr = 4; spc = 4; }
-    else if (per >= 8) { spr = 4; spc = 2; }
-    else if (per >= 4) { spr = 2; spc = 2; }
-    else if (per >= 2) { spr = 2; spc = 1; }
-  }
-  const bool use_stream = spr > 0 && nb >= 4 && nb <= 128;
+  if (!st->force_panel) plan_chol_grid(st->cus, batch, nb, &spr, &spc);
+  const bool use_stream = spr > 0;
   // The split-K partial Gram matrices of an adaptive pass are added up by its defect kernel, which reads the whole
   // Gram matrix anyway (and stores the sum); other passes run a reduction kernel.  (Adding them up inside the
   // single-launch factorisation, every workgroup its own tiles, was measured slower than that kernel.)
@@ -421,7 +477,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ta.step_counter = st->step_counter;
     ta.pass = pass;
     ta.spin_limit = st->chol_spin_limit;
-    HIPCHK(launch_inv_tree(ta, spr * spc, batch, s));
+    HIPCHK(launch_inv_tree(ta, spr * spc, batch, st->cus, s));
   } else {
     // one launch per product: an odd block is carried to the next level, so any multiple of 64 works; runs of equal,
     // evenly spaced pairs go out as one launch
@@ -911,39 +967,13 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
   dion_state* st = nullptr;
   try {
     st = new dion_state();
-    st->count = count; st->g_dtype = g_dtype; st->math = math;
-    build_plan(count, m, n, r, form, st->entries, st->groups);
-    st->ws = (char*)workspace_dev;
-    st->ws_bytes = workspace_bytes;
-    st->table = (void**)st->ws;
-    st->status = (int*)(st->ws + align_up((size_t)count * NSLOTS * sizeof(void*), 256));
-    st->step_counter = (unsigned long long*)((char*)st->status + align_up((size_t)count * sizeof(int), 256));
+    std::vector<void*> host;
+    const int prc = plan_state(st, count, m, n, r, form, g_dtype, math, workspace_dev, workspace_bytes, M_dev, Q_dev, host);
+    if (prc != DION_OK) {
+      delete st;
+      return prc;
+    }
     st->last_stream = s;
-    st->timing = false;
-    st->orth_mode = DION_ORTH_CHOLQR2;
-    st->chol_spin_limit = 1u << 20;
-    st->group_timed.assign(st->groups.size(), 0);
-    // host image of the pointer table
-    std::vector<void*> host((size_t)count * NSLOTS, nullptr);
-    size_t pos = header_bytes(count);
-    std::vector<size_t> group_base(st->groups.size());
-    for (size_t k = 0; k < st->groups.size(); ++k) {
-      group_base[k] = pos;
-      st->groups[k].ws_off = pos;
-      pos += st->groups[k].bytes_per_entry * st->groups[k].count;
-    }
-    for (int i = 0; i < count; ++i) {
-      const Entry& e = st->entries[i];
-      const Group& g = st->groups[e.group];
-      const Carve c = carve_entry(g);
-      char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
-      void** rowp = &host[(size_t)e.row * NSLOTS];
-      for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-      for (int sl = SLOT_QT16; sl <= SLOT_B16T; ++sl) rowp[sl] = base + c.off[sl];
-      rowp[SLOT_STATUS] = st->status + e.row;
-      rowp[SLOT_M] = M_dev[i];
-      rowp[SLOT_Q] = Q_dev[i];
-    }
     const unsigned long long zero = 0;
     if (hipMemcpy(st->step_counter, &zero, sizeof(zero), hipMemcpyHostToDevice) != hipSuccess ||
         (count > 0 && hipMemcpy(st->table, host.data(), host.size() * sizeof(void*), hipMemcpyHostToDevice) != hipSuccess)) {
@@ -1140,12 +1170,15 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
   st->last_stream = s;
   std::fill(st->group_timed.begin(), st->group_timed.end(), 0);
   const int saved_mode = st->orth_mode;
-  st->orth_mode = DION_ORTH_SHIFTED_CHOLQR3;
   int retried = 0, rc = DION_OK;
   for (int i = 0; i < count && rc == DION_OK; ++i) {
     const Entry& e = st->entries[i];
     if (host[e.row] == 0) continue;
     const Group& g = st->groups[e.group];
+    // a wait that timed out says nothing about the matrix: same orthonormalisation, without the kernels that wait;
+    // a breakdown: the shifted three-pass variant
+    st->force_panel = host[e.row] == ST_TIMEOUT;
+    st->orth_mode = st->force_panel ? saved_mode : DION_ORTH_SHIFTED_CHOLQR3;
     void* xs[1] = {X[i]};
     const void* gs[1] = {G[i]};
     void* ms[1] = {M[i]};
@@ -1155,6 +1188,7 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
     ++retried;
   }
   st->orth_mode = saved_mode;
+  st->force_panel = false;
   if (retried_out) *retried_out = retried;
   return rc;
 }
@@ -1167,10 +1201,10 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {
     try {
       std::vector<int> host(st->count);
       HIPCHK(hipMemcpy(host.data(), st->status, sizeof(int) * st->count, hipMemcpyDeviceToHost));
-      for (int i = 0; i < st->count; ++i)
+      for (int i = 0; i < st->count && bad < 0; ++i)
         if (host[st->entries[i].row] != 0) {
-          status = DION_NUM_BREAKDOWN;
-          if (bad < 0) bad = i;
+          status = host[st->entries[i].row] == ST_TIMEOUT ? DION_WAIT_TIMEOUT : DION_NUM_BREAKDOWN;
+          bad = i;
         }
     } catch (const std::bad_alloc&) {
       return DION_ENOMEM;
@@ -1184,6 +1218,12 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {
 int dion_set_orth_mode(dion_state_t* st, int mode) {
   if (!st || (mode != DION_ORTH_CHOLQR2 && mode != DION_ORTH_SHIFTED_CHOLQR3)) return DION_EINVAL;
   st->orth_mode = mode;
+  return DION_OK;
+}
+
+int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* pr_out, int* pc_out) {
+  if (compute_units < 1 || batch < 1 || r < 1 || r > 32768 || !pr_out || !pc_out) return DION_EINVAL;
+  plan_chol_grid(compute_units, batch, padded_rank(r) / CHOL_NB, pr_out, pc_out);
   return DION_OK;
 }
 
@@ -1264,6 +1304,7 @@ const char* dion_strerror(int code) {
     case DION_ELAUNCH: return "HIP runtime error";
     case DION_ENOMEM: return "host allocation failed";
     case DION_NUM_BREAKDOWN: return "Cholesky breakdown: Z rank deficient or too ill conditioned";
+    case DION_WAIT_TIMEOUT: return "a wait between workgroups timed out: the GPU could not keep a single-launch kernel resident";
     default: return "unknown code";
   }
 }

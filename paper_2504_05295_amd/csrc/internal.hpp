@@ -44,6 +44,14 @@ enum Slot {
   NSLOTS = 32
 };
 
+// Values of a matrix' device status word (SLOT_STATUS).  0 = fine; anything else gates the state-writing kernels.
+enum StatusWord {
+  ST_OK = 0,
+  ST_BREAKDOWN = 1,   // a Cholesky pivot outside its bounds: numerical property of the matrix
+  ST_TIMEOUT = 2,     // a bounded wait inside a single-launch kernel gave up: scheduling, not numerics
+  ST_UPSTREAM = 3     // Double Dion: the first stage of this matrix failed, the second was not attempted
+};
+
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
 constexpr float COLNORM_EPS = 1e-8f;
 constexpr int GRAM_DEFECT_PARTS = 1024;   // workgroups (and partial sums) of the kernel that measures ||C - I||_F
@@ -177,7 +185,11 @@ struct InvTreeArgs {
   int pass;
   unsigned spin_limit;
 };
-hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, hipStream_t s);
+hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, int cus, hipStream_t s);
+// Workgroup grid pr x pc per matrix of the single-launch factorisation (and pr * pc groups for the inverse) for `batch`
+// matrices of nb 64-wide panels on a GPU with `cus` compute units; pr = 0: use a launch per panel instead.  All
+// pr * pc * batch workgroups must be resident at once, one per compute unit.
+void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc);
 // 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
 constexpr int chol_sync_words(int nb) { return 2 * nb + 2; }
 constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }

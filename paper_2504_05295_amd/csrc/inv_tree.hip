@@ -10,7 +10,7 @@
 // the workgroups of a matrix meet at a barrier made of one arrival word per workgroup (tagged with the
 // launch's epoch, so never cleared); what crosses between workgroups is written and read with device-scope accesses.
 // Waits are bounded as in the factorisation kernel: who gives up raises the abort word, the others follow,
-// and the matrix is reported as failed.  All workgroups of a launch must be resident at once (the host keeps
+// and the matrix is reported with the wait-timeout status.  All workgroups of a launch must be resident at once (the host keeps
 // the grid within one workgroup per compute unit).
 #include <type_traits>
 
@@ -60,11 +60,11 @@ __device__ __forceinline__ bool group_barrier(const TreeCtx& x, unsigned& count,
     unsigned n = 0;
     for (;;) {
       const u64 v = flag_load(x.arrive + t);
-      if ((v >> 32) == x.epoch && (unsigned)v >= count) break;
+      if ((unsigned)(v >> 32) == (unsigned)x.epoch && (unsigned)v >= count) break;   // (the tag holds the epoch's low 32 bits)
       __builtin_amdgcn_s_sleep(1);
       if (++n > x.spin_limit) {
         flag_store(x.abort_word, x.epoch);
-        if (*x.status == 0) *x.status = 1;
+        if (*x.status == 0) *x.status = ST_TIMEOUT;
         *(volatile int*)gave_up = 1;
         break;
       }
@@ -201,8 +201,8 @@ __global__ void __launch_bounds__(256) inv_tree_kernel(InvTreeArgs p) {
   }
 }
 
-hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, hipStream_t s) {
-  if (groups < 1 || groups > INV_TREE_MAX_GROUPS || (long long)groups * batch > 256) return hipErrorInvalidValue;
+hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, int cus, hipStream_t s) {
+  if (groups < 1 || groups > INV_TREE_MAX_GROUPS || (long long)groups * batch > cus) return hipErrorInvalidValue;
   hipLaunchKernelGGL(inv_tree_kernel, dim3(groups, batch), dim3(256), 0, s, p);
   return hipGetLastError();
 }

@@ -45,7 +45,7 @@ struct RowPairChunk {
 };
 __global__ void copy_status_rows_kernel(const int* src_status, int* dst_status, const RowPairChunk c) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < c.count) dst_status[c.dst[t]] = src_status[c.src[t]] != 0 ? 2 : 0;   // 2: failed before this stage began
+  if (t < c.count) dst_status[c.dst[t]] = src_status[c.src[t]] != 0 ? ST_UPSTREAM : ST_OK;   // failed before this stage began
 }
 hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,
                                    hipStream_t s) {

@@ -59,6 +59,57 @@ def test_workspace_bytes_validation(lib):
     assert lib.dion_workspace_bytes(0, None, None, None, 0, 0, None) == B.DION_EINVAL
 
 
+def test_wait_timeout_has_its_own_code(lib):
+    assert B.DION_WAIT_TIMEOUT not in (B.DION_OK, B.DION_NUM_BREAKDOWN)
+    assert "wait" in B.strerror(B.DION_WAIT_TIMEOUT)
+
+
+def test_cholesky_grid_fits_the_compute_units(lib):
+    """The single-launch factorisation needs all its workgroups resident at once: whatever the planner picks must
+    fit the compute units it was told about, for any batch and rank, and it must fall back to a launch per panel
+    (0 x 0) when nothing fits."""
+    for cus in (1, 2, 7, 64, 104, 228, 256, 304, 1024):
+        for batch in (1, 2, 3, 4, 5, 16, 28, 56, 112, 128, 129, 196, 256, 257, 1000):
+            for r in (1, 63, 64, 255, 256, 257, 512, 768, 1024, 2048, 4096, 8192, 8193, 32768):
+                pr, pc = B.dion_cholesky_grid(cus, batch, r)
+                nb = (r + 63) // 64
+                assert (pr == 0) == (pc == 0)
+                assert pr * pc * batch <= cus and pr * pc <= 256
+                if nb < 4 or nb > 128 or cus // batch < 2:
+                    assert (pr, pc) == (0, 0)
+                if pr:
+                    assert pr >= pc >= 1
+    assert B.dion_cholesky_grid(256, 1, 2048) == (16, 16)
+    assert B.dion_cholesky_grid(256, 1, 768) == (8, 8)
+    assert B.dion_cholesky_grid(256, 112, 768) == (2, 1)
+    assert B.dion_cholesky_grid(256, 196, 768) == (0, 0)
+    for bad in [(0, 1, 64), (256, 0, 64), (256, 1, 0), (256, 1, 40000)]:
+        with pytest.raises(B.DionError):
+            B.dion_cholesky_grid(*bad)
+    assert lib.dion_cholesky_grid(256, 1, 64, None, None) == B.DION_EINVAL
+
+
+def test_workspace_bytes_sweep(lib):
+    """Planning arithmetic over a grid of shapes and batch sizes, beyond 256 matrices per group (all divisions by
+    the batch size are exercised): sizes are 256-byte multiples between what Z, P and R alone take and a generous
+    bound.  (The total need not grow with the batch: buffers of split-k partial results shrink as a batch fills the
+    GPU without splitting.)"""
+    import itertools
+    for g_dtype, math in ((B.DION_G_F32, B.DION_MATH_F32), (B.DION_G_BF16, B.DION_MATH_BF16)):
+        for (m, n, r) in [(64, 64, 1), (200, 136, 24), (256, 256, 64), (512, 256, 128), (1024, 768, 512), (3072, 8192, 768),
+                          (8192, 3072, 768), (8192, 8192, 2048), (16384, 53248, 4096), (70000, 96, 96), (96, 70000, 96)]:
+            for count in (1, 2, 3, 7, 112, 196, 255, 256, 257, 300, 1024):
+                b = B.dion_workspace_bytes([(m, n, r)] * count, g_dtype, math)
+                assert b > 0 and b % 256 == 0
+                assert b >= count * 4 * (2 * m * r + n * r)          # at least Z, P and R
+                assert b <= 512 + count * (256 * 40 + 4 * (8 * max(m, n) * r + 80 * ((r + 63) // 64 * 64) ** 2 + m * n + 2 * (m + n) * r)) + 8 * 600 * count
+    # mixed groups: the total does not depend on the order of the matrices
+    shapes = [(256, 256, 64)] * 5 + [(512, 256, 128)] * 3 + [(200, 136, 24)]
+    ref = B.dion_workspace_bytes(shapes, B.DION_G_BF16, B.DION_MATH_BF16)
+    for perm in itertools.islice(itertools.permutations(range(len(shapes))), 0, 5000, 577):
+        assert B.dion_workspace_bytes([shapes[i] for i in perm], B.DION_G_BF16, B.DION_MATH_BF16) == ref
+
+
 def test_null_state_is_rejected(lib):
     assert lib.dion_step(None, None, None, None, None, 4, 4, 2, 0.9, 0.1, None) == B.DION_EINVAL
     assert lib.dion_step_batched(None, 0, None, None, None, None, None, None, None, 0.9, 0.1, None) == B.DION_EINVAL
