@@ -170,6 +170,25 @@ int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* cons
                      const int64_t* m, const int64_t* n, const int64_t* r1, const int64_t* r2,
                      float mu1, float mu2, float eta, void* hip_stream);
 
+/* For callers that cannot allocate device memory and cannot let a library do it: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  One Dion step for one matrix in the standard form, as
+ * dion_step computes it, on a workspace that is part of the library: a static device array of
+ * DION_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.  There is no state
+ * object: the caller owns the optimizer state M (m x n, zero before the first step) and Q (n x r, columns of unit
+ * norm before the first step) and passes it to every call, with the storage type of G and the operand mode that
+ * dion_init_state would have been given.  status_dev: device pointer (4-byte aligned, or NULL) that receives the
+ * matrix' status word once the step has run on the stream: 0, DION_NUM_BREAKDOWN or DION_WAIT_TIMEOUT.
+ * The call enqueues kernels on hip_stream and nothing else: no hipMalloc, hipFree, memset, copy or host wait.
+ * The first call on a device does the one-time set-up of that device (looks up the array's address, gives the
+ * large-tile kernels leave to use more than 64 KB of LDS) and should be made outside a capture.
+ * Errors: DION_EINVAL as for dion_step; DION_EWORKSPACE when dion_workspace_bytes of the shape exceeds
+ * DION_STATIC_SCRATCH_BYTES (1024 x 1024 at r = 256 still fits; nothing is launched then).
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (two streams, two
+ * threads) race; calls on one stream, or ordered by events, are fine.  Not thread-safe per device. */
+#define DION_STATIC_SCRATCH_BYTES (32u << 20)
+int dion_step_static(void* X, const void* G, void* M, void* Q, int64_t m, int64_t n, int64_t r, int g_dtype, int math,
+                     float mu, float eta, int* status_dev, void* hip_stream);
+
 /* Waits for the stream of the last step and reports its status: *first_bad_index is the lowest matrix index
  * whose step did not complete (-1 if none), *status_out what happened to that matrix (DION_OK,
  * DION_NUM_BREAKDOWN or DION_WAIT_TIMEOUT).  Either pointer may be NULL. */

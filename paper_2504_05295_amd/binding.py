@@ -29,7 +29,7 @@ DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",
-           "dion_double_step", "dion_last_status",
+           "dion_double_step", "dion_step_static", "dion_last_status",
            "dion_set_orth_mode", "dion_retry_breakdowns", "dion_set_wait_limit", "dion_cholesky_grid", "dion_set_stage_timing", "dion_stage_times", "dion_measure_ceilings", "dion_debug_buffer", "dion_destroy_state", "dion_strerror")
 
 _lib = None
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
                                              C.c_float, C.c_int, C.c_void_p]
         L.dion_double_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, vpp, vpp, vpp, vpp, vpp, vpp, vpp, i64p, i64p, i64p, i64p,
                                        C.c_float, C.c_float, C.c_float, C.c_void_p]
+        L.dion_step_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int,
+                                       C.c_int, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
         L.dion_last_status.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
@@ -269,6 +271,25 @@ def dion_double_step(state1: DionState, state2: DionState, X: List, G: List, M1:
                                   _ptrs(V2), _ptrs(D), _i64([s[0] for s in sh1]), _i64([s[1] for s in sh1]),
                                   _i64([s[2] for s in sh1]), _i64([s[2] for s in sh2]), mu1, mu2, eta, _stream(stream)),
            "dion_double_step")
+
+
+DION_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def dion_step_static(X, G, M, Q, g_dtype: int, math: int, mu: float, eta: float, status=None, stream=None) -> None:
+    """One Dion step on the library's static workspace (no state object, nothing allocated); `status`: an int32
+    device tensor of one element that receives the status word, or None."""
+    import torch
+    m, n = X.shape
+    r = Q.shape[1]
+    _check_tensor(X, torch.float32, (m, n), "X")
+    _check_tensor(G, torch.bfloat16 if g_dtype == DION_G_BF16 else torch.float32, (m, n), "G")
+    _check_tensor(M, torch.float32, (m, n), "M")
+    _check_tensor(Q, torch.float32, (n, r), "Q")
+    if status is not None:
+        _check_tensor(status, torch.int32, (1,), "status")
+    _check(lib().dion_step_static(_ptr(X), _ptr(G), _ptr(M), _ptr(Q), m, n, r, g_dtype, math, mu, eta,
+                                  C.c_void_p(_ptr(status)) if status is not None else None, _stream(stream)), "dion_step_static")
 
 
 def dion_retry_breakdowns(state: DionState, X: List, G: List, M: List, Q: List, mu: float, eta: float, stream=None) -> int:

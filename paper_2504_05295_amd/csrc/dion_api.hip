@@ -1310,3 +1310,84 @@ const char* dion_strerror(int code) {
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------------------------------------
+// dion_step_static: the Dion step on a workspace that lives in the library itself.
+constexpr size_t kStaticScratchBytes = DION_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+// What the library knows about the static workspace of one device.  `ptr` is the array's address on that device
+// (hipGetSymbolAddress; the array's name itself means nothing in host code); `st` is the host-side plan of the shape
+// the last call used, carved over `ptr`.
+struct StaticSlot {
+  bool ready;
+  unsigned char* ptr;
+  dion_state* st;
+  int64_t m, n, r;
+  int g_dtype, math;
+};
+StaticSlot g_static[16];
+}  // namespace
+
+extern "C" int dion_step_static(void* X, const void* G, void* M, void* Q, int64_t m, int64_t n, int64_t r, int g_dtype, int math,
+                                float mu, float eta, int* status_dev, void* hip_stream) {
+  if (!coeffs_ok(mu, eta)) return DION_EINVAL;
+  if (!aligned16(X) || !aligned16(G) || !aligned16(M) || !aligned16(Q)) return DION_EINVAL;
+  if (status_dev && ((uintptr_t)status_dev & 3u)) return DION_EINVAL;
+  size_t need = 0;
+  int rc = dion_workspace_bytes(1, &m, &n, &r, g_dtype, math, &need);   // validates the shape and the two type codes
+  if (rc != DION_OK) return rc;
+  if (need > kStaticScratchBytes) return DION_EWORKSPACE;              // beyond what the static workspace holds
+  int dev = 0;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 16) return DION_EINVAL;
+  StaticSlot& slot = g_static[dev];
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (!slot.ready) {
+    // set-up, once per device, with that device current: every GPU has its own copy of the array at its own address
+    void* p = nullptr;
+    HIPCHK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255u)) return DION_ELAUNCH;
+    if (gemm2_nt_prepare() != hipSuccess || gemm2_k5_prepare() != hipSuccess) return DION_ELAUNCH;
+    slot.ptr = (unsigned char*)p;
+    slot.st = nullptr;
+    slot.ready = true;
+  }
+  if (!slot.st || slot.m != m || slot.n != n || slot.r != r || slot.g_dtype != g_dtype || slot.math != math) {
+    // another shape than last time: a new host-side plan over the same memory (host memory only)
+    dion_state* st = nullptr;
+    try {
+      st = new dion_state();
+      std::vector<void*> host;
+      rc = plan_state(st, 1, &m, &n, &r, nullptr, g_dtype, math, slot.ptr, kStaticScratchBytes, nullptr, nullptr, host);
+      if (rc == DION_OK && launch_set_table_row(st->table, host.data(), s) != hipSuccess) rc = DION_ELAUNCH;
+    } catch (const std::bad_alloc&) {
+      rc = DION_ENOMEM;
+    }
+    if (rc != DION_OK) {
+      delete st;
+      return rc;
+    }
+    delete slot.st;
+    slot.st = st;
+    slot.m = m; slot.n = n; slot.r = r; slot.g_dtype = g_dtype; slot.math = math;
+  }
+  dion_state* st = slot.st;
+  st->last_stream = s;
+  const Group& g = st->groups[0];
+  // The array keeps what the last call left there, of whatever shape: everything that a step expects to find zero is
+  // cleared by fill kernels (no memset: the call may be captured).  The step counter, at a fixed place at the start of
+  // the array, is never cleared: it only has to differ from one call to the next.
+  HIPCHK(launch_fill(st->table, NSLOTS, 1, SLOT_SYNC, 2 * sync_words(g.rp / CHOL_NB), 0.f, s));
+  HIPCHK(launch_fill(st->table, NSLOTS, 1, SLOT_W, (long long)g.rp * g.rp, 0.f, s));
+  void* xs[1] = {X};
+  const void* gs[1] = {G};
+  void* ms[1] = {M};
+  void* qs[1] = {Q};
+  HIPCHK(launch_set_user_ptrs(st->table, NSLOTS, 0, 1, xs, gs, ms, qs, s, st->status, st->step_counter));
+  rc = step_rows(st, 0, 0, 1, mu, eta, s);
+  if (rc != DION_OK) return rc;
+  if (status_dev) HIPCHK(launch_copy_i32(st->status, status_dev, s));
+  return DION_OK;
+}

@@ -97,6 +97,9 @@ hipError_t gemm_f32_tn(int variant, GemmArgs g, int batch, hipStream_t s);      
 // status != nullptr: clears status[first_row .. first_row + count) as well; counter != nullptr: increments that word
 hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int count, void* const* X, const void* const* G,
                                 void* const* M, void* const* Q, hipStream_t s, int* status, unsigned long long* counter);
+// table[0 .. NSLOTS) = values[0 .. NSLOTS) (host array), by a kernel whose arguments carry the values
+hipError_t launch_set_table_row(void** table, void* const* values, hipStream_t s);
+hipError_t launch_copy_i32(const int* src, int* dst, hipStream_t s);   // *dst = *src on the device
 // count_slot >= 0: also adds one to the 64-bit word number count_index of that slot (a launch counter kept on the device)
 // dst_status[dst_rows[i]] = 2 where src_status[src_rows[i]] != 0, else 0, for i < count (row lists are host arrays)
 hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,

@@ -37,6 +37,28 @@ hipError_t launch_set_user_ptrs(void** table, int nslots, int first_row, int cou
   return hipSuccess;
 }
 
+// One whole row of the pointer table from kernel arguments (a state whose table cannot be written with a host copy:
+// the call may be part of a stream capture); also copies an int32 from *src to *dst when both are given.
+struct TableRow {
+  void* p[NSLOTS];
+};
+__global__ void set_table_row_kernel(void** table, const TableRow row) {
+  if (threadIdx.x < NSLOTS) table[threadIdx.x] = row.p[threadIdx.x];
+}
+hipError_t launch_set_table_row(void** table, void* const* values, hipStream_t s) {
+  TableRow row;
+  for (int i = 0; i < NSLOTS; ++i) row.p[i] = values[i];
+  hipLaunchKernelGGL(set_table_row_kernel, dim3(1), dim3(64), 0, s, table, row);
+  return hipGetLastError();
+}
+__global__ void copy_i32_kernel(const int* src, int* dst) {
+  if (threadIdx.x == 0) *dst = *src;
+}
+hipError_t launch_copy_i32(const int* src, int* dst, hipStream_t s) {
+  hipLaunchKernelGGL(copy_i32_kernel, dim3(1), dim3(64), 0, s, src, dst);
+  return hipGetLastError();
+}
+
 // status[dst_row[i]] = other_status[src_row[i]]: the second stage of a Double Dion step starts from the outcome of the
 // first (a matrix that failed there is skipped here as well)
 struct RowPairChunk {
