@@ -110,6 +110,65 @@ def orthonormalize(Z, method="householder"):
     return P, T, status
 
 
+RANK_TOL = 1e-3         # a column whose squared distance to the span of the columns before it is at most
+                        # RANK_TOL times its own squared norm counts as linearly dependent on them
+
+
+def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL):
+    """Orthonormalize for a Z whose columns may be linearly dependent (the second stage of Double Dion, whose
+    buffer is a sum of a few low-rank sketches at first).
+
+    A QR factorisation of such a Z has zero diagonal entries in T, and the matching columns of its orthogonal factor
+    are an arbitrary completion of the basis: they are orthogonal to range(Z), meet only zero columns of
+    W = B^T P whenever range(Z) = range(B), and so never reach the update.  The reading taken here makes that
+    exact and unique: the columns are taken in order; column j is *dependent* when the distance from z_j to the
+    span of the independent columns before it is at most sqrt(tol) ||z_j|| (i.e. |T_jj|^2 <= tol ||z_j||^2 in the
+    Householder factorisation of the independent columns so far followed by z_j).  Dependent columns get a zero
+    column of P and do not join the basis; the independent ones get the thin-QR factor (positive diagonal) of the
+    sub-matrix they form.  Returns (P, keep): P is m x r, keep[j] is False for dependent columns.
+    With all columns independent this is orthonormalize()."""
+    Z = _f64(Z)
+    m, r = Z.shape
+    P = np.zeros((m, r))
+    keep = np.zeros(r, dtype=bool)
+    norms2 = np.sum(Z * Z, axis=0)
+    if method == "householder":
+        V = []                                  # reflectors of the independent columns so far
+        cols = []
+        for j in range(r):
+            y = Z[:, j].copy()
+            for k, v in enumerate(V):           # apply H_{k-1} ... H_0
+                y[k:] -= 2.0 * v * np.dot(v, y[k:])
+            k = len(V)
+            if k >= m:
+                continue
+            x = y[k:]
+            dist2 = np.dot(x, x)
+            if not (dist2 > tol * norms2[j]):
+                continue                         # dependent (also: a zero column)
+            normx = np.sqrt(dist2)
+            v = x.copy()
+            v[0] -= -normx if x[0] >= 0.0 else normx
+            v /= np.sqrt(np.dot(v, v))
+            V.append(v)
+            cols.append(j)
+            keep[j] = True
+        if cols:
+            Ps, _ = householder_qr(Z[:, cols])
+            P[:, cols] = Ps
+    elif method == "lapack":
+        # the decisions from one factorisation of the whole matrix (safe when they are clear-cut: a dependent column
+        # leaves a diagonal entry at rounding level), then the factor of the independent columns alone
+        _, T = np.linalg.qr(Z, mode="reduced")
+        keep = np.abs(np.diag(T)) ** 2 > tol * norms2
+        if keep.any():
+            Ps, _ = lapack_qr(Z[:, keep])
+            P[:, keep] = Ps
+    else:
+        raise ValueError(method)
+    return P, keep
+
+
 def power_iter1(B, Q, method="householder"):
     """One power-iteration step (PowerIter1, without the data-parallel all-reduces):
     Z = B Q;  P = Orthonormalize(Z);  R = B^T P.  Returns (P, R, Z, T, status)."""
@@ -185,14 +244,18 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
         stage 2 (rank r2):  B2 = M2 + U1 W1^T;  U2, W2 = PowerIter1(B2, V2);  M2 <- B2 - beta2 U2 W2^T;  V2 <- ColNorm(W2)
         X <- X - eta sqrt(m/n) U2 V2_new^T
 
-    Returns the new state (X, M1, V1, M2, V2), the stage-1 sketch D = U1 W1^T and `status`.  The paper says nothing
-    about failures; the convention here: a breakdown in stage 1 leaves the whole state unchanged; a breakdown in
-    stage 2 (which is what happens while M2, a sum of rank-r1 sketches, still has rank below r2, e.g. on the
-    first r2/r1 steps from M2 = 0) leaves X and V2 unchanged, stage 1 (M1, V1) has taken its step, and M2 only
-    accumulates the sketch, M2 <- M2 + D, so that it can grow into full rank."""
+    The buffer of stage 2 is a sum of rank-r1 sketches, so while it has collected fewer than r2 / r1 of them (from
+    M2 = 0: the first steps) B2 V2 is rank deficient.  The algorithm has no failure branch: a QR-based Orthonormalize
+    returns a basis anyway, and the step uses the rank that is there.  Stage 2 therefore orthonormalises with
+    orthonormalize_dependent(): dependent columns of B2 V2 get zero columns in U2, hence in W2, contribute nothing
+    to M2 and X, and their columns of V2 stay as they were (ColNorm of a zero column has nothing to normalise; keeping
+    the old column is what lets the rank grow as M2 fills up).  X moves on every step, also from M2 = 0.
+    Stage 1 is the standard step; a breakdown there (reported as `status`) leaves the whole state unchanged.
+    Returns the new state (X, M1, V1, M2, V2), the sketch D = U1 W1^T, `keep` (which columns of stage 2 were
+    independent) and `status`."""
     X = _f64(X)
     m, n = X.shape
-    same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None)
+    same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None, keep=None)
     B1 = accumulate(M1, G)
     U1, W1, _, _, status = power_iter1(B1, V1, method)
     if status != STATUS_OK:
@@ -201,13 +264,14 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
     M1_new = B1 - (1.0 - mu1) * D
     V1_new, _ = col_norm(W1)
     B2 = accumulate(M2, D)
-    U2, W2, _, _, status = power_iter1(B2, V2, method)
-    if status != STATUS_OK:
-        return dict(same, M1=M1_new, V1=V1_new, M2=B2, D=D, status=status)
+    V2 = _f64(V2)
+    U2, keep = orthonormalize_dependent(B2 @ V2, method)
+    W2 = B2.T @ U2
     M2_new = B2 - (1.0 - mu2) * (U2 @ W2.T)
     V2_new, _ = col_norm(W2)
-    X_new = X - eta * np.sqrt(m / n) * (U2 @ V2_new.T)
-    return dict(X=X_new, M1=M1_new, V1=V1_new, M2=M2_new, V2=V2_new, D=D, status=status)
+    V2_new[:, ~keep] = V2[:, ~keep]
+    X_new = X - eta * np.sqrt(m / n) * (U2[:, keep] @ V2_new[:, keep].T)
+    return dict(X=X_new, M1=M1_new, V1=V1_new, M2=M2_new, V2=V2_new, D=D, keep=keep, status=STATUS_OK)
 
 
 def sym_power_iter1(B, V, method="householder"):
