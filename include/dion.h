@@ -159,12 +159,15 @@ int dion_lazy_step_batched(dion_state_t* st, int count, void* const* X, const vo
  *                         V2 <- ColNorm(W2);   X <- X - eta sqrt(m/n) U2 V2^T
  * st1 / st2: states created for the shapes (m, n, r1) / (m, n, r2) in this order, standard form, on separate
  * workspaces; st1 with the storage type of G, st2 with DION_G_F32.  D: host array of `count` device buffers of
- * m x n floats (caller-owned scratch) that receive the sketch U1 W1^T between the stages.  A matrix whose stage 1
- * breaks down is skipped in stage 2 as well, so its X, M1, V1, M2, V2 all stay untouched; when only stage 2 breaks
- * down (it must while M2, a sum of rank-r1 sketches, has rank below r2: the first r2/r1 steps from M2 = 0), X and
- * V2 stay untouched, stage 1 has taken its step and M2 only accumulates the sketch, M2 <- M2 + U1 W1^T.  dion_last_status(st2) reports breakdowns of
- * either stage (dion_last_status(st1) those of stage 1).  Other conventions as for
- * dion_step_batched; both states must be used on the same stream. */
+ * m x n floats (caller-owned scratch) that receive the sketch U1 W1^T between the stages.
+ * Stage 2 has no failure branch (the algorithm's Orthonormalize is a QR, which cannot fail): while M2, a sum of
+ * rank-r1 sketches, has rank below r2 (from M2 = 0: the first r2/r1 steps) the columns of B2 V2 that depend on the
+ * columns before them (pivot of the Gram matrix' factorisation at most 1e-3 of that column's squared norm) get zero
+ * columns in U2 and W2, add nothing to M2 and X, and keep their columns of V2; the remaining columns are the QR factor
+ * of the independent ones, so X moves on every step by the rank that is there.  A matrix whose stage 1 breaks down
+ * (rank-deficient B1 V1, as in dion_step) is skipped in stage 2 as well, so its X, M1, V1, M2, V2 all stay untouched.
+ * dion_last_status(st2) reports breakdowns of stage 1 and non-finite input of stage 2 (dion_last_status(st1) those
+ * of stage 1).  Other conventions as for dion_step_batched; both states must be used on the same stream. */
 int dion_double_step(dion_state_t* st1, dion_state_t* st2, int count, void* const* X, const void* const* G,
                      void* const* M1, void* const* V1, void* const* M2, void* const* V2, void* const* D,
                      const int64_t* m, const int64_t* n, const int64_t* r1, const int64_t* r2,
@@ -262,7 +265,8 @@ int dion_measure_ceilings(void* scratch_dev, size_t scratch_bytes, double* mfma_
 /* Test access to the intermediates of matrix `index` left in the workspace by the last step:
  * which = 0: Z (m x r; after a Lazy-Dion step: W), 1: P (m x r), 2: R (n x r), 3: column norms s (r),
  * 4: status word (int32), 5: the output of the first Cholesky-QR pass, 6 / 7 / 8: Gram matrix, its Cholesky
- * factor and that factor's inverse of the last pass (rp x rp, rp = r rounded up to 64), 9: 1 / (s + eps).
+ * factor and that factor's inverse of the last pass (rp x rp, rp = r rounded up to 64), 9: 1 / (s + eps),
+ * 10: int32 per column (rp of them), 1 where stage 2 of the last Double Dion step found the column dependent.
  * Writes the device pointer and the leading dimension (elements). */
 int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, int64_t* ld_out);
 

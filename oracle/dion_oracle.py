@@ -114,7 +114,7 @@ RANK_TOL = 1e-3         # a column whose squared distance to the span of the col
                         # RANK_TOL times its own squared norm counts as linearly dependent on them
 
 
-def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL):
+def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL, forced=None):
     """Orthonormalize for a Z whose columns may be linearly dependent (the second stage of Double Dion, whose
     buffer is a sum of a few low-rank sketches at first).
 
@@ -125,13 +125,18 @@ def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL):
     span of the independent columns before it is at most sqrt(tol) ||z_j|| (i.e. |T_jj|^2 <= tol ||z_j||^2 in the
     Householder factorisation of the independent columns so far followed by z_j).  Dependent columns get a zero
     column of P and do not join the basis; the independent ones get the thin-QR factor (positive diagonal) of the
-    sub-matrix they form.  Returns (P, keep): P is m x r, keep[j] is False for dependent columns.
-    With all columns independent this is orthonormalize()."""
+    sub-matrix they form.  Returns (P, keep, ratio): P is m x r, keep[j] is False for dependent columns, ratio[j] is
+    the squared relative distance the decision was taken on.  With all columns independent this is orthonormalize().
+    `forced` (length r, entries -1 / 0 / 1): 0 and 1 override the decision for that column (drop / keep); a test uses
+    it to take borderline decisions the way the implementation under test took them in its own precision."""
     Z = _f64(Z)
     m, r = Z.shape
     P = np.zeros((m, r))
     keep = np.zeros(r, dtype=bool)
+    ratio = np.zeros(r)
     norms2 = np.sum(Z * Z, axis=0)
+    if forced is None:
+        forced = -np.ones(r, dtype=int)
     if method == "householder":
         V = []                                  # reflectors of the independent columns so far
         cols = []
@@ -144,7 +149,8 @@ def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL):
                 continue
             x = y[k:]
             dist2 = np.dot(x, x)
-            if not (dist2 > tol * norms2[j]):
+            ratio[j] = dist2 / norms2[j] if norms2[j] > 0.0 else 0.0
+            if forced[j] == 0 or (forced[j] < 0 and not (dist2 > tol * norms2[j])) or dist2 == 0.0:
                 continue                         # dependent (also: a zero column)
             normx = np.sqrt(dist2)
             v = x.copy()
@@ -157,16 +163,26 @@ def orthonormalize_dependent(Z, method="householder", tol=RANK_TOL):
             Ps, _ = householder_qr(Z[:, cols])
             P[:, cols] = Ps
     elif method == "lapack":
-        # the decisions from one factorisation of the whole matrix (safe when they are clear-cut: a dependent column
-        # leaves a diagonal entry at rounding level), then the factor of the independent columns alone
-        _, T = np.linalg.qr(Z, mode="reduced")
-        keep = np.abs(np.diag(T)) ** 2 > tol * norms2
+        # The same decisions, column by column, with the distances taken from an orthonormal basis of the independent
+        # columns so far that is extended by two Gram-Schmidt sweeps per column (library matrix products); then the
+        # library QR factor of the independent columns alone.
+        Qb = np.zeros((m, 0))
+        for j in range(r):
+            z = Z[:, j]
+            res = z - Qb @ (Qb.T @ z)
+            res = res - Qb @ (Qb.T @ res)
+            dist2 = np.dot(res, res)
+            ratio[j] = dist2 / norms2[j] if norms2[j] > 0.0 else 0.0
+            if forced[j] == 0 or (forced[j] < 0 and not (dist2 > tol * norms2[j])) or dist2 == 0.0 or Qb.shape[1] >= m:
+                continue
+            keep[j] = True
+            Qb = np.concatenate([Qb, (res / np.sqrt(dist2))[:, None]], axis=1)
         if keep.any():
             Ps, _ = lapack_qr(Z[:, keep])
             P[:, keep] = Ps
     else:
         raise ValueError(method)
-    return P, keep
+    return P, keep, ratio
 
 
 def power_iter1(B, Q, method="householder"):
@@ -236,7 +252,7 @@ def dion_step_transposed(X, G, M, Vt, mu, eta, method="householder"):
     return dict(X=X_new, M=M_new, Vt=Vt_new, Zt=Zt, Pt=Pt, Rt=Rt, s=s, B=B, status=status)
 
 
-def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
+def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder", forced=None):
     """One Double Dion step (Section 5.2 and the Double Dion algorithm, without the sharding and the
     data-parallel synchronisation of stage 1) for one m x n matrix, beta_i = 1 - mu_i:
 
@@ -252,10 +268,11 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
     the old column is what lets the rank grow as M2 fills up).  X moves on every step, also from M2 = 0.
     Stage 1 is the standard step; a breakdown there (reported as `status`) leaves the whole state unchanged.
     Returns the new state (X, M1, V1, M2, V2), the sketch D = U1 W1^T, `keep` (which columns of stage 2 were
-    independent) and `status`."""
+    independent), `ratio` (the numbers those decisions were taken on) and `status`.  `forced`: see
+    orthonormalize_dependent()."""
     X = _f64(X)
     m, n = X.shape
-    same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None, keep=None)
+    same = dict(X=X, M1=_f64(M1), V1=_f64(V1), M2=_f64(M2), V2=_f64(V2), D=None, keep=None, ratio=None)
     B1 = accumulate(M1, G)
     U1, W1, _, _, status = power_iter1(B1, V1, method)
     if status != STATUS_OK:
@@ -265,13 +282,13 @@ def double_dion_step(X, G, M1, V1, M2, V2, mu1, mu2, eta, method="householder"):
     V1_new, _ = col_norm(W1)
     B2 = accumulate(M2, D)
     V2 = _f64(V2)
-    U2, keep = orthonormalize_dependent(B2 @ V2, method)
+    U2, keep, ratio = orthonormalize_dependent(B2 @ V2, method, RANK_TOL, forced)
     W2 = B2.T @ U2
     M2_new = B2 - (1.0 - mu2) * (U2 @ W2.T)
     V2_new, _ = col_norm(W2)
     V2_new[:, ~keep] = V2[:, ~keep]
     X_new = X - eta * np.sqrt(m / n) * (U2[:, keep] @ V2_new[:, keep].T)
-    return dict(X=X_new, M1=M1_new, V1=V1_new, M2=M2_new, V2=V2_new, D=D, keep=keep, status=STATUS_OK)
+    return dict(X=X_new, M1=M1_new, V1=V1_new, M2=M2_new, V2=V2_new, D=D, keep=keep, ratio=ratio, status=STATUS_OK)
 
 
 def sym_power_iter1(B, V, method="householder"):

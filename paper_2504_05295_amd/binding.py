@@ -23,7 +23,7 @@ DION_WAIT_TIMEOUT = 2
 DION_G_F32, DION_G_BF16 = 0, 1
 DION_MATH_F32, DION_MATH_BF16 = 0, 1
 STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
-DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D = range(10)
+DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D, DEBUG_NULL = range(11)
 
 DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
 DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
@@ -351,10 +351,10 @@ def dion_debug_buffer(state: DionState, index: int, which: int):
     p, ld = C.c_void_p(None), C.c_int64(0)
     _check(lib().dion_debug_buffer(state.handle, index, which, C.byref(p), C.byref(ld)), "dion_debug_buffer")
     m, n, r = state.shapes[index]
-    rows = {DEBUG_Z: m, DEBUG_P: m, DEBUG_P1: m, DEBUG_R: n, DEBUG_S: r, DEBUG_D: r, DEBUG_STATUS: 1,
+    rows = {DEBUG_Z: m, DEBUG_P: m, DEBUG_P1: m, DEBUG_R: n, DEBUG_S: r, DEBUG_D: r, DEBUG_STATUS: 1, DEBUG_NULL: (r + 63) // 64 * 64,
             DEBUG_C: int(ld.value), DEBUG_L: int(ld.value), DEBUG_W: int(ld.value)}[which]
     cols = int(ld.value)
-    dtype = torch.int32 if which == DEBUG_STATUS else torch.float32
+    dtype = torch.int32 if which in (DEBUG_STATUS, DEBUG_NULL) else torch.float32
     nbytes = rows * cols * 4
     ws = state.workspace
     off = int(p.value) - ws.data_ptr()

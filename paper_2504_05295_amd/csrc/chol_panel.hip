@@ -75,8 +75,15 @@ __device__ __forceinline__ float lane_value(float x, int src_lane) {   // x of l
 // column j's update of the entries further right (k >= j+3) is applied one step late, from the copy of the
 // raw column that went through LDS meanwhile.  Raw column j is left in row j of S0 (its first reader, this
 // wave, took the whole block into registers before the first column is written) and *raw_done counts them.
-__device__ __forceinline__ void eliminate_wave(lds_float* S0, lds_counter* raw_done, int lane) {
+// RANK (the factorisation that tolerates linearly dependent columns): a column whose pivot is not above its
+// threshold thr[j] (a fraction of the Gram matrix' original diagonal entry) is dependent on the columns before it; it
+// eliminates nothing, so that the factorisation goes on as if the column were not there.  The two follower waves
+// take the same decision from the same two numbers.
+template <bool RANK>
+__device__ __forceinline__ void eliminate_wave(lds_float* S0, lds_counter* raw_done, int lane, const float* thr) {
     float a[CB];
+    float thr_lane = 0.f;
+    if constexpr (RANK) thr_lane = thr[lane];
     static_for<0, CB>([&](auto kc) __attribute__((always_inline)) { a[decltype(kc)::value] = S0[lane * CBP + decltype(kc)::value]; });
     f32x4_t cv0[CB / 4], cv1[CB / 4];   // raw columns j (even / odd) as read back from LDS
     float gprev = 0.f;
@@ -85,7 +92,10 @@ __device__ __forceinline__ void eliminate_wave(lds_float* S0, lds_counter* raw_d
       f32x4_t* cur = (jj & 1) ? cv1 : cv0;
       const f32x4_t* prev = (jj & 1) ? cv0 : cv1;
       const float piv = lane_value(a[jj], jj);
-      const float gj = a[jj] * __builtin_amdgcn_rcpf(piv);
+      float gj = a[jj] * __builtin_amdgcn_rcpf(piv);
+      if constexpr (RANK) {
+        if (!(piv > lane_value(thr_lane, jj))) gj = 0.f;   // uniform
+      }
       if constexpr (jj + 1 < CB) a[jj + 1] -= gj * lane_value(a[jj], jj + 1);
       if constexpr (jj + 2 < CB) {
         if constexpr (jj >= 1) a[jj + 2] -= gprev * prev[(jj + 2) / 4][(jj + 2) % 4];
@@ -128,8 +138,12 @@ __device__ __forceinline__ void eliminate_wave(lds_float* S0, lds_counter* raw_d
 // Wave 2: follows wave 0 and turns raw columns into columns of L: L[i][j] = raw[i][j] / sqrt(raw[j][j]).
 // Leaves 1 / sqrt(raw[j][j]) in rsv and sets *scaled when all of them are there.  When Lout is given
 // (writer workgroup) also stores L11 and the status.
+// RANK: a dependent column (pivot not above thr[j]) becomes a zero column of L with a zero diagonal entry and 0 in rsv,
+// which makes row and column j of the inverse zero as well; nullmask[j] (writer only) records the decision.
+template <bool RANK>
 __device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw_done, lds_float* rsv, lds_counter* scaled, int lane,
-                                           float piv_lo, float piv_hi, float* Lout, long long ld, int* status) {
+                                           float piv_lo, float piv_hi, float* Lout, long long ld, int* status, const float* thr,
+                                           int* nullmask) {
     float l[CB];
     bool bad = false;
     int seen = 0;
@@ -150,9 +164,16 @@ __device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw
       const float raw = (jj & 1) ? raw1 : raw0, piv = (jj & 1) ? piv1 : piv0;
       if constexpr (jj + 1 < CB) fetch(std::integral_constant<int, jj + 1>{}, (jj & 1) ? raw0 : raw1, (jj & 1) ? piv0 : piv1);
       __builtin_amdgcn_sched_barrier(0);
-      bad = bad || !(piv > piv_lo) || !(piv < piv_hi);
       float rs = __builtin_amdgcn_rsqf(piv);
       rs = rs * (1.5f - 0.5f * piv * rs * rs);   // one Newton step on the hardware estimate
+      if constexpr (RANK) {
+        const bool dependent = !(piv > thr[jj]);
+        if (dependent) rs = 0.f;
+        bad = bad || !(piv == piv) || (!dependent && (!(piv > piv_lo) || !(piv < piv_hi)));   // a NaN pivot is no dependent column
+        if (nullmask && lane == 0) nullmask[jj] = dependent ? 1 : 0;
+      } else {
+        bad = bad || !(piv > piv_lo) || !(piv < piv_hi);
+      }
       l[jj] = raw * rs;
       rsv[jj] = rs;   // every lane stores the same value
       asm volatile("" : "+v"(l[jj]));   // keeps this column's arithmetic from being moved past the next wait loop
@@ -174,7 +195,9 @@ __device__ __forceinline__ void scale_wave(const lds_float* S0, lds_counter* raw
 // with acc_i = delta_ic - sum_{k<j} L[i][k] w_k, step j sets acc_i -= raw[i][j] * (acc_j / raw[j][j]) for i > j,
 // and w_j = acc_j / sqrt(raw[j][j]) is applied to all rows at the end.  The work per step shrinks as the
 // elimination's does, so this wave finishes right behind wave 0.
-__device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done, const lds_float* rsv, lds_counter* scaled, int lane) {
+template <bool RANK>
+__device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done, const lds_float* rsv, lds_counter* scaled, int lane,
+                                            const float* thr) {
     float w[CB];
     static_for<0, CB>([&](auto ic) __attribute__((always_inline)) { w[decltype(ic)::value] = (lane == decltype(ic)::value) ? 1.f : 0.f; });
     f32x4_t cv0[CB / 4], cv1[CB / 4];
@@ -208,7 +231,10 @@ __device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done
       const float piv = (jj & 1) ? piv1 : piv0;
       if constexpr (jj + 1 < CB) fetch(std::integral_constant<int, jj + 1>{}, (jj & 1) ? cv0 : cv1, (jj & 1) ? piv0 : piv1);
       __builtin_amdgcn_sched_barrier(0);
-      const float u = w[jj] * __builtin_amdgcn_rcpf(piv);
+      float u = w[jj] * __builtin_amdgcn_rcpf(piv);
+      if constexpr (RANK) {
+        if (!(piv > thr[jj])) u = 0.f;   // a dependent column takes no part in the substitution
+      }
       static_for<(jj + 1) / 4, CB / 4>([&](auto qc) __attribute__((always_inline)) {
         constexpr int q = decltype(qc)::value;
         if constexpr (4 * q + 0 > jj) w[4 * q + 0] -= cv[q][0] * u;
@@ -232,6 +258,7 @@ __device__ __forceinline__ void invert_wave(lds_float* S0, lds_counter* raw_done
     });
 }
 
+template <bool RANK>
 __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int k0, int rp, float piv_lo, float piv_hi, int mode) {
   // mode 0: fused (workgroup 0 writes L11/W11, the others own tiles and redo the factorisation)
   // mode 1: diagonal block only (one workgroup per matrix)      mode 2: tiles only, W11 read back from memory
@@ -242,6 +269,8 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
   float* L = p.L + mat;
   float* W = p.W + mat;
   int* status = p.status + blockIdx.y;
+  const float* thr = RANK ? p.thr + mat + k0 : nullptr;
+  int* nullmask = RANK ? p.nullmask + mat + k0 : nullptr;
   // Only the second Cholesky-QR pass carries a skip flag (set when it needs no factorisation); the first pass
   // starts its loads without this extra memory round trip.
   if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole workgroup
@@ -297,12 +326,12 @@ __global__ void __launch_bounds__(256, 2) chol_panel_kernel(CholPanelPtrs p, int
       if (j != i) *(f32x4_t*)(S2 + rr * CBP + cc) = *(const f32x4_t*)(C + (rowj + rr) * ld + k0 + cc);
     }
   } else if (wave == 0) {
-    eliminate_wave((lds_float*)S0, (lds_counter*)&raw_done, lane);
+    eliminate_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, lane, thr);
   } else if (wave == 2) {
-    scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, piv_lo, piv_hi,
-               writer ? L + (long long)k0 * ld + k0 : nullptr, ld, status);
+    scale_wave<RANK>((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, piv_lo, piv_hi,
+                     writer ? L + (long long)k0 * ld + k0 : nullptr, ld, status, thr, writer ? nullmask : nullptr);
   } else if (wave == 1) {
-    invert_wave((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane);
+    invert_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane, thr);
   } else if (!writer) {
     for (int idx = lane; idx < CB * CB / 4; idx += 64) {
       const int rr = idx >> 4, cc = (idx & 15) * 4;
@@ -439,6 +468,7 @@ __device__ __forceinline__ bool wait_until(const StreamCtx& x, int* gave_up, boo
 }
 }  // namespace
 
+template <bool RANK>
 __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   const long long mat = (long long)blockIdx.y * p.stride;
   if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole grid row of this matrix
@@ -457,6 +487,8 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   x.piv_lo = p.piv_lo;
   x.piv_hi = p.piv_hi;
   const int ld = p.rp;
+  const float* thr = RANK ? p.thr + mat : nullptr;
+  int* nullmask = RANK ? p.nullmask + mat : nullptr;
 
   __shared__ __attribute__((aligned(16))) float S0[CB * CBP];   // diagonal block / W11
   __shared__ __attribute__((aligned(16))) float S1[CB * CBP];
@@ -497,12 +529,13 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
     if (t == 0) { scaled = 0; raw_done = 0; }
     __syncthreads();
     if (wave == 0) {
-      eliminate_wave((lds_float*)S0, (lds_counter*)&raw_done, lane);
+      eliminate_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, lane, RANK ? thr + k * CB : nullptr);
     } else if (wave == 2) {
-      scale_wave((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, x.piv_lo, x.piv_hi,
-                 (float*)(x.L + at), ld, x.status);
+      scale_wave<RANK>((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, x.piv_lo, x.piv_hi,
+                       (float*)(x.L + at), ld, x.status, RANK ? thr + k * CB : nullptr, RANK ? nullmask + k * CB : nullptr);
     } else if (wave == 1) {
-      invert_wave((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane);
+      invert_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane,
+                        RANK ? thr + k * CB : nullptr);
     } else if (pending_flag) {
 #pragma unroll 8
       for (int rr = 0; rr < CB; ++rr) shared_store(pending_tile + rr * ld + lane, S1[rr * CBP + lane]);
@@ -625,22 +658,23 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
   // 32 KB of unused dynamic LDS on top of the 52 KB the kernel declares: one workgroup per compute unit, so the
   // workgroup on the critical chain shares its unit with nobody
-  hipLaunchKernelGGL(chol_stream_kernel, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
+  if (p.thr) hipLaunchKernelGGL(chol_stream_kernel<true>, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
+  else hipLaunchKernelGGL(chol_stream_kernel<false>, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
   return hipGetLastError();
 }
 
 hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s) {
   const int nb = (rp - k0 - CB) / CB;
   const int tiles = nb * (nb + 1) / 2;
-  if ((long long)(1 + tiles) * batch <= 1024 || tiles == 0) {
-    hipLaunchKernelGGL(chol_panel_kernel, dim3(1 + tiles, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 0);
+  auto go = [&](int blocks, int mode) {
+    if (p.thr) hipLaunchKernelGGL(chol_panel_kernel<true>, dim3(blocks, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, mode);
+    else hipLaunchKernelGGL(chol_panel_kernel<false>, dim3(blocks, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, mode);
     return hipGetLastError();
-  }
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(1, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 1);
-  hipError_t e = hipGetLastError();
+  };
+  if ((long long)(1 + tiles) * batch <= 1024 || tiles == 0) return go(1 + tiles, 0);
+  hipError_t e = go(1, 1);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(chol_panel_kernel, dim3(tiles, batch), dim3(256), 0, s, p, k0, rp, piv_lo, piv_hi, 2);
-  return hipGetLastError();
+  return go(tiles, 2);
 }
 
 }  // namespace dion

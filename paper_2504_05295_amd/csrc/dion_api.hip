@@ -168,6 +168,8 @@ Carve carve_entry(const Group& g) {
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
   take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
   take(SLOT_B16T, g.direct12 ? ((size_t)g.m * g.n + 1) / 2 : 0);
+  take(SLOT_THR, g.rp);
+  take(SLOT_NULL, g.rp);
   c.total = pos;
   return c;
 }
@@ -294,7 +296,7 @@ int plan_state(dion_state* st, int count, const int64_t* m, const int64_t* n, co
     char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
     void** rowp = &host[(size_t)e.row * NSLOTS];
     for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-    for (int sl = SLOT_QT16; sl <= SLOT_B16T; ++sl) rowp[sl] = base + c.off[sl];
+    for (int sl = SLOT_QT16; sl <= SLOT_NULL; ++sl) rowp[sl] = base + c.off[sl];
     rowp[SLOT_STATUS] = st->status + e.row;
     rowp[SLOT_M] = M_dev ? M_dev[i] : nullptr;
     rowp[SLOT_Q] = Q_dev ? Q_dev[i] : nullptr;
@@ -331,8 +333,11 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
 // With `split` the two large products run on the bf16 matrix pipe with split operands (x = hi + lo,
 // three partial products), which carries about 16 mantissa bits at a fraction of the fp32 MFMA cost; the
 // Cholesky factorisation and the triangular inverse stay in fp32.
+// rank_tol > 0: the factorisation tolerates linearly dependent columns (see CholPanelPtrs::thr): they come out as zero
+// columns of `out` and are marked in SLOT_NULL, instead of a breakdown.
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long rows, const GramPlan& gp, int slot_in,
-                int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, int pass, hipStream_t s) {
+                int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, int pass, hipStream_t s,
+                float rank_tol = 0.f) {
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -419,6 +424,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
   HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
+  if (rank_tol > 0.f) HIPCHK(launch_rank_threshold(tab, NSLOTS, batch, rp, rank_tol, s));
   // (W needs no clearing: its part above the block diagonal was zeroed at init and nothing ever writes there; the
   // rest is overwritten in full by the factorisation kernels, the merges below or the first-order factor)
   // Second pass: the input is already orthonormal to about 1e-5, so its Gram matrix is I + E with tiny E
@@ -443,6 +449,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     pp.skip = adaptive ? (const int*)(e0 + g.carve.off[SLOT_FAST]) : nullptr;
     pp.stride = (long long)(g.bytes_per_entry / sizeof(float));
     pp.status = st->status + g.first_row + row0;
+    pp.thr = rank_tol > 0.f ? (const float*)(e0 + g.carve.off[SLOT_THR]) : nullptr;
+    pp.nullmask = rank_tol > 0.f ? (int*)(e0 + g.carve.off[SLOT_NULL]) : nullptr;
   }
   if (use_stream) {
     // the whole factorisation in one launch of at most 256 co-resident workgroups
@@ -457,6 +465,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ca.step_counter = st->step_counter;
     ca.pass = pass;
     ca.spin_limit = st->chol_spin_limit;
+    ca.thr = pp.thr; ca.nullmask = pp.nullmask;
     HIPCHK(launch_chol_stream(ca, batch, s));
   } else {
     for (int k = 0; k < rp; k += CHOL_NB)
@@ -705,11 +714,25 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunk
 // final, so final must not be a).  On the split-bf16 path the products read bf16 copies of their input, never the
 // fp32 original, so a pass may write where it reads: the first pass already writes to slot_final and the last,
 // adaptive one runs there in place, which leaves it nothing to do when it finds its input orthonormal enough.
-int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final) {
+// rank_tol > 0: CholeskyQR2 that tolerates linearly dependent columns (zero columns of the result, marked in SLOT_NULL).
+int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol = 0.f) {
   dion_state* st = c.st;
   const Group& g = *c.g;
   const bool in_place = c.big;
   int rc;
+  if (rank_tol > 0.f) {
+    // Three passes.  Every column's pivot is measured against that column's own squared norm; columns that the first
+    // pass drops come out exactly zero, meet a zero threshold and a zero pivot in the later passes, and are dropped
+    // again.  The columns that stay can be badly conditioned among themselves (condition numbers of a few thousand
+    // while the buffer is still filling up), which is more than two passes repair: the second pass brings the
+    // first one's result to within the reach of the third, whose pivots are checked as usual.
+    const int mid = in_place ? slot_final : slot_a;
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s, rank_tol);
+    if (rc != DION_OK) return rc;
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, mid, 0.f, 3.0e38f, c.big, false, 0.f, 2, c.s, rank_tol);
+    if (rc != DION_OK) return rc;
+    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 3, c.s, rank_tol);
+  }
   // first pass: any positive finite pivot; last pass: the Gram matrix of a nearly orthonormal input has pivots near 1
   if (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) {
     // Shifted Cholesky-QR first (the Gram matrix plus a small multiple of its trace cannot break down and
@@ -783,8 +806,8 @@ int stage_k5(const RowCtx& c, int a16, int b16, int b2_16, int a32, int b32, int
 // One Dion step (Algorithm 1 with the unsharded update rule) for the matrices of one shape group.
 // The two stages of a Double Dion step (Section 5.2) are such steps with a twist each:
 //   STEP_SKETCH     the X buffer is a scratch matrix that receives P R^T instead of a weight update (stage 1)
-//   STEP_KEEP_STATUS the status words hold the outcome of stage 1; a breakdown of this stage's own still lets the
-//                    momentum take in the gradient (stage 2)
+//   STEP_KEEP_STATUS the status words hold the outcome of stage 1; the orthonormalisation tolerates linearly dependent
+//                    columns, since this stage's buffer is a sum of a few low-rank sketches at first (stage 2)
 // The status words are cleared by the kernel that refreshes the pointer table before the step.
 enum { STEP_PLAIN = 0, STEP_SKETCH = 1, STEP_KEEP_STATUS = 2 };
 int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, hipStream_t s, int mode = STEP_PLAIN) {
@@ -797,7 +820,8 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(stage_k1(c, true));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
-  STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P));
+  const float rank_tol = mode == STEP_KEEP_STATUS ? RANK_TOL : 0.f;
+  STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P, rank_tol));
   // bf16 copies of P for K2 and K5.  When the last Cholesky-QR pass found its input orthonormal enough, that input is
   // P, and the pass has left the very same copies (the high parts of its split) in the same two slots.
   if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s, SLOT_FAST));
@@ -809,13 +833,12 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
   if (colsq_chunks > 0) HIPCHK(launch_colnorm_final(c.tab, NSLOTS, batch, colsq_chunks, r, s));   // K2 has left the partial sums
   else HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_R, n, r, s));
-  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s));
+  // (dependent columns: P and R have zero columns there, which add nothing to the update; Q keeps its old column)
+  HIPCHK(launch_scale_cols(c.tab, NSLOTS, batch, SLOT_R, SLOT_Q, n, r, SLOT_STATUS, c.big ? SLOT_Q16 : -1, c.big ? SLOT_R16 : -1, s,
+                           rank_tol > 0.f ? SLOT_NULL : -1));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 1));
   STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 0));
   STAGECHK(stage_k5(c, SLOT_P16, SLOT_R16, SLOT_Q16, SLOT_P, SLOT_R, SLOT_Q, mu, eta, mode == STEP_SKETCH));
-  // a second stage that could not orthonormalise (its buffer is a sum of a few low-rank sketches at first) still
-  // takes the sketch into its momentum
-  if (mode == STEP_KEEP_STATUS) HIPCHK(launch_accumulate_failed(c.tab, NSLOTS, batch, (long long)m * n, s));
   STAGECHK(mark(c, DION_STAGE_K5_UPDATE, 1));
   return DION_OK;
 }
@@ -1274,7 +1297,7 @@ int dion_stage_times(dion_state_t* st, float* ms_out) {
 
 int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, int64_t* ld_out) {
   if (!st || index < 0 || index >= st->count || !ptr_out) return DION_EINVAL;
-  static const int slots[] = {SLOT_Z, SLOT_P, SLOT_R, SLOT_S, SLOT_STATUS, SLOT_P1, SLOT_C, SLOT_L, SLOT_W, SLOT_D};
+  static const int slots[] = {SLOT_Z, SLOT_P, SLOT_R, SLOT_S, SLOT_STATUS, SLOT_P1, SLOT_C, SLOT_L, SLOT_W, SLOT_D, SLOT_NULL};
   if (which < 0 || which >= (int)(sizeof(slots) / sizeof(slots[0]))) return DION_EINVAL;
   const Entry& e = st->entries[index];
   void* p = nullptr;
@@ -1283,7 +1306,7 @@ int dion_debug_buffer(dion_state_t* st, int index, int which, void** ptr_out, in
   if (ld_out) {
     const int sl = slots[which];
     *ld_out = (sl == SLOT_C || sl == SLOT_L || sl == SLOT_W) ? st->groups[e.group].rp
-              : (sl == SLOT_S || sl == SLOT_D || sl == SLOT_STATUS) ? 1 : e.r;
+              : (sl == SLOT_S || sl == SLOT_D || sl == SLOT_STATUS || sl == SLOT_NULL) ? 1 : e.r;
   }
   return DION_OK;
 }

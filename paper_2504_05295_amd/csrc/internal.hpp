@@ -41,7 +41,9 @@ enum Slot {
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
   SLOT_B16,    // bf16(M + G), m x n: A operand of K1 on the direct-load path; else written by K1 on its way for K2
   SLOT_B16T,   // its transpose, n x m: A operand of K2 on the direct-load path
-  NSLOTS = 32
+  SLOT_THR,    // rp floats: pivot thresholds of the factorisation that tolerates dependent columns
+  SLOT_NULL,   // rp int32: 1 for the columns that factorisation found dependent on the ones before them
+  NSLOTS = 40
 };
 
 // Values of a matrix' device status word (SLOT_STATUS).  0 = fine; anything else gates the state-writing kernels.
@@ -54,6 +56,7 @@ enum StatusWord {
 
 constexpr int CHOL_NB = 64;        // Cholesky panel width (diagonal block factored by one wavefront)
 constexpr float COLNORM_EPS = 1e-8f;
+constexpr float RANK_TOL = 1e-3f;   // a pivot at most this fraction of the Gram matrix' own diagonal entry: dependent column
 constexpr int GRAM_DEFECT_PARTS = 1024;   // workgroups (and partial sums) of the kernel that measures ||C - I||_F
 constexpr int COLNORM_ROWS = 256;  // rows per partial sum of squares (colnorm_partial_kernel)
 constexpr int COLNORM_CHUNK_MIN = 128;   // fewest rows per partial sum that any producer uses (sizes SLOT_SPART)
@@ -104,8 +107,8 @@ hipError_t launch_copy_i32(const int* src, int* dst, hipStream_t s);   // *dst =
 // dst_status[dst_rows[i]] = 2 where src_status[src_rows[i]] != 0, else 0, for i < count (row lists are host arrays)
 hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int count, const int* src_rows, const int* dst_rows,
                                    hipStream_t s);
-// M += G (fp32 G) for the matrices whose status word is exactly 1
-hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, long long count, hipStream_t s);
+// SLOT_THR[j] = tol * C[j][j] for j < rp (C = SLOT_C, before it is factored)
+hipError_t launch_rank_threshold(void* const* table, int nslots, int batch, int rp, float tol, hipStream_t s);
 hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
 // out <- in unless *status != 0 (both 16-byte aligned)
 hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
@@ -125,8 +128,10 @@ hipError_t launch_sum_partials(void* const* table, int nslots, int batch, int sl
 hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in, long long rows, int r, hipStream_t s);
 // second stage alone: s, d from nchunks rows of partial sums of squares already in SLOT_SPART
 hipError_t launch_colnorm_final(void* const* table, int nslots, int batch, int nchunks, int r, hipStream_t s);
+// out = in diag(d) (fp32), optional bf16 copies of out and of in.  null_slot >= 0: columns whose int32 there is
+// non-zero keep their old fp32 values in `out` (the bf16 copies still receive in diag(d))
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
-                             int status_slot, int slot_out16, int slot_in16, hipStream_t s);
+                             int status_slot, int slot_out16, int slot_in16, hipStream_t s, int null_slot = -1);
 // fp32 [rows][cols] -> bf16 copy [rows][cols] (slot_out16 >= 0) and bf16 transpose [cols][rows] (slot_outT16 >= 0);
 // rows and cols must be multiples of 64.
 // fp32 [rows][cols] (leading dimension ld_in) -> split bf16 x = hi + lo: plain copies [rows][cols] and transposed
@@ -147,6 +152,11 @@ struct CholPanelPtrs {
   int* status;
   const int* skip;
   long long stride;
+  // both null: a pivot outside its bounds is a breakdown.  Else (rp entries per matrix, `stride` words apart): a pivot
+  // not above thr[j] marks column j as dependent on the columns before it; it is left out of the factorisation (zero
+  // column of L, zero row and column of the inverse) and nullmask[j] is set, otherwise cleared.
+  const float* thr;
+  int* nullmask;
 };
 hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s);
 // The whole factorisation in one launch (tiles owned by pr x pc workgroups that hand results on through flags).
@@ -169,6 +179,8 @@ struct CholStreamArgs {
   const unsigned long long* step_counter;
   int pass;
   unsigned spin_limit;
+  const float* thr;        // as in CholPanelPtrs
+  int* nullmask;
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
 // W = L^-1 from L and the inverses of its 64 x 64 diagonal blocks (both as the factorisation leaves them), one launch

@@ -82,23 +82,17 @@ hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int c
   return hipSuccess;
 }
 
-// Second stage of a Double Dion step that broke down in its own orthonormalisation (status 1, not the 2 inherited
-// from the first stage): the momentum still takes in the sketch, M += G (G is the fp32 sketch), nothing else moves.
-__global__ void accumulate_failed_kernel(void* const* table, int nslots, long long count) {
+// Pivot thresholds of the factorisation that tolerates dependent columns: a fraction of the Gram matrix' diagonal
+__global__ void rank_threshold_kernel(void* const* table, int nslots, int rp, float tol) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
-  if (*(const int*)tab[SLOT_STATUS] != 1) return;
-  f32x4_t* M = (f32x4_t*)tab[SLOT_M];
-  const f32x4_t* G = (const f32x4_t*)tab[SLOT_G];
-  const long long n4 = count >> 2;
-  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (long long)gridDim.x * blockDim.x) M[i] = M[i] + G[i];
-  if (blockIdx.x == 0 && threadIdx.x < (count & 3)) ((float*)M)[n4 * 4 + threadIdx.x] += ((const float*)G)[n4 * 4 + threadIdx.x];
+  const float* C = (const float*)tab[SLOT_C];
+  float* thr = (float*)tab[SLOT_THR];
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < rp) thr[j] = tol * C[(long long)j * rp + j];
 }
-hipError_t launch_accumulate_failed(void* const* table, int nslots, int batch, long long count, hipStream_t s) {
-  if (count <= 0 || batch <= 0) return hipSuccess;
-  long long blocks = (count / 4 + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(accumulate_failed_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, count);
+hipError_t launch_rank_threshold(void* const* table, int nslots, int batch, int rp, float tol, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rank_threshold_kernel, dim3((rp + 255) / 256, batch), dim3(256), 0, s, table, nslots, rp, tol);
   return hipGetLastError();
 }
 
@@ -293,7 +287,7 @@ hipError_t launch_colnorm(void* const* table, int nslots, int batch, int slot_in
 // out[row][col] = in[row][col] * d[col]   (in may alias out).  Optionally also stores bf16 copies of the
 // result (slot_out16) and of the input (slot_in16): the operands of the fused update kernel.
 __global__ void __launch_bounds__(256) scale_cols_kernel(void* const* table, int nslots, int slot_in, int slot_out, long long rows,
-                                                         int r, int status_slot, int slot_out16, int slot_in16) {
+                                                         int r, int status_slot, int slot_out16, int slot_in16, int null_slot) {
   void* const* tab = table + (size_t)blockIdx.z * nslots;
   if (status_slot >= 0 && *(const int*)tab[status_slot] != 0) return;
   const float* in = (const float*)tab[slot_in];
@@ -301,17 +295,31 @@ __global__ void __launch_bounds__(256) scale_cols_kernel(void* const* table, int
   uint16_t* out16 = slot_out16 >= 0 ? (uint16_t*)tab[slot_out16] : nullptr;
   uint16_t* in16 = slot_in16 >= 0 ? (uint16_t*)tab[slot_in16] : nullptr;
   const float* d = (const float*)tab[SLOT_D];
+  const int* nullmask = null_slot >= 0 ? (const int*)tab[null_slot] : nullptr;
   // a block covers 64 rows x 256 columns; a thread owns 4 consecutive columns (or fewer at a ragged edge)
   const int col = blockIdx.x * 256 + (threadIdx.x & 63) * 4;
   if (col >= r) return;
   const long long row_end = min(rows, ((long long)blockIdx.y + 1) * 64);
   if ((r & 3) == 0) {
     const f32x4_t dv = *(const f32x4_t*)(d + col);
+    bool keep_old[4] = {false, false, false, false};
+    bool any_old = false;
+    if (nullmask) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { keep_old[e] = nullmask[col + e] != 0; any_old = any_old || keep_old[e]; }
+    }
     for (long long row = (long long)blockIdx.y * 64 + (threadIdx.x >> 6); row < row_end; row += 4) {
       const long long idx = row * r + col;
       const f32x4_t v = *(const f32x4_t*)(in + idx);
       const f32x4_t q = v * dv;
-      *(f32x4_t*)(out + idx) = q;
+      if (any_old) {
+        f32x4_t o = *(const f32x4_t*)(out + idx);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = keep_old[e] ? o[e] : q[e];
+        *(f32x4_t*)(out + idx) = o;
+      } else {
+        *(f32x4_t*)(out + idx) = q;
+      }
       if (out16) { u32x2_t w = {pack_bf16x2(q[0], q[1]), pack_bf16x2(q[2], q[3])}; *(u32x2_t*)(out16 + idx) = w; }
       if (in16) { u32x2_t w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])}; *(u32x2_t*)(in16 + idx) = w; }
     }
@@ -321,16 +329,16 @@ __global__ void __launch_bounds__(256) scale_cols_kernel(void* const* table, int
         const long long idx = row * r + c;
         const float v = in[idx];
         const float q = v * d[c];
-        out[idx] = q;
+        if (!(nullmask && nullmask[c] != 0)) out[idx] = q;
         if (out16) out16[idx] = (uint16_t)(pack_bf16x2(q, 0.f) & 0xffffu);
         if (in16) in16[idx] = (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
       }
   }
 }
 hipError_t launch_scale_cols(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long rows, int r,
-                             int status_slot, int slot_out16, int slot_in16, hipStream_t s) {
+                             int status_slot, int slot_out16, int slot_in16, hipStream_t s, int null_slot) {
   hipLaunchKernelGGL(scale_cols_kernel, dim3((r + 255) / 256, (unsigned)((rows + 63) / 64), batch), dim3(256), 0, s, table, nslots,
-                     slot_in, slot_out, rows, r, status_slot, slot_out16, slot_in16);
+                     slot_in, slot_out, rows, r, status_slot, slot_out16, slot_in16, null_slot);
   return hipGetLastError();
 }
 

@@ -48,8 +48,23 @@ class DoubleProblem:
         return [t[i].cpu().numpy() for t in (self.X, self.M1, self.V1, self.M2, self.V2)]
 
 
-def run(shapes, r1, r2, g_bf16, math, steps, tol):
-    dp = DoubleProblem(shapes, r1, r2, g_bf16, math)
+def oracle_with_gpu_decisions(dp, i, x, g32, m1, v1, m2, v2, method, band=2.0):
+    """The oracle step of matrix i with the dependent / independent decisions of stage 2 taken as the library took them
+    in its own precision (both sides have to take a decision that floating point makes in the same precision), after
+    checking that every one of them is right or borderline: with the squared relative distances r_j that the oracle
+    finds along that sequence of decisions, kept columns have r_j > RANK_TOL / band, dropped ones r_j < RANK_TOL * band."""
+    r2 = v2.shape[1]
+    null = B.dion_debug_buffer(dp.s2, i, B.DEBUG_NULL).cpu().numpy().reshape(-1)[:r2]
+    gpu_keep = null == 0
+    ref = orc.double_dion_step(x, g32, m1, v1, m2, v2, MU1, MU2, ETA, method, forced=gpu_keep.astype(int))
+    r = ref["ratio"]
+    assert np.all(r[gpu_keep] > orc.RANK_TOL / band), ("kept a dependent column", np.sort(r[gpu_keep])[:4])
+    assert np.all(r[~gpu_keep] < orc.RANK_TOL * band), ("dropped an independent column", np.sort(r[~gpu_keep])[-4:])
+    return ref
+
+
+def run(shapes, r1, r2, g_bf16, math, steps, tol, method="householder", warm=True, dx_tol=None):
+    dp = DoubleProblem(shapes, r1, r2, g_bf16, math, warm=warm)
     for t in range(steps):
         grads = [inputs.gradient(m, n, t, 0, i, bf16=g_bf16) for i, (m, n) in enumerate(shapes)]
         before = [dp.host(i) for i in range(len(shapes))]
@@ -58,14 +73,19 @@ def run(shapes, r1, r2, g_bf16, math, steps, tol):
         for i in range(len(shapes)):
             g32 = inputs.bf16_bits_to_f32(grads[i]) if g_bf16 else grads[i]
             x, m1, v1, m2, v2 = before[i]
-            ref = orc.double_dion_step(x, g32, m1, v1, m2, v2, MU1, MU2, ETA)
+            ref = oracle_with_gpu_decisions(dp, i, x, g32, m1, v1, m2, v2, method)
             X, M1, V1, M2, V2 = dp.host(i)
+            kept = int(ref["keep"].sum())
+            assert np.array_equal(V2[:, ~ref["keep"]], v2[:, ~ref["keep"]])       # dependent columns keep their factor
+            assert abs(np.linalg.norm(X.astype(np.float64) - x) / (ETA * np.sqrt(shapes[i][0] / shapes[i][1]) * np.sqrt(kept)) - 1) < 10 * tol
             err = dict(X=relf(X, ref["X"]), M1=relf(M1, ref["M1"]), M2=relf(M2, ref["M2"]),
                        dX=relf(X.astype(np.float64) - x, ref["X"] - x), D=relf(dp.D[i].cpu().numpy(), ref["D"]),
                        v1=float(np.min(np.abs(np.sum(V1.astype(np.float64) * ref["V1"], axis=0)))),
                        v2=float(np.min(np.abs(np.sum(V2.astype(np.float64) * ref["V2"], axis=0)))))
             assert max(err["X"], err["M1"], err["M2"], err["D"]) <= tol and err["dX"] <= 3 * tol, (t, i, err)
-            assert err["v1"] > 1 - 10 * tol and err["v2"] > 1 - 10 * tol, (t, i, err)
+            print("double step", t, shapes[i], (r1, r2), "independent columns in stage 2:", kept, {k: "%.2e" % v for k, v in err.items()}, flush=True)
+            assert max(err["X"], err["M1"], err["M2"], err["D"]) <= tol and err["dX"] <= (dx_tol or 3 * tol), (t, i, err)
+            assert err["v1"] > 1 - 10 * tol and (err["v2"] > 1 - 10 * tol or dx_tol), (t, i, err)
 
 
 def test_double_dion_fp32():
@@ -77,7 +97,16 @@ def test_double_dion_bf16_large_tile_path():
     run([(512, 256), (256, 768)], 128, 128, True, "bf16", 2, 2e-2)
 
 
-def test_double_dion_breakdowns():
+def test_double_dion_bf16_full_size_direct_load_path():
+    # 8192 x 8192 with r2 = 1024: stage 2 reads the stored bf16 copies of M2 + sketch.  Once from a full-rank M2 and once
+    # from M2 = 0, where the buffer of stage 2 has rank r1 = 256 and three quarters of its columns are dependent.
+    run([(8192, 8192)], 256, 1024, True, "bf16", 1, 2e-2, method="lapack")
+    # (while the buffer fills up the independent columns are badly conditioned among themselves, so the bf16 rounding of
+    # the operands, 3e-3 per entry of B2 V2, weighs more on the update's direction than in a full-rank step)
+    run([(8192, 8192)], 256, 1024, True, "bf16", 2, 2e-2, method="lapack", warm=False, dx_tol=0.15)
+
+
+def test_double_dion_stage_one_breakdown_and_dependent_column_in_stage_two():
     m, n, r1, r2 = 256, 192, 8, 32
     good1 = [inputs.right_factor_raw(n, r1, 2, i) for i in range(2)]
     good2 = [inputs.right_factor_raw(n, r2, 3, i) for i in range(2)]
@@ -94,35 +123,46 @@ def test_double_dion_breakdowns():
         assert np.array_equal(u, v)
     ref = orc.double_dion_step(*before[0][:1], grads[0], *before[0][1:], MU1, MU2, ETA)
     assert relf(dp.host(0)[0], ref["X"]) < 1e-4
-    # stage 2 of matrix 1 fails: stage 1 has taken its step, M2 takes in the sketch, X and V2 are untouched
+    # V2 of matrix 1 has two identical columns: no failure, the second of them is dependent, takes no part in the step
+    # and stays as it was; everything else is the step on the other 31 columns
     dp = DoubleProblem([(m, n)] * 2, r1, r2, False, "f32", v2_raw=[good2[0], bad2])
     before = [dp.host(i) for i in range(2)]
     dp.upload(grads)
-    st1, st2 = dp.step()
-    assert st1 == (0, -1) and st2 == (B.DION_NUM_BREAKDOWN, 1)
+    assert dp.step() == ((0, -1), (0, -1))
     X, M1, V1, M2, V2 = dp.host(1)
-    assert np.array_equal(X, before[1][0]) and np.array_equal(V2, before[1][4])
-    ref = orc.double_dion_step(before[1][0], grads[1], before[1][1], before[1][2], before[1][3], before[1][4], MU1, MU2, ETA)
-    assert ref["status"] == orc.STATUS_BREAKDOWN and relf(M1, ref["M1"]) < 1e-4
-    assert relf(M2, ref["M2"]) < 1e-5                                     # M2 <- M2 + sketch
+    ref = oracle_with_gpu_decisions(dp, 1, before[1][0], grads[1], before[1][1], before[1][2], before[1][3], before[1][4], "householder")
+    assert ref["status"] == orc.STATUS_OK and int(ref["keep"].sum()) == r2 - 1 and not ref["keep"][9]
+    assert np.array_equal(V2[:, 9], before[1][4][:, 9])
+    assert relf(X, ref["X"]) < 1e-4 and relf(M2, ref["M2"]) < 1e-4 and relf(M1, ref["M1"]) < 1e-4
+    assert relf(X.astype(np.float64) - before[1][0], ref["X"] - before[1][0]) < 3e-4
+    assert float(np.min(np.abs(np.sum(V2.astype(np.float64) * ref["V2"], axis=0)))) > 1 - 1e-3
 
 
-def test_double_dion_cold_start():
-    # from M2 = 0 the second stage cannot orthonormalise until M2 has collected r2 / r1 sketches
-    m, n, r1, r2 = 256, 192, 16, 32
-    dp = DoubleProblem([(m, n)], r1, r2, False, "f32", warm=False)
-    statuses = []
-    for t in range(4):
-        g = inputs.gradient(m, n, t, 0, 0, bf16=False)
-        x, m1, v1, m2, v2 = dp.host(0)
-        dp.upload([g])
-        st1, st2 = dp.step()
-        assert st1 == (0, -1)
-        ref = orc.double_dion_step(x, g, m1, v1, m2, v2, MU1, MU2, ETA)
-        X, M1, V1, M2, V2 = dp.host(0)
-        statuses.append((st2[0], ref["status"]))
-        assert relf(M2, ref["M2"]) < 1e-4 and relf(M1, ref["M1"]) < 1e-4, t
-        if st2[0] != 0:
-            assert np.array_equal(X, x) and np.array_equal(V2, v2)
-    assert statuses[0] == (B.DION_NUM_BREAKDOWN, orc.STATUS_BREAKDOWN)      # rank 16 < 32
-    assert statuses[-1] == (0, orc.STATUS_OK)
+def test_double_dion_cold_start_moves_the_weights_from_the_first_step():
+    # from M2 = 0 the buffer of stage 2 has rank r1, 2 r1, ...: the step uses the rank that is there.  While the buffer
+    # fills up, the independent columns of B2 V2 are badly conditioned among themselves (squared relative distances down
+    # to RANK_TOL, condition numbers of a few thousand), which amplifies the forward error of any QR factor: the bound on
+    # the update's error is wider on those steps, the one on X, M1, M2 is the usual one.
+    for (m, n, r1, r2, g_bf16, math, tol, dx_tol) in [(256, 192, 16, 32, False, "f32", 1e-4, 3e-3), (1024, 768, 128, 512, True, "bf16", 2e-2, 0.15)]:
+        dp = DoubleProblem([(m, n)], r1, r2, g_bf16, math, warm=False)
+        ranks = []
+        for t in range(5):
+            g = inputs.gradient(m, n, t, 0, 0, bf16=g_bf16)
+            g32 = inputs.bf16_bits_to_f32(g) if g_bf16 else g
+            x, m1, v1, m2, v2 = dp.host(0)
+            dp.upload([g])
+            assert dp.step() == ((0, -1), (0, -1))
+            ref = oracle_with_gpu_decisions(dp, 0, x, g32, m1, v1, m2, v2, "lapack")
+            X, M1, V1, M2, V2 = dp.host(0)
+            k = int(ref["keep"].sum())
+            ranks.append(k)
+            dx = np.linalg.norm(X.astype(np.float64) - x)
+            edx = relf(X.astype(np.float64) - x, ref["X"] - x)
+            print((m, n, r1, r2), "step", t, "independent columns", k, "X %.2e M2 %.2e dX %.2e" % (relf(X, ref["X"]), relf(M2, ref["M2"]), edx), flush=True)
+            assert abs(dx / (ETA * np.sqrt(m / n) * np.sqrt(k)) - 1) < 10 * tol          # the weights move, by the rank that is there
+            assert relf(X, ref["X"]) < tol and relf(M2, ref["M2"]) < tol and relf(M1, ref["M1"]) < tol, t
+            assert edx < (3 * tol if t == 0 else dx_tol), (t, edx)
+            assert np.array_equal(V2[:, ~ref["keep"]], v2[:, ~ref["keep"]])
+            assert np.abs(np.linalg.norm(V2.astype(np.float64), axis=0) - 1).max() < 1e-5
+        print("independent columns per step:", ranks, flush=True)
+        assert r1 - 2 <= ranks[0] <= r1 and ranks[1] > ranks[0] and ranks[-1] > ranks[1]       # the rank grows as M2 fills up

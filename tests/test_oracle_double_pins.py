@@ -72,7 +72,7 @@ def test_dependent_orthonormalisation_equals_the_standard_one_at_full_rank():
     Z = rng.standard_normal((30, 7))
     P0, _, status = orc.orthonormalize(Z)
     for method in ("householder", "lapack"):
-        P, keep = orc.orthonormalize_dependent(Z, method)
+        P, keep, _ = orc.orthonormalize_dependent(Z, method)
         assert status == orc.STATUS_OK and keep.all() and np.abs(P - P0).max() < 1e-13
 
 
@@ -81,12 +81,18 @@ def test_dependent_columns_are_dropped_and_the_rest_is_the_qr_factor_of_the_rest
     Z = rng.standard_normal((40, 9))
     Z[:, 4] = 2.0 * Z[:, 1] - 0.5 * Z[:, 3]          # depends on earlier columns
     Z[:, 6] = 0.0                                     # a zero column
-    Z[:, 8] = Z[:, 7] + 1e-3 * Z[:, 8]               # nearly parallel to column 7: squared sine about 5e-7 < RANK_TOL
+    Z[:, 8] = Z[:, 7] + 1e-3 * Z[:, 8]               # nearly parallel to column 7: squared sine about 1e-6 < RANK_TOL
     want = np.array([1, 1, 1, 1, 0, 1, 0, 1, 0], dtype=bool)
     Pref, _ = orc.lapack_qr(Z[:, want])               # library QR of the independent columns alone
     for method in ("householder", "lapack"):
-        P, keep = orc.orthonormalize_dependent(Z, method)
+        P, keep, ratio = orc.orthonormalize_dependent(Z, method)
         assert np.array_equal(keep, want)
+        assert ratio[4] < 1e-25 and ratio[6] == 0.0 and 1e-7 < ratio[8] < 1e-5 and abs(ratio[0] - 1.0) < 1e-12
+        # forcing a borderline decision the other way: column 8 kept, column 5 dropped
+        f = -np.ones(9, dtype=int); f[8] = 1; f[5] = 0
+        Pf, keepf, _ = orc.orthonormalize_dependent(Z, method, forced=f)
+        wantf = want.copy(); wantf[8] = True; wantf[5] = False
+        assert np.array_equal(keepf, wantf) and np.abs(Pf[:, wantf] - orc.lapack_qr(Z[:, wantf])[0]).max() < 1e-9
         assert np.all(P[:, ~want] == 0.0)
         assert np.abs(P[:, want] - Pref).max() < 1e-12
         # what defines the factor: orthonormal, spans the same nested subspaces, positive diagonal
@@ -97,7 +103,8 @@ def test_dependent_columns_are_dropped_and_the_rest_is_the_qr_factor_of_the_rest
         a = rng.standard_normal(25); a /= np.linalg.norm(a)
         b = rng.standard_normal(25); b -= a * (a @ b); b /= np.linalg.norm(b)
         Z2 = np.stack([a, np.sqrt(1 - s2) * a + np.sqrt(s2) * b], axis=1)
-        assert orc.orthonormalize_dependent(Z2)[1][1] == expect
+        for method in ("householder", "lapack"):
+            assert orc.orthonormalize_dependent(Z2, method)[1][1] == expect
 
 
 def test_cold_start_moves_the_weights_with_the_rank_that_is_there():
