@@ -164,7 +164,9 @@ Carve carve_entry(const Group& g) {
   take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
   take(SLOT_EPART, GRAM_DEFECT_PARTS);
   take(SLOT_FAST, 1);
-  take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : 0);
+  // split-k partial results of K1 / K2: whole partial matrices off the direct-load path; on it (one matrix only) the
+  // partial 256 x 256 tiles of a split last round, at most 256 of them
+  take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : (g.direct12 && g.count == 1) ? (size_t)256 * 256 * 256 : 0);
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
   take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
   take(SLOT_B16T, g.direct12 ? ((size_t)g.m * g.n + 1) / 2 : 0);
@@ -315,6 +317,7 @@ GemmArgs base_args(const dion_state* st, const Group& g) {
   a.noop_slot = -1;
   a.E.colsq_slot = -1;
   a.side_slot = -1;
+  a.tail_slot = -1;
   a.E.alpha = 1.f;
   return a;
 }
@@ -646,6 +649,7 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
     if (direct12(c)) {
       a.A = opnd(SLOT_B16, 0, n);
       a.group_n = kDirect12GroupN;
+      if (g.count == 1) { a.cus = c.st->cus; a.tail_slot = SLOT_KPART; }   // a short last round is split over k
       HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
       return DION_OK;
     }
@@ -685,6 +689,7 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunk
     if (direct12(c)) {
       a.A = opnd(SLOT_B16T, 0, m);
       a.group_n = kDirect12GroupN;
+      if (g.count == 1) { a.cus = c.st->cus; a.tail_slot = SLOT_KPART; }   // a short last round is split over k
       if (colsq_chunks) {
         *colsq_chunks = gemm2_nt_colsq_chunks(G2_256x256, a);
         if (*colsq_chunks > 0) a.E.colsq_slot = SLOT_SPART;

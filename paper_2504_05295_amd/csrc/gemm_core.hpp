@@ -72,6 +72,13 @@ struct GemmArgs {
                         // second round of workgroups fills in behind the first (needs xcd_remap, one matrix, split-K 1)
   int tri_grid;         // set by the direct-load launcher: lower_only grids hold the lower-triangle tiles only
   int side_slot;        // large-tile K1 only, >= 0: bf16(M + G) is also written there ([M][K] row-major, bf16)
+  // Direct-load core, plain store, one matrix, no split over k: when the tiles make a last round that would leave most
+  // compute units idle (tail_tiles of them, fewer than half the compute units), each of those tiles is split over k by
+  // tail_split workgroups whose partial tiles go to tail_slot ([tail tile][split][BM][BN] floats); launch_gemm3 follows
+  // up with a kernel that adds them into the result (and forms the column sums of squares the main kernel would have).
+  int cus;              // host side: compute units of the device (0: no tail split)
+  int tail_slot;        // >= 0: buffer for the partial tiles, at least 256 tiles of BM x BN floats (-1: no tail split)
+  int tail_tiles, tail_split, tail_first;   // set by the launcher
   Operand A, B, B2;
   EpilogueDesc E;
 };

@@ -18,6 +18,8 @@
 // to the compiler, every LDS read would wait for all loads in flight, since it cannot tell their LDS
 // destinations apart.
 #pragma once
+#include <algorithm>
+
 #include "gemm_core.hpp"
 
 namespace dion {
@@ -84,28 +86,11 @@ __device__ __forceinline__ int lds_swizzle(int row) {
   return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3;
 }
 
-template <class Cfg, bool GBF16, int EPI, bool DUAL>
-__global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArgs g) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, CPR = Cfg::CPR, ROWB = Cfg::ROWB;
-  constexpr int MI = Cfg::MI, NI = Cfg::NI, KSTEPS = BK / 16;
-  constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES;
-  constexpr int STAGE_BYTES = A_BYTES + B_BYTES * (DUAL ? 2 : 1);
-  constexpr int SP = 36;   // epilogue patch row stride in floats
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-
-  int bid = blockIdx.x;
-  if (g.xcd_remap) {
-    const int per = gridDim.x >> 3;
-    bid = (bid & 7) * per + (bid >> 3);
-  }
-  // tri_grid: the grid holds the tiles on and below the diagonal only (tile t -> row tm, column tn <= tm), so that
-  // no workgroup is launched just to return and the live ones spread evenly over the XCDs
-  const int ntile = g.tri_grid ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
-  const int tile = bid % ntile;
-  int rest = bid / ntile;
-  const int ks = rest % g.splitk;
-  const int b = rest / g.splitk;
-  int tn = tile % g.tiles_n, tm = tile / g.tiles_n;
+// Tile (row, column) of the `tile`-th tile in the order in which a launch visits them.
+template <int BM, int BN>
+__device__ __forceinline__ void gemm3_tile_coords(const GemmArgs& g, int tile, int& tm, int& tn) {
+  tn = tile % g.tiles_n;
+  tm = tile / g.tiles_n;
   if (g.tri_grid) {
     tm = (int)((__builtin_sqrtf(8.f * (float)tile + 1.f) - 1.f) * 0.5f);
     while (tm * (tm + 1) / 2 > tile) --tm;
@@ -125,6 +110,44 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
     tm = rem / width;
     tn = first + rem % width;
   }
+}
+
+template <class Cfg, bool GBF16, int EPI, bool DUAL>
+__global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, CPR = Cfg::CPR, ROWB = Cfg::ROWB;
+  constexpr int MI = Cfg::MI, NI = Cfg::NI, KSTEPS = BK / 16;
+  constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES;
+  constexpr int STAGE_BYTES = A_BYTES + B_BYTES * (DUAL ? 2 : 1);
+  constexpr int SP = 36;   // epilogue patch row stride in floats
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  int bid = blockIdx.x;
+  if (g.xcd_remap) {
+    // (with a split last round the remapping covers the full rounds only: the tail keeps its place at the end)
+    const int main_blocks = g.tail_split > 1 ? g.tail_first : (int)gridDim.x;
+    if (bid < main_blocks) {
+      const int per = main_blocks >> 3;
+      bid = (bid & 7) * per + (bid >> 3);
+    }
+  }
+  // tri_grid: the grid holds the tiles on and below the diagonal only (tile t -> row tm, column tn <= tm), so that
+  // no workgroup is launched just to return and the live ones spread evenly over the XCDs
+  const int ntile = g.tri_grid ? g.tiles_m * (g.tiles_m + 1) / 2 : g.tiles_m * g.tiles_n;
+  int tile = bid % ntile;
+  int rest = bid / ntile;
+  int ks = rest % g.splitk;
+  int b = rest / g.splitk;
+  // a tile of the last, short round: tail_split workgroups share its contraction (one matrix, splitk == 1; the grid
+  // then holds tail_first + tail_tiles * tail_split workgroups, more than there are tiles)
+  int tail_q = -1;
+  if (g.tail_split > 1 && bid >= g.tail_first) {
+    tail_q = bid - g.tail_first;
+    tile = g.tail_first + tail_q / g.tail_split;
+    ks = tail_q % g.tail_split;
+    b = 0;
+  }
+  int tn, tm;
+  gemm3_tile_coords<BM, BN>(g, tile, tm, tn);
   if (g.lower_only && tn * BN > tm * BM + BM - 1) return;
 
   void* const* tab = g.table + (size_t)b * g.nslots;
@@ -159,8 +182,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   const int kseg_eff = g.tri_k ? min(kseg, (tn + 1) * BN) : kseg;
   const int slabs_per_seg = kseg_eff / BK;
   const int total = nseg * slabs_per_seg;
-  const int s_begin = ks * g.k_per_split;
-  const int s_end = min(total, s_begin + g.k_per_split);
+  const int kps = tail_q >= 0 ? (total + g.tail_split - 1) / g.tail_split : g.k_per_split;
+  const int s_begin = ks * kps;
+  const int s_end = min(total, s_begin + kps);
   // Operand base addresses of the (up to three) operand pairs, read once and kept in scalar registers: a look-up
   // in the pointer table inside the loop is a memory load, and the wait for it would also wait for every tile
   // load in flight.  (Separate variables: an array indexed by the pair number would live in scratch memory.)
@@ -295,6 +319,14 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   };
   if constexpr (EPI == EPI_STORE) {
     float* C = (float*)tab[g.E.slot] + g.E.off + (long long)ks * g.E.split_stride;
+    long long c_ld = g.E.ld;
+    int c_row0 = row0, c_col0 = col0;
+    if (tail_q >= 0) {   // a partial tile of the last round: to the buffer of partial tiles, a BM x BN block of its own
+      C = (float*)tab[g.tail_slot] + (long long)tail_q * (BM * BN);
+      c_ld = BN;
+      c_row0 = 0;
+      c_col0 = 0;
+    }
     float colsq[NI];   // sums of squares of this wave's WTM rows, per column (lane & 31) of each column block
 #pragma unroll
     for (int j = 0; j < NI; ++j) colsq[j] = 0.f;
@@ -307,15 +339,15 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
         to_patch(acc[i][j]);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-          const int row = row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
-          const int col = col0 + wn * Cfg::WTN + j * 32 + pcol;
-          gstore<f32x4_t>(C + (long long)row * g.E.ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
+          const int row = c_row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
+          const int col = c_col0 + wn * Cfg::WTN + j * 32 + pcol;
+          gstore<f32x4_t>(C + (long long)row * c_ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
         }
       }
     // Column norms of the result (ColNorm of the update rule) without another pass over it: one partial sum of
     // squares per column and block of WTM rows, chunk (tile row, wave row) at part[chunk * N + column]; whoever
     // finishes adds the chunks up in their order.  Only for whole products (no split over k).
-    if (g.E.colsq_slot >= 0) {
+    if (g.E.colsq_slot >= 0 && tail_q < 0) {
       float* part = (float*)tab[g.E.colsq_slot] + (long long)(tm * Cfg::WAVES_M + wm) * g.N + col0 + wn * Cfg::WTN;
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
@@ -395,6 +427,43 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   }
 }
 
+// Adds up the partial tiles of a launch's last round (GemmArgs::tail_*) into the result, in a fixed order, and forms
+// the per-column sums of squares that the main kernel's epilogue forms for whole tiles.  One workgroup of 256 threads
+// per tail tile and block of WTM rows: a thread owns four consecutive columns of every RPP-th row.
+template <class Cfg>
+__global__ void __launch_bounds__(256) gemm3_tail_reduce_kernel(const GemmArgs g) {
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, WTM = Cfg::WTM;
+  constexpr int TPR = BN / 4, RPP = 256 / TPR;   // threads per row, rows per pass
+  static_assert(256 % TPR == 0 && WTM % RPP == 0, "tile shape");
+  void* const* tab = g.table;
+  if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
+  if (g.noop_slot >= 0 && *(const int*)tab[g.noop_slot] != 0) return;
+  const int t = blockIdx.x, chunk = blockIdx.y;
+  const int cx = threadIdx.x % TPR, ry = threadIdx.x / TPR;
+  int tm, tn;
+  gemm3_tile_coords<BM, BN>(g, g.tail_first + t, tm, tn);
+  const float* part = (const float*)tab[g.tail_slot] + (long long)t * g.tail_split * (BM * BN) + (long long)chunk * WTM * BN + cx * 4;
+  float* C = (float*)tab[g.E.slot] + g.E.off + (long long)(tm * BM + chunk * WTM) * g.E.ld + tn * BN + cx * 4;
+  f32x4_t sq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int row = ry; row < WTM; row += RPP) {
+    f32x4_t acc = gload<f32x4_t>(part + (long long)row * BN);
+    for (int sp = 1; sp < g.tail_split; ++sp) acc += gload<f32x4_t>(part + (long long)sp * (BM * BN) + (long long)row * BN);
+    gstore<f32x4_t>(C + (long long)row * g.E.ld, acc);
+    sq += acc * acc;
+  }
+  if (g.E.colsq_slot >= 0) {
+    __shared__ f32x4_t red[RPP][TPR];
+    red[ry][cx] = sq;
+    __syncthreads();
+    if (ry == 0) {
+      f32x4_t tot = red[0][cx];
+      for (int q = 1; q < RPP; ++q) tot += red[q][cx];
+      gstore<f32x4_t>((float*)tab[g.E.colsq_slot] + (long long)(tm * Cfg::WAVES_M + chunk) * g.N + tn * BN + cx * 4, tot);
+    }
+  }
+}
+
 // True when launch_gemm3 can take these arguments: tile-aligned shapes and operands small enough for the
 // 32-bit byte offsets of the direct loads.
 template <class Cfg>
@@ -452,13 +521,32 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   const long long blocks = ntile * g.splitk * batch;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  g.xcd_remap = (g.xcd_remap && (blocks % 8 == 0)) ? 1 : 0;
+  // last round: when its tiles would occupy fewer than half the compute units, split each over k
+  long long grid = blocks;
+  g.tail_tiles = 0; g.tail_split = 1; g.tail_first = 0;
+  if (EPI == EPI_STORE && !DUAL && g.cus > 0 && g.tail_slot >= 0 && batch == 1 && g.splitk == 1 && !g.tri_grid && !g.lower_only &&
+      !g.heavy_first && ntile > g.cus) {
+    const int tail = (int)(ntile % g.cus);
+    const int sp = tail > 0 ? std::min(8, g.cus / tail) : 1;
+    if (sp >= 2 && total / sp >= 16) {
+      g.tail_tiles = tail; g.tail_split = sp; g.tail_first = (int)(ntile - tail);
+      grid = (ntile - tail) + (long long)tail * sp;
+    }
+  }
+  // (the XCD remapping permutes the workgroups of the full rounds; a split tail keeps its place at the end)
+  g.xcd_remap = (g.xcd_remap && ((g.tail_split > 1 ? (long long)g.tail_first : grid) % 8 == 0)) ? 1 : 0;
   g.heavy_first = (g.heavy_first && g.xcd_remap && !g.tri_grid && g.group_n == 0 && g.splitk == 1 && batch == 1 && g.tiles_m % 8 == 0) ? 1 : 0;
   constexpr int LDS_BYTES = gemm3_lds_bytes<Cfg, DUAL>();
   hipError_t e = gemm3_prepare<Cfg, GBF16, EPI, DUAL>();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL>), dim3((unsigned)blocks), dim3(Cfg::NT), LDS_BYTES, stream, g);
-  return hipGetLastError();
+  hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL>), dim3((unsigned)grid), dim3(Cfg::NT), LDS_BYTES, stream, g);
+  e = hipGetLastError();
+  if (e != hipSuccess || g.tail_split < 2) return e;
+  if constexpr (EPI == EPI_STORE && !DUAL) {
+    hipLaunchKernelGGL((gemm3_tail_reduce_kernel<Cfg>), dim3(g.tail_tiles, Cfg::BM / Cfg::WTM), dim3(256), 0, stream, g);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 }  // namespace dion
