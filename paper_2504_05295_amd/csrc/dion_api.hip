@@ -169,7 +169,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : (g.direct12 && g.count == 1) ? (size_t)256 * 256 * 256 : 0);
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
   take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
-  take(SLOT_B16T, g.direct12 ? ((size_t)g.m * g.n + 1) / 2 : 0);
+  take(SLOT_B16T, 0);   // (no transposed copy: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
   take(SLOT_THR, g.rp);
   take(SLOT_NULL, g.rp);
   c.total = pos;
@@ -331,6 +331,45 @@ Operand opnd(int slot0, long long off, long long ld, long long sub_stride = 0, i
   return o;
 }
 
+// Tile size and split over the rows of the Gram matrix of `batch` rows x r matrices on the split-bf16 path.
+// 256 x 256 tiles (direct-load kernel) when the lower triangle of such tiles, split over the rows as far as the
+// partial-result buffer allows, fills at least half of the GPU and every split still has a contraction worth
+// starting a pipeline for; else 128 x 128 tiles with a deeper split.
+// Split over the rows.  The plain choice: as many workgroups per tile as it takes to reach the number of compute
+// units.  With s workgroups per tile the kernel runs in ceil(tiles s / 256) rounds of 1/s of the contraction each,
+// and the partial results cost a pass over s of them afterwards (about 0.06 us per tile and partial): where that
+// estimate finds a split at least a fifth cheaper (136 tiles at r = 4096: two per tile make a second round for 16
+// workgroups, seven make four full rounds), it is taken; smaller predicted gains did not show up in measurements
+// (r = 2048: seven per tile slower than six).  Every split must keep a contraction worth starting a pipeline for.
+struct GramChoice {
+  bool big;
+  int split;
+};
+GramChoice choose_gram(const Group& g, int batch, long long rows, const GramPlan& gp) {
+  const long long r = g.r;
+  const long long t256 = r / 256, tiles256 = t256 * (t256 + 1) / 2 * batch;
+  int big_split = 1;
+  if (tiles256 > 0) {
+    const double t_full = 3.0 * (double)(rows / 64) * 1.8, t_red = 0.06 * (double)tiles256;
+    auto cost = [&](int sp) {
+      const double rounds = (double)((tiles256 * sp + 255) / 256);
+      return rounds / sp * t_full + (sp > 1 ? sp * t_red + 5.0 : 0.0);
+    };
+    big_split = (int)std::min<long long>(std::min(gp.splitk2, gp.split_cap256), (256 + tiles256 - 1) / tiles256);
+    if (big_split < 1) big_split = 1;
+    int best = big_split;
+    for (int sp = 1; sp <= gp.split_cap256; ++sp) {
+      if (sp > 1 && 3 * (rows / 64) / sp < 16) break;
+      if (cost(sp) < cost(best)) best = sp;
+    }
+    if (cost(best) < 0.8 * cost(big_split)) big_split = best;
+  }
+  GramChoice c;
+  c.big = r % 256 == 0 && rows % 64 == 0 && tiles256 * big_split >= 128 && 3 * (rows / 64) / big_split >= 16;
+  c.split = big_split;
+  return c;
+}
+
 // One Cholesky-QR pass (Appendix A): out = in * chol(in^T in)^-T, for `batch` matrices of `rows` x r starting at
 // table row `row0` of group g (rows = m in a Dion step, n in a Lazy-Dion refresh; gp is the matching plan).
 // With `split` the two large products run on the bf16 matrix pipe with split operands (x = hi + lo,
@@ -358,44 +397,24 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   int c_nsplit = 1;
   // Gram matrix (lower tiles), split over m when the tile count alone cannot fill the GPU
   if (split) {
-    // (an adaptive pass needs the low part in row-major order only if it goes on to its product: made after the decision)
-    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, adaptive ? -1 : SLOT_ZL16, SLOT_PT16, SLOT_ZLT16, s));
+    const GramChoice gc = choose_gram(g, batch, rows, gp);
+    const bool gram_big = gc.big;
+    const int big_split = gc.split;
+    // On 256 x 256 tiles the Gram matrix reads the two row-major halves as operands stored with k (the row index) as
+    // the slow index; the 128-wide-tile kernel needs transposed copies.  (An adaptive pass on the latter needs the low
+    // part in row-major order only if it goes on to its product: made after the decision.)
+    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, (gram_big || !adaptive) ? SLOT_ZL16 : -1,
+                             gram_big ? -1 : SLOT_PT16, gram_big ? -1 : SLOT_ZLT16, s));
     GemmArgs a = base;
     a.M = r; a.N = r; a.K = 3 * (int)rows;
     a.nseg = 3; a.kseg = (int)rows;
-    a.segA[0] = SLOT_PT16; a.segB[0] = SLOT_PT16;
-    a.segA[1] = SLOT_PT16; a.segB[1] = SLOT_ZLT16;
-    a.segA[2] = SLOT_ZLT16; a.segB[2] = SLOT_PT16;
-    a.A = opnd(SLOT_PT16, 0, rows);
-    a.B = opnd(SLOT_PT16, 0, rows);
+    const int hi = gram_big ? SLOT_P16 : SLOT_PT16, lo = gram_big ? SLOT_ZL16 : SLOT_ZLT16;
+    a.segA[0] = hi; a.segB[0] = hi;
+    a.segA[1] = hi; a.segB[1] = lo;
+    a.segA[2] = lo; a.segB[2] = hi;
+    a.A = opnd(hi, 0, gram_big ? r : rows);
+    a.B = opnd(hi, 0, gram_big ? r : rows);
     a.lower_only = 1;
-    // 256x256 tiles (direct-load kernel) when the lower triangle of such tiles, split over the rows as far as the
-    // partial-result buffer allows, fills at least half of the GPU and every split still has a contraction worth
-    // starting a pipeline for; else 128x128 tiles with a deeper split
-    const long long t256 = r / 256, tiles256 = t256 * (t256 + 1) / 2 * batch;
-    // Split over the rows.  The plain choice: as many workgroups per tile as it takes to reach the number of compute
-    // units.  With s workgroups per tile the kernel runs in ceil(tiles s / 256) rounds of 1/s of the contraction each,
-    // and the partial results cost a pass over s of them afterwards (about 0.06 us per tile and partial): where that
-    // estimate finds a split at least a fifth cheaper (136 tiles at r = 4096: two per tile make a second round for 16
-    // workgroups, seven make four full rounds), it is taken; smaller predicted gains did not show up in measurements
-    // (r = 2048: seven per tile slower than six).  Every split must keep a contraction worth starting a pipeline for.
-    int big_split = 1;
-    if (tiles256 > 0) {
-      const double t_full = 3.0 * (double)(rows / 64) * 1.8, t_red = 0.06 * (double)tiles256;
-      auto cost = [&](int sp) {
-        const double rounds = (double)((tiles256 * sp + 255) / 256);
-        return rounds / sp * t_full + (sp > 1 ? sp * t_red + 5.0 : 0.0);
-      };
-      big_split = (int)std::min<long long>(std::min(gp.splitk2, gp.split_cap256), (256 + tiles256 - 1) / tiles256);
-      if (big_split < 1) big_split = 1;
-      int best = big_split;
-      for (int sp = 1; sp <= gp.split_cap256; ++sp) {
-        if (sp > 1 && 3 * (rows / 64) / sp < 16) break;
-        if (cost(sp) < cost(best)) best = sp;
-      }
-      if (cost(best) < 0.8 * cost(big_split)) big_split = best;
-    }
-    const bool gram_big = r % 256 == 0 && rows % 64 == 0 && tiles256 * big_split >= 128 && 3 * (rows / 64) / big_split >= 16;
     const int gcfg = gram_big ? G2_256x256 : G2_128x128;
     a.splitk = gram_big ? big_split : gp.splitk2;
     // consecutive tiles of one split on one XCD: they share the rows of the split and many operand panels, so an
@@ -405,7 +424,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.E.slot = (eff > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
     a.E.split_stride = rr;
-    HIPCHK(gemm2_nt(gcfg, a, batch, s));
+    HIPCHK(gemm2_nt(gcfg, a, batch, s, gram_big ? (KS_A | KS_B) : 0));
     c_nsplit = eff;
   } else {
     GemmArgs a = base;
@@ -541,7 +560,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     // below 1e-3, would survive.  Such a pass runs in place, slot_out == slot_in: the product reads the bf16 copies
     // of its input, never the fp32 original, so it may overwrite that; and when the flag is set it has nothing to do.)
     HIPCHK(launch_split_bf16(tab, NSLOTS, batch, SLOT_W, rp, r, r, SLOT_WH16, SLOT_WL16, -1, -1, s, skip));
-    if (adaptive) HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, -1, SLOT_ZL16, -1, -1, s, skip));
+    if (adaptive && !choose_gram(g, batch, rows, gp).big)
+      HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, -1, SLOT_ZL16, -1, -1, s, skip));
     GemmArgs a = base;  // out = in W^T with in = hi + lo, W = Wh + Wl
     if (adaptive) {
       if (slot_out != slot_in) return DION_EINVAL;
@@ -626,10 +646,9 @@ bool direct12(const RowCtx& c) {
 }
 // The bf16 copies of M + G for the K1 / K2 of this call (a no-op off the direct-load path); the transposed one only
 // when a K2 will run.
-int stage_b16(const RowCtx& c, bool with_transpose = true) {
+int stage_b16(const RowCtx& c) {
   if (!direct12(c)) return DION_OK;
-  HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, with_transpose ? SLOT_B16T : -1, c.g->m, c.g->n,
-                         c.s));
+  HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, -1, c.g->m, c.g->n, c.s));
   return DION_OK;
 }
 
@@ -644,15 +663,18 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
   a.E.slot = SLOT_Z; a.E.ld = r;
   a.xcd_remap = 1;
   if (c.big) {
-    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, -1, SLOT_QT16, n, r, c.s));
-    a.B = opnd(SLOT_QT16, 0, n);
     if (direct12(c)) {
+      // Q as bf16 in its own row-major order (n x r): the right operand with k, its row index, as the slow index
+      HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, SLOT_QT16, -1, n, r, c.s));
+      a.B = opnd(SLOT_QT16, 0, r);
       a.A = opnd(SLOT_B16, 0, n);
       a.group_n = kDirect12GroupN;
       if (g.count == 1) { a.cus = c.st->cus; a.tail_slot = SLOT_KPART; }   // a short last round is split over k
-      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
+      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_B));
       return DION_OK;
     }
+    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, -1, SLOT_QT16, n, r, c.s));
+    a.B = opnd(SLOT_QT16, 0, n);
     if (keep_b16) a.side_slot = SLOT_B16;
     const int c1 = tile_cfg2(c, m, r);
     if (c1 == G2_128x128 && g.k12_splitk > 1) {
@@ -670,7 +692,8 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
   return DION_OK;
 }
 
-// K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile path, its bf16 transpose in SLOT_PT16.
+// K2: R = (M+G)^T P with P (m x r) in slot_p (fp32) and, on the large-tile paths, a bf16 copy of it: row-major in
+// SLOT_P16 for the direct-load path, transposed in SLOT_PT16 for the 128-wide-tile kernel.
 // from_b16: a K1 of this step has left bf16(M+G) in SLOT_B16 (large-tile path only).
 // colsq_chunks: if given, the product may leave per-column partial sums of squares of R in SLOT_SPART (it does on the
 // direct-load path); *colsq_chunks then is their number of chunks, else 0.
@@ -687,14 +710,17 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunk
     // M + G was rounded to bf16 once, by K1, and is read back from there (2 bytes per element instead of 6)
     a.B = opnd(SLOT_PT16, 0, m);
     if (direct12(c)) {
-      a.A = opnd(SLOT_B16T, 0, m);
+      // both operands with k (the row index of M + G and of P) as the slow index: bf16(M + G) as K1 reads it, and the
+      // row-major bf16 copy of P
+      a.A = opnd(SLOT_B16, 0, n);
+      a.B = opnd(SLOT_P16, 0, r);
       a.group_n = kDirect12GroupN;
       if (g.count == 1) { a.cus = c.st->cus; a.tail_slot = SLOT_KPART; }   // a short last round is split over k
       if (colsq_chunks) {
-        *colsq_chunks = gemm2_nt_colsq_chunks(G2_256x256, a);
+        *colsq_chunks = gemm2_nt_colsq_chunks(G2_256x256, a, KS_A | KS_B);
         if (*colsq_chunks > 0) a.E.colsq_slot = SLOT_SPART;
       }
-      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s));
+      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_A | KS_B));
       return DION_OK;
     }
     if (from_b16) a.A = opnd(SLOT_B16, 0, n);
@@ -829,7 +855,14 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P, rank_tol));
   // bf16 copies of P for K2 and K5.  When the last Cholesky-QR pass found its input orthonormal enough, that input is
   // P, and the pass has left the very same copies (the high parts of its split) in the same two slots.
-  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, SLOT_PT16, m, r, s, SLOT_FAST));
+  // (The product with (M + G)^T on the direct-load path reads the row-major copy; the 128-wide-tile kernel needs the
+  // transposed one, which the split leaves only when the Gram matrix took that kernel too.)
+  if (c.big) {
+    const bool d12 = direct12(c);
+    const bool split_left_pt16 = !choose_gram(g, batch, g.m, g.gram_m).big;
+    HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_P, SLOT_P16, d12 ? -1 : SLOT_PT16, m, r, s,
+                               (d12 || split_left_pt16) ? SLOT_FAST : -1));
+  }
   STAGECHK(mark(c, DION_STAGE_ORTH, 1));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   int colsq_chunks = 0;
@@ -860,10 +893,10 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (c.ev) st->group_timed[gi] = 1;
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
-  STAGECHK(stage_b16(c, refresh));
+  STAGECHK(stage_b16(c));
   if (refresh) {
     STAGECHK(stage_k1(c, true));                                                  // Z = B V
-    if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, -1, SLOT_PT16, m, r, s));
+    if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, direct12(c) ? SLOT_P16 : -1, direct12(c) ? -1 : SLOT_PT16, m, r, s));
     STAGECHK(stage_k2(c, SLOT_Z));                                                // R = B^T Z
     const int fin = (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) ? SLOT_P1 : SLOT_R;
     STAGECHK(stage_orth(c, g.n, g.gram_n, SLOT_R, SLOT_P1, fin));
@@ -902,7 +935,7 @@ int transposed_rows(dion_state* st, int gi, int row0, int batch, float mu, float
   // stage names as in the standard step: "K2" is the product with B^T, "K1" the one with B
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   STAGECHK(stage_b16(c));
-  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Q, -1, SLOT_PT16, m, r, s));
+  if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Q, direct12(c) ? SLOT_P16 : -1, direct12(c) ? -1 : SLOT_PT16, m, r, s));
   STAGECHK(stage_k2(c, SLOT_Q, false));                                           // R = B^T Vt   (n x r)
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));

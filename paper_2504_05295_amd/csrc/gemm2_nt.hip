@@ -8,7 +8,15 @@
 namespace dion {
 using NtBig = TileCfg2<256, 256, 64, 2, 4, 2, 1>;
 using NtMid = TileCfg2<128, 128, 64, 2, 2, 1, 2>;
-hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
+hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s, int ks) {
+  if (ks != 0) {
+    // operands stored with k as the slow index (direct-load core, 256 x 256 tiles only)
+    using Direct = TileCfg3<256, 256, 2, 4>;
+    if (cfg != G2_256x256) return hipErrorInvalidValue;
+    if (ks == (KS_A | KS_B)) return launch_gemm3<Direct, false, EPI_STORE, false, true, true>(g, batch, s);
+    if (ks == KS_B) return launch_gemm3<Direct, false, EPI_STORE, false, false, true>(g, batch, s);
+    return hipErrorInvalidValue;
+  }
   if (cfg == G2_256x128) {
     // narrower column tiles for the triangular multiply of a single matrix: twice as many workgroups as compute
     // units, costliest first (GemmArgs::heavy_first), instead of one round in which the last column tile sets the time
@@ -26,12 +34,16 @@ hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s) {
 hipError_t gemm2_nt_prepare() {
   hipError_t e = gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false>();
   if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 128, 4, 2>, false, EPI_STORE, false>();
+  if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false, true, true>();
+  if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false, false, true>();
   return e;
 }
-int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g) {
+int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g, int ks) {
   using Direct = TileCfg3<256, 256, 2, 4>;
-  if (cfg != G2_256x256 || !gemm3_fits<Direct>(g) || g.splitk > 1) return 0;
-  return g.M / Direct::WTM;
+  if (cfg != G2_256x256 || g.splitk > 1) return 0;
+  const bool fits = ks == (KS_A | KS_B) ? gemm3_fits<Direct, true, true>(g) : ks == KS_B ? gemm3_fits<Direct, false, true>(g)
+                    : ks == 0 ? gemm3_fits<Direct>(g) : false;
+  return fits ? g.M / Direct::WTM : 0;
 }
 int gemm2_nt_splitk(int cfg, const GemmArgs& g) {
   return cfg == G2_256x256 ? gemm2_effective_splitk<NtBig>(g) : gemm2_effective_splitk<NtMid>(g);

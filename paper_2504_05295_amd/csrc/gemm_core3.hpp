@@ -112,9 +112,41 @@ __device__ __forceinline__ void gemm3_tile_coords(const GemmArgs& g, int tile, i
   }
 }
 
-template <class Cfg, bool GBF16, int EPI, bool DUAL>
+// Transposing LDS read of gfx950 (ds_read_b64_tr_b16).  Within every group of 16 lanes, with chunk[j] the four 16-bit
+// elements at lane j's address and M[r][c] = chunk[4 r + c / 4][c % 4] (4 x 16), lane i of the group receives
+// (M[0][i], M[1][i], M[2][i], M[3][i]).  With lane 4 r + q pointing at elements 4 q .. 4 q + 3 of row k0 + r of a
+// [k][row] tile, lane i ends up with k0 .. k0 + 3 of matrix row i: four consecutive k of one row, which is what the
+// matrix instruction wants, from an operand that is stored with k as the slow index.
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+typedef short v8s_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4s_t lds_v4s_t;
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+__device__ __forceinline__ bf16x8_t lds_read_tr_pair(const lds_byte_t* p0, const lds_byte_t* p1) {
+  const v4s_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_t*)p0);
+  const v4s_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_t*)p1);
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// Scheduling hint "one MFMA, then its share of READS LDS reads", MMAS times (the counts must be compile-time constants)
+template <int Q, int MMAS, int READS>
+__device__ __forceinline__ void gemm3_sched_pairs() {
+  if constexpr (Q < MMAS) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, READS / MMAS + (Q < READS % MMAS ? 1 : 0), 0);
+    gemm3_sched_pairs<Q + 1, MMAS, READS>();
+  }
+}
+
+// AKS / BKS: that operand is stored with k as the slow index, element (row, k) at p[k * ld + row] (a row-major matrix
+// used as the left operand of X^T Y, say).  Its slab is then BK rows of the tile's BM (BN) elements; chunk c of k-row kr
+// sits at chunk position c ^ (4 (kr & 3)) of its row, and fragments come out through the transposing LDS read: the 32
+// lanes of a half-wave then touch 16 different 16-byte bank groups, two lanes each on their own halves.
+template <class Cfg, bool GBF16, int EPI, bool DUAL, bool AKS = false, bool BKS = false>
 __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArgs g) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, NW = Cfg::NW, CPR = Cfg::CPR, ROWB = Cfg::ROWB;
+  static_assert(!(AKS || BKS) || (BK == 64 && !DUAL), "k-slow operands: 64-deep slabs, single product");
+  static_assert(!AKS || BM % 128 == 0, "k-slow A: tile rows");
+  static_assert(!BKS || BN % 128 == 0, "k-slow B: tile columns");
   constexpr int MI = Cfg::MI, NI = Cfg::NI, KSTEPS = BK / 16;
   constexpr int A_BYTES = Cfg::A_BYTES, B_BYTES = Cfg::B_BYTES;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES * (DUAL ? 2 : 1);
@@ -163,14 +195,24 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
 #pragma unroll
   for (int q = 0; q < Cfg::A_LOADS; ++q) {
     const int pos = (q * NW + wave) * 64 + lane;
-    const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
-    aoff[q] = (unsigned)(((long long)(row0 + row) * g.A.ld + kc * 8) * 2);
+    if constexpr (AKS) {
+      const int kr = pos / (BM / 8), c = (pos % (BM / 8)) ^ (4 * (kr & 3));
+      aoff[q] = (unsigned)(((long long)kr * g.A.ld + row0 + c * 8) * 2);
+    } else {
+      const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
+      aoff[q] = (unsigned)(((long long)(row0 + row) * g.A.ld + kc * 8) * 2);
+    }
   }
 #pragma unroll
   for (int q = 0; q < Cfg::B_LOADS; ++q) {
     const int pos = (q * NW + wave) * 64 + lane;
-    const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
-    boff[q] = (unsigned)(((long long)(col0 + row) * g.B.ld + kc * 8) * 2);
+    if constexpr (BKS) {
+      const int kr = pos / (BN / 8), c = (pos % (BN / 8)) ^ (4 * (kr & 3));
+      boff[q] = (unsigned)(((long long)kr * g.B.ld + col0 + c * 8) * 2);
+    } else {
+      const int row = pos / CPR, kc = (pos % CPR) ^ lds_swizzle<CPR>(row);
+      boff[q] = (unsigned)(((long long)(col0 + row) * g.B.ld + kc * 8) * 2);
+    }
   }
   const unsigned lds0 = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem);
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -198,8 +240,10 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   // running addresses of the next slab to be loaded, advanced by one slab per load
   int ld_seg = slabs_per_seg > 0 ? s_begin / slabs_per_seg : 0;
   int ld_k0 = (s_begin - ld_seg * slabs_per_seg) * BK;
-  const unsigned char* a_run = (ld_seg <= 0 ? A0 : ld_seg == 1 ? A1 : A2) + (size_t)ld_k0 * 2;
-  const unsigned char* b_run = (ld_seg <= 0 ? B0 : ld_seg == 1 ? B1 : B2) + (size_t)ld_k0 * 2;
+  // bytes from one k to the next in either operand
+  const size_t a_kstep = AKS ? (size_t)g.A.ld * 2 : 2, b_kstep = BKS ? (size_t)g.B.ld * 2 : 2;
+  const unsigned char* a_run = (ld_seg <= 0 ? A0 : ld_seg == 1 ? A1 : A2) + (size_t)ld_k0 * a_kstep;
+  const unsigned char* b_run = (ld_seg <= 0 ? B0 : ld_seg == 1 ? B1 : B2) + (size_t)ld_k0 * b_kstep;
   const unsigned char* b2_run = DUAL ? (const unsigned char*)(tab[g.B2.slot0]) + (size_t)ld_k0 * 2 : nullptr;
 
   auto issue = [&](int stage, const unsigned char* Ap, const unsigned char* Bp, const unsigned char* B2k) __attribute__((always_inline)) {
@@ -233,15 +277,35 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   const int sw = lds_swizzle<CPR>(lr);
   const int a_row_off = (wm * Cfg::WTM + lr) * ROWB, b_row_off = A_BYTES + (wn * Cfg::WTN + lr) * ROWB;
   bf16x8_t af[2][MI], bf[2][NI], bf2[2][DUAL ? NI : 1];
+  // k-slow operands: lane 4 r + q of a group of 16 lanes reads elements 4 q .. 4 q + 3 of the group's 16 tile rows
+  // at k-row 8 lk + r (+ 16 kk, + 4 for the second half of the fragment)
+  const int tr_r = (lane >> 2) & 3, tr_q = lane & 3, tr_g = (lane >> 4) & 1;
+  const lds_byte_t* const smem_lds = (const lds_byte_t*)smem;
+  auto ks_off = [&](int tile_row0, int row_bytes) __attribute__((always_inline)) {   // tile_row0: multiple of 32
+    const int chunk = (((tile_row0 + 16 * tr_g) >> 3) + (tr_q >> 1)) ^ (4 * tr_r);
+    return (8 * lk + tr_r) * row_bytes + chunk * 16 + (tr_q & 1) * 8;
+  };
   auto fetch = [&](int stage, int set, int kk) __attribute__((always_inline)) {
     const unsigned char* sa = smem + stage * STAGE_BYTES + a_row_off;
     const unsigned char* sb = smem + stage * STAGE_BYTES + b_row_off;
     const int co = ((kk * 2 + lk) ^ sw) * 16;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) af[set][i] = *(const bf16x8_t*)(sa + i * 32 * ROWB + co);
+    for (int i = 0; i < MI; ++i) {
+      if constexpr (AKS) {
+        const lds_byte_t* p = smem_lds + stage * STAGE_BYTES + kk * 16 * (BM * 2) + ks_off(wm * Cfg::WTM + i * 32, BM * 2);
+        af[set][i] = lds_read_tr_pair(p, p + 4 * (BM * 2));
+      } else {
+        af[set][i] = *(const bf16x8_t*)(sa + i * 32 * ROWB + co);
+      }
+    }
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
-      bf[set][j] = *(const bf16x8_t*)(sb + j * 32 * ROWB + co);
+      if constexpr (BKS) {
+        const lds_byte_t* p = smem_lds + stage * STAGE_BYTES + A_BYTES + kk * 16 * (BN * 2) + ks_off(wn * Cfg::WTN + j * 32, BN * 2);
+        bf[set][j] = lds_read_tr_pair(p, p + 4 * (BN * 2));
+      } else {
+        bf[set][j] = *(const bf16x8_t*)(sb + j * 32 * ROWB + co);
+      }
       if constexpr (DUAL) bf2[set][j] = *(const bf16x8_t*)(sb + B_BYTES + j * 32 * ROWB + co);
     }
   };
@@ -257,22 +321,26 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   // schedule of one k-step: MFMA, LDS read, MFMA, LDS read, ... so that the fragments of the next k-step trickle
   // in behind the MFMAs of this one
   auto interleave = [&]() __attribute__((always_inline)) {
-    constexpr int READS = MI + NI * (DUAL ? 2 : 1), MMAS = MI * NI * (DUAL ? 2 : 1);
-    static_assert(MMAS >= READS, "fewer MFMAs than fragment reads");
+    constexpr int READS = MI * (AKS ? 2 : 1) + NI * (BKS ? 2 : 1) * (DUAL ? 2 : 1), MMAS = MI * NI * (DUAL ? 2 : 1);
+    if constexpr (MMAS >= READS) {
 #pragma unroll
-    for (int q = 0; q < READS; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      for (int q = 0; q < READS; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      if constexpr (MMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MMAS - READS, 0);
+    } else {
+      // more reads than MFMAs (k-slow operands take two reads per fragment): the surplus goes to the first MFMAs
+      gemm3_sched_pairs<0, MMAS, READS>();
     }
-    if constexpr (MMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MMAS - READS, 0);
   };
 
   // loads of the next slab into the given stage; then the running addresses move on
 #define DION_GEMM3_ISSUE(stage)                                                                        \
   do {                                                                                                 \
     issue((stage), a_run, b_run, b2_run);                                                              \
-    a_run += BK * 2;                                                                                   \
-    b_run += BK * 2;                                                                                   \
+    a_run += BK * a_kstep;                                                                             \
+    b_run += BK * b_kstep;                                                                             \
     if constexpr (DUAL) b2_run += BK * 2;                                                              \
     ld_k0 += BK;                                                                                       \
     if (ld_k0 == kseg_eff && ld_seg + 1 < nseg) {                                                      \
@@ -466,14 +534,19 @@ __global__ void __launch_bounds__(256) gemm3_tail_reduce_kernel(const GemmArgs g
 
 // True when launch_gemm3 can take these arguments: tile-aligned shapes and operands small enough for the
 // 32-bit byte offsets of the direct loads.
-template <class Cfg>
+template <class Cfg, bool AKS = false, bool BKS = false>
 inline bool gemm3_fits(const GemmArgs& g) {
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   if (g.M % Cfg::BM || g.N % Cfg::BN || kseg % Cfg::BK || kseg <= 0) return false;
   if (g.tri_k && Cfg::BN % Cfg::BK) return false;
   if (g.A.ld % 8 || g.B.ld % 8) return false;                         // 16-byte aligned chunks
   const long long lim = 1ll << 32;
-  return (long long)g.M * g.A.ld * 2 < lim && (long long)g.N * g.B.ld * 2 < lim;
+  // (a lane's offset stays inside one matrix for a k-fast operand, inside one slab of BK k-rows for a k-slow one)
+  const long long a_span = AKS ? ((long long)Cfg::BK * g.A.ld + g.M) * 2 : (long long)g.M * g.A.ld * 2;
+  const long long b_span = BKS ? ((long long)Cfg::BK * g.B.ld + g.N) * 2 : (long long)g.N * g.B.ld * 2;
+  if (AKS && g.A.ld < g.M) return false;
+  if (BKS && g.B.ld < g.N) return false;
+  return a_span < lim && b_span < lim;
 }
 
 template <class Cfg, bool DUAL>
@@ -488,7 +561,7 @@ constexpr int gemm3_lds_bytes() {
 // More than 64 KB of dynamic LDS has to be allowed once per kernel and device.  The library does it for all its
 // instantiations when a state is created (that call must not end up inside a stream capture); the launcher
 // repeats it for a device it has not seen.
-template <class Cfg, bool GBF16, int EPI, bool DUAL>
+template <class Cfg, bool GBF16, int EPI, bool DUAL, bool AKS = false, bool BKS = false>
 inline hipError_t gemm3_prepare() {
   static bool allowed[16] = {};
   int dev = 0;
@@ -496,7 +569,7 @@ inline hipError_t gemm3_prepare() {
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
   if (!allowed[dev]) {
-    e = hipFuncSetAttribute((const void*)gemm3_kernel<Cfg, GBF16, EPI, DUAL>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    e = hipFuncSetAttribute((const void*)gemm3_kernel<Cfg, GBF16, EPI, DUAL, AKS, BKS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             gemm3_lds_bytes<Cfg, DUAL>());
     if (e != hipSuccess) return e;
     allowed[dev] = true;
@@ -504,9 +577,9 @@ inline hipError_t gemm3_prepare() {
   return hipSuccess;
 }
 
-template <class Cfg, bool GBF16, int EPI, bool DUAL>
+template <class Cfg, bool GBF16, int EPI, bool DUAL, bool AKS = false, bool BKS = false>
 inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
-  if (!gemm3_fits<Cfg>(g)) return hipErrorInvalidValue;
+  if (!gemm3_fits<Cfg, AKS, BKS>(g)) return hipErrorInvalidValue;
   if (DUAL && g.B2.ld != g.B.ld) return hipErrorInvalidValue;          // B2 is fetched with B's offsets
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   g.tiles_m = g.M / Cfg::BM;
@@ -537,9 +610,9 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   g.xcd_remap = (g.xcd_remap && ((g.tail_split > 1 ? (long long)g.tail_first : grid) % 8 == 0)) ? 1 : 0;
   g.heavy_first = (g.heavy_first && g.xcd_remap && !g.tri_grid && g.group_n == 0 && g.splitk == 1 && batch == 1 && g.tiles_m % 8 == 0) ? 1 : 0;
   constexpr int LDS_BYTES = gemm3_lds_bytes<Cfg, DUAL>();
-  hipError_t e = gemm3_prepare<Cfg, GBF16, EPI, DUAL>();
+  hipError_t e = gemm3_prepare<Cfg, GBF16, EPI, DUAL, AKS, BKS>();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL>), dim3((unsigned)grid), dim3(Cfg::NT), LDS_BYTES, stream, g);
+  hipLaunchKernelGGL((gemm3_kernel<Cfg, GBF16, EPI, DUAL, AKS, BKS>), dim3((unsigned)grid), dim3(Cfg::NT), LDS_BYTES, stream, g);
   e = hipGetLastError();
   if (e != hipSuccess || g.tail_split < 2) return e;
   if constexpr (EPI == EPI_STORE && !DUAL) {

@@ -87,10 +87,13 @@ hipError_t run_ceiling_probes(void* scratch, long long elems, double* mfma_tflop
 // dynamic-LDS permissions of the direct-load kernels on the current device (once per device; not inside a capture)
 hipError_t gemm2_nt_prepare();
 hipError_t gemm2_k5_prepare();
-hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s);   // bf16 A (KC) x bf16 B (KC), up to 3 operand pairs
+// bf16 A x bf16 B, up to 3 operand pairs; element (row, k) of an operand at p[row * ld + k], or, for the operands named
+// in `ks` (KS_A | KS_B; 256 x 256 tiles of the direct-load core only), at p[k * ld + row]
+enum { KS_A = 1, KS_B = 2 };
+hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s, int ks = 0);
 // rows of per-column partial sums of squares that gemm2_nt writes for these arguments when GemmArgs::E.colsq_slot is set
 // (0: this product cannot, leave the slot at -1)
-int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g);
+int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g, int ks = 0);
 int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
 hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
