@@ -377,9 +377,19 @@ GramChoice choose_gram(const Group& g, int batch, long long rows, const GramPlan
 // Cholesky factorisation and the triangular inverse stay in fp32.
 // rank_tol > 0: the factorisation tolerates linearly dependent columns (see CholPanelPtrs::thr): they come out as zero
 // columns of `out` and are marked in SLOT_NULL, instead of a breakdown.
+// Where a split-bf16 pass finds the bf16 halves of its input (row-major, x = hi + lo) and whether its producer has
+// already left them there; where its triangular multiply may leave the halves of its output for the next pass
+// (-1: nowhere).  *wrote_out tells whether it did (only the direct-load core can).
+struct SplitIO {
+  int in_hi = SLOT_P16, in_lo = SLOT_ZL16;
+  bool ready = false;
+  int out_hi = -1, out_lo = -1;
+  bool* wrote_out = nullptr;
+};
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long rows, const GramPlan& gp, int slot_in,
                 int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, int pass, hipStream_t s,
-                float rank_tol = 0.f) {
+                float rank_tol = 0.f, SplitIO io = SplitIO()) {
+  if (io.wrote_out) *io.wrote_out = false;
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -403,12 +413,14 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     // On 256 x 256 tiles the Gram matrix reads the two row-major halves as operands stored with k (the row index) as
     // the slow index; the 128-wide-tile kernel needs transposed copies.  (An adaptive pass on the latter needs the low
     // part in row-major order only if it goes on to its product: made after the decision.)
-    HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, SLOT_P16, (gram_big || !adaptive) ? SLOT_ZL16 : -1,
-                             gram_big ? -1 : SLOT_PT16, gram_big ? -1 : SLOT_ZLT16, s));
+    if (!gram_big && (io.in_hi != SLOT_P16 || io.in_lo != SLOT_ZL16 || io.ready)) return DION_EINVAL;   // (that kernel's copies go to fixed slots)
+    if (!io.ready)
+      HIPCHK(launch_split_bf16(tab, NSLOTS, batch, slot_in, r, rows, r, io.in_hi, (gram_big || !adaptive) ? io.in_lo : -1,
+                               gram_big ? -1 : SLOT_PT16, gram_big ? -1 : SLOT_ZLT16, s));
     GemmArgs a = base;
     a.M = r; a.N = r; a.K = 3 * (int)rows;
     a.nseg = 3; a.kseg = (int)rows;
-    const int hi = gram_big ? SLOT_P16 : SLOT_PT16, lo = gram_big ? SLOT_ZL16 : SLOT_ZLT16;
+    const int hi = gram_big ? io.in_hi : SLOT_PT16, lo = gram_big ? io.in_lo : SLOT_ZLT16;
     a.segA[0] = hi; a.segB[0] = hi;
     a.segA[1] = hi; a.segB[1] = lo;
     a.segA[2] = lo; a.segB[2] = hi;
@@ -569,10 +581,10 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     }
     a.M = (int)rows; a.N = r; a.K = 3 * r;
     a.nseg = 3; a.kseg = r;
-    a.segA[0] = SLOT_P16; a.segB[0] = SLOT_WH16;
-    a.segA[1] = SLOT_P16; a.segB[1] = SLOT_WL16;
-    a.segA[2] = SLOT_ZL16; a.segB[2] = SLOT_WH16;
-    a.A = opnd(SLOT_P16, 0, r);
+    a.segA[0] = io.in_hi; a.segB[0] = SLOT_WH16;
+    a.segA[1] = io.in_hi; a.segB[1] = SLOT_WL16;
+    a.segA[2] = io.in_lo; a.segB[2] = SLOT_WH16;
+    a.A = opnd(io.in_hi, 0, r);
     a.B = opnd(SLOT_WH16, 0, r);
     a.tri_k = 1;
     a.E.slot = slot_out; a.E.ld = r;
@@ -586,6 +598,14 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
       a.heavy_first = 1;
     } else if (cfg == G2_256x256 && batch == 1 && (rows / 256) % 8 == 0) {
       a.heavy_first = 1;   // several rounds of 256-wide tiles: still the costliest columns first, so that the cheap ones fill the tail
+    }
+    if (io.out_hi >= 0 && gemm2_nt_is_direct(cfg, a)) {
+      // the halves of the result, for the pass that follows (other buffers than this pass' input: other workgroups
+      // still read that)
+      if (io.out_hi == io.in_hi || io.out_lo == io.in_lo) return DION_EINVAL;
+      a.E.split_hi1 = io.out_hi + 1;
+      a.E.split_lo1 = io.out_lo + 1;
+      if (io.wrote_out) *io.wrote_out = true;
     }
     HIPCHK(gemm2_nt(cfg, a, batch, s));
   } else {
@@ -654,7 +674,10 @@ int stage_b16(const RowCtx& c) {
 
 // K1: Z = (M+G) Q with Q (n x r, fp32) taken from slot_q.  keep_b16: the large-tile kernel also leaves bf16(M+G) in
 // SLOT_B16 for a K2 that follows.
-int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
+// split_out: on the direct-load path, also leave the result's bf16 halves in (SLOT_PT16, SLOT_ZLT16) for an
+// orthonormalisation that follows (*split_done tells whether that happened).
+int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out = false, bool* split_done = nullptr) {
+  if (split_done) *split_done = false;
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   GemmArgs a = c.base;
@@ -670,6 +693,11 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q) {
       a.A = opnd(SLOT_B16, 0, n);
       a.group_n = kDirect12GroupN;
       if (g.count == 1) { a.cus = c.st->cus; a.tail_slot = SLOT_KPART; }   // a short last round is split over k
+      if (split_out) {
+        a.E.split_hi1 = SLOT_PT16 + 1;
+        a.E.split_lo1 = SLOT_ZLT16 + 1;
+        if (split_done) *split_done = true;
+      }
       HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_B));
       return DION_OK;
     }
@@ -745,8 +773,15 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunk
 // final, so final must not be a).  On the split-bf16 path the products read bf16 copies of their input, never the
 // fp32 original, so a pass may write where it reads: the first pass already writes to slot_final and the last,
 // adaptive one runs there in place, which leaves it nothing to do when it finds its input orthonormal enough.
+// True when the orthonormalisation of these rows x r matrices runs as plain CholeskyQR2 on the split-bf16 path with the
+// Gram matrix on 256 x 256 tiles: then the halves of a pass' input may come from the epilogue of whatever produced it.
+bool orth_fuses(const RowCtx& c, long long rows, const GramPlan& gp, float rank_tol) {
+  return c.big && rank_tol == 0.f && c.st->orth_mode == DION_ORTH_CHOLQR2 && choose_gram(*c.g, c.batch, rows, gp).big;
+}
 // rank_tol > 0: CholeskyQR2 that tolerates linearly dependent columns (zero columns of the result, marked in SLOT_NULL).
-int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol = 0.f) {
+// in_split_ready: the producer of slot_a has left its bf16 halves in (SLOT_PT16, SLOT_ZLT16), row-major (see orth_fuses).
+int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol = 0.f,
+               bool in_split_ready = false) {
   dion_state* st = c.st;
   const Group& g = *c.g;
   const bool in_place = c.big;
@@ -777,6 +812,22 @@ int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, 
     return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 3, c.s);
   }
   const int mid = in_place ? slot_final : slot_b;
+  if (orth_fuses(c, rows, gp, rank_tol)) {
+    // Both passes read row-major halves (the Gram matrix takes them with k as the slow index), so nothing has to be
+    // transposed and the two transposed-copy buffers are free: the first pass takes its input's halves from there
+    // (left by the product that made the input, or by the split kernel) and its triangular multiply leaves the halves
+    // of its result where the second pass, and in the end the consumers of P, look for them.
+    bool wrote = false;
+    SplitIO io1;
+    io1.in_hi = SLOT_PT16; io1.in_lo = SLOT_ZLT16; io1.ready = in_split_ready;
+    io1.out_hi = SLOT_P16; io1.out_lo = SLOT_ZL16; io1.wrote_out = &wrote;
+    rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, mid, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s, 0.f, io1);
+    if (rc != DION_OK) return rc;
+    SplitIO io2;
+    io2.ready = wrote;
+    return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 2, c.s, 0.f, io2);
+  }
+  if (in_split_ready) return DION_EINVAL;
   rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, mid, 0.f, 3.0e38f, c.big, false, 0.f, 1, c.s);
   if (rc != DION_OK) return rc;
   return cholqr_pass(st, g, c.row0, c.batch, rows, gp, mid, slot_final, 0.1f, 10.f, c.big, true, 0.f, 2, c.s);
@@ -848,11 +899,12 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
   STAGECHK(stage_b16(c));
-  STAGECHK(stage_k1(c, true));
+  const float rank_tol = mode == STEP_KEEP_STATUS ? RANK_TOL : 0.f;
+  bool z_split = false;
+  STAGECHK(stage_k1(c, true, SLOT_Q, orth_fuses(c, g.m, g.gram_m, rank_tol), &z_split));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
-  const float rank_tol = mode == STEP_KEEP_STATUS ? RANK_TOL : 0.f;
-  STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P, rank_tol));
+  STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P, rank_tol, z_split));
   // bf16 copies of P for K2 and K5.  When the last Cholesky-QR pass found its input orthonormal enough, that input is
   // P, and the pass has left the very same copies (the high parts of its split) in the same two slots.
   // (The product with (M + G)^T on the direct-load path reads the row-major copy; the 128-wide-tile kernel needs the

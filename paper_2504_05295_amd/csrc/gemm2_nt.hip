@@ -38,6 +38,10 @@ hipError_t gemm2_nt_prepare() {
   if (e == hipSuccess) e = gemm3_prepare<TileCfg3<256, 256, 2, 4>, false, EPI_STORE, false, false, true>();
   return e;
 }
+bool gemm2_nt_is_direct(int cfg, const GemmArgs& g) {
+  if (cfg == G2_256x128 && gemm3_fits<TileCfg3<256, 128, 4, 2>>(g)) return true;
+  return (cfg == G2_256x128 || cfg == G2_256x256) && gemm3_fits<TileCfg3<256, 256, 2, 4>>(g);
+}
 int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g, int ks) {
   using Direct = TileCfg3<256, 256, 2, 4>;
   if (cfg != G2_256x256 || g.splitk > 1) return 0;

@@ -47,6 +47,9 @@ struct EpilogueDesc {
   int x_overwrite;      // EPI_UPDATE: X = -c_x*acc2, the old contents of X are not read
   int colsq_slot;       // EPI_STORE of the direct-load core, whole products only: >= 0: per-column partial sums of squares
                         // of the result go there, one row of N floats per block of Cfg::WTM result rows
+  int split_hi1, split_lo1;   // EPI_STORE of the direct-load core, whole products only: slot + 1 (0: none) of two bf16
+                        // matrices of the result's shape and leading dimension that receive the result split as
+                        // x = hi + lo, hi = bf16(x), lo = bf16(x - hi): the operands of a split-bf16 product that follows
   int stream_hint;      // host side: take the EPI_UPDATE_STREAM kernel (M, X and G loaded and stored with the
                         // non-temporal hint; for working sets far beyond the last-level cache)
 };

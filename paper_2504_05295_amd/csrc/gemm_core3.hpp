@@ -127,6 +127,8 @@ __device__ __forceinline__ bf16x8_t lds_read_tr_pair(const lds_byte_t* p0, const
   return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+__device__ __forceinline__ void gemm3_store_split(uint16_t* hi, uint16_t* lo, long long idx, const f32x4_t v);
+
 // Scheduling hint "one MFMA, then its share of READS LDS reads", MMAS times (the counts must be compile-time constants)
 template <int Q, int MMAS, int READS>
 __device__ __forceinline__ void gemm3_sched_pairs() {
@@ -395,6 +397,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
       c_row0 = 0;
       c_col0 = 0;
     }
+    uint16_t* const split_hi = (g.E.split_hi1 > 0 && tail_q < 0) ? (uint16_t*)tab[g.E.split_hi1 - 1] + g.E.off : nullptr;
+    uint16_t* const split_lo = (g.E.split_hi1 > 0 && tail_q < 0) ? (uint16_t*)tab[g.E.split_lo1 - 1] + g.E.off : nullptr;
     float colsq[NI];   // sums of squares of this wave's WTM rows, per column (lane & 31) of each column block
 #pragma unroll
     for (int j = 0; j < NI; ++j) colsq[j] = 0.f;
@@ -409,7 +413,9 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
         for (int p = 0; p < 4; ++p) {
           const int row = c_row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = c_col0 + wn * Cfg::WTN + j * 32 + pcol;
-          gstore<f32x4_t>(C + (long long)row * c_ld + col, *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol));
+          const f32x4_t v4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          gstore<f32x4_t>(C + (long long)row * c_ld + col, v4);
+          if (split_hi) gemm3_store_split(split_hi, split_lo, (long long)row * c_ld + col, v4);
         }
       }
     // Column norms of the result (ColNorm of the update rule) without another pass over it: one partial sum of
@@ -495,6 +501,14 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   }
 }
 
+// x = hi + lo with hi = bf16(x), lo = bf16(x - hi), four consecutive elements
+__device__ __forceinline__ void gemm3_store_split(uint16_t* hi, uint16_t* lo, long long idx, const f32x4_t v) {
+  const uint32_t h01 = pack_bf16x2(v[0], v[1]), h23 = pack_bf16x2(v[2], v[3]);
+  const uint32_t l01 = pack_bf16x2(v[0] - bf16_lo(h01), v[1] - bf16_hi(h01)), l23 = pack_bf16x2(v[2] - bf16_lo(h23), v[3] - bf16_hi(h23));
+  gstore<u32x2_t>(hi + idx, u32x2_t{h01, h23});
+  gstore<u32x2_t>(lo + idx, u32x2_t{l01, l23});
+}
+
 // Adds up the partial tiles of a launch's last round (GemmArgs::tail_*) into the result, in a fixed order, and forms
 // the per-column sums of squares that the main kernel's epilogue forms for whole tiles.  One workgroup of 256 threads
 // per tail tile and block of WTM rows: a thread owns four consecutive columns of every RPP-th row.
@@ -512,12 +526,16 @@ __global__ void __launch_bounds__(256) gemm3_tail_reduce_kernel(const GemmArgs g
   gemm3_tile_coords<BM, BN>(g, g.tail_first + t, tm, tn);
   const float* part = (const float*)tab[g.tail_slot] + (long long)t * g.tail_split * (BM * BN) + (long long)chunk * WTM * BN + cx * 4;
   float* C = (float*)tab[g.E.slot] + g.E.off + (long long)(tm * BM + chunk * WTM) * g.E.ld + tn * BN + cx * 4;
+  const long long c_first = (long long)(tm * BM + chunk * WTM) * g.E.ld + tn * BN + cx * 4;
+  uint16_t* const split_hi = g.E.split_hi1 > 0 ? (uint16_t*)tab[g.E.split_hi1 - 1] + g.E.off : nullptr;
+  uint16_t* const split_lo = g.E.split_hi1 > 0 ? (uint16_t*)tab[g.E.split_lo1 - 1] + g.E.off : nullptr;
   f32x4_t sq = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int row = ry; row < WTM; row += RPP) {
     f32x4_t acc = gload<f32x4_t>(part + (long long)row * BN);
     for (int sp = 1; sp < g.tail_split; ++sp) acc += gload<f32x4_t>(part + (long long)sp * (BM * BN) + (long long)row * BN);
     gstore<f32x4_t>(C + (long long)row * g.E.ld, acc);
+    if (split_hi) gemm3_store_split(split_hi, split_lo, c_first + (long long)row * g.E.ld, acc);
     sq += acc * acc;
   }
   if (g.E.colsq_slot >= 0) {

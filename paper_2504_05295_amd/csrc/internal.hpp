@@ -94,6 +94,9 @@ hipError_t gemm2_nt(int cfg, GemmArgs g, int batch, hipStream_t s, int ks = 0);
 // rows of per-column partial sums of squares that gemm2_nt writes for these arguments when GemmArgs::E.colsq_slot is set
 // (0: this product cannot, leave the slot at -1)
 int gemm2_nt_colsq_chunks(int cfg, const GemmArgs& g, int ks = 0);
+// true when gemm2_nt (ks = 0) will run these arguments on the direct-load core, whose plain-store epilogue can also leave
+// the result split into bf16 halves (EpilogueDesc::split_hi1 / split_lo1)
+bool gemm2_nt_is_direct(int cfg, const GemmArgs& g);
 int gemm2_nt_splitk(int cfg, const GemmArgs& g);                       // number of split-K partials gemm2_nt will write
 hipError_t gemm_f32_nt(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KC
 hipError_t gemm_f32_nn(int variant, GemmArgs g, int batch, hipStream_t s);                      // A KC, B KS
