@@ -230,10 +230,10 @@ int dion_retry_breakdowns(dion_state_t* st, int count, void* const* X, const voi
 int dion_set_wait_limit(dion_state_t* st, unsigned polls);
 
 /* How the r x r factorisation of Cholesky-QR (Appendix A) would be scheduled for `batch` matrices of rank r on a
- * GPU with `compute_units` compute units: *pr_out x *pc_out workgroups per matrix in one launch whose
- * pr * pc * batch workgroups all have to be resident at once (never more than compute_units), or 0 x 0 for one
- * launch per 64-column panel with no waits between workgroups.  Host only: touches no GPU. */
-int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* pr_out, int* pc_out);
+ * GPU with `compute_units` compute units: *workgroups_out workgroups per matrix in one launch, all of which
+ * (workgroups x batch, never more than compute_units) have to be resident at once, or 0 for one launch per
+ * 64-column panel with no waits between workgroups.  Host only: touches no GPU. */
+int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* workgroups_out);
 
 /* Stage timing.  With enable != 0 every later step brackets its stages with HIP events on
  * the step's stream.  dion_stage_times waits for the last step and writes, for stage s <

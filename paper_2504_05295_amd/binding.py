@@ -73,7 +73,7 @@ def lib() -> C.CDLL:
         L.dion_set_stage_timing.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_orth_mode.argtypes = [C.c_void_p, C.c_int]
         L.dion_set_wait_limit.argtypes = [C.c_void_p, C.c_uint]
-        L.dion_cholesky_grid.argtypes = [C.c_int, C.c_int, C.c_int64, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.dion_cholesky_grid.argtypes = [C.c_int, C.c_int, C.c_int64, C.POINTER(C.c_int)]
         L.dion_stage_times.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.dion_measure_ceilings.argtypes = [C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
         L.dion_debug_buffer.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p), i64p]
@@ -317,11 +317,11 @@ def dion_set_wait_limit(state: DionState, polls: int) -> None:
     _check(lib().dion_set_wait_limit(state.handle, int(polls)), "dion_set_wait_limit")
 
 
-def dion_cholesky_grid(compute_units: int, batch: int, r: int) -> Tuple[int, int]:
-    """(pr, pc): workgroups per matrix of the single-launch factorisation, or (0, 0) for a launch per panel.  Host only."""
-    pr, pc = C.c_int(0), C.c_int(0)
-    _check(lib().dion_cholesky_grid(int(compute_units), int(batch), int(r), C.byref(pr), C.byref(pc)), "dion_cholesky_grid")
-    return int(pr.value), int(pc.value)
+def dion_cholesky_grid(compute_units: int, batch: int, r: int) -> int:
+    """Workgroups per matrix of the single-launch factorisation, or 0 for a launch per panel.  Host only."""
+    w = C.c_int(0)
+    _check(lib().dion_cholesky_grid(int(compute_units), int(batch), int(r), C.byref(w)), "dion_cholesky_grid")
+    return int(w.value)
 
 
 def dion_set_stage_timing(state: DionState, enable: bool) -> None:

@@ -655,9 +655,256 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The same factorisation with the chain of dependent steps kept inside ONE workgroup (used when a matrix has sixteen
+// workgroups or more to itself).  In the kernel above the chain D(k) -> T(k+1, k) -> U(k+1, k+1, k) -> D(k+1) changes
+// workgroups once per panel, and that hand-over (W11 out to memory, a flag, a poll, W11 back in) is about a quarter of
+// the panel period.  Here workgroup 0 does nothing but the chain, for all k, with W11 never leaving its LDS on the
+// way, and the others ("helpers": pr x pc of them, numbered from 1) do everything else:
+//   chain     D(k);  L[k+1][k] = C'[k+1][k] W11^T;  C''[k+1][k+1] = C'[k+1][k+1] - L[k+1][k] L[k+1][k]^T  -> D(k+1)
+//   helpers   every other T(i, k) and all updates U(i, j, p) except the last one of a diagonal tile
+// where C'[k+1][k] and C'[k+1][k+1] are those two tiles with the updates of all panels before k applied.  Their owner
+// (the helper that owns (i, i), (i, i-1) and (i, i-2), so that L[i][i-2] goes from its T task into those two updates
+// without leaving LDS) applies the last of them, from panel k-1, before its other work of that panel, and hands the
+// tiles to the chain through memory (cflag[k+1]).  That hand-over is off the chain: it happens while the chain
+// workgroup factors D(k), whose idle wave polls the flag and fetches the two tiles into LDS.  W11 and L[k+1][k] go out
+// to the helpers likewise without the chain waiting for anything but its own stores.
+// Tiles that cross between workgroups, the two kinds of look-ahead tile included, are only ever written and read with
+// device-scope accesses.  Waits are bounded as above.
+template <bool RANK>
+__global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
+  const long long mat = (long long)blockIdx.y * p.stride;
+  if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole grid row of this matrix
+  const int nb = p.rp / CB, pr = p.pr, pc = p.pc;
+  StreamCtx x;
+  x.C = (gfloat*)(p.C + mat);
+  x.L = (gfloat*)(p.L + mat);
+  x.W = (gfloat*)(p.W + mat);
+  x.status = p.status + blockIdx.y;
+  x.wflag = (gu64*)(p.sync + (long long)blockIdx.y * p.sync_stride);
+  x.lflag = x.wflag + nb;
+  gu64* const cflag = x.lflag + nb;
+  x.abort_word = cflag + nb;
+  x.epoch = *p.step_counter * 8ull + (u64)p.pass;
+  x.spin_limit = p.spin_limit;
+  x.ld = p.rp;
+  x.piv_lo = p.piv_lo;
+  x.piv_hi = p.piv_hi;
+  const int ld = p.rp;
+  const float* thr = RANK ? p.thr + mat : nullptr;
+  int* nullmask = RANK ? p.nullmask + mat : nullptr;
+
+  __shared__ __attribute__((aligned(16))) float S0[CB * CBP];   // diagonal block / W11
+  __shared__ __attribute__((aligned(16))) float S1[CB * CBP];
+  __shared__ __attribute__((aligned(16))) float S2[CB * CBP];
+  __shared__ __attribute__((aligned(16))) float S3[CB * CBP];
+  __shared__ float rsv[CB];
+  __shared__ volatile int scaled;
+  __shared__ volatile int raw_done;
+  __shared__ int gave_up;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave & 1, wn = wave >> 1, lr = lane & 31, lk = lane >> 5;
+  const int frow = wm * 32 + 4 * lk, fcol = wn * 32 + lr;
+  const int foff = frow * ld + fcol;
+  if (t == 0) gave_up = 0;
+  __syncthreads();
+  const u64 ep32 = x.epoch << 32;
+  auto tile_at = [&](gfloat* base, int i, int j) __attribute__((always_inline)) { return base + (i * CB) * ld + j * CB; };
+
+  if (blockIdx.x == 0) {
+    // ---------------------------------------------------------------- the chain
+    // diagonal tile 0 (lower part, zeros above the diagonal)
+    for (int idx = t; idx < CB * CB / 4; idx += 256) {
+      const int rr = idx >> 4, cc = (idx & 15) * 4;
+      f32x4_t v = *(const gf32x4*)(x.C + rr * ld + cc);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (cc + e > rr) v[e] = 0.f;
+      *(f32x4_t*)(S0 + rr * CBP + cc) = v;
+    }
+    bool pending = false;   // S1 holds L[k][k-1], still to be written out and announced
+    for (int k = 0; k < nb; ++k) {
+      const int at = (k * CB) * ld + k * CB;
+      if (t == 0) { scaled = 0; raw_done = 0; }
+      __syncthreads();
+      if (wave == 0) {
+        eliminate_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, lane, RANK ? thr + k * CB : nullptr);
+      } else if (wave == 2) {
+        scale_wave<RANK>((const lds_float*)S0, (lds_counter*)&raw_done, (lds_float*)rsv, (lds_counter*)&scaled, lane, x.piv_lo, x.piv_hi,
+                         (float*)(x.L + at), ld, x.status, RANK ? thr + k * CB : nullptr, RANK ? nullmask + k * CB : nullptr);
+      } else if (wave == 1) {
+        invert_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane,
+                          RANK ? thr + k * CB : nullptr);
+      } else {
+        // the idle wave: L[k][k-1] out to the helpers, then the two tiles of the next step in
+        if (pending) {
+          gfloat* dst = tile_at(x.L, k, k - 1);
+#pragma unroll 8
+          for (int rr = 0; rr < CB; ++rr) shared_store(dst + rr * ld + lane, S1[rr * CBP + lane]);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          if (lane == 0) flag_store(x.lflag + k, ep32 | (u64)k);
+        }
+        if (k + 1 < nb) {
+          bool ok = true;
+          if (k >= 1) {   // (the tiles of row 1 have no update before panel 0: nothing to wait for)
+            unsigned n = 0;
+            while (flag_load(cflag + k + 1) != x.epoch) {
+              __builtin_amdgcn_s_sleep(1);
+              if (++n > x.spin_limit) {
+                flag_store(x.abort_word, x.epoch);
+                if (*x.status == 0) *x.status = ST_TIMEOUT;
+                *(volatile int*)&gave_up = 1;
+                ok = false;
+                break;
+              }
+              if ((n & 31u) == 0 && flag_load(x.abort_word) == x.epoch) {
+                *(volatile int*)&gave_up = 1;
+                ok = false;
+                break;
+              }
+            }
+          }
+          if (ok) {
+            const gfloat* sub = tile_at(x.C, k + 1, k);
+            const gfloat* dia = tile_at(x.C, k + 1, k + 1);
+#pragma unroll 4
+            for (int rr = 0; rr < CB; rr += 4) {
+              float a[4], d[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) { a[e] = shared_load(sub + (rr + e) * ld + lane); d[e] = shared_load(dia + (rr + e) * ld + lane); }
+#pragma unroll
+              for (int e = 0; e < 4; ++e) { S2[(rr + e) * CBP + lane] = a[e]; S3[(rr + e) * CBP + lane] = d[e]; }
+            }
+          }
+        }
+      }
+      __syncthreads();
+      if (*(volatile int*)&gave_up) return;   // uniform: written before the barrier
+      // W11 out to the helpers; nobody here waits for these stores before the product below has been issued
+      lds_to_shared_tile(x.W + at, ld, S0, t);
+      if (k + 1 == nb) break;
+      const f32x16_t li = mma_64(S2, S0, wm, wn, lr, lk);   // L[k+1][k] = C'[k+1][k] W11^T
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's part of W11 is in memory
+      __syncthreads();                                      // everybody's is, and everybody has read S0 and S2
+      if (t == 0) flag_store(x.wflag + k, x.epoch);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) S1[(frow + 8 * (v / 4) + (v % 4)) * CBP + fcol] = li[v];
+      pending = true;
+      __syncthreads();
+      const f32x16_t up = mma_64(S1, S1, wm, wn, lr, lk);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = frow + 8 * (v / 4) + (v % 4);
+        S0[row * CBP + fcol] = (fcol <= row) ? S3[row * CBP + fcol] - up[v] : 0.f;
+      }
+    }
+    return;
+  }
+
+  // ------------------------------------------------------------------ a helper
+  // Ownership: the tiles (i, i), (i, i-1), (i, i-2) of a row i go together, to helper (i mod pr) pc + (i mod pc); any
+  // other tile (i, j) to helper (i mod pr) pc + (j mod pc).  With pr and pc coprime the rows of the first kind that a
+  // helper owns are i0, i0 + pr pc, ...
+  const int h = (int)blockIdx.x - 1, a = h / pc, b = h % pc;
+  int i0 = -1;
+  for (int i = a; i < pr * pc; i += pr)
+    if (i % pc == b) { i0 = i; break; }
+  const int istep = pr * pc;
+  auto owns_row = [&](int i) __attribute__((always_inline)) { return i0 >= 0 && i >= i0 && (i - i0) % istep == 0; };
+  int s0_holds = -1;   // panel whose W11 is in S0
+  // T(i, p): L[i][p] = C[i][p] W11(p)^T, published; leaves it in S1 as well
+  auto column_tile = [&](int i, int p_) __attribute__((always_inline)) -> bool {
+    __syncthreads();   // earlier readers of S0 / S1 are through
+    tile_to_lds(S1, tile_at(x.C, i, p_), ld, t);
+    if (s0_holds != p_) {
+      if (!wait_until(x, &gave_up, t == 0, [&] { return flag_load(x.wflag + p_) == x.epoch; })) return false;
+      shared_tile_to_lds(S0, tile_at(x.W, p_, p_), ld, t);
+      s0_holds = p_;
+    }
+    __syncthreads();
+    const f32x16_t li = mma_64(S1, S0, wm, wn, lr, lk);
+    __syncthreads();
+    gfloat* dst = tile_at(x.L, i, p_);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      S1[(frow + 8 * (v / 4) + (v % 4)) * CBP + fcol] = li[v];
+      shared_store(dst + foff + (8 * (v / 4) + (v % 4)) * ld, li[v]);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();   // S1 is complete, everybody's stores have completed
+    if (t == 0) flag_store(x.lflag + i, ep32 | (u64)(p_ + 1));
+    return true;
+  };
+  // U(i, j, p): C[i][j] -= L[i][p] L[j][p]^T.  li_in_s1: L[i][p] is in S1 already.  shared: the tile is of the kind that
+  // ends up with the chain (diagonal and first sub-diagonal): device-scope accesses throughout.
+  auto update = [&](int i, int j, int p_, bool li_in_s1, bool shared) __attribute__((always_inline)) {
+    gfloat* ct = tile_at(x.C, i, j) + foff;
+    float cold[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cold[v] = shared ? shared_load(ct + (8 * (v / 4) + (v % 4)) * ld) : ct[(8 * (v / 4) + (v % 4)) * ld];
+    __syncthreads();   // earlier readers of S1 / S2 are through
+    if (!li_in_s1) shared_tile_to_lds(S1, tile_at(x.L, i, p_), ld, t);
+    if (j != i) shared_tile_to_lds(S2, tile_at(x.L, j, p_), ld, t);
+    __syncthreads();
+    const f32x16_t up = mma_64(S1, (j != i) ? S2 : S1, wm, wn, lr, lk);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (shared) shared_store(ct + (8 * (v / 4) + (v % 4)) * ld, cold[v] - up[v]);
+      else ct[(8 * (v / 4) + (v % 4)) * ld] = cold[v] - up[v];
+    }
+  };
+  auto row_ready = [&](int row, int cols) __attribute__((always_inline)) {   // L[row][0 .. cols) are out
+    const u64 v = flag_load(x.lflag + row);
+    return (unsigned)(v >> 32) == (unsigned)x.epoch && (unsigned)v >= (unsigned)cols;
+  };
+
+  for (int p_ = 0; p_ + 1 < nb; ++p_) {
+    // Row p_ + 2 feeds the chain's next step: its owner turns (p_ + 2, p_) into a tile of L first and applies that
+    // row's two look-ahead updates at once, before anything else of this panel.
+    if (p_ + 2 < nb && owns_row(p_ + 2)) {
+      const int i = p_ + 2;
+      if (!column_tile(i, p_)) return;
+      update(i, i, p_, true, true);                                         // needs L[i][p_] only
+      if (!wait_until(x, &gave_up, t == 0, [&] { return row_ready(p_ + 1, p_ + 1); })) return;   // L[p_+1][p_]: the chain's
+      update(i, i - 1, p_, true, true);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (t == 0) flag_store(cflag + i, x.epoch);   // both tiles of row i carry all updates up to panel i - 2
+    }
+    // the other tiles of column p_ that this helper turns into tiles of L (three rows below the diagonal and further)
+    if (p_ % pc == b)
+      for (int i = a + ((p_ + 3 - a + pr - 1) / pr) * pr; i < nb; i += pr)
+        if (!column_tile(i, p_)) return;
+    // the tiles of L that this helper's other updates of panel p_ need: one thread per block row (a superset)
+    {
+      bool need = false;
+      if (t > p_ && t < nb) need = (t % pr) == a || (t % pc) == b || owns_row(t) || owns_row(t + 1) || owns_row(t + 2);
+      if (!wait_until(x, &gave_up, need, [&] { return row_ready(t, p_ + 1); })) return;
+    }
+    // updates of the tiles three and more below the diagonal
+    for (int j = b + ((p_ + 1 - b + pc - 1) / pc) * pc; j < nb; j += pc)
+      for (int i = a + ((j + 3 - a + pr - 1) / pr) * pr; i < nb; i += pr) update(i, j, p_, false, false);
+    // ... and of the rows whose near-diagonal tiles are this helper's (row p_ + 2 was done above; the last update of a
+    // diagonal tile, from the panel just left of it, is the chain's)
+    if (i0 >= 0)
+      for (int i = i0; i < nb; i += istep) {
+        if (i < p_ + 3) continue;
+        update(i, i, p_, false, true);
+        update(i, i - 1, p_, false, true);
+        update(i, i - 2, p_, false, false);
+      }
+  }
+}
+
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
   // 32 KB of unused dynamic LDS on top of the 52 KB the kernel declares: one workgroup per compute unit, so the
   // workgroup on the critical chain shares its unit with nobody
+  if (p.chain) {
+    // (70 KB of declared LDS and 32 KB of unused dynamic LDS: more than half of a compute unit's, so one workgroup each)
+    if (p.thr) hipLaunchKernelGGL(chol_chain_kernel<true>, dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
+    else hipLaunchKernelGGL(chol_chain_kernel<false>, dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
+    return hipGetLastError();
+  }
   if (p.thr) hipLaunchKernelGGL(chol_stream_kernel<true>, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
   else hipLaunchKernelGGL(chol_stream_kernel<false>, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);
   return hipGetLastError();

@@ -32,19 +32,21 @@ int pick_variant(long long M, long long N, long long K, long long batch, bool al
   }
   return small_ok ? VAR_SMALL : VAR_SMALL_CHECKED;
 }
-void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc) {
-  *pr = 0; *pc = 0;
+void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc, int* chain) {
+  *pr = 0; *pc = 0; *chain = 0;
   if (cus < 1 || batch < 1 || nb < 4 || nb > 128) return;
   // From two workgroups per matrix on the single launch still beats a launch per panel, in which every workgroup redoes
-  // the diagonal block and the second pass costs a launch per panel to skip.
+  // the diagonal block and the second pass costs a launch per panel to skip.  With sixteen and more per matrix one of
+  // them carries the whole chain of diagonal blocks and the others (pr x pc, coprime) help.
   const int per = cus / batch;
-  if (per >= 256 && nb >= 16) { *pr = 16; *pc = 16; }
-  else if (per >= 64) { *pr = 8; *pc = 8; }
-  else if (per >= 16) { *pr = 4; *pc = 4; }
+  if (per >= 256 && nb >= 16) { *pr = 15; *pc = 17; *chain = 1; }
+  else if (per >= 64) { *pr = 7; *pc = 9; *chain = 1; }
+  else if (per >= 16) { *pr = 3; *pc = 5; *chain = 1; }
   else if (per >= 8) { *pr = 4; *pc = 2; }
   else if (per >= 4) { *pr = 2; *pc = 2; }
   else if (per >= 2) { *pr = 2; *pc = 1; }
-  if ((long long)*pr * *pc * batch > cus || *pr * *pc > INV_TREE_MAX_GROUPS) { *pr = 0; *pc = 0; }
+  const long long groups = (long long)*pr * *pc + *chain;
+  if (groups * batch > cus || groups > INV_TREE_MAX_GROUPS) { *pr = 0; *pc = 0; *chain = 0; }
 }
 }  // namespace dion
 
@@ -397,8 +399,8 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   const int nb = rp / CHOL_NB;
   // Workgroups per matrix for the single-launch driver: all of a launch must be resident at once (one per compute
   // unit), so a batch shares the compute units this GPU has (read once, when the state was created).
-  int spr = 0, spc = 0;
-  if (!st->force_panel) plan_chol_grid(st->cus, batch, nb, &spr, &spc);
+  int spr = 0, spc = 0, chain = 0;
+  if (!st->force_panel) plan_chol_grid(st->cus, batch, nb, &spr, &spc, &chain);
   const bool use_stream = spr > 0;
   // The split-K partial Gram matrices of an adaptive pass are added up by its defect kernel, which reads the whole
   // Gram matrix anyway (and stores the sum); other passes run a reduction kernel.  (Adding them up inside the
@@ -500,6 +502,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ca.pass = pass;
     ca.spin_limit = st->chol_spin_limit;
     ca.thr = pp.thr; ca.nullmask = pp.nullmask;
+    ca.chain = chain;
     HIPCHK(launch_chol_stream(ca, batch, s));
   } else {
     for (int k = 0; k < rp; k += CHOL_NB)
@@ -520,7 +523,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ta.step_counter = st->step_counter;
     ta.pass = pass;
     ta.spin_limit = st->chol_spin_limit;
-    HIPCHK(launch_inv_tree(ta, spr * spc, batch, st->cus, s));
+    HIPCHK(launch_inv_tree(ta, spr * spc + chain, batch, st->cus, s));
   } else {
     // one launch per product: an odd block is carried to the next level, so any multiple of 64 works; runs of equal,
     // evenly spaced pairs go out as one launch
@@ -1334,9 +1337,11 @@ int dion_set_orth_mode(dion_state_t* st, int mode) {
   return DION_OK;
 }
 
-int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* pr_out, int* pc_out) {
-  if (compute_units < 1 || batch < 1 || r < 1 || r > 32768 || !pr_out || !pc_out) return DION_EINVAL;
-  plan_chol_grid(compute_units, batch, padded_rank(r) / CHOL_NB, pr_out, pc_out);
+int dion_cholesky_grid(int compute_units, int batch, int64_t r, int* workgroups_out) {
+  if (compute_units < 1 || batch < 1 || r < 1 || r > 32768 || !workgroups_out) return DION_EINVAL;
+  int pr = 0, pc = 0, chain = 0;
+  plan_chol_grid(compute_units, batch, padded_rank(r) / CHOL_NB, &pr, &pc, &chain);
+  *workgroups_out = pr * pc + chain;
   return DION_OK;
 }
 

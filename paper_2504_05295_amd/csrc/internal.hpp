@@ -166,7 +166,7 @@ struct CholPanelPtrs {
 };
 hipError_t launch_chol_panel(CholPanelPtrs p, int batch, int k0, int rp, float piv_lo, float piv_hi, hipStream_t s);
 // The whole factorisation in one launch (tiles owned by pr x pc workgroups that hand results on through flags).
-// sync: per matrix 2 * rp / 64 + 2 64-bit words that were zero before the first launch: flags and the abort word.
+// sync: per matrix chol_sync_words(rp / 64) 64-bit words that were zero before the first launch: flags and the abort word.
 // Flags are tagged with *step_counter * 8 + pass: the counter is a device word that a kernel increments once per
 // step (on the device, so that a captured graph can be replayed), pass (1..7) tells the launches of one step
 // apart.  Every wait inside the kernel gives up after spin_limit polls.
@@ -187,6 +187,7 @@ struct CholStreamArgs {
   unsigned spin_limit;
   const float* thr;        // as in CholPanelPtrs
   int* nullmask;
+  int chain;               // 1: one more workgroup, number 0, carries the whole chain of diagonal blocks (pr x pc helpers)
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
 // W = L^-1 from L and the inverses of its 64 x 64 diagonal blocks (both as the factorisation leaves them), one launch
@@ -210,9 +211,10 @@ hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, int cus, hipStr
 // Workgroup grid pr x pc per matrix of the single-launch factorisation (and pr * pc groups for the inverse) for `batch`
 // matrices of nb 64-wide panels on a GPU with `cus` compute units; pr = 0: use a launch per panel instead.  All
 // pr * pc * batch workgroups must be resident at once, one per compute unit.
-void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc);
+// *chain = 1: pr x pc helper workgroups plus one that carries the chain of diagonal blocks (pr * pc + 1 in all).
+void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc, int* chain);
 // 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
-constexpr int chol_sync_words(int nb) { return 2 * nb + 2; }
+constexpr int chol_sync_words(int nb) { return 3 * nb + 2; }
 constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the identity in
 // Frobenius norm, SLOT_FAST is set to 1 (else 0) and, unless decision_only, W receives chol(C)^-1 = I - Phi(C - I) up to
