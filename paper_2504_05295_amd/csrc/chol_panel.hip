@@ -722,11 +722,17 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
         if (cc + e > rr) v[e] = 0.f;
       *(f32x4_t*)(S0 + rr * CBP + cc) = v;
     }
-    bool pending = false;   // S1 holds L[k][k-1], still to be written out and announced
     for (int k = 0; k < nb; ++k) {
       const int at = (k * CB) * ld + k * CB;
       if (t == 0) { scaled = 0; raw_done = 0; }
-      __syncthreads();
+      __syncthreads();   // (also: everybody's stores of the last step, W11(k-1) and L[k][k-1], have completed)
+#ifdef DION_CHOL_TIMING
+      if (t == 0 && p.dbg) p.dbg[8 * k + 0] = wall_clock64();
+#endif
+      if (t == 0 && k >= 1) {
+        flag_store(x.wflag + k - 1, x.epoch);           // W11(k-1) is out, and so is L[k][k-1]:
+        flag_store(x.lflag + k, ep32 | (u64)k);         // the helper of the next look-ahead row fetches both at once
+      }
       if (wave == 0) {
         eliminate_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, lane, RANK ? thr + k * CB : nullptr);
       } else if (wave == 2) {
@@ -735,61 +741,66 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
       } else if (wave == 1) {
         invert_wave<RANK>((lds_float*)S0, (lds_counter*)&raw_done, (const lds_float*)rsv, (lds_counter*)&scaled, lane,
                           RANK ? thr + k * CB : nullptr);
-      } else {
-        // the idle wave: L[k][k-1] out to the helpers, then the two tiles of the next step in
-        if (pending) {
-          gfloat* dst = tile_at(x.L, k, k - 1);
-#pragma unroll 8
-          for (int rr = 0; rr < CB; ++rr) shared_store(dst + rr * ld + lane, S1[rr * CBP + lane]);
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-          if (lane == 0) flag_store(x.lflag + k, ep32 | (u64)k);
+      } else if (k + 1 < nb) {
+        // the idle wave: the two tiles of the next step in, once their owner has applied their last update
+        bool ok = true;
+#ifdef DION_CHOL_TIMING
+        if (lane == 0 && p.dbg) p.dbg[8 * k + 3] = wall_clock64();
+#endif
+        if (k >= 1) {   // (the tiles of row 1 have no update before panel 0: nothing to wait for)
+          unsigned n = 0;
+          while (flag_load(cflag + k + 1) != x.epoch) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++n > x.spin_limit) {
+              flag_store(x.abort_word, x.epoch);
+              if (*x.status == 0) *x.status = ST_TIMEOUT;
+              *(volatile int*)&gave_up = 1;
+              ok = false;
+              break;
+            }
+            if ((n & 31u) == 0 && flag_load(x.abort_word) == x.epoch) {
+              *(volatile int*)&gave_up = 1;
+              ok = false;
+              break;
+            }
+          }
         }
-        if (k + 1 < nb) {
-          bool ok = true;
-          if (k >= 1) {   // (the tiles of row 1 have no update before panel 0: nothing to wait for)
-            unsigned n = 0;
-            while (flag_load(cflag + k + 1) != x.epoch) {
-              __builtin_amdgcn_s_sleep(1);
-              if (++n > x.spin_limit) {
-                flag_store(x.abort_word, x.epoch);
-                if (*x.status == 0) *x.status = ST_TIMEOUT;
-                *(volatile int*)&gave_up = 1;
-                ok = false;
-                break;
-              }
-              if ((n & 31u) == 0 && flag_load(x.abort_word) == x.epoch) {
-                *(volatile int*)&gave_up = 1;
-                ok = false;
-                break;
-              }
-            }
-          }
-          if (ok) {
-            const gfloat* sub = tile_at(x.C, k + 1, k);
-            const gfloat* dia = tile_at(x.C, k + 1, k + 1);
-#pragma unroll 4
-            for (int rr = 0; rr < CB; rr += 4) {
-              float a[4], d[4];
+#ifdef DION_CHOL_TIMING
+        if (lane == 0 && p.dbg) p.dbg[8 * k + 4] = wall_clock64();
+#endif
+        if (ok) {
+          const gfloat* sub = tile_at(x.C, k + 1, k);
+          const gfloat* dia = tile_at(x.C, k + 1, k + 1);
+          // (all loads of both tiles are issued before the first of them is waited for: one memory round trip)
+          float a[CB], d[CB];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) { a[e] = shared_load(sub + (rr + e) * ld + lane); d[e] = shared_load(dia + (rr + e) * ld + lane); }
+          for (int rr = 0; rr < CB; ++rr) a[rr] = shared_load(sub + rr * ld + lane);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) { S2[(rr + e) * CBP + lane] = a[e]; S3[(rr + e) * CBP + lane] = d[e]; }
-            }
-          }
+          for (int rr = 0; rr < CB; ++rr) d[rr] = shared_load(dia + rr * ld + lane);
+#pragma unroll
+          for (int rr = 0; rr < CB; ++rr) S2[rr * CBP + lane] = a[rr];
+#pragma unroll
+          for (int rr = 0; rr < CB; ++rr) S3[rr * CBP + lane] = d[rr];
+#ifdef DION_CHOL_TIMING
+          if (lane == 0 && p.dbg) p.dbg[8 * k + 5] = wall_clock64();
+#endif
         }
       }
       __syncthreads();
+#ifdef DION_CHOL_TIMING
+      if (t == 0 && p.dbg) p.dbg[8 * k + 1] = wall_clock64();
+#endif
       if (*(volatile int*)&gave_up) return;   // uniform: written before the barrier
-      // W11 out to the helpers; nobody here waits for these stores before the product below has been issued
+      // W11 out to the helpers; nobody here waits for these stores before the step is through
       lds_to_shared_tile(x.W + at, ld, S0, t);
       if (k + 1 == nb) break;
       const f32x16_t li = mma_64(S2, S0, wm, wn, lr, lk);   // L[k+1][k] = C'[k+1][k] W11^T
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's part of W11 is in memory
-      __syncthreads();                                      // everybody's is, and everybody has read S0 and S2
-      if (t == 0) flag_store(x.wflag + k, x.epoch);
+      gfloat* dst = tile_at(x.L, k + 1, k);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) shared_store(dst + foff + (8 * (v / 4) + (v % 4)) * ld, li[v]);
+      __syncthreads();                                      // everybody has read S0 and S2
 #pragma unroll
       for (int v = 0; v < 16; ++v) S1[(frow + 8 * (v / 4) + (v % 4)) * CBP + fcol] = li[v];
-      pending = true;
       __syncthreads();
       const f32x16_t up = mma_64(S1, S1, wm, wn, lr, lk);
 #pragma unroll
@@ -797,6 +808,10 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
         const int row = frow + 8 * (v / 4) + (v % 4);
         S0[row * CBP + fcol] = (fcol <= row) ? S3[row * CBP + fcol] - up[v] : 0.f;
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this thread's parts of W11(k) and L[k+1][k] are in memory
+#ifdef DION_CHOL_TIMING
+      if (t == 0 && p.dbg) p.dbg[8 * k + 2] = wall_clock64();
+#endif
     }
     return;
   }
@@ -862,14 +877,47 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     // Row p_ + 2 feeds the chain's next step: its owner turns (p_ + 2, p_) into a tile of L first and applies that
     // row's two look-ahead updates at once, before anything else of this panel.
     if (p_ + 2 < nb && owns_row(p_ + 2)) {
+      // (Everything that does not depend on W11(p_) is fetched before the wait for it, results are stored without
+      // waiting in between, and one wait for all stores comes before the flags: this path decides whether the chain
+      // finds its tiles ready when it has factored its diagonal block.)
       const int i = p_ + 2;
-      if (!column_tile(i, p_)) return;
-      update(i, i, p_, true, true);                                         // needs L[i][p_] only
-      if (!wait_until(x, &gave_up, t == 0, [&] { return row_ready(p_ + 1, p_ + 1); })) return;   // L[p_+1][p_]: the chain's
-      update(i, i - 1, p_, true, true);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();   // earlier readers of S0 / S1 / S2 are through
+      tile_to_lds(S1, tile_at(x.C, i, p_), ld, t);
+      gfloat* cd = tile_at(x.C, i, i) + foff;
+      gfloat* cs = tile_at(x.C, i, i - 1) + foff;
+      float cold_d[16], cold_s[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        cold_d[v] = shared_load(cd + (8 * (v / 4) + (v % 4)) * ld);
+        cold_s[v] = shared_load(cs + (8 * (v / 4) + (v % 4)) * ld);
+      }
+      // (the chain announces W11(p_) once L[p_+1][p_] is out as well: one wait, both tiles in one go)
+      if (!wait_until(x, &gave_up, t == 0, [&] { return flag_load(x.wflag + p_) == x.epoch; })) return;
+      shared_tile_to_lds(S0, tile_at(x.W, p_, p_), ld, t);
+      shared_tile_to_lds(S2, tile_at(x.L, p_ + 1, p_), ld, t);
+      s0_holds = p_;
       __syncthreads();
-      if (t == 0) flag_store(cflag + i, x.epoch);   // both tiles of row i carry all updates up to panel i - 2
+      const f32x16_t li = mma_64(S1, S0, wm, wn, lr, lk);   // L[i][p_]
+      __syncthreads();
+      gfloat* dst = tile_at(x.L, i, p_);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        S1[(frow + 8 * (v / 4) + (v % 4)) * CBP + fcol] = li[v];
+        shared_store(dst + foff + (8 * (v / 4) + (v % 4)) * ld, li[v]);
+      }
+      __syncthreads();   // S1 is complete
+      const f32x16_t upd = mma_64(S1, S1, wm, wn, lr, lk);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) shared_store(cd + (8 * (v / 4) + (v % 4)) * ld, cold_d[v] - upd[v]);
+      const f32x16_t ups = mma_64(S1, S2, wm, wn, lr, lk);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) shared_store(cs + (8 * (v / 4) + (v % 4)) * ld, cold_s[v] - ups[v]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();   // everybody's stores (L[i][p_] and the two updated tiles) have completed
+      if (t == 0) {
+        flag_store(cflag + i, x.epoch);   // both tiles of row i carry all updates up to panel i - 2
+        flag_store(x.lflag + i, ep32 | (u64)(p_ + 1));
+      }
     }
     // the other tiles of column p_ that this helper turns into tiles of L (three rows below the diagonal and further)
     if (p_ % pc == b)

@@ -188,6 +188,9 @@ struct CholStreamArgs {
   const float* thr;        // as in CholPanelPtrs
   int* nullmask;
   int chain;               // 1: one more workgroup, number 0, carries the whole chain of diagonal blocks (pr x pc helpers)
+#ifdef DION_CHOL_TIMING
+  long long* dbg;          // timing build only: eight time stamps per panel of the chain workgroup
+#endif
 };
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s);
 // W = L^-1 from L and the inverses of its 64 x 64 diagonal blocks (both as the factorisation leaves them), one launch
