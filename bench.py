@@ -196,7 +196,7 @@ def cpu_baseline(cfg, p, budget_s=30.0, variant="dion", refresh_every=1):
 
 
 def run_workload(tag, steps, warmup, stage_timing=True, variant="dion", refresh_every=1, form="standard",
-                 calibration_copy=False):
+                 calibration_copy=False, orth_mode=0):
     """Builds the workload, runs `warmup` untimed and exactly `steps` timed steps (inputs resident in HBM, host clock
     bracketed by device synchronisations).  Returns the problem, ms per step and the per-stage ms."""
     import torch
@@ -204,6 +204,8 @@ def run_workload(tag, steps, warmup, stage_timing=True, variant="dion", refresh_
     p = build_problem(cfg, form=form)
     p["variant"], p["refresh_every"] = variant, max(1, refresh_every)
     B = p["B"]
+    if orth_mode:
+        B.dion_set_orth_mode(p["state"], orth_mode)
     for t in range(warmup):
         do_step(p, t)
     status, bad = B.dion_last_status(p["state"])
@@ -278,6 +280,8 @@ def main():
     ap.add_argument("--form", default="standard", choices=["standard", "transposed", "short-side"],
                     help="power iteration on M (standard), on M^T (transposed), or per matrix on whichever side makes the "
                          "orthonormalised factor shorter (transposed where n < m)")
+    ap.add_argument("--orth-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0 CholeskyQR2 (default), 1 shifted CholeskyQR3, 2 CholeskyQR2 with the on-device fallback passes enqueued")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the two micro-kernels that measure this GPU's MFMA and streaming ceilings")
@@ -303,7 +307,7 @@ def main():
         args.warmup += (-args.warmup) % refresh_every
         args.steps += (-args.steps) % refresh_every
     p, ms_per_step, stages = run_workload(args.workload, args.steps, args.warmup, not args.no_stage_timing, args.variant,
-                                          refresh_every, args.form, args.calibration_copy)
+                                          refresh_every, args.form, args.calibration_copy, args.orth_mode)
     B = p["B"]
     # measured ceilings of this GPU, in the same run: bf16 MFMA issue loop, 18-byte-per-element streaming pass
     ceilings = None
@@ -322,7 +326,7 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[args.workload], "matrices": len(cfg["shapes"]),
                    "shape": list(cfg["shapes"][0]) if len(set(cfg["shapes"])) == 1 else "mixed",
                    "mu": inputs.MU, "eta": inputs.ETA, "g_dtype": "bf16" if cfg["g_bf16"] else "f32",
-                   "variant": args.variant, "form": args.form},
+                   "variant": args.variant, "form": args.form, "orth_mode": args.orth_mode},
         "stage_ms": stages,
         "roofline": dict(rooflines[dominant], kernel=dominant) if dominant else None,
         "rooflines": rooflines,

@@ -204,8 +204,18 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index);
  *   DION_ORTH_SHIFTED_CHOLQR3  a shifted Cholesky-QR pass in front of the two (about 1.5x the orthonormalisation
  *                              cost): does not break down for condition numbers up to about 1e5; an exactly rank
  *                              deficient B Q is still reported.  Since a breakdown leaves X, M, Q untouched, a
- *                              caller can switch to this mode and repeat the step. */
-enum { DION_ORTH_CHOLQR2 = 0, DION_ORTH_SHIFTED_CHOLQR3 = 1 };
+ *                              caller can switch to this mode and repeat the step.
+ *   DION_ORTH_CHOLQR2_FALLBACK the default passes, and behind them, in the same step and without the host taking
+ *                              part, the fallback: the matrices whose factorisation broke down (decided on the
+ *                              device) are orthonormalised again from the untouched B Q by shifted CholeskyQR3 in
+ *                              fp32 arithmetic, in either arithmetic mode; for all other matrices those launches
+ *                              return at once (about 20 of them per shape group: measured 0.03-0.08 ms per step).  The step
+ *                              then completes with DION_OK for condition numbers up to about 1e5;
+ *                              DION_NUM_BREAKDOWN is left for B Q that is rank deficient outright.  Applies to
+ *                              dion_step, dion_step_batched and the first stage of dion_double_step for matrices of
+ *                              the standard form; the transposed form and the Lazy-Dion refresh have no third
+ *                              buffer for it and behave as with DION_ORTH_CHOLQR2. */
+enum { DION_ORTH_CHOLQR2 = 0, DION_ORTH_SHIFTED_CHOLQR3 = 1, DION_ORTH_CHOLQR2_FALLBACK = 2 };
 int dion_set_orth_mode(dion_state_t* st, int mode);
 
 /* Fallback for matrices whose last step did not complete (Appendix A: when Cholesky-QR fails the step falls

@@ -25,7 +25,7 @@ DION_MATH_F32, DION_MATH_BF16 = 0, 1
 STAGES = ("k1_BQ", "orth", "k2_BtP", "colnorm", "k5_update")
 DEBUG_Z, DEBUG_P, DEBUG_R, DEBUG_S, DEBUG_STATUS, DEBUG_P1, DEBUG_C, DEBUG_L, DEBUG_W, DEBUG_D, DEBUG_NULL = range(11)
 
-DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3 = 0, 1
+DION_ORTH_CHOLQR2, DION_ORTH_SHIFTED_CHOLQR3, DION_ORTH_CHOLQR2_FALLBACK = 0, 1, 2
 DION_FORM_STANDARD, DION_FORM_TRANSPOSED = 0, 1
 
 EXPORTS = ("dion_workspace_bytes", "dion_init_state", "dion_init_state_ex", "dion_step", "dion_step_batched", "dion_lazy_step", "dion_lazy_step_batched",

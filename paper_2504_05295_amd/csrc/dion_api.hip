@@ -3,9 +3,10 @@
 // Sequence per shape group (Algorithm 1 + unsharded update rule + PowerIter1 of the paper; the
 // data-parallel all-reduces of PowerIter1 are absent because everything runs on one GPU):
 //   K1  Z = (M+G) Q                      MFMA GEMM; M+G fused into the operand load, or (shapes that fill the GPU with
-//                                        256-wide tiles) read from bf16 copies of M+G that one pass writes first
+//                                        256-wide tiles) read from the one bf16 copy of M+G that a pass writes first
 //   orth: CholeskyQR2 (Appendix A applied twice): Gram, blocked Cholesky, triangular inverse, Z L^-T
-//   K2  R = (M+G)^T P                    MFMA GEMM, transposing operand load or the transposed bf16 copy
+//   K2  R = (M+G)^T P                    MFMA GEMM; the operand is transposed on its way into the registers (from
+//                                        M and G, or from the same bf16 copy through transposing LDS reads)
 //   K6  s_j = ||R_j||, d_j = 1/(s_j + eps);   K7  Q = R diag(d)
 //   K5  M = (M+G) - (1-mu) P R^T ;  X = X - eta sqrt(m/n) P Q^T     one fused pass
 // The stages are functions of their own (stage_k1, stage_orth, ...); the Dion step, its transposed form, the
@@ -174,6 +175,7 @@ Carve carve_entry(const Group& g) {
   take(SLOT_B16T, 0);   // (no transposed copy: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
   take(SLOT_THR, g.rp);
   take(SLOT_NULL, g.rp);
+  take(SLOT_GATE, 1);
   c.total = pos;
   return c;
 }
@@ -300,7 +302,7 @@ int plan_state(dion_state* st, int count, const int64_t* m, const int64_t* n, co
     char* base = st->ws + group_base[e.group] + (size_t)(e.row - g.first_row) * g.bytes_per_entry;
     void** rowp = &host[(size_t)e.row * NSLOTS];
     for (int sl = SLOT_Z; sl <= SLOT_D; ++sl) rowp[sl] = base + c.off[sl];
-    for (int sl = SLOT_QT16; sl <= SLOT_NULL; ++sl) rowp[sl] = base + c.off[sl];
+    for (int sl = SLOT_QT16; sl <= SLOT_GATE; ++sl) rowp[sl] = base + c.off[sl];
     rowp[SLOT_STATUS] = st->status + e.row;
     rowp[SLOT_M] = M_dev ? M_dev[i] : nullptr;
     rowp[SLOT_Q] = Q_dev ? Q_dev[i] : nullptr;
@@ -390,8 +392,10 @@ struct SplitIO {
 };
 int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long rows, const GramPlan& gp, int slot_in,
                 int slot_out, float piv_lo, float piv_hi, bool split, bool adaptive, float shift_rel, int pass, hipStream_t s,
-                float rank_tol = 0.f, SplitIO io = SplitIO()) {
+                float rank_tol = 0.f, SplitIO io = SplitIO(), int gate_slot = -1) {
   if (io.wrote_out) *io.wrote_out = false;
+  // gate_slot >= 0 (fp32 passes only): every launch of the pass leaves alone the matrices whose int32 there is non-zero
+  if (gate_slot >= 0 && (split || adaptive || rank_tol > 0.f)) return DION_EINVAL;
   void* const* tab = st->table + (size_t)(g.first_row + row0) * NSLOTS;
   const int r = (int)g.r, rp = g.rp;
   const long long rr = (long long)rp * rp;
@@ -451,15 +455,16 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.E.slot = (gp.splitk > 1) ? SLOT_CPART : SLOT_C;
     a.E.ld = rp;
     a.E.split_stride = rr;
+    a.status_slot = gate_slot;
     HIPCHK(gemm_f32_tn(gp.variant, a, batch, s));
     c_nsplit = gp.splitk;
   }
   if (c_nsplit > 1 && !sum_in_defect) {
-    HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, c_nsplit, rr, s));
+    HIPCHK(launch_reduce_partials(tab, NSLOTS, batch, SLOT_CPART, SLOT_C, r, rp, c_nsplit, rr, s, gate_slot));
     c_nsplit = 1;
   }
-  if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s));
-  HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s));
+  if (shift_rel > 0.f) HIPCHK(launch_shift_diagonal(tab, NSLOTS, batch, r, rp, shift_rel, s, gate_slot));
+  HIPCHK(launch_pad_identity(tab, NSLOTS, batch, SLOT_C, r, rp, s, gate_slot));
   if (rank_tol > 0.f) HIPCHK(launch_rank_threshold(tab, NSLOTS, batch, rp, rank_tol, s));
   // (W needs no clearing: its part above the block diagonal was zeroed at init and nothing ever writes there; the
   // rest is overwritten in full by the factorisation kernels, the merges below or the first-order factor)
@@ -467,7 +472,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   // and chol(I + E)^-1 = I - Phi(E) + O(E^2): no factorisation needed.  The decision is taken on the device
   // (||E||_F <= 1e-3, i.e. a second-order error below 1e-6); when it fails, the launches below do the full
   // factorisation, otherwise they return at once.
-  const int skip = adaptive ? SLOT_FAST : -1;
+  const int skip = adaptive ? SLOT_FAST : gate_slot;
   if (adaptive) {
     // (bf16 mode: decision only, see the product at the end)
     HIPCHK(launch_first_order_inverse(tab, NSLOTS, batch, r, rp, 1e-3f, split, c_nsplit, rr, s));
@@ -482,7 +487,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     pp.C = (float*)(e0 + g.carve.off[SLOT_C]);
     pp.L = (float*)(e0 + g.carve.off[SLOT_L]);
     pp.W = (float*)(e0 + g.carve.off[SLOT_W]);
-    pp.skip = adaptive ? (const int*)(e0 + g.carve.off[SLOT_FAST]) : nullptr;
+    pp.skip = skip >= 0 ? (const int*)(e0 + g.carve.off[skip]) : nullptr;
     pp.stride = (long long)(g.bytes_per_entry / sizeof(float));
     pp.status = st->status + g.first_row + row0;
     pp.thr = rank_tol > 0.f ? (const float*)(e0 + g.carve.off[SLOT_THR]) : nullptr;
@@ -618,6 +623,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     a.B = opnd(SLOT_W, 0, rp);
     a.E.slot = slot_out; a.E.ld = r;
     a.xcd_remap = 1;
+    a.status_slot = gate_slot;
     HIPCHK(gemm_f32_nt(pick_variant(a.M, a.N, a.K, batch, true), a, batch, s));
   }
   return DION_OK;
@@ -655,9 +661,10 @@ int tile_cfg2(const RowCtx& c, long long Mo, long long No) {
   return (Mo % 256 == 0 && No % 256 == 0 && (Mo / 256) * (No / 256) * c.batch >= 128) ? G2_256x256 : G2_128x128;
 }
 
-// Direct-load path of K1 and K2: both read bf16(M + G) from memory, K1 as m x n, K2 its transpose, so that both are
-// plain bf16 products with the contraction index contiguous in either operand.  Taken when the plan has the two
-// buffers and this call's batch still fills the GPU with 256 x 256 tiles.
+// Direct-load path of K1 and K2: both read the same row-major bf16 copy of M + G from memory.  For K1 its contraction
+// index is the fast one; K2 contracts over its rows and takes it with k as the slow index (transposing LDS reads), as
+// both products take their r-column operands (Q, P) in their own row-major order.  Taken when the plan has the buffer
+// and this call's batch still fills the GPU with 256 x 256 tiles.
 // Tile order of these two products: column groups of four 256-wide tile columns (all row tiles of a group before the
 // next group).  The 32 tiles that run at one time on an XCD then form about 8 x 4 tiles instead of 2 x 16 at r = 4096,
 // two thirds of the operand panels: K2 at 16384 x 53248 r = 4096 7.2 -> 6.1 ms, K1 1 %; r <= 1024 has no more than four
@@ -667,8 +674,7 @@ bool direct12(const RowCtx& c) {
   const Group& g = *c.g;
   return c.big && g.direct12 && tile_cfg2(c, g.m, g.r) == G2_256x256 && tile_cfg2(c, g.n, g.r) == G2_256x256;
 }
-// The bf16 copies of M + G for the K1 / K2 of this call (a no-op off the direct-load path); the transposed one only
-// when a K2 will run.
+// The bf16 copy of M + G for the K1 / K2 of this call (a no-op off the direct-load path).
 int stage_b16(const RowCtx& c) {
   if (!direct12(c)) return DION_OK;
   HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, -1, c.g->m, c.g->n, c.s));
@@ -779,12 +785,37 @@ int stage_k2(const RowCtx& c, int slot_p, bool from_b16 = true, int* colsq_chunk
 // True when the orthonormalisation of these rows x r matrices runs as plain CholeskyQR2 on the split-bf16 path with the
 // Gram matrix on 256 x 256 tiles: then the halves of a pass' input may come from the epilogue of whatever produced it.
 bool orth_fuses(const RowCtx& c, long long rows, const GramPlan& gp, float rank_tol) {
-  return c.big && rank_tol == 0.f && c.st->orth_mode == DION_ORTH_CHOLQR2 && choose_gram(*c.g, c.batch, rows, gp).big;
+  return c.big && rank_tol == 0.f && c.st->orth_mode != DION_ORTH_SHIFTED_CHOLQR3 && choose_gram(*c.g, c.batch, rows, gp).big;
 }
 // rank_tol > 0: CholeskyQR2 that tolerates linearly dependent columns (zero columns of the result, marked in SLOT_NULL).
 // in_split_ready: the producer of slot_a has left its bf16 halves in (SLOT_PT16, SLOT_ZLT16), row-major (see orth_fuses).
+int stage_orth_plain(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol,
+                     bool in_split_ready);
+// With DION_ORTH_CHOLQR2_FALLBACK (and three distinct buffers, slot_a left intact by the plain passes): after the plain
+// passes a small kernel looks at the status words; for the matrices that report a numerical breakdown it clears the
+// word and opens the gate of three more passes, which are enqueued in any case and return at once for everybody else:
+// shifted CholeskyQR3 in fp32 arithmetic from the untouched input (a -> b -> a -> final), whatever the state's
+// arithmetic mode, since the split-bf16 products carry 16 bits and a Gram matrix squares the condition number.
+// A matrix that these passes cannot factor either (exact rank deficiency) gets its breakdown status back from them.
 int stage_orth(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol = 0.f,
                bool in_split_ready = false) {
+  int rc = stage_orth_plain(c, rows, gp, slot_a, slot_b, slot_final, rank_tol, in_split_ready);
+  if (rc != DION_OK || c.st->orth_mode != DION_ORTH_CHOLQR2_FALLBACK || rank_tol > 0.f) return rc;
+  if (slot_final == slot_a || slot_final == slot_b || slot_a == slot_b) return DION_OK;   // (callers without a third buffer: plain)
+  dion_state* st = c.st;
+  const Group& g = *c.g;
+  HIPCHK(launch_fallback_decide(c.tab, NSLOTS, c.batch, c.s));
+  SplitIO none;
+  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_b, 0.f, 3.0e38f, false, false, 1e-5f, 4, c.s, 0.f, none, SLOT_GATE);
+  if (rc != DION_OK) return rc;
+  // (the shifted pass leaves singular values sigma_j / sqrt(sigma_j^2 + shift): a pivot below 1e-6 here means a
+  // condition number beyond 1e5 or a rank-deficient input, whose pivot is rounding noise of either sign)
+  rc = cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_b, slot_a, 1e-6f, 3.0e38f, false, false, 0.f, 5, c.s, 0.f, none, SLOT_GATE);
+  if (rc != DION_OK) return rc;
+  return cholqr_pass(st, g, c.row0, c.batch, rows, gp, slot_a, slot_final, 0.1f, 10.f, false, false, 0.f, 6, c.s, 0.f, none, SLOT_GATE);
+}
+int stage_orth_plain(const RowCtx& c, long long rows, const GramPlan& gp, int slot_a, int slot_b, int slot_final, float rank_tol,
+                     bool in_split_ready) {
   dion_state* st = c.st;
   const Group& g = *c.g;
   const bool in_place = c.big;
@@ -1332,7 +1363,7 @@ int dion_last_status(dion_state_t* st, int* status_out, int* first_bad_index) {
 }
 
 int dion_set_orth_mode(dion_state_t* st, int mode) {
-  if (!st || (mode != DION_ORTH_CHOLQR2 && mode != DION_ORTH_SHIFTED_CHOLQR3)) return DION_EINVAL;
+  if (!st || (mode != DION_ORTH_CHOLQR2 && mode != DION_ORTH_SHIFTED_CHOLQR3 && mode != DION_ORTH_CHOLQR2_FALLBACK)) return DION_EINVAL;
   st->orth_mode = mode;
   return DION_OK;
 }

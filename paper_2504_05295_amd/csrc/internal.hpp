@@ -40,9 +40,10 @@ enum Slot {
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
   SLOT_B16,    // bf16(M + G), m x n: A operand of K1 on the direct-load path; else written by K1 on its way for K2
-  SLOT_B16T,   // its transpose, n x m: A operand of K2 on the direct-load path
+  SLOT_B16T,   // (unused: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
   SLOT_THR,    // rp floats: pivot thresholds of the factorisation that tolerates dependent columns
   SLOT_NULL,   // rp int32: 1 for the columns that factorisation found dependent on the ones before them
+  SLOT_GATE,   // int32: 0 when the orthonormalisation of this matrix has to be redone by the fallback passes, else 1
   NSLOTS = 40
 };
 
@@ -115,6 +116,10 @@ hipError_t launch_copy_status_rows(const int* src_status, int* dst_status, int c
                                    hipStream_t s);
 // SLOT_THR[j] = tol * C[j][j] for j < rp (C = SLOT_C, before it is factored)
 hipError_t launch_rank_threshold(void* const* table, int nslots, int batch, int rp, float tol, hipStream_t s);
+// Per matrix: a status word that reports a numerical breakdown is cleared and SLOT_GATE set to 0 (the fallback passes that
+// follow redo this matrix; SLOT_FAST is cleared too, so that the copies made of their result are not skipped); every
+// other matrix gets SLOT_GATE = 1.
+hipError_t launch_fallback_decide(void* const* table, int nslots, int batch, hipStream_t s);
 hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long long count, float value, hipStream_t s);
 // out <- in unless *status != 0 (both 16-byte aligned)
 hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
@@ -124,10 +129,11 @@ hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m
                            int slot_outT16, long long rows, long long cols, hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
-hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s);
-hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s);
+// (skip_slot >= 0 here and below: the int32 there non-zero means that the launch leaves this matrix alone)
+hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s, int skip_slot = -1);
+hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s, int skip_slot = -1);
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
-                                  int nsplit, long long split_stride, hipStream_t s);
+                                  int nsplit, long long split_stride, hipStream_t s, int skip_slot = -1);
 // out = sum over `nsplit` partial matrices of `count` floats each, stored back to back in slot_part (fixed order)
 hipError_t launch_sum_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, long long count,
                                int nsplit, hipStream_t s);

@@ -96,6 +96,27 @@ hipError_t launch_rank_threshold(void* const* table, int nslots, int batch, int 
   return hipGetLastError();
 }
 
+// Which matrices the fallback passes of the orthonormalisation have to redo (one thread per matrix)
+__global__ void fallback_decide_kernel(void* const* table, int nslots, int batch) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= batch) return;
+  void* const* tab = table + (size_t)i * nslots;
+  int* status = (int*)tab[SLOT_STATUS];
+  int* gate = (int*)tab[SLOT_GATE];
+  if (*status == ST_BREAKDOWN) {
+    *status = ST_OK;
+    *gate = 0;
+    *(int*)tab[SLOT_FAST] = 0;
+  } else {
+    *gate = 1;
+  }
+}
+hipError_t launch_fallback_decide(void* const* table, int nslots, int batch, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fallback_decide_kernel, dim3((batch + 63) / 64), dim3(64), 0, s, table, nslots, batch);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- fills
 __global__ void fill_kernel(void* const* table, int nslots, int slot, long long count, float value) {
   float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
@@ -144,7 +165,8 @@ hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, 
 
 // Gram matrix padding: rows/columns r..rp-1 of the rp x rp matrix become those of the identity, so
 // that the Cholesky factor of the padded matrix is diag(L, I).
-__global__ void pad_identity_kernel(void* const* table, int nslots, int slot, int r, int rp) {
+__global__ void pad_identity_kernel(void* const* table, int nslots, int slot, int r, int rp, int skip_slot) {
+  if (skip_slot >= 0 && *(const int*)table[(size_t)blockIdx.y * nslots + skip_slot] != 0) return;
   float* p = (float*)table[(size_t)blockIdx.y * nslots + slot];
   const long long total = (long long)rp * rp;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
@@ -152,15 +174,16 @@ __global__ void pad_identity_kernel(void* const* table, int nslots, int slot, in
     if (row >= r || col >= r) p[i] = (row == col) ? 1.f : 0.f;
   }
 }
-hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s) {
+hipError_t launch_pad_identity(void* const* table, int nslots, int batch, int slot, int r, int rp, hipStream_t s, int skip_slot) {
   if (rp == r || batch <= 0) return hipSuccess;
   long long blocks = ((long long)rp * rp + 1023) / 1024;
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(pad_identity_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, r, rp);
+  hipLaunchKernelGGL(pad_identity_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot, r, rp, skip_slot);
   return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256) shift_diagonal_kernel(void* const* table, int nslots, int r, int rp, float shift_rel) {
+__global__ void __launch_bounds__(256) shift_diagonal_kernel(void* const* table, int nslots, int r, int rp, float shift_rel, int skip_slot) {
+  if (skip_slot >= 0 && *(const int*)table[(size_t)blockIdx.x * nslots + skip_slot] != 0) return;   // uniform, before any barrier
   float* C = (float*)table[(size_t)blockIdx.x * nslots + SLOT_C];
   __shared__ float red[256];
   float acc = 0.f;
@@ -174,15 +197,16 @@ __global__ void __launch_bounds__(256) shift_diagonal_kernel(void* const* table,
   const float shift = shift_rel * red[0];
   for (int j = threadIdx.x; j < r; j += 256) C[(long long)j * rp + j] += shift;
 }
-hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s) {
-  hipLaunchKernelGGL(shift_diagonal_kernel, dim3(batch), dim3(256), 0, s, table, nslots, r, rp, shift_rel);
+hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int r, int rp, float shift_rel, hipStream_t s, int skip_slot) {
+  hipLaunchKernelGGL(shift_diagonal_kernel, dim3(batch), dim3(256), 0, s, table, nslots, r, rp, shift_rel, skip_slot);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- split-K reduction (fixed order => deterministic)
 // Lower triangle only (that is what is produced and consumed); a block takes rows, a thread four columns at a time.
 __global__ void __launch_bounds__(256) reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r,
-                                                              long long ld, int nsplit, long long split_stride) {
+                                                              long long ld, int nsplit, long long split_stride, int skip_slot) {
+  if (skip_slot >= 0 && *(const int*)table[(size_t)blockIdx.y * nslots + skip_slot] != 0) return;
   const float* part = (const float*)table[(size_t)blockIdx.y * nslots + slot_part];
   float* out = (float*)table[(size_t)blockIdx.y * nslots + slot_out];
   for (int i = blockIdx.x; i < r; i += gridDim.x)
@@ -202,11 +226,11 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(void* const* table
     }
 }
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
-                                  int nsplit, long long split_stride, hipStream_t s) {
+                                  int nsplit, long long split_stride, hipStream_t s, int skip_slot) {
   if (ld % 4 || split_stride % 4) return hipErrorInvalidValue;
   const int blocks = r < 2048 ? r : 2048;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_part, slot_out, r,
-                     ld, nsplit, split_stride);
+                     ld, nsplit, split_stride, skip_slot);
   return hipGetLastError();
 }
 

@@ -333,10 +333,61 @@ def test_shifted_cholqr3_matches_oracle_on_regular_inputs():
     check_batch([(512, 512, 256)], False, "f32", orth_mode=1)
 
 
+def test_fallback_mode_equals_default_on_regular_inputs():
+    # nothing breaks down: the fallback passes return at once and the step is the default step, bit for bit
+    for shapes, g_bf16, math in [([(256, 256, 64), (200, 136, 24)], False, "f32"), ([(1024, 768, 256)] * 2, True, "bf16"),
+                                 ([(512, 512, 256)], False, "f32")]:
+        a = check_batch(shapes, g_bf16, math)
+        b = check_batch(shapes, g_bf16, math, orth_mode=2)
+        for i in range(len(shapes)):
+            for u, v in zip(a.host(i), b.host(i)):
+                assert np.array_equal(u, v), (shapes[i], math)
+
+
+def test_fallback_mode_completes_the_step_on_the_device():
+    # a batch of three whose middle matrix is too ill conditioned for CholeskyQR2: with the fallback mode the one call
+    # completes all three, no host round trip, and the other two come out exactly as without it
+    shape = (512, 384, 64)
+    results = {}
+    for mode in (0, 2):
+        gp = GpuProblem([shape] * 3, False, "f32")
+        gp.B.dion_set_orth_mode(gp.state, mode)
+        grads = gp.grads_np(0)
+        grads[1] = inputs.structured_gradient(512, 384, 0, k=32, noise=2e-4)
+        gp.upload_grads(grads)
+        before = [gp.host(i) for i in range(3)]
+        results[mode] = (gp, gp.step(MU, ETA, batched=True), before, grads)
+    assert results[0][1] == (results[0][0].B.DION_NUM_BREAKDOWN, 1)
+    gp, outcome, before, grads = results[2]
+    assert outcome == (0, -1)
+    for i in (0, 2):
+        for u, v in zip(results[0][0].host(i), gp.host(i)):
+            assert np.array_equal(u, v)
+    pr = qr_properties(gp, 1, before[1][1], before[1][2], grads[1])
+    assert 1e4 < pr["cond"] < 3e5, pr
+    assert pr["orth"] < 1e-5 and pr["resid"] < 1e-5 and pr["diag_min"] > 0, pr
+    rest = rest_of_step_from_P(gp, 1, *before[1], grads[1], MU, ETA)
+    assert max(rest.values()) < 1e-5, rest
+    rep, _ = one_step_report(gp, 1, *before[1], grads[1], MU, ETA)
+    assert rep["PQt"] < 1e-6 * pr["cond"] and rep["PRt"] < 1e-6 * pr["cond"], (pr, rep)
+    # an exactly rank-deficient product is still reported, and the state left alone
+    q_raw = inputs.right_factor_raw(192, 32)
+    q_raw[:, 7] = q_raw[:, 3]                       # two identical columns
+    for kind in ("duplicate column", "zero buffer"):
+        gp = GpuProblem([(256, 192, 32)], False, "f32", q_raw=[q_raw] if kind == "duplicate column" else None)
+        gp.B.dion_set_orth_mode(gp.state, 2)
+        gp.upload_grads(gp.grads_np(0) if kind == "duplicate column" else [np.zeros((256, 192), dtype=np.float32)])
+        x_in, m_in, q_in = gp.host()
+        assert gp.step(MU, ETA) == (gp.B.DION_NUM_BREAKDOWN, 0), kind
+        for u, v in zip((x_in, m_in, q_in), gp.host()):
+            assert np.array_equal(u, v)
+
+
 def test_orth_mode_validation():
     gp = GpuProblem([(128, 128, 16)], False, "f32")
     L = gp.B.lib()
-    assert L.dion_set_orth_mode(gp.state.handle, 2) == gp.B.DION_EINVAL
+    assert L.dion_set_orth_mode(gp.state.handle, 3) == gp.B.DION_EINVAL
+    assert L.dion_set_orth_mode(gp.state.handle, 2) == 0
     assert L.dion_set_orth_mode(None, 0) == gp.B.DION_EINVAL
     assert L.dion_set_orth_mode(gp.state.handle, 1) == 0
 
