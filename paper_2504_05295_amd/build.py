@@ -4,7 +4,9 @@
 
 Every .hip file under csrc/ is compiled to an object under _build/ (in parallel) and the objects
 are linked into paper_2504_05295_amd/libdion.so.  The checking program of the direct-load GEMM core
-(tests/native/gemm3_check.hip, run by a GPU test) is built next to its source.
+(tests/native/gemm3_check.hip, run by a GPU test) is built next to its source, and so is tests/native/host_san: the
+host-only entry points of the C ABI with the host half of dion_api.hip compiled under AddressSanitizer and
+UndefinedBehaviorSanitizer (device code is not instrumented), run by a CPU test.
 """
 from __future__ import annotations
 
@@ -20,6 +22,10 @@ BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libdion.so")
 CHECK_SRC = os.path.join(ROOT, "tests", "native", "gemm3_check.hip")
 CHECK_BIN = os.path.join(ROOT, "tests", "native", "gemm3_check")
+SAN_MAIN = os.path.join(ROOT, "tests", "native", "host_san_main.cpp")
+SAN_BIN = os.path.join(ROOT, "tests", "native", "host_san")
+SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined"]
+SAN_LINK = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-fno-gpu-sanitize"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -51,11 +57,23 @@ def build(verbose: bool = True, jobs: int | None = None) -> str:
         if os.path.exists(CHECK_SRC):
             _run([HIPCC] + [f for f in FLAGS if f != "-fPIC"] + [CHECK_SRC, "-o", CHECK_BIN])
 
+    san_objs = [os.path.join(BUILD, "dion_api_san.o"), os.path.join(BUILD, "host_san_main.o")]
+
+    def sanitized_host_objects(_):
+        if os.path.exists(SAN_MAIN):
+            flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g"]
+            _run([HIPCC] + flags + SAN_HOST + ["-c", os.path.join(CSRC, "dion_api.hip"), "-o", san_objs[0]])
+            _run([HIPCC, "-O1", "-g", "-std=c++17"] + SAN_LINK + ["-c", SAN_MAIN, "-o", san_objs[1]])
+
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        extra = ex.submit(check_program, None)
+        extra = [ex.submit(check_program, None), ex.submit(sanitized_host_objects, None)]
         list(ex.map(one, zip(srcs, objs)))
-        extra.result()
+        for e in extra:
+            e.result()
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB] + objs)
+    if os.path.exists(SAN_MAIN):
+        others = [o for o in objs if os.path.basename(o) != "dion_api.o"]
+        _run([HIPCC, "--offload-arch=gfx950"] + SAN_LINK + others + san_objs + ["-o", SAN_BIN])
     if verbose:
         print("built", LIB)
     return LIB

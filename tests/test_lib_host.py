@@ -3,6 +3,7 @@ include/dion.h declares, and its host-only entry points validate their arguments
 import ctypes as C
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -119,3 +120,19 @@ def test_null_state_is_rejected(lib):
     h = C.c_void_p(None)
     assert lib.dion_init_state(None, 0, None, None, None, 0, 0, None, 0, None, None, 1, 0, None) == B.DION_EINVAL
     assert lib.dion_init_state(C.byref(h), 1, None, None, None, 0, 0, None, 0, None, None, 1, 0, None) == B.DION_EINVAL
+
+
+def test_host_entry_points_under_the_sanitizers(lib):
+    """tests/native/host_san: the host-only entry points (workspace planning over a grid of shapes and batch sizes up to
+    the documented limits, the factorisation's grid planner, the argument checks in front of every other call) in a
+    build whose host code runs under AddressSanitizer and UndefinedBehaviorSanitizer."""
+    exe = os.path.join(ROOT, "tests", "native", "host_san")
+    if not os.path.exists(exe):
+        from paper_2504_05295_amd import build
+        build.build(verbose=False)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
+    p = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300, env=env)
+    print(p.stdout)
+    assert p.returncode == 0, p.stdout[-2000:]
+    assert "0 failed expectations" in p.stdout
+    assert "runtime error" not in p.stdout and "AddressSanitizer" not in p.stdout
