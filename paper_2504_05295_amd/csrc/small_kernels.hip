@@ -445,9 +445,42 @@ __global__ void __launch_bounds__(256) sum_bf16_kernel(void* const* table, int n
     *(u32x2_t*)(outT + (col0 + cc) * rows + row0 + r4) = w;
   }
 }
+// The same without a transposed copy: a plain streaming pass, eight elements per thread and step (32 + 16 bytes in,
+// 16 bytes out), nothing through LDS.
+template <bool GBF16>
+__global__ void __launch_bounds__(256) sum_bf16_stream_kernel(void* const* table, int nslots, int slot_m, int slot_g, int slot_out16,
+                                                              long long count8) {
+  void* const* tab = table + (size_t)blockIdx.y * nslots;
+  const f32x4_t* M = (const f32x4_t*)tab[slot_m];
+  const void* G = tab[slot_g];
+  u32x4_t* out = (u32x4_t*)tab[slot_out16];
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count8; i += stride) {
+    f32x4_t a = M[2 * i], b = M[2 * i + 1];
+    if constexpr (GBF16) {
+      const u32x4_t w = ((const u32x4_t*)G)[i];
+      a += f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
+      b += f32x4_t{bf16_lo(w[2]), bf16_hi(w[2]), bf16_lo(w[3]), bf16_hi(w[3])};
+    } else {
+      a += ((const f32x4_t*)G)[2 * i];
+      b += ((const f32x4_t*)G)[2 * i + 1];
+    }
+    out[i] = u32x4_t{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+  }
+}
 hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
                            int slot_outT16, long long rows, long long cols, hipStream_t s) {
   if (rows % 64 || cols % 64 || rows / 64 > 65535 || batch > 65535) return hipErrorInvalidValue;
+  if (slot_outT16 < 0) {
+    const long long count8 = rows * cols / 8;
+    long long blocks = (count8 + 255) / 256;
+    const long long cap = 256LL * 64 / (batch < 64 ? batch : 64) + 1;   // about 64 workgroups per compute unit over the whole launch
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((unsigned)blocks, batch);
+    if (gbf16) hipLaunchKernelGGL(sum_bf16_stream_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
+    else hipLaunchKernelGGL(sum_bf16_stream_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
+    return hipGetLastError();
+  }
   const dim3 grid((unsigned)(cols / 64), (unsigned)(rows / 64), batch);
   if (gbf16) hipLaunchKernelGGL(sum_bf16_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, slot_outT16, rows, cols);
   else hipLaunchKernelGGL(sum_bf16_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, slot_outT16, rows, cols);
