@@ -20,8 +20,8 @@
  * take it as an operand: in DION_MATH_F32, and in DION_MATH_BF16 for shapes whose outputs cannot fill the GPU with
  * 256 x 256 tiles, the sum is formed in registers on the way into the matrix cores; for the large shapes of
  * DION_MATH_BF16 (m, n multiples of 256, r a multiple of 256, at least 128 output tiles of 256 x 256 per group of
- * equal shapes) one pass first stores bf16(M + G) and its transpose in the workspace (4 bytes per element) and
- * the products read those.
+ * equal shapes) one pass first stores bf16(M + G) in the workspace, once and row-major (2 bytes per element), and
+ * both products read that copy (the product with (M + G)^T transposes it on the way from LDS into the registers).
  *
  * Conventions
  *   - All matrices are row-major and contiguous: X, G, M have leading dimension n, Q has r.

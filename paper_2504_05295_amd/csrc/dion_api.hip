@@ -77,8 +77,10 @@ struct Group {
   int first_row, count;
   GramPlan gram_m, gram_n;   // Gram products over the m x r matrices of a Dion step / the n x r ones of a Lazy-Dion refresh
   int k12_splitk;     // split-K of K1 / K2 on the large-tile path when their outputs have too few tiles
-  bool direct12;      // K1 / K2 may read bf16(M + G) and its transpose from memory (direct-load kernels): the shape
-                      // fills the GPU with 256 x 256 tiles and the copies fit the kernels' 32-bit offsets
+  bool direct12;      // K1 / K2 may read bf16(M + G) from memory (direct-load kernels): the shape fills the GPU with
+                      // 256 x 256 tiles and the copy fits the kernels' 32-bit offsets
+  bool big;           // the large-tile bf16 kernels serve this group (bf16 operand mode, tile-aligned shape): only then
+                      // are the bf16 operand copies carved
   size_t bytes_per_entry;
   Carve carve;     // slot offsets inside one matrix' share of the workspace
   size_t ws_off;   // offset of the group's first matrix in the workspace (set by dion_init_state)
@@ -155,23 +157,24 @@ Carve carve_entry(const Group& g) {
   take(SLOT_SPART, (size_t)((std::max(g.m, g.n) + COLNORM_CHUNK_MIN - 1) / COLNORM_CHUNK_MIN) * g.r);
   take(SLOT_S, g.r);
   take(SLOT_D, g.r);
-  // bf16 operand copies (two bf16 values per float slot)
-  take(SLOT_QT16, (nr + 1) / 2);
-  take(SLOT_P16, (xr + 1) / 2);
-  take(SLOT_PT16, (xr + 1) / 2);
-  take(SLOT_R16, (nr + 1) / 2);
-  take(SLOT_Q16, (nr + 1) / 2);
-  take(SLOT_ZL16, (xr + 1) / 2);
-  take(SLOT_ZLT16, (xr + 1) / 2);
-  take(SLOT_WH16, ((size_t)g.r * g.r + 1) / 2);
-  take(SLOT_WL16, ((size_t)g.r * g.r + 1) / 2);
+  // bf16 operand copies (two bf16 values per float slot): only the large-tile bf16 kernels read them
+  const size_t b = g.big ? 1 : 0;
+  take(SLOT_QT16, b * ((nr + 1) / 2));
+  take(SLOT_P16, b * ((xr + 1) / 2));
+  take(SLOT_PT16, b * ((xr + 1) / 2));
+  take(SLOT_R16, b * ((nr + 1) / 2));
+  take(SLOT_Q16, b * ((nr + 1) / 2));
+  take(SLOT_ZL16, b * ((xr + 1) / 2));
+  take(SLOT_ZLT16, b * ((xr + 1) / 2));
+  take(SLOT_WH16, b * (((size_t)g.r * g.r + 1) / 2));
+  take(SLOT_WL16, b * (((size_t)g.r * g.r + 1) / 2));
   take(SLOT_EPART, GRAM_DEFECT_PARTS);
   take(SLOT_FAST, 1);
   // split-k partial results of K1 / K2: whole partial matrices off the direct-load path; on it (one matrix only) the
   // partial 256 x 256 tiles of a split last round, at most 256 of them
-  take(SLOT_KPART, g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : (g.direct12 && g.count == 1) ? (size_t)256 * 256 * 256 : 0);
+  take(SLOT_KPART, !g.big ? 0 : g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : (g.direct12 && g.count == 1) ? (size_t)256 * 256 * 256 : 0);
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
-  take(SLOT_B16, ((size_t)g.m * g.n + 1) / 2);
+  take(SLOT_B16, b * (((size_t)g.m * g.n + 1) / 2));
   take(SLOT_B16T, 0);   // (no transposed copy: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
   take(SLOT_THR, g.rp);
   take(SLOT_NULL, g.rp);
@@ -192,8 +195,8 @@ bool shapes_ok(int count, const int64_t* m, const int64_t* n, const int64_t* r) 
   return true;
 }
 
-bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r, const int* form, std::vector<Entry>& entries,
-                std::vector<Group>& groups) {
+bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r, const int* form, int math,
+                std::vector<Entry>& entries, std::vector<Group>& groups) {
   entries.resize(count);
   groups.clear();
   for (int i = 0; i < count; ++i) {
@@ -207,6 +210,7 @@ bool build_plan(int count, const int64_t* m, const int64_t* n, const int64_t* r,
       g.m = m[i]; g.n = n[i]; g.r = r[i];
       g.form = f;
       g.rp = padded_rank(r[i]);
+      g.big = math == DION_MATH_BF16 && g.m % 256 == 0 && g.n % 256 == 0 && g.r % 128 == 0;
       groups.push_back(g);
       gi = (int)groups.size() - 1;
     }
@@ -268,7 +272,7 @@ int plan_state(dion_state* st, int count, const int64_t* m, const int64_t* n, co
                int math, void* workspace_dev, size_t workspace_bytes, void* const* M_dev, void* const* Q_dev,
                std::vector<void*>& host) {
   st->count = count; st->g_dtype = g_dtype; st->math = math;
-  build_plan(count, m, n, r, form, st->entries, st->groups);
+  build_plan(count, m, n, r, form, math, st->entries, st->groups);
   st->ws = (char*)workspace_dev;
   st->ws_bytes = workspace_bytes;
   st->table = (void**)st->ws;
@@ -648,7 +652,7 @@ RowCtx make_ctx(dion_state* st, int gi, int row0, int batch, hipStream_t s) {
   c.tab = st->table + (size_t)(c.g->first_row + row0) * NSLOTS;
   c.bf16 = st->math == DION_MATH_BF16;
   c.gbf16 = st->g_dtype == DION_G_BF16;
-  c.big = c.bf16 && c.g->m % 256 == 0 && c.g->n % 256 == 0 && c.g->r % 128 == 0;
+  c.big = c.g->big;
   c.base = rebase(base_args(st, *c.g), row0);
   c.ev = st->timing ? &st->events[(size_t)gi * kEventsPerGroup] : nullptr;
   return c;
@@ -1074,7 +1078,7 @@ int dion_workspace_bytes(int count, const int64_t* m, const int64_t* n, const in
   try {
     std::vector<Entry> entries;
     std::vector<Group> groups;
-    build_plan(count, m, n, r, nullptr, entries, groups);   // the form does not change any size
+    build_plan(count, m, n, r, nullptr, math, entries, groups);   // the form does not change any size
     size_t total = header_bytes(count);
     for (auto& g : groups) total += g.bytes_per_entry * g.count;
     *bytes_out = total + 256;
