@@ -175,7 +175,6 @@ Carve carve_entry(const Group& g) {
   take(SLOT_KPART, !g.big ? 0 : g.k12_splitk > 1 ? (size_t)g.k12_splitk * std::max(mr, nr) : (g.direct12 && g.count == 1) ? (size_t)256 * 256 * 256 : 0);
   take(SLOT_SYNC, 2 * (size_t)sync_words(g.rp / CHOL_NB));
   take(SLOT_B16, b * (((size_t)g.m * g.n + 1) / 2));
-  take(SLOT_B16T, 0);   // (no transposed copy: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
   take(SLOT_THR, g.rp);
   take(SLOT_NULL, g.rp);
   take(SLOT_GATE, 1);
@@ -681,7 +680,7 @@ bool direct12(const RowCtx& c) {
 // The bf16 copy of M + G for the K1 / K2 of this call (a no-op off the direct-load path).
 int stage_b16(const RowCtx& c) {
   if (!direct12(c)) return DION_OK;
-  HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, -1, c.g->m, c.g->n, c.s));
+  HIPCHK(launch_sum_bf16(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, c.g->m, c.g->n, c.s));
   return DION_OK;
 }
 

@@ -39,8 +39,8 @@ enum Slot {
   SLOT_FAST,   // int32: 1 when the last Cholesky-QR pass found its input orthonormal to the tolerance
   SLOT_KPART,  // split-K partial results of K1 / K2 (small outputs that cannot fill the GPU otherwise)
   SLOT_SYNC,   // flags of the single-launch Cholesky factorisation (64-bit words)
-  SLOT_B16,    // bf16(M + G), m x n: A operand of K1 on the direct-load path; else written by K1 on its way for K2
-  SLOT_B16T,   // (unused: the product with (M + G)^T reads SLOT_B16 with k as the slow index)
+  SLOT_B16,    // bf16(M + G), m x n: operand of K1 and (read with k as the slow index) of K2 on the direct-load path; else
+               // written by K1 on its way for K2
   SLOT_THR,    // rp floats: pivot thresholds of the factorisation that tolerates dependent columns
   SLOT_NULL,   // rp int32: 1 for the columns that factorisation found dependent on the ones before them
   SLOT_GATE,   // int32: 0 when the orthonormalisation of this matrix has to be redone by the fallback passes, else 1
@@ -124,9 +124,9 @@ hipError_t launch_fill(void* const* table, int nslots, int batch, int slot, long
 // out <- in unless *status != 0 (both 16-byte aligned)
 hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot_in, int slot_out, long long count, int status_slot,
                              hipStream_t s);
-// out16 = bf16(M + G) as [rows][cols]; outT16 (if >= 0) = the same as [cols][rows]  (rows, cols multiples of 64)
+// out16 = bf16(M + G) as [rows][cols]  (rows * cols a multiple of 8)
 hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
-                           int slot_outT16, long long rows, long long cols, hipStream_t s);
+                           long long rows, long long cols, hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
 // (skip_slot >= 0 here and below: the int32 there non-zero means that the launch leaves this matrix alone)

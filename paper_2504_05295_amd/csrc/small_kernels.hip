@@ -405,48 +405,10 @@ hipError_t launch_convert_bf16(void* const* table, int nslots, int batch, int sl
   return hipGetLastError();
 }
 
-// bf16(M + G) as [rows][cols] and as [cols][rows], 64x64 tiles transposed through LDS: the accumulated buffer
-// B = M + G of the step (Algorithm 1) rounded once to the operand precision of the bf16 products, in the two
-// layouts in which B Q and B^T P read it with the contraction index contiguous.
-template <bool GBF16>
-__global__ void __launch_bounds__(256) sum_bf16_kernel(void* const* table, int nslots, int slot_m, int slot_g, int slot_out16,
-                                                       int slot_outT16, long long rows, long long cols) {
-  void* const* tab = table + (size_t)blockIdx.z * nslots;
-  const float* M = (const float*)tab[slot_m];
-  const void* G = tab[slot_g];
-  uint16_t* out16 = (uint16_t*)tab[slot_out16];
-  uint16_t* outT = slot_outT16 >= 0 ? (uint16_t*)tab[slot_outT16] : nullptr;   // (the same for the whole grid)
-  __shared__ float tile[64][65];
-  const long long row0 = (long long)blockIdx.y * 64, col0 = (long long)blockIdx.x * 64;
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int rr = p * 16 + (t >> 4), c4 = (t & 15) * 4;
-    const long long idx = (row0 + rr) * cols + col0 + c4;
-    f32x4_t v = *(const f32x4_t*)(M + idx);
-    if constexpr (GBF16) {
-      const u32x2_t w = *(const u32x2_t*)((const uint16_t*)G + idx);
-      v += f32x4_t{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
-    } else {
-      v += *(const f32x4_t*)((const float*)G + idx);
-    }
-    // the transposed copy is made from the rounded values, so that both copies hold the same numbers
-    const u32x2_t w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-    *(u32x2_t*)(out16 + idx) = w;
-    tile[rr][c4 + 0] = bf16_lo(w[0]); tile[rr][c4 + 1] = bf16_hi(w[0]);
-    tile[rr][c4 + 2] = bf16_lo(w[1]); tile[rr][c4 + 3] = bf16_hi(w[1]);
-  }
-  if (!outT) return;
-  __syncthreads();
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int cc = p * 16 + (t >> 4), r4 = (t & 15) * 4;
-    u32x2_t w = {pack_bf16x2(tile[r4 + 0][cc], tile[r4 + 1][cc]), pack_bf16x2(tile[r4 + 2][cc], tile[r4 + 3][cc])};
-    *(u32x2_t*)(outT + (col0 + cc) * rows + row0 + r4) = w;
-  }
-}
-// The same without a transposed copy: a plain streaming pass, eight elements per thread and step (32 + 16 bytes in,
-// 16 bytes out), nothing through LDS.
+// bf16(M + G), row-major: the accumulated buffer B = M + G of the step (Algorithm 1) rounded once to the operand
+// precision of the bf16 products; B Q reads it with its contraction index contiguous, B^T P with that index as the
+// slow one.  A plain streaming pass, eight elements per thread and step (32 + 16 bytes in, 16 bytes out), nothing
+// through LDS.
 template <bool GBF16>
 __global__ void __launch_bounds__(256) sum_bf16_stream_kernel(void* const* table, int nslots, int slot_m, int slot_g, int slot_out16,
                                                               long long count8) {
@@ -469,21 +431,15 @@ __global__ void __launch_bounds__(256) sum_bf16_stream_kernel(void* const* table
   }
 }
 hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
-                           int slot_outT16, long long rows, long long cols, hipStream_t s) {
-  if (rows % 64 || cols % 64 || rows / 64 > 65535 || batch > 65535) return hipErrorInvalidValue;
-  if (slot_outT16 < 0) {
-    const long long count8 = rows * cols / 8;
-    long long blocks = (count8 + 255) / 256;
-    const long long cap = 256LL * 64 / (batch < 64 ? batch : 64) + 1;   // about 64 workgroups per compute unit over the whole launch
-    if (blocks > cap) blocks = cap;
-    const dim3 grid((unsigned)blocks, batch);
-    if (gbf16) hipLaunchKernelGGL(sum_bf16_stream_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
-    else hipLaunchKernelGGL(sum_bf16_stream_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
-    return hipGetLastError();
-  }
-  const dim3 grid((unsigned)(cols / 64), (unsigned)(rows / 64), batch);
-  if (gbf16) hipLaunchKernelGGL(sum_bf16_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, slot_outT16, rows, cols);
-  else hipLaunchKernelGGL(sum_bf16_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, slot_outT16, rows, cols);
+                           long long rows, long long cols, hipStream_t s) {
+  if (rows * cols % 8 || batch > 65535 || batch < 1) return hipErrorInvalidValue;
+  const long long count8 = rows * cols / 8;
+  long long blocks = (count8 + 255) / 256;
+  const long long cap = 256LL * 64 / (batch < 64 ? batch : 64) + 1;   // about 64 workgroups per compute unit over the whole launch
+  if (blocks > cap) blocks = cap;
+  const dim3 grid((unsigned)blocks, batch);
+  if (gbf16) hipLaunchKernelGGL(sum_bf16_stream_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
+  else hipLaunchKernelGGL(sum_bf16_stream_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, count8);
   return hipGetLastError();
 }
 
