@@ -2,7 +2,8 @@
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions), for the products of the Dion
 // step whose operands are both bf16 matrices with k contiguous:
 //   the Gram matrix and the triangular multiply of Cholesky-QR (up to three split-bf16 operand pairs),
-//   Z = (M+G) Q and R = (M+G)^T P from the two bf16 copies of M + G (m x n and n x m) that one pass writes first,
+//   Z = (M+G) Q and R = (M+G)^T P from the bf16 copy of M + G that one pass writes first (R reads it with k as the
+//   slow index),
 //   the fused rank-r updates of M and X (A = P, B = R, B2 = Q_new).
 // Conventions as in gemm_core2.hpp: C[i,j] = sum_k A(i,k) B(j,k), same GemmArgs, same epilogues.
 //
