@@ -86,3 +86,10 @@ def test_structured_gradient_fp32():
 def test_c3_8192_bf16_steps(r):
     # full-size configuration, same launch configuration as the benchmark; oracle uses LAPACK's QR here
     run_trajectory((8192, 8192, r), True, "bf16", 2, "lapack")
+
+
+@pytest.mark.parametrize("shape", [(200, 136, 24), (1024, 768, 256), (8192, 8192, 1024)])
+def test_fp32_gradient_with_bf16_operands(shape):
+    # the gradient's storage type and the operand type of the products are independent: fp32 G on the ragged path, on the
+    # 128-wide-tile path and on the direct-load path (where the copy pass adds an fp32 G)
+    run_trajectory(shape, False, "bf16", 2, "lapack" if shape[0] > 512 else "householder")
