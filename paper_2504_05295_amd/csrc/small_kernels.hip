@@ -285,8 +285,18 @@ __global__ void __launch_bounds__(256) colnorm_final_kernel(void* const* table, 
   const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
   float acc = 0.f;
-  if (col < r)
-    for (int c = ry; c < nchunks; c += 4) acc += part[(long long)c * r + col];
+  if (col < r) {
+    // eight loads in flight per thread (a single running sum would make the pass a chain of load latencies); the
+    // order of the additions is fixed
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int c = ry;
+    for (; c + 28 < nchunks; c += 32) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += part[(long long)(c + 4 * u) * r + col];
+    }
+    for (int u = 0; c < nchunks; c += 4, ++u) a[u] += part[(long long)c * r + col];
+    acc = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  }
   red[ry][cx] = acc;
   __syncthreads();
   if (ry == 0 && col < r) {
