@@ -108,6 +108,26 @@ def test_c4_llama_mlp_stagewise(r):
         print("update %s: %d segments, worst X %.2e M %.2e dX %.2e dM %.2e" % (name, ex.size, ex.max(), em.max(), edx.max(), edm.max()), flush=True)
         assert ex.max() <= TOL and em.max() <= TOL
         assert edx.max() <= TOL + 1e-3 and edm.max() <= TOL     # (dX: plus the fp32 rounding of X, see above)
+    # whole-matrix digests: M_new y and X_new y for Gaussian probe vectors y against the update rule evaluated in fp64
+    # from the factors (E ||E y||^2 = ||E||_F^2 for Gaussian y, so an error anywhere in the matrices shows up here)
+    def matvec(A, y, extra=None):                     # fp64 product of an fp32 (or bf16-as-fp32) matrix, by row blocks
+        out = np.empty(A.shape[0])
+        for i in range(0, A.shape[0], 1024):
+            blk = A[i:i + 1024].astype(np.float64)
+            if extra is not None:
+                blk += extra[i:i + 1024]
+            out[i:i + 1024] = blk @ y
+        return out
+    P64r, R64, Q64 = P.astype(np.float64), R.astype(np.float64), Q.astype(np.float64)
+    for probe in range(2):
+        y = np.random.default_rng(100 + probe).standard_normal(n)
+        by = matvec(m_in, y, g32)                                   # (M + G) y
+        pr_y = P64r @ (R64.T @ y)
+        pq_y = P64r @ (Q64.T @ y)
+        em = np.linalg.norm(matvec(M, y) - (by - (1 - MU) * pr_y)) / np.linalg.norm((1 - MU) * pr_y)
+        ex = np.linalg.norm((matvec(X, y) - matvec(x_in, y)) + ETA * np.sqrt(m / n) * pq_y) / np.linalg.norm(ETA * np.sqrt(m / n) * pq_y)
+        print("probe %d: error of the M update %.2e, of the X update %.2e (relative to the update's image of y)" % (probe, em, ex), flush=True)
+        assert em <= TOL and ex <= TOL + 1e-2          # (X: plus the fp32 rounding of X itself, as above)
     # whole-matrix invariant of the step: ||X_new - X|| = eta sqrt(m/n) sqrt(r)  (P orthonormal, Q unit columns)
     dxn = np.linalg.norm(X.astype(np.float64) - x_in)
     assert abs(dxn / (ETA * np.sqrt(m / n) * np.sqrt(r)) - 1) <= 1e-2
