@@ -491,3 +491,21 @@ def test_measured_ceilings_are_plausible():
     assert 1500.0 < c["stream_gbps"] < 8100.0
     with pytest.raises(B.DionError):
         B.dion_measure_ceilings(scratch[: 1 << 20])
+
+
+def test_empty_batch_is_a_no_op():
+    import torch
+    from paper_2504_05295_amd import binding as B
+    lib = B.lib()
+    need = C.c_size_t(0)
+    assert lib.dion_workspace_bytes(0, None, None, None, B.DION_G_F32, B.DION_MATH_F32, C.byref(need)) == B.DION_OK
+    ws = torch.empty(need.value + 256, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    h = C.c_void_p(None)
+    assert lib.dion_init_state(C.byref(h), 0, None, None, None, B.DION_G_F32, B.DION_MATH_F32, C.c_void_p(base), need.value,
+                               None, None, 1, 0, None) == B.DION_OK
+    assert lib.dion_step_batched(h, 0, None, None, None, None, None, None, None, C.c_float(0.95), C.c_float(0.01), None) == B.DION_OK
+    status, bad = C.c_int(7), C.c_int(7)
+    assert lib.dion_last_status(h, C.byref(status), C.byref(bad)) == B.DION_OK
+    assert (status.value, bad.value) == (0, -1)
+    assert lib.dion_destroy_state(h) == B.DION_OK

@@ -93,3 +93,7 @@ def test_fp32_gradient_with_bf16_operands(shape):
     # the gradient's storage type and the operand type of the products are independent: fp32 G on the ragged path, on the
     # 128-wide-tile path and on the direct-load path (where the copy pass adds an fp32 G)
     run_trajectory(shape, False, "bf16", 2, "lapack" if shape[0] > 512 else "householder")
+
+
+def test_bf16_gradient_with_fp32_math_on_a_ragged_shape():
+    run_trajectory((200, 136, 24), True, "f32", 3, "householder")
