@@ -511,13 +511,13 @@ __device__ __forceinline__ void gemm3_store_split(uint16_t* hi, uint16_t* lo, lo
 }
 
 // Adds up the partial tiles of a launch's last round (GemmArgs::tail_*) into the result, in a fixed order, and forms
-// the per-column sums of squares that the main kernel's epilogue forms for whole tiles.  One workgroup of 256 threads
-// per tail tile and block of WTM rows: a thread owns four consecutive columns of every RPP-th row.
+// the per-column sums of squares that the main kernel's epilogue forms for whole tiles.  One workgroup of 1024 threads
+// per tail tile and block of WTM rows (there are few such blocks, and each has half a megabyte to read): a thread owns four consecutive columns of every RPP-th row.
 template <class Cfg>
-__global__ void __launch_bounds__(256) gemm3_tail_reduce_kernel(const GemmArgs g) {
+__global__ void __launch_bounds__(1024) gemm3_tail_reduce_kernel(const GemmArgs g) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, WTM = Cfg::WTM;
-  constexpr int TPR = BN / 4, RPP = 256 / TPR;   // threads per row, rows per pass
-  static_assert(256 % TPR == 0 && WTM % RPP == 0, "tile shape");
+  constexpr int TPR = BN / 4, RPP = 1024 / TPR;   // threads per row, rows per pass
+  static_assert(1024 % TPR == 0 && WTM % RPP == 0, "tile shape");
   void* const* tab = g.table;
   if (g.status_slot >= 0 && *(const int*)tab[g.status_slot] != 0) return;
   if (g.noop_slot >= 0 && *(const int*)tab[g.noop_slot] != 0) return;
@@ -635,7 +635,7 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   e = hipGetLastError();
   if (e != hipSuccess || g.tail_split < 2) return e;
   if constexpr (EPI == EPI_STORE && !DUAL) {
-    hipLaunchKernelGGL((gemm3_tail_reduce_kernel<Cfg>), dim3(g.tail_tiles, Cfg::BM / Cfg::WTM), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL((gemm3_tail_reduce_kernel<Cfg>), dim3(g.tail_tiles, Cfg::BM / Cfg::WTM), dim3(1024), 0, stream, g);
     e = hipGetLastError();
   }
   return e;
