@@ -1,6 +1,6 @@
 """Builds libdion.so (the HIP kernels and their C ABI) for gfx950, in-tree.
 
-    python -m paper_2504_05295_amd.build
+    python -m paper_2504_05295_amd.build [--host-trap]
 
 Every .hip file under csrc/ is compiled to an object under _build/ (in parallel) and the objects
 are linked into paper_2504_05295_amd/libdion.so.  The checking program of the direct-load GEMM core
@@ -40,15 +40,20 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = True, jobs: int | None = None) -> str:
+def build(verbose: bool = True, jobs: int | None = None, host_trap: bool = False) -> str:
+    """host_trap: the host half of every source is compiled so that undefined behaviour (integer overflow, division by
+    zero, misaligned or null accesses ...) traps; device code is untouched.  For a run of the GPU tests that also checks
+    the host sequencing; rebuild without it afterwards."""
     os.makedirs(BUILD, exist_ok=True)
     srcs = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
     objs = [os.path.join(BUILD, f[:-4] + ".o") for f in srcs]
     jobs = jobs or min(8, len(srcs))
 
+    trap = ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=undefined"] if host_trap else []
+
     def one(pair):
         src, obj = pair
-        out = _run([HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj])
+        out = _run([HIPCC] + FLAGS + trap + ["-c", os.path.join(CSRC, src), "-o", obj])
         if verbose and out.strip():
             print(out)
         return obj
@@ -80,5 +85,5 @@ def build(verbose: bool = True, jobs: int | None = None) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(host_trap="--host-trap" in sys.argv[1:])
     sys.exit(0)
