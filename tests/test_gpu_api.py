@@ -509,3 +509,41 @@ def test_empty_batch_is_a_no_op():
     assert lib.dion_last_status(h, C.byref(status), C.byref(bad)) == B.DION_OK
     assert (status.value, bad.value) == (0, -1)
     assert lib.dion_destroy_state(h) == B.DION_OK
+
+
+def test_fallback_mode_in_a_bf16_batch_on_the_large_tile_path():
+    # three matrices on the 128-wide-tile bf16 path, the middle one with cond(B Q) of a few 1e4: the fallback passes run
+    # in fp32 for that one only, gated per matrix; its neighbours come out exactly as in the default mode
+    shape = (1024, 768, 256)
+    m, n, r = shape
+    out = {}
+    for mode in (0, 2):
+        gp = GpuProblem([shape] * 3, True, "bf16")
+        gp.B.dion_set_orth_mode(gp.state, mode)
+        grads = gp.grads_np(0)
+        grads[1] = inputs.structured_gradient(m, n, 0, k=r, noise=1e-4, decay=1.0, bf16=True)
+        gp.upload_grads(grads)
+        before = [gp.host(i) for i in range(3)]
+        out[mode] = (gp, gp.step(MU, ETA, batched=True), before, grads)
+    assert out[0][1] == (out[0][0].B.DION_NUM_BREAKDOWN, 1)
+    gp, outcome, before, grads = out[2]
+    assert outcome == (0, -1)
+    for i in (0, 2):
+        for u, v in zip(out[0][0].host(i), gp.host(i)):
+            assert np.array_equal(u, v)
+    B = gp.B
+    x_in, m_in, q_in = before[1]
+    g32 = inputs.bf16_bits_to_f32(grads[1]).astype(np.float64)
+    Bm = m_in.astype(np.float64) + g32
+    Z = out[0][0].debug(1, B.DEBUG_Z)[:, :r].astype(np.float64)     # the default-mode run formed the same Z and kept it
+    P = gp.debug(1, B.DEBUG_P)[:, :r].astype(np.float64)
+    R = gp.debug(1, B.DEBUG_R)[:, :r].astype(np.float64)
+    X, M, Q = gp.host(1)
+    w = np.linalg.eigvalsh(Z.T @ Z)
+    assert 3e3 < np.sqrt(w[-1] / w[0]) < 1e5
+    T = P.T @ Z
+    assert np.abs(P.T @ P - np.eye(r)).max() < 1e-5 and relf(P @ np.triu(T), Z) < 1e-5 and np.min(np.diag(T)) > 0
+    assert relf(R, Bm.T @ P) < 2e-2 and relf(M, Bm - (1 - MU) * P @ R.T) < 2e-2
+    Qn, _ = orc.col_norm(R)
+    assert relf(Q, Qn) < 1e-5
+    assert relf(X.astype(np.float64) - x_in, -ETA * np.sqrt(m / n) * P @ Q.astype(np.float64).T) < 2e-2
