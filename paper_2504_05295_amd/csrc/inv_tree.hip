@@ -6,9 +6,10 @@
 // at level l blocks of 64 * 2^l (the last one may be shorter; a block without a right-hand neighbour waits for
 // the next level).  A merge is two products of triangular with full matrices, T = C A^-1 and then -D^-1 T,
 // cut into 64 x 64 output tiles that skip the zero tiles of the triangular operand; the tiles of all merges
-// of a level go round-robin over the workgroups of the matrix.  Between the two products, and between levels,
-// the workgroups of a matrix meet at a barrier made of one arrival word per workgroup (tagged with the
-// launch's epoch, so never cleared); what crosses between workgroups is written and read with device-scope accesses.
+// of a level are dealt out to the workgroups of the matrix by length, so that each gets about the same work.
+// Between the two products, and between levels, the workgroups of a matrix meet at a barrier made of one arrival
+// word per workgroup (tagged with the launch's epoch, so never cleared); what crosses between workgroups is
+// written and read with device-scope accesses.
 // Waits are bounded as in the factorisation kernel: who gives up raises the abort word, the others follow,
 // and the matrix is reported with the wait-timeout status.  All workgroups of a launch must be resident at once (the host keeps
 // the grid within one workgroup per compute unit).
@@ -179,11 +180,17 @@ __global__ void __launch_bounds__(256) inv_tree_kernel(InvTreeArgs p) {
   };
 
   for (int S = 1; S < nb; S *= 2) {
-    const int nblocks = (nb + S - 1) / S, npairs = nblocks / 2, per_pair = S * S;
+    const int nblocks = (nb + S - 1) / S, npairs = nblocks / 2, per_cost = npairs * S, total = per_cost * S;
     for (int phase = 0; phase < 2; ++phase) {
-      for (int id = x.wg; id < npairs * per_pair; id += x.groups) {
-        const int q = id / per_pair, rem = id % per_pair;
-        const int ti = rem / S, tj = rem % S;
+      // A tile of the first product sums S - tj tile pairs, one of the second ti + 1.  The tiles are ranked by that
+      // length, longest first, and dealt out back and forth (round 0 to workgroups 0, 1, ..., round 1 to ..., 1, 0),
+      // so that every workgroup gets about the same number of pairs.
+      for (int round = 0; round * x.groups < total; ++round) {
+        const int rank = round * x.groups + ((round & 1) ? x.groups - 1 - x.wg : x.wg);
+        if (rank >= total) continue;
+        const int len = rank / per_cost, rem = rank % per_cost;
+        const int q = rem / S, other = rem % S;
+        const int ti = phase == 0 ? other : S - 1 - len, tj = phase == 0 ? len : other;
         const int a0 = 2 * q * S, d0 = a0 + S;
         const int sd = min(S, nb - d0);
         if (ti >= sd) continue;
