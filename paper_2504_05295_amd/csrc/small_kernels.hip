@@ -203,32 +203,45 @@ hipError_t launch_shift_diagonal(void* const* table, int nslots, int batch, int 
 }
 
 // ---------------------------------------------------------------- split-K reduction (fixed order => deterministic)
-// Lower triangle only (that is what is produced and consumed); a block takes rows, a thread four columns at a time.
+// Sum of nsplit partial results `stride` floats apart, added in the order of the splits; eight loads are in flight
+// at a time (a split beyond the last contributes +0, which changes no sum).
+template <class T>
+__device__ __forceinline__ T sum_planes(const float* p, long long stride, int nsplit) {
+  T acc = T{};
+  for (int sp = 0; sp < nsplit; sp += 8) {
+    T v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = sp + u < nsplit ? gload<T>(p + (long long)(sp + u) * stride) : T{};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  return acc;
+}
+// Lower triangle only (that is what is produced and consumed), in pieces of four columns: consecutive threads take
+// consecutive pieces of a row, pieces above the diagonal are skipped.
 __global__ void __launch_bounds__(256) reduce_partials_kernel(void* const* table, int nslots, int slot_part, int slot_out, int r,
                                                               long long ld, int nsplit, long long split_stride, int skip_slot) {
   if (skip_slot >= 0 && *(const int*)table[(size_t)blockIdx.y * nslots + skip_slot] != 0) return;
   const float* part = (const float*)table[(size_t)blockIdx.y * nslots + slot_part];
   float* out = (float*)table[(size_t)blockIdx.y * nslots + slot_out];
-  for (int i = blockIdx.x; i < r; i += gridDim.x)
-    for (int j0 = threadIdx.x * 4; j0 <= i; j0 += 1024) {
-      const long long idx = (long long)i * ld + j0;
-      if (j0 + 3 <= i) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int sp = 0; sp < nsplit; ++sp) acc += gload<f32x4_t>(part + sp * split_stride + idx);
-        gstore<f32x4_t>(out + idx, acc);
-      } else {
-        for (int j = j0; j <= i; ++j) {
-          float acc = 0.f;
-          for (int sp = 0; sp < nsplit; ++sp) acc += part[sp * split_stride + idx + (j - j0)];
-          out[idx + (j - j0)] = acc;
-        }
-      }
+  const int ppr = (r + 3) / 4;   // pieces per row
+  const long long total = (long long)r * ppr;
+  for (long long w = (long long)blockIdx.x * 256 + threadIdx.x; w < total; w += (long long)gridDim.x * 256) {
+    const int i = (int)(w / ppr), j0 = 4 * (int)(w % ppr);
+    if (j0 > i) continue;
+    const long long idx = (long long)i * ld + j0;
+    if (j0 + 3 <= i) {
+      gstore<f32x4_t>(out + idx, sum_planes<f32x4_t>(part + idx, split_stride, nsplit));
+    } else {
+      for (int j = j0; j <= i; ++j) out[idx + (j - j0)] = sum_planes<float>(part + idx + (j - j0), split_stride, nsplit);
     }
+  }
 }
 hipError_t launch_reduce_partials(void* const* table, int nslots, int batch, int slot_part, int slot_out, int r, long long ld,
                                   int nsplit, long long split_stride, hipStream_t s, int skip_slot) {
   if (ld % 4 || split_stride % 4) return hipErrorInvalidValue;
-  const int blocks = r < 2048 ? r : 2048;
+  long long blocks = ((long long)r * ((r + 3) / 4) + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)blocks, batch), dim3(256), 0, s, table, nslots, slot_part, slot_out, r,
                      ld, nsplit, split_stride, skip_slot);
   return hipGetLastError();
@@ -511,40 +524,41 @@ __global__ void __launch_bounds__(256) gram_defect_kernel(void* const* table, in
   float* part = (float*)tab[SLOT_EPART];
   __shared__ float red[256];
   float acc = 0.f;
-  // a block takes rows, a thread four columns of the lower triangle at a time
-  for (int i = blockIdx.x; i < r; i += gridDim.x)
-    for (int j0 = threadIdx.x * 4; j0 <= i; j0 += 1024) {
-      const long long idx = (long long)i * ld + j0;
-      if (j0 + 3 <= i) {
-        f32x4_t c;
-        if (nsplit > 1) {
-          c = f32x4_t{0.f, 0.f, 0.f, 0.f};
-          for (int sp = 0; sp < nsplit; ++sp) c += gload<f32x4_t>(cpart + sp * split_stride + idx);
-          gstore<f32x4_t>(C + idx, c);
-        } else {
-          c = gload<f32x4_t>(C + idx);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool diag = j0 + e == i;
-          const float d = c[e] - (diag ? 1.f : 0.f);
-          acc += (diag ? 1.f : 2.f) * d * d;
-        }
+  // the lower triangle in pieces of four columns, consecutive threads on consecutive pieces of a row
+  const int ppr = (r + 3) / 4;
+  const long long total = (long long)r * ppr;
+  for (long long w = (long long)blockIdx.x * 256 + threadIdx.x; w < total; w += (long long)gridDim.x * 256) {
+    const int i = (int)(w / ppr), j0 = 4 * (int)(w % ppr);
+    if (j0 > i) continue;
+    const long long idx = (long long)i * ld + j0;
+    if (j0 + 3 <= i) {
+      f32x4_t c;
+      if (nsplit > 1) {
+        c = sum_planes<f32x4_t>(cpart + idx, split_stride, nsplit);
+        gstore<f32x4_t>(C + idx, c);
       } else {
-        for (int j = j0; j <= i; ++j) {
-          float c;
-          if (nsplit > 1) {
-            c = 0.f;
-            for (int sp = 0; sp < nsplit; ++sp) c += cpart[sp * split_stride + idx + (j - j0)];
-            C[idx + (j - j0)] = c;
-          } else {
-            c = C[idx + (j - j0)];
-          }
-          const float d = c - (i == j ? 1.f : 0.f);
-          acc += (i == j ? 1.f : 2.f) * d * d;
+        c = gload<f32x4_t>(C + idx);
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool diag = j0 + e == i;
+        const float d = c[e] - (diag ? 1.f : 0.f);
+        acc += (diag ? 1.f : 2.f) * d * d;
+      }
+    } else {
+      for (int j = j0; j <= i; ++j) {
+        float c;
+        if (nsplit > 1) {
+          c = sum_planes<float>(cpart + idx + (j - j0), split_stride, nsplit);
+          C[idx + (j - j0)] = c;
+        } else {
+          c = C[idx + (j - j0)];
         }
+        const float d = c - (i == j ? 1.f : 0.f);
+        acc += (i == j ? 1.f : 2.f) * d * d;
       }
     }
+  }
   red[threadIdx.x] = acc;
   __syncthreads();
   for (int sft = 128; sft > 0; sft >>= 1) {
