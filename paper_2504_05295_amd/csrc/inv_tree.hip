@@ -16,6 +16,7 @@
 #include <type_traits>
 
 #include "internal.hpp"
+#include "inv_tree_order.hpp"
 
 namespace dion {
 
@@ -180,20 +181,12 @@ __global__ void __launch_bounds__(256) inv_tree_kernel(InvTreeArgs p) {
   };
 
   for (int S = 1; S < nb; S *= 2) {
-    const int nblocks = (nb + S - 1) / S, npairs = nblocks / 2, per_cost = npairs * S, total = per_cost * S;
+    const int rounds = inv_tree_rounds(nb, S, x.groups);
     for (int phase = 0; phase < 2; ++phase) {
-      // A tile of the first product sums S - tj tile pairs, one of the second ti + 1.  The tiles are ranked by that
-      // length, longest first, and dealt out back and forth (round 0 to workgroups 0, 1, ..., round 1 to ..., 1, 0),
-      // so that every workgroup gets about the same number of pairs.
-      for (int round = 0; round * x.groups < total; ++round) {
-        const int rank = round * x.groups + ((round & 1) ? x.groups - 1 - x.wg : x.wg);
-        if (rank >= total) continue;
-        const int len = rank / per_cost, rem = rank % per_cost;
-        const int q = rem / S, other = rem % S;
-        const int ti = phase == 0 ? other : S - 1 - len, tj = phase == 0 ? len : other;
+      for (int round = 0; round < rounds; ++round) {
+        int q, ti, tj;
+        if (!inv_tree_tile(nb, S, phase, x.groups, x.wg, round, q, ti, tj)) continue;
         const int a0 = 2 * q * S, d0 = a0 + S;
-        const int sd = min(S, nb - d0);
-        if (ti >= sd) continue;
         if (phase == 0) {
           // T[d0+ti][a0+tj] = sum_{k=tj}^{S-1} L[d0+ti][a0+k] W[a0+k][a0+tj]      (A^-1 is lower triangular)
           product(std::false_type{}, L, d0 + ti, a0, W, a0, a0 + tj, tj, S - 1, T + ((long long)(d0 + ti) * ld + (a0 + tj)) * CB, 1.f);

@@ -4,14 +4,19 @@
 // What it calls: the planning behind dion_workspace_bytes (shape grouping, Gram-matrix splits, the carving of the
 // workspace) over a grid of shapes and batch sizes up to the limits the header allows, dion_cholesky_grid over
 // compute-unit counts, batches and ranks, dion_strerror over all codes, and the argument checks that every other
-// entry point makes before it touches the device.
+// entry point makes before it touches the device; and the integer arithmetic that deals the output tiles of the
+// triangular inverse out to its workgroups (csrc/inv_tree_order.hpp, the header the kernel itself includes): every
+// tile of every level exactly once, for all tile counts up to r = 5120 and a range of workgroup counts, and no
+// workgroup more than one tile's length above another.
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "../../include/dion.h"
+#include "../../paper_2504_05295_amd/csrc/inv_tree_order.hpp"
 
 static int failures = 0;
 #define EXPECT(cond)                                                   \
@@ -80,6 +85,38 @@ int main() {
     EXPECT(dion_step(nullptr, nullptr, nullptr, nullptr, nullptr, 8, 8, 2, 0.9f, 0.1f, nullptr) == DION_EINVAL);
     EXPECT(dion_destroy_state(nullptr) == DION_OK || dion_destroy_state(nullptr) == DION_EINVAL);
   }
+  // tile order of the triangular inverse
+  size_t orders = 0;
+  const int group_counts[] = {1, 2, 3, 4, 5, 7, 8, 15, 16, 35, 63, 64, 100, 255, 256};
+  for (int nb = 2; nb <= 80; ++nb)
+    for (int groups : group_counts)
+      for (int S = 1; S < nb; S *= 2) {
+        const int npairs = dion::inv_tree_pairs(nb, S), rounds = dion::inv_tree_rounds(nb, S, groups);
+        for (int phase = 0; phase < 2; ++phase) {
+          std::vector<int> taken((size_t)npairs * S * S, 0);
+          std::vector<long> load(groups, 0);
+          for (int wg = 0; wg < groups; ++wg)
+            for (int round = 0; round < rounds; ++round) {
+              int q = -1, ti = -1, tj = -1;
+              if (!dion::inv_tree_tile(nb, S, phase, groups, wg, round, q, ti, tj)) continue;
+              const int sd = std::min(S, nb - (2 * q * S + S));
+              EXPECT(q >= 0 && q < npairs && ti >= 0 && ti < sd && tj >= 0 && tj < S);
+              if (!(q >= 0 && q < npairs && ti >= 0 && ti < S && tj >= 0 && tj < S)) continue;
+              ++taken[((size_t)q * S + ti) * S + tj];
+              load[wg] += phase == 0 ? S - tj : ti + 1;
+            }
+          for (int q = 0; q < npairs; ++q) {
+            const int sd = std::min(S, nb - (2 * q * S + S));
+            for (int ti = 0; ti < S; ++ti)
+              for (int tj = 0; tj < S; ++tj) EXPECT(taken[((size_t)q * S + ti) * S + tj] == (ti < sd ? 1 : 0));
+          }
+          long lo = load[0], hi = load[0];
+          for (long l : load) { lo = std::min(lo, l); hi = std::max(hi, l); }
+          EXPECT(hi - lo <= S);
+          ++orders;
+        }
+      }
+  printf("tile order of the triangular inverse: %zu (tile count, workgroups, level, product) cases\n", orders);
   printf("host entry points under the sanitizers: %zu calls, %d failed expectations\n", calls, failures);
   return failures == 0 ? 0 : 1;
 }
