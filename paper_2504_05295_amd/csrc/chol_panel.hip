@@ -416,6 +416,15 @@ __device__ __forceinline__ void shared_tile_to_lds(float* S, const gfloat* src, 
 #pragma unroll
   for (int e = 0; e < 16; ++e) S[(r0 + 4 * e) * CBP + c] = v[e];
 }
+// the same, transposed on the way: S[c][r] = tile[r][c]
+__device__ __forceinline__ void shared_tile_to_lds_transposed(float* S, const gfloat* src, int ld, int t) {
+  float v[16];
+  const int r0 = t >> 6, c = t & 63;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) v[e] = shared_load(src + (r0 + 4 * e) * ld + c);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) S[c * CBP + r0 + 4 * e] = v[e];
+}
 __device__ __forceinline__ void lds_to_shared_tile(gfloat* dst, int ld, const float* S, int t) {
   const int r0 = t >> 6, c = t & 63;
 #pragma unroll
@@ -671,7 +680,18 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
 // to the helpers likewise without the chain waiting for anything but its own stores.
 // Tiles that cross between workgroups, the two kinds of look-ahead tile included, are only ever written and read with
 // device-scope accesses.  Waits are bounded as above.
-template <bool RANK>
+//
+// FUSE_INV: the helpers also form W = L^-1, row by row behind the factorisation, so that no separate pass over L
+// follows it.  With W'(j, e) the running value of tile (j, e), e < j, that starts at zero,
+//   UW(j, e, p)  W'(j, e) -= L[j][p] W(p, e)        for e <= p < j        (needs lflag[j] > p and row p of W)
+//   TW(p, e)     W(p, e) = W11(p) W'(p, e)           once UW(p, e, p - 1) is through   -> vflag[p][e]
+// and W(p, p) = W11(p) as the chain leaves it (wflag[p]; the last one is announced when the chain ends).  Tile (j, e)
+// belongs to helper (j mod pr) pc + (e mod pc), which applies UW(j, e, p) among its work of panel p for j >= p + 2 and
+// keeps UW(p + 1, e, p) for the start of panel p + 1, right before TW(p + 1, e): a helper only ever waits for tiles of
+// row p of W while it works on panel p or p + 1, and their owners produce them from flags of the chain and of row
+// p - 1 alone, so the order of the factorisation's own tasks is untouched.  Running values are the owner's private
+// data (ordinary accesses); finished tiles are written and read with device-scope accesses like the tiles of L.
+template <bool RANK, bool FUSE_INV>
 __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
   const long long mat = (long long)blockIdx.y * p.stride;
   if (p.skip && p.skip[mat] != 0) return;   // uniform for the whole grid row of this matrix
@@ -685,6 +705,7 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
   x.lflag = x.wflag + nb;
   gu64* const cflag = x.lflag + nb;
   x.abort_word = cflag + nb;
+  gu64* const vflag = x.wflag + p.vflag_off;   // FUSE_INV: nb x nb words, [p][e] = tile (p, e) of W is final
   x.epoch = *p.step_counter * 8ull + (u64)p.pass;
   x.spin_limit = p.spin_limit;
   x.ld = p.rp;
@@ -793,7 +814,14 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
       if (*(volatile int*)&gave_up) return;   // uniform: written before the barrier
       // W11 out to the helpers; nobody here waits for these stores before the step is through
       lds_to_shared_tile(x.W + at, ld, S0, t);
-      if (k + 1 == nb) break;
+      if (k + 1 == nb) {
+        if (FUSE_INV) {   // the last row of W waits for this W11
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+          if (t == 0) flag_store(x.wflag + k, x.epoch);
+        }
+        break;
+      }
       const f32x16_t li = mma_64(S2, S0, wm, wn, lr, lk);   // L[k+1][k] = C'[k+1][k] W11^T
       gfloat* dst = tile_at(x.L, k + 1, k);
 #pragma unroll
@@ -872,6 +900,54 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     const u64 v = flag_load(x.lflag + row);
     return (unsigned)(v >> 32) == (unsigned)x.epoch && (unsigned)v >= (unsigned)cols;
   };
+  // ---- the inverse (FUSE_INV)
+  auto w_ready = [&](int p_, int e) __attribute__((always_inline)) {   // tile (p_, e) of W is final
+    return flag_load(e == p_ ? x.wflag + p_ : vflag + p_ * nb + e) == x.epoch;
+  };
+  // UW(j, e, p): W'(j, e) -= L[j][p] W(p, e); the first one, p = e, starts from zero
+  auto w_update = [&](int j, int e, int p_) __attribute__((always_inline)) {
+    gfloat* wt = tile_at(x.W, j, e) + foff;
+    float cold[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cold[v] = p_ > e ? wt[(8 * (v / 4) + (v % 4)) * ld] : 0.f;
+    __syncthreads();   // earlier readers of S1 / S2 are through
+    shared_tile_to_lds(S1, tile_at(x.L, j, p_), ld, t);
+    shared_tile_to_lds_transposed(S2, tile_at(x.W, p_, e), ld, t);
+    __syncthreads();
+    const f32x16_t up = mma_64(S1, S2, wm, wn, lr, lk);   // L[j][p] (W(p, e)^T)^T
+#pragma unroll
+    for (int v = 0; v < 16; ++v) wt[(8 * (v / 4) + (v % 4)) * ld] = cold[v] - up[v];
+  };
+  // Row p_ of W, for the tiles of it that this helper owns: their last update, then W(p_, e) = W11(p_) W'(p_, e)
+  auto w_row = [&](int p_) __attribute__((always_inline)) -> bool {
+    if (p_ < 1 || p_ % pr != a || b > p_ - 1) return true;   // (uniform)
+    if (!wait_until(x, &gave_up, t < p_ && t % pc == b, [&] { return w_ready(p_ - 1, t); })) return false;
+    if (!wait_until(x, &gave_up, t == 0, [&] { return row_ready(p_, p_); })) return false;
+    for (int e = b; e < p_; e += pc) w_update(p_, e, p_ - 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's parts of the running values are in memory
+    for (int e = b; e < p_; e += pc) {
+      gfloat* wt = tile_at(x.W, p_, e) + foff;
+      float run[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) run[v] = wt[(8 * (v / 4) + (v % 4)) * ld];
+      __syncthreads();   // earlier readers of S0 / S1 are through
+#pragma unroll
+      for (int v = 0; v < 16; ++v) S1[fcol * CBP + frow + 8 * (v / 4) + (v % 4)] = run[v];   // W'(p_, e)^T
+      if (s0_holds != p_) {
+        if (!wait_until(x, &gave_up, t == 0, [&] { return flag_load(x.wflag + p_) == x.epoch; })) return false;
+        shared_tile_to_lds(S0, tile_at(x.W, p_, p_), ld, t);
+        s0_holds = p_;
+      }
+      __syncthreads();
+      const f32x16_t res = mma_64(S0, S1, wm, wn, lr, lk);   // W11(p_) W'(p_, e)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) shared_store(wt + (8 * (v / 4) + (v % 4)) * ld, res[v]);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();   // everybody's stores have completed
+      if (t == 0) flag_store(vflag + p_ * nb + e, x.epoch);
+    }
+    return true;
+  };
 
   for (int p_ = 0; p_ + 1 < nb; ++p_) {
     // Row p_ + 2 feeds the chain's next step: its owner turns (p_ + 2, p_) into a tile of L first and applies that
@@ -923,6 +999,7 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     if (p_ % pc == b)
       for (int i = a + ((p_ + 3 - a + pr - 1) / pr) * pr; i < nb; i += pr)
         if (!column_tile(i, p_)) return;
+    if (FUSE_INV && !w_row(p_)) return;
     // the tiles of L that this helper's other updates of panel p_ need: one thread per block row (a superset)
     {
       bool need = false;
@@ -941,7 +1018,18 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
         update(i, i - 1, p_, false, true);
         update(i, i - 2, p_, false, false);
       }
+    if (FUSE_INV) {
+      // row p_ of W into the running values of the rows from p_ + 2 down (L[j][p_] is out: the wait above covers the
+      // rows j = a mod pr)
+      const int j0 = a + ((p_ + 2 - a + pr - 1) / pr) * pr;
+      if (j0 < nb && b <= p_) {
+        if (!wait_until(x, &gave_up, t <= p_ && t % pc == b, [&] { return w_ready(p_, t); })) return;
+        for (int j = j0; j < nb; j += pr)
+          for (int e = b; e <= p_; e += pc) w_update(j, e, p_);
+      }
+    }
   }
+  if (FUSE_INV) w_row(nb - 1);
 }
 
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
@@ -949,8 +1037,11 @@ hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
   // workgroup on the critical chain shares its unit with nobody
   if (p.chain) {
     // (70 KB of declared LDS and 32 KB of unused dynamic LDS: more than half of a compute unit's, so one workgroup each)
-    if (p.thr) hipLaunchKernelGGL(chol_chain_kernel<true>, dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
-    else hipLaunchKernelGGL(chol_chain_kernel<false>, dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
+    // (the inverse needs a flag word per tile of W, and at 64 panels and more the helpers have no time left for it)
+    if (p.vflag_off > 0 && (p.thr || p.rp / CB > FUSED_INV_MAX_NB || p.rp / CB > 256)) return hipErrorInvalidValue;
+    if (p.thr) hipLaunchKernelGGL((chol_chain_kernel<true, false>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
+    else if (p.vflag_off > 0) hipLaunchKernelGGL((chol_chain_kernel<false, true>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
+    else hipLaunchKernelGGL((chol_chain_kernel<false, false>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
     return hipGetLastError();
   }
   if (p.thr) hipLaunchKernelGGL(chol_stream_kernel<true>, dim3(p.pr * p.pc, batch), dim3(256), 32768, s, p);

@@ -496,6 +496,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     pp.thr = rank_tol > 0.f ? (const float*)(e0 + g.carve.off[SLOT_THR]) : nullptr;
     pp.nullmask = rank_tol > 0.f ? (int*)(e0 + g.carve.off[SLOT_NULL]) : nullptr;
   }
+  bool fused_inverse = false;
   if (use_stream) {
     // the whole factorisation in one launch of at most 256 co-resident workgroups
     CholStreamArgs ca;
@@ -511,6 +512,9 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ca.spin_limit = st->chol_spin_limit;
     ca.thr = pp.thr; ca.nullmask = pp.nullmask;
     ca.chain = chain;
+    // with the chain in a workgroup of its own and up to 32 panels the helpers form W = L^-1 behind the factorisation
+    fused_inverse = chain && nb <= FUSED_INV_MAX_NB && rank_tol <= 0.f;
+    ca.vflag_off = fused_inverse ? fused_inv_flag_offset(nb) : 0;
     HIPCHK(launch_chol_stream(ca, batch, s));
   } else {
     for (int k = 0; k < rp; k += CHOL_NB)
@@ -518,7 +522,9 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
   }
   // W = L^-1 by merging neighbouring diagonal blocks: [[A,0],[C,D]]^-1 = [[A^-1,0],[-D^-1 C A^-1, D^-1]].
   // Blocks start as the 64-wide inverses left by the factorisation.
-  if (use_stream) {
+  if (fused_inverse) {
+    // (done by the factorisation kernel)
+  } else if (use_stream) {
     // all levels in one launch, by the same number of co-resident workgroups as the factorisation had
     InvTreeArgs ta;
     char* e0 = st->ws + g.ws_off + (size_t)row0 * g.bytes_per_entry;

@@ -194,6 +194,8 @@ struct CholStreamArgs {
   const float* thr;        // as in CholPanelPtrs
   int* nullmask;
   int chain;               // 1: one more workgroup, number 0, carries the whole chain of diagonal blocks (pr x pc helpers)
+  int vflag_off;           // chain only: > 0: the helpers form W = L^-1 as well (no inverse pass afterwards), and (rp / 64)^2
+                           // flag words for it start this many 64-bit words into the matrix' sync array; 0: they do not
 #ifdef DION_CHOL_TIMING
   long long* dbg;          // timing build only: eight time stamps per panel of the chain workgroup
 #endif
@@ -224,7 +226,9 @@ hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, int cus, hipStr
 void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc, int* chain);
 // 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
 constexpr int chol_sync_words(int nb) { return 3 * nb + 2; }
-constexpr int sync_words(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
+constexpr int FUSED_INV_MAX_NB = 32;   // most panels for which the factorisation kernel forms the inverse as well
+constexpr int fused_inv_flag_offset(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
+constexpr int sync_words(int nb) { return fused_inv_flag_offset(nb) + (nb <= FUSED_INV_MAX_NB ? nb * nb : 0); }
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the identity in
 // Frobenius norm, SLOT_FAST is set to 1 (else 0) and, unless decision_only, W receives chol(C)^-1 = I - Phi(C - I) up to
 // O(tau^2), Phi = strict lower part + half the diagonal.  nsplit > 1: C still is nsplit split-K partial results in
