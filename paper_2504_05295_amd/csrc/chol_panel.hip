@@ -686,11 +686,12 @@ __global__ void __launch_bounds__(256, 1) chol_stream_kernel(CholStreamArgs p) {
 //   UW(j, e, p)  W'(j, e) -= L[j][p] W(p, e)        for e <= p < j        (needs lflag[j] > p and row p of W)
 //   TW(p, e)     W(p, e) = W11(p) W'(p, e)           once UW(p, e, p - 1) is through   -> vflag[p][e]
 // and W(p, p) = W11(p) as the chain leaves it (wflag[p]; the last one is announced when the chain ends).  Tile (j, e)
-// belongs to helper (j mod pr) pc + (e mod pc), which applies UW(j, e, p) among its work of panel p for j >= p + 2 and
-// keeps UW(p + 1, e, p) for the start of panel p + 1, right before TW(p + 1, e): a helper only ever waits for tiles of
-// row p of W while it works on panel p or p + 1, and their owners produce them from flags of the chain and of row
-// p - 1 alone, so the order of the factorisation's own tasks is untouched.  Running values are the owner's private
-// data (ordinary accesses); finished tiles are written and read with device-scope accesses like the tiles of L.
+// belongs to helper (j mod pr) pc + (e mod pc), which applies UW(j, e, p) for j >= p + 2 after the look-ahead work of
+// panel p + 1 (before it, the chain found its next tiles 3 us late) and UW(p + 1, e, p) right before TW(p + 1, e),
+// also in panel p + 1: a helper only ever waits for tiles of row p of W while it works on panel p + 1, and their
+// owners produce them from flags of the chain and of row p - 1 alone, so the order of the factorisation's own tasks
+// is untouched.  Running values are the owner's private data (ordinary accesses); finished tiles are written and
+// read with device-scope accesses like the tiles of L.
 template <bool RANK, bool FUSE_INV>
 __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
   const long long mat = (long long)blockIdx.y * p.stride;
@@ -918,6 +919,16 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) wt[(8 * (v / 4) + (v % 4)) * ld] = cold[v] - up[v];
   };
+  // Row p_ of W into the running values of the rows from p_ + 2 down that this helper has tiles in (L[j][p_] is out:
+  // the wait before the updates of panel p_ covers the rows j = a mod pr)
+  auto w_rest = [&](int p_) __attribute__((always_inline)) -> bool {
+    const int j0 = a + ((p_ + 2 - a + pr - 1) / pr) * pr;
+    if (j0 >= nb || b > p_) return true;   // (uniform)
+    if (!wait_until(x, &gave_up, t <= p_ && t % pc == b, [&] { return w_ready(p_, t); })) return false;
+    for (int j = j0; j < nb; j += pr)
+      for (int e = b; e <= p_; e += pc) w_update(j, e, p_);
+    return true;
+  };
   // Row p_ of W, for the tiles of it that this helper owns: their last update, then W(p_, e) = W11(p_) W'(p_, e)
   auto w_row = [&](int p_) __attribute__((always_inline)) -> bool {
     if (p_ < 1 || p_ % pr != a || b > p_ - 1) return true;   // (uniform)
@@ -999,6 +1010,9 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     if (p_ % pc == b)
       for (int i = a + ((p_ + 3 - a + pr - 1) / pr) * pr; i < nb; i += pr)
         if (!column_tile(i, p_)) return;
+    // the inverse: row p_ - 1 of W into the rows from p_ + 1 down (kept until now so that it does not stand between
+    // the previous panel and this one's look-ahead work), then this helper's part of row p_
+    if (FUSE_INV && p_ >= 1 && !w_rest(p_ - 1)) return;
     if (FUSE_INV && !w_row(p_)) return;
     // the tiles of L that this helper's other updates of panel p_ need: one thread per block row (a superset)
     {
@@ -1018,18 +1032,8 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
         update(i, i - 1, p_, false, true);
         update(i, i - 2, p_, false, false);
       }
-    if (FUSE_INV) {
-      // row p_ of W into the running values of the rows from p_ + 2 down (L[j][p_] is out: the wait above covers the
-      // rows j = a mod pr)
-      const int j0 = a + ((p_ + 2 - a + pr - 1) / pr) * pr;
-      if (j0 < nb && b <= p_) {
-        if (!wait_until(x, &gave_up, t <= p_ && t % pc == b, [&] { return w_ready(p_, t); })) return;
-        for (int j = j0; j < nb; j += pr)
-          for (int e = b; e <= p_; e += pc) w_update(j, e, p_);
-      }
-    }
   }
-  if (FUSE_INV) w_row(nb - 1);
+  if (FUSE_INV) w_row(nb - 1);   // (row nb - 2 of W has no rows from nb down to go into)
 }
 
 hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
