@@ -1041,8 +1041,8 @@ hipError_t launch_chol_stream(CholStreamArgs p, int batch, hipStream_t s) {
   // workgroup on the critical chain shares its unit with nobody
   if (p.chain) {
     // (70 KB of declared LDS and 32 KB of unused dynamic LDS: more than half of a compute unit's, so one workgroup each)
-    // (the inverse needs a flag word per tile of W, and at 64 panels and more the helpers have no time left for it)
-    if (p.vflag_off > 0 && (p.thr || p.rp / CB > FUSED_INV_MAX_NB || p.rp / CB > 256)) return hipErrorInvalidValue;
+    // (the inverse needs a flag word per tile of W, and its waits one thread per panel; measured up to 64 panels)
+    if (p.vflag_off > 0 && (p.thr || p.rp / CB > FUSED_INV_MAX_NB)) return hipErrorInvalidValue;
     if (p.thr) hipLaunchKernelGGL((chol_chain_kernel<true, false>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
     else if (p.vflag_off > 0) hipLaunchKernelGGL((chol_chain_kernel<false, true>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);
     else hipLaunchKernelGGL((chol_chain_kernel<false, false>), dim3(p.pr * p.pc + 1, batch), dim3(256), 32768, s, p);

@@ -512,7 +512,7 @@ int cholqr_pass(dion_state* st, const Group& g, int row0, int batch, long long r
     ca.spin_limit = st->chol_spin_limit;
     ca.thr = pp.thr; ca.nullmask = pp.nullmask;
     ca.chain = chain;
-    // with the chain in a workgroup of its own and up to 32 panels the helpers form W = L^-1 behind the factorisation
+    // with the chain in a workgroup of its own and up to 64 panels the helpers form W = L^-1 behind the factorisation
     fused_inverse = chain && nb <= FUSED_INV_MAX_NB && rank_tol <= 0.f;
     ca.vflag_off = fused_inverse ? fused_inv_flag_offset(nb) : 0;
     HIPCHK(launch_chol_stream(ca, batch, s));

@@ -226,7 +226,8 @@ hipError_t launch_inv_tree(InvTreeArgs p, int groups, int batch, int cus, hipStr
 void plan_chol_grid(int cus, int batch, int nb, int* pr, int* pc, int* chain);
 // 64-bit words of SLOT_SYNC for a matrix with nb 64-wide panels: the factorisation's flags, then the inverse's
 constexpr int chol_sync_words(int nb) { return 3 * nb + 2; }
-constexpr int FUSED_INV_MAX_NB = 32;   // most panels for which the factorisation kernel forms the inverse as well
+constexpr int FUSED_INV_MAX_NB = 64;   // most panels for which the factorisation kernel forms the inverse as well (< 256:
+                                       // its waits take one thread per panel)
 constexpr int fused_inv_flag_offset(int nb) { return chol_sync_words(nb) + INV_TREE_MAX_GROUPS + 2; }
 constexpr int sync_words(int nb) { return fused_inv_flag_offset(nb) + (nb <= FUSED_INV_MAX_NB ? nb * nb : 0); }
 // Second Cholesky-QR pass shortcut.  When the Gram matrix C of the first pass' output is within tau of the identity in
