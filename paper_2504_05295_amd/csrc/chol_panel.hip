@@ -416,14 +416,17 @@ __device__ __forceinline__ void shared_tile_to_lds(float* S, const gfloat* src, 
 #pragma unroll
   for (int e = 0; e < 16; ++e) S[(r0 + 4 * e) * CBP + c] = v[e];
 }
-// the same, transposed on the way: S[c][r] = tile[r][c]
-__device__ __forceinline__ void shared_tile_to_lds_transposed(float* S, const gfloat* src, int ld, int t) {
-  float v[16];
+// The two halves of it, so that a caller can have the loads of several tiles in flight before it waits for the first:
+__device__ __forceinline__ void shared_tile_to_regs(float (&v)[16], const gfloat* src, int ld, int t) {
   const int r0 = t >> 6, c = t & 63;
 #pragma unroll
   for (int e = 0; e < 16; ++e) v[e] = shared_load(src + (r0 + 4 * e) * ld + c);
+}
+template <bool TRANSPOSED>
+__device__ __forceinline__ void regs_to_lds(float* S, const float (&v)[16], int t) {
+  const int r0 = t >> 6, c = t & 63;
 #pragma unroll
-  for (int e = 0; e < 16; ++e) S[c * CBP + r0 + 4 * e] = v[e];
+  for (int e = 0; e < 16; ++e) S[TRANSPOSED ? c * CBP + r0 + 4 * e : (r0 + 4 * e) * CBP + c] = v[e];
 }
 __device__ __forceinline__ void lds_to_shared_tile(gfloat* dst, int ld, const float* S, int t) {
   const int r0 = t >> 6, c = t & 63;
@@ -886,9 +889,13 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     float cold[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) cold[v] = shared ? shared_load(ct + (8 * (v / 4) + (v % 4)) * ld) : ct[(8 * (v / 4) + (v % 4)) * ld];
+    // (all three tiles are requested before the first wait: one memory round trip per update, not three)
+    float li[16], lj[16];
+    if (!li_in_s1) shared_tile_to_regs(li, tile_at(x.L, i, p_), ld, t);
+    if (j != i) shared_tile_to_regs(lj, tile_at(x.L, j, p_), ld, t);
     __syncthreads();   // earlier readers of S1 / S2 are through
-    if (!li_in_s1) shared_tile_to_lds(S1, tile_at(x.L, i, p_), ld, t);
-    if (j != i) shared_tile_to_lds(S2, tile_at(x.L, j, p_), ld, t);
+    if (!li_in_s1) regs_to_lds<false>(S1, li, t);
+    if (j != i) regs_to_lds<false>(S2, lj, t);
     __syncthreads();
     const f32x16_t up = mma_64(S1, (j != i) ? S2 : S1, wm, wn, lr, lk);
 #pragma unroll
@@ -911,9 +918,12 @@ __global__ void __launch_bounds__(256, 1) chol_chain_kernel(CholStreamArgs p) {
     float cold[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) cold[v] = p_ > e ? wt[(8 * (v / 4) + (v % 4)) * ld] : 0.f;
+    float lj[16], wp[16];
+    shared_tile_to_regs(lj, tile_at(x.L, j, p_), ld, t);
+    shared_tile_to_regs(wp, tile_at(x.W, p_, e), ld, t);
     __syncthreads();   // earlier readers of S1 / S2 are through
-    shared_tile_to_lds(S1, tile_at(x.L, j, p_), ld, t);
-    shared_tile_to_lds_transposed(S2, tile_at(x.W, p_, e), ld, t);
+    regs_to_lds<false>(S1, lj, t);
+    regs_to_lds<true>(S2, wp, t);
     __syncthreads();
     const f32x16_t up = mma_64(S1, S2, wm, wn, lr, lk);   // L[j][p] (W(p, e)^T)^T
 #pragma unroll
