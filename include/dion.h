@@ -31,7 +31,11 @@
  *   - X, G, M, Q and the workspace must not overlap one another.
  *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without waiting; only dion_last_status and
- *     dion_stage_times synchronise.
+ *     dion_stage_times synchronise.  For very large matrices (the stated rule: where a copy pass over M and G hides
+ *     behind the first product of the step for longer than the parts it is cut into cost) a step also enqueues on
+ *     a second stream that the state created at dion_init_state (non-blocking, default priority) and orders the two
+ *     with events; all of that work has been waited for on the given stream before the step's later stages, so the
+ *     caller sees one stream, and a stream capture of the given stream captures both.
  *   - Return value: 0 on success, < 0 for a usage or runtime error found on the host (then
  *     nothing was launched by that call and no state was touched).  Numerical trouble is
  *     found on the device and reported later by dion_last_status.

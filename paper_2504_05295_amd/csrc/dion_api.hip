@@ -86,7 +86,8 @@ struct Group {
   size_t ws_off;   // offset of the group's first matrix in the workspace (set by dion_init_state)
 };
 
-constexpr int kEventsPerGroup = 2 * DION_STAGE_COUNT;   // a start and an end event per stage
+constexpr int kEventsPerGroup = 2 * DION_STAGE_COUNT;
+constexpr int K1_PARTS = 4;   // parts of the contraction of K1 when the bf16 copy of M + G is made alongside it   // a start and an end event per stage
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -254,6 +255,11 @@ struct dion_state {
   int orth_mode;
   unsigned chol_spin_limit;  // polls after which a wait inside that kernel gives up
   std::vector<hipEvent_t> events;      // groups * kEventsPerGroup
+  // K1 on the direct-load path in parts (see stage_k1): a second stream for the parts of the bf16 copy, and events that
+  // order them against the parts of the product.  Null when the state was made without them (the entry point that
+  // allocates nothing): the copy then runs before the product, on the caller's stream.
+  hipStream_t side_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_part[K1_PARTS] = {}, ev_main[K1_PARTS] = {};
   std::vector<char> group_timed;       // which groups ran in the last call with timing on
 };
 
@@ -264,6 +270,31 @@ struct dion_state {
   } while (0)
 
 namespace {
+
+void destroy_side_stream(dion_state* st) {
+  if (st->ev_fork) (void)hipEventDestroy(st->ev_fork);
+  for (int q = 0; q < K1_PARTS; ++q) {
+    if (st->ev_part[q]) (void)hipEventDestroy(st->ev_part[q]);
+    if (st->ev_main[q]) (void)hipEventDestroy(st->ev_main[q]);
+    st->ev_part[q] = st->ev_main[q] = nullptr;
+  }
+  if (st->side_stream) (void)hipStreamDestroy(st->side_stream);
+  st->ev_fork = nullptr;
+  st->side_stream = nullptr;
+}
+// The second stream and its events (default priority; the stream does not synchronise with the legacy default stream,
+// which may be the caller's).  On failure the state simply goes without them.
+void create_side_stream(dion_state* st) {
+  bool ok = hipStreamCreateWithFlags(&st->side_stream, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&st->ev_fork, hipEventDisableTiming) == hipSuccess;
+  for (int q = 0; ok && q < K1_PARTS; ++q)
+    ok = hipEventCreateWithFlags(&st->ev_part[q], hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&st->ev_main[q], hipEventDisableTiming) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    destroy_side_stream(st);
+  }
+}
 
 // Host part of creating a state: the plan, the carving of the workspace and the host image of the pointer table
 // (M_dev / Q_dev may be null: those two slots are refreshed by every step anyway).  Touches no device memory.
@@ -694,7 +725,33 @@ int stage_b16(const RowCtx& c) {
 // SLOT_B16 for a K2 that follows.
 // split_out: on the direct-load path, also leave the result's bf16 halves in (SLOT_PT16, SLOT_ZLT16) for an
 // orthonormalisation that follows (*split_done tells whether that happened).
-int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out = false, bool* split_done = nullptr) {
+// b16_in_parts: bf16(M+G) has not been made yet (direct-load path, k1_in_parts(c) holds): it is made here, in K1_PARTS
+// column blocks on the state's second stream, and the product contracts over block q once it is there, adding to what
+// the blocks before it gave.  A streaming pass and a product running side by side take less than one after the other
+// (the product leaves the memory system idle, the pass leaves the matrix cores idle), and started in this order -
+// each part of the pass only once the product before it is on its way - the product's workgroups get their compute
+// units first and the pass fills in.  Everything on the second stream is back on the caller's before the last part of
+// the product starts; a caller capturing its stream into a graph captures both.
+bool k1_in_parts(const RowCtx& c) {
+  const Group& g = *c.g;
+  if (!direct12(c) || !c.st->side_stream) return false;
+  if ((g.n / 64) % K1_PARTS || (g.n / K1_PARTS) % 8) return false;
+  // (a single matrix whose tiles leave a short last round has that round split over k, which a part of a contraction
+  // does not do)
+  const long long tiles = (g.m / 256) * (g.r / 256) * c.batch;
+  if (!(c.batch > 1 || tiles % c.st->cus == 0 || tiles < c.st->cus)) return false;
+  // Worth it?  Side by side, the pass and the product took 0.65 of what they take one after the other as long as
+  // neither outlasts the other (measured at 16384 x 53248, r = 1024: 2.85 -> 2.62 ms for the stage), and every part
+  // after the first reads and rewrites the m x r result and ramps up and down once more (about 50 us).  At r = 4096
+  // the two balance (7.26 against 7.33 ms); with short contractions (8192 x 8192, or the 196 matrices of the 3B
+  // model) the parts cost far more than they hide.
+  // (Judged per matrix, whatever the batch: a matrix is then stepped with the same arithmetic alone and in a batch.)
+  const double hidden = 0.35 * (8.0 * (double)g.m * (double)g.n / 5.2e12);
+  const double extra = (K1_PARTS - 1) * (8.0 * (double)g.m * (double)g.r / 5.0e12 + 50e-6);
+  return hidden > 1.25 * extra;
+}
+int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out = false, bool* split_done = nullptr,
+             bool b16_in_parts = false) {
   if (split_done) *split_done = false;
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
@@ -705,6 +762,12 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out
   a.xcd_remap = 1;
   if (c.big) {
     if (direct12(c)) {
+      dion_state* st = c.st;
+      if (b16_in_parts) {
+        if (!k1_in_parts(c)) return DION_EINVAL;
+        HIPCHK(hipEventRecord(st->ev_fork, c.s));
+        HIPCHK(hipStreamWaitEvent(st->side_stream, st->ev_fork, 0));
+      }
       // Q as bf16 in its own row-major order (n x r): the right operand with k, its row index, as the slow index
       HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, SLOT_QT16, -1, n, r, c.s));
       a.B = opnd(SLOT_QT16, 0, r);
@@ -716,7 +779,25 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out
         a.E.split_lo1 = SLOT_ZLT16 + 1;
         if (split_done) *split_done = true;
       }
-      HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_B));
+      if (!b16_in_parts) {
+        HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_B));
+        return DION_OK;
+      }
+      // (equal parts: unequal ones, a short first part of the copy or a short last part of the product, measured the same)
+      const long long cols = n / K1_PARTS;
+      for (int q = 0; q < K1_PARTS; ++q) {
+        if (q >= 1) HIPCHK(hipStreamWaitEvent(st->side_stream, st->ev_main[q - 1], 0));
+        HIPCHK(launch_sum_bf16_cols(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, m, n, q * cols, cols, st->side_stream));
+        HIPCHK(hipEventRecord(st->ev_part[q], st->side_stream));
+        HIPCHK(hipStreamWaitEvent(c.s, st->ev_part[q], 0));
+        HIPCHK(hipEventRecord(st->ev_main[q], c.s));
+        GemmArgs ap = a;
+        ap.slab_first = q * (int)(cols / 64);
+        ap.slab_count = (int)(cols / 64);
+        ap.E.beta = q ? 1.f : 0.f;
+        if (q + 1 < K1_PARTS) { ap.E.split_hi1 = 0; ap.E.split_lo1 = 0; }   // the halves of the result come from its last part
+        HIPCHK(gemm2_nt(G2_256x256, ap, c.batch, c.s, KS_B));
+      }
       return DION_OK;
     }
     HIPCHK(launch_convert_bf16(c.tab, NSLOTS, c.batch, slot_q, -1, SLOT_QT16, n, r, c.s));
@@ -941,10 +1022,11 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  STAGECHK(stage_b16(c));
+  const bool parts = k1_in_parts(c);
+  if (!parts) STAGECHK(stage_b16(c));
   const float rank_tol = mode == STEP_KEEP_STATUS ? RANK_TOL : 0.f;
   bool z_split = false;
-  STAGECHK(stage_k1(c, true, SLOT_Q, orth_fuses(c, g.m, g.gram_m, rank_tol), &z_split));
+  STAGECHK(stage_k1(c, true, SLOT_Q, orth_fuses(c, g.m, g.gram_m, rank_tol), &z_split, parts));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
   STAGECHK(stage_orth(c, g.m, g.gram_m, SLOT_Z, SLOT_P1, SLOT_P, rank_tol, z_split));
@@ -1140,8 +1222,13 @@ int dion_init_state_ex(dion_state_t** out, int count, const int64_t* m, const in
     delete st;
     return DION_ENOMEM;
   }
+  for (const Group& g : st->groups)
+    if (g.direct12) {
+      create_side_stream(st);
+      break;
+    }
   // device-side initialisation: M = 0, Q = ColNorm(Q or Gaussian draw)
-  auto fail = [&](int code) { delete st; return code; };
+  auto fail = [&](int code) { destroy_side_stream(st); delete st; return code; };
   for (int i = 0; i < count; ++i) {
     const Entry& e = st->entries[i];
     void* const* rowtab = st->table + (size_t)e.row * NSLOTS;
@@ -1450,6 +1537,7 @@ int dion_destroy_state(dion_state_t* st) {
   if (!st) return DION_OK;
   for (auto& e : st->events)
     if (e) (void)hipEventDestroy(e);
+  destroy_side_stream(st);
   delete st;
   return DION_OK;
 }

@@ -70,6 +70,9 @@ struct GemmArgs {
   int group_n;          // > 0: tiles are visited column group by column group (group_n column tiles wide, all row
                         // tiles inside a group before the next group), so the B panels of a group stay in L2
   int noop_slot;        // large-tile kernels: >= 0 and the int32 there non-zero: the launch does nothing (like status_slot)
+  int slab_first, slab_count;   // direct-load core, slab_count > 0: this launch contracts over the k-slabs [slab_first, slab_first +
+                        // slab_count) only (plain products: one operand pair, no split over k, no split tail); with E.beta = 1
+                        // it adds to what is in the output, so that a contraction can be spread over launches
   int heavy_first;      // direct-load core, triangular B (tri_k): column tiles cost (tn + 1) units each; every XCD gets
                         // tiles_m / 8 tile rows and visits their column tiles from the costliest down, so that the
                         // second round of workgroups fills in behind the first (needs xcd_remap, one matrix, split-K 1)

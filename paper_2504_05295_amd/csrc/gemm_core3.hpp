@@ -228,8 +228,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   const int slabs_per_seg = kseg_eff / BK;
   const int total = nseg * slabs_per_seg;
   const int kps = tail_q >= 0 ? (total + g.tail_split - 1) / g.tail_split : g.k_per_split;
-  const int s_begin = ks * kps;
-  const int s_end = min(total, s_begin + kps);
+  const int s_begin = g.slab_count > 0 ? g.slab_first : ks * kps;
+  const int s_end = min(total, s_begin + (g.slab_count > 0 ? g.slab_count : kps));
   // Operand base addresses of the (up to three) operand pairs, read once and kept in scalar registers: a look-up
   // in the pointer table inside the loop is a memory load, and the wait for it would also wait for every tile
   // load in flight.  (Separate variables: an array indexed by the pair number would live in scratch memory.)
@@ -414,7 +414,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
         for (int p = 0; p < 4; ++p) {
           const int row = c_row0 + wm * Cfg::WTM + i * 32 + prow + 8 * p;
           const int col = c_col0 + wn * Cfg::WTN + j * 32 + pcol;
-          const f32x4_t v4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          f32x4_t v4 = *(const f32x4_t*)(patch + (prow + 8 * p) * SP + pcol);
+          if (g.E.beta != 0.f) v4 += gload<f32x4_t>(C + (long long)row * c_ld + col);   // a later part of a contraction spread over launches
           gstore<f32x4_t>(C + (long long)row * c_ld + col, v4);
           if (split_hi) gemm3_store_split(split_hi, split_lo, (long long)row * c_ld + col, v4);
         }
@@ -600,6 +601,11 @@ template <class Cfg, bool GBF16, int EPI, bool DUAL, bool AKS = false, bool BKS 
 inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
   if (!gemm3_fits<Cfg, AKS, BKS>(g)) return hipErrorInvalidValue;
   if (DUAL && g.B2.ld != g.B.ld) return hipErrorInvalidValue;          // B2 is fetched with B's offsets
+  if (g.slab_count > 0 && (EPI != EPI_STORE || DUAL || g.nseg > 0 || g.splitk > 1 || g.slab_first < 0 ||
+                           g.slab_first + g.slab_count > g.K / Cfg::BK))
+    return hipErrorInvalidValue;
+  if (g.E.beta != 0.f && (g.E.beta != 1.f || g.slab_count <= 0)) return hipErrorInvalidValue;
+  if (g.slab_count > 0) g.tail_slot = -1;   // (no split last round for a part of a contraction)
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   g.tiles_m = g.M / Cfg::BM;
   g.tiles_n = g.N / Cfg::BN;

@@ -215,3 +215,34 @@ def test_fallback_orthonormalisation_at_8192_bf16():
     assert relf(Q, Qn) < 1e-5
     assert relf(M, Bm - (1 - MU) * P @ R.T) < TOL
     assert relf(X.astype(np.float64) - x_in, -ETA * np.sqrt(m / n) * P @ Q.astype(np.float64).T) < TOL
+
+
+def test_captured_step_at_c4_replays_like_eager_steps():
+    """At 16384 x 53248, r = 1024 the first product runs in parts next to the parts of the bf16 copy of M + G, which are
+    launched on a second stream of the library's own.  A caller capturing its stream into a HIP graph captures both;
+    every replay must give what the eager step gives, bit for bit, with the program's own work between the replays."""
+    import torch
+    shape = (16384, 53248, 1024)
+    eager = GpuProblem([shape], True, "bf16")
+    graphed = GpuProblem([shape], True, "bf16")
+    B = graphed.B
+    g0 = eager.grads_np(0)
+    eager.upload_grads(g0)
+    graphed.upload_grads(g0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.dion_step(graphed.state, graphed.X[0], graphed.G[0], graphed.M[0], graphed.Q[0], MU, ETA)
+    torch.cuda.synchronize()
+    for t in range(3):
+        eager.upload_grads(eager.grads_np(t))
+        graphed.G[0].copy_(eager.G[0])
+        assert eager.step(MU, ETA) == (0, -1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert B.dion_last_status(graphed.state) == (0, -1)
+        for name in ("X", "M", "Q"):
+            assert torch.equal(getattr(eager, name)[0], getattr(graphed, name)[0]), (t, name)
+        print("replay", t, "equal", flush=True)
