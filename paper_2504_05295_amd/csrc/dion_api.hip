@@ -741,7 +741,7 @@ bool k1_in_parts(const RowCtx& c) {
   const long long tiles = (g.m / 256) * (g.r / 256) * c.batch;
   if (!(c.batch > 1 || tiles % c.st->cus == 0 || tiles < c.st->cus)) return false;
   // Worth it?  Side by side, the pass and the product took 0.65 of what they take one after the other as long as
-  // neither outlasts the other (measured at 16384 x 53248, r = 1024: 2.85 -> 2.62 ms for the stage), and every part
+  // neither outlasts the other (measured at 16384 x 53248, r = 1024: 2.85 -> 2.45 ms for the stage), and every part
   // after the first reads and rewrites the m x r result and ramps up and down once more (about 50 us).  At r = 4096
   // the two balance (7.26 against 7.33 ms); with short contractions (8192 x 8192, or the 196 matrices of the 3B
   // model) the parts cost far more than they hide.

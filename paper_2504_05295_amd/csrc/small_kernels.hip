@@ -465,16 +465,16 @@ __global__ void __launch_bounds__(256) sum_bf16_cols_kernel(void* const* table, 
   const long long stride = (long long)gridDim.x * blockDim.x, total = rows * c8_count;
   for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < total; w += stride) {
     const long long row = w / c8_count, i = row * cols8 + c8_first + (w - row * c8_count);
-    f32x4_t a = M[2 * i], b = M[2 * i + 1];
+    f32x4_t a = gload_nt<f32x4_t>(M + 2 * i), b = gload_nt<f32x4_t>(M + 2 * i + 1);
     if constexpr (GBF16) {
-      const u32x4_t g4 = ((const u32x4_t*)G)[i];
+      const u32x4_t g4 = gload_nt<u32x4_t>((const u32x4_t*)G + i);
       a += f32x4_t{bf16_lo(g4[0]), bf16_hi(g4[0]), bf16_lo(g4[1]), bf16_hi(g4[1])};
       b += f32x4_t{bf16_lo(g4[2]), bf16_hi(g4[2]), bf16_lo(g4[3]), bf16_hi(g4[3])};
     } else {
       a += ((const f32x4_t*)G)[2 * i];
       b += ((const f32x4_t*)G)[2 * i + 1];
     }
-    out[i] = u32x4_t{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
+    gstore_nt<u32x4_t>(out + i, u32x4_t{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])});
   }
 }
 hipError_t launch_sum_bf16_cols(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
@@ -484,7 +484,10 @@ hipError_t launch_sum_bf16_cols(void* const* table, int nslots, int batch, int s
     return hipErrorInvalidValue;
   const long long total = rows * (col_count / 8);
   long long blocks = (total + 255) / 256;
-  const long long cap = 256LL * 16 / (batch < 16 ? batch : 16) + 1;   // about 16 workgroups per compute unit over the whole launch
+  // Many short-lived workgroups (one or two steps per thread) and non-temporal accesses: this pass runs beside a product,
+  // and that is how it disturbs it least (C4 r = 1024, the K1 stage: 2.59 ms with 4097 workgroups per launch, 2.43 ms with
+  // 65537; plain accesses instead of hinted ones: + 0.15 ms)
+  const long long cap = 256LL * 256 / (batch < 16 ? batch : 16) + 1;
   if (blocks > cap) blocks = cap;
   const dim3 grid((unsigned)blocks, batch);
   if (gbf16) hipLaunchKernelGGL(sum_bf16_cols_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, rows, cols / 8, col_first / 8, col_count / 8);
