@@ -1070,9 +1070,11 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   if (c.ev) st->group_timed[gi] = 1;
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
-  STAGECHK(stage_b16(c));
+  // (the bf16 copy of M + G either here, or in parts beside the first product that reads it)
+  const bool parts = k1_in_parts(c);
+  if (!parts) STAGECHK(stage_b16(c));
   if (refresh) {
-    STAGECHK(stage_k1(c, true));                                                  // Z = B V
+    STAGECHK(stage_k1(c, true, SLOT_Q, false, nullptr, parts));                   // Z = B V
     if (c.big) HIPCHK(launch_convert_bf16(c.tab, NSLOTS, batch, SLOT_Z, direct12(c) ? SLOT_P16 : -1, direct12(c) ? -1 : SLOT_PT16, m, r, s));
     STAGECHK(stage_k2(c, SLOT_Z));                                                // R = B^T Z
     const int fin = (st->orth_mode == DION_ORTH_SHIFTED_CHOLQR3) ? SLOT_P1 : SLOT_R;
@@ -1084,7 +1086,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  STAGECHK(stage_k1(c, false));                                                   // W = B V
+  STAGECHK(stage_k1(c, false, SLOT_Q, false, nullptr, parts && !refresh));        // W = B V
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
   HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_Z, m, r, s));                  // d from the columns of W

@@ -246,3 +246,28 @@ def test_captured_step_at_c4_replays_like_eager_steps():
         for name in ("X", "M", "Q"):
             assert torch.equal(getattr(eager, name)[0], getattr(graphed, name)[0]), (t, name)
         print("replay", t, "equal", flush=True)
+
+
+def test_lazy_step_at_c4_product_in_parts():
+    """Lazy-Dion between refreshes at 16384 x 53248, r = 1024: W = (M + G) V is the product that runs in four parts
+    beside the parts of the bf16 copy.  W against its formula in fp64 on one whole row per 256-row tile and one whole
+    column per 256-column tile, segment by segment, on a second step (non-zero momentum)."""
+    m, n, r = 16384, 53248, 1024
+    gp = GpuProblem([(m, n, r)], True, "bf16")
+    B = gp.B
+    rng = np.random.default_rng(11)
+    for t in range(2):
+        g = gp.grads_np(t)[0]
+        gp.upload_grads([g])
+        x_in, m_in, v_in = gp.host()
+        assert gp.lazy_step(MU, ETA, False) == (0, -1)
+    g32 = gp.grad_as_f32(g, True)
+    W = gp.debug(0, B.DEBUG_Z)
+    zr, zc = one_per_tile(rng, m, 256), one_per_tile(rng, r, 256)
+    e = seg_relf(W[zr, :], orc.rows_Z(m_in, g32, v_in, zr), 256, 1)
+    assert e.max() <= 2e-2, e.max()
+    e = seg_relf(W[:, zc], orc.cols_Z(m_in, g32, v_in, zc), 256, 0)
+    assert e.max() <= 2e-2, e.max()
+    X, M, V = gp.host()
+    assert np.array_equal(V, v_in)                       # no refresh: V is untouched
+    assert np.isfinite(X).all() and np.isfinite(M).all()
