@@ -732,6 +732,21 @@ int stage_b16(const RowCtx& c) {
 // each part of the pass only once the product before it is on its way - the product's workgroups get their compute
 // units first and the pass fills in.  Everything on the second stream is back on the caller's before the last part of
 // the product starts; a caller capturing its stream into a graph captures both.
+// Parts over blocks of rows instead (K1_ROW_PARTS): each part a product of its own over a block of rows of M + G, whole
+// rounds of tiles each, nothing to add up and nothing read back - possible where a quarter of the output still has
+// a multiple of the compute units' number of tiles (16384 x 53248 at r = 4096: 4 x 256), and then the better choice
+// (there the parts over the contraction gained nothing: they reread and rewrite a 268 MB result three times).
+enum { K1_WHOLE = 0, K1_K_PARTS = 1, K1_ROW_PARTS = 2 };
+bool k1_in_parts(const RowCtx& c);
+int k1_parts_mode(const RowCtx& c) {
+  const Group& g = *c.g;
+  if (direct12(c) && c.st->side_stream && (g.m / 256) % K1_PARTS == 0) {
+    const long long tiles = (g.m / 256 / K1_PARTS) * (g.r / 256) * c.batch;
+    const double hidden = 0.35 * (8.0 * (double)g.m * (double)g.n / 5.2e12);
+    if (tiles % c.st->cus == 0 && hidden > 1.25 * (K1_PARTS - 1) * 50e-6) return K1_ROW_PARTS;
+  }
+  return k1_in_parts(c) ? K1_K_PARTS : K1_WHOLE;
+}
 bool k1_in_parts(const RowCtx& c) {
   const Group& g = *c.g;
   if (!direct12(c) || !c.st->side_stream) return false;
@@ -751,7 +766,7 @@ bool k1_in_parts(const RowCtx& c) {
   return hidden > 1.25 * extra;
 }
 int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out = false, bool* split_done = nullptr,
-             bool b16_in_parts = false) {
+             int b16_in_parts = K1_WHOLE) {
   if (split_done) *split_done = false;
   const Group& g = *c.g;
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
@@ -764,7 +779,7 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out
     if (direct12(c)) {
       dion_state* st = c.st;
       if (b16_in_parts) {
-        if (!k1_in_parts(c)) return DION_EINVAL;
+        if (k1_parts_mode(c) != b16_in_parts) return DION_EINVAL;
         HIPCHK(hipEventRecord(st->ev_fork, c.s));
         HIPCHK(hipStreamWaitEvent(st->side_stream, st->ev_fork, 0));
       }
@@ -783,11 +798,27 @@ int stage_k1(const RowCtx& c, bool keep_b16, int slot_q = SLOT_Q, bool split_out
         HIPCHK(gemm2_nt(G2_256x256, a, c.batch, c.s, KS_B));
         return DION_OK;
       }
+      if (b16_in_parts == K1_ROW_PARTS) {
+        const long long rows = m / K1_PARTS;
+        for (int q = 0; q < K1_PARTS; ++q) {
+          if (q >= 1) HIPCHK(hipStreamWaitEvent(st->side_stream, st->ev_main[q - 1], 0));
+          HIPCHK(launch_sum_bf16_cols(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, m, n, q * rows, rows, 0, n, st->side_stream));
+          HIPCHK(hipEventRecord(st->ev_part[q], st->side_stream));
+          HIPCHK(hipStreamWaitEvent(c.s, st->ev_part[q], 0));
+          HIPCHK(hipEventRecord(st->ev_main[q], c.s));
+          GemmArgs ap = a;
+          ap.M = (int)rows;
+          ap.A.off = q * rows * n;
+          ap.E.off = q * rows * r;
+          HIPCHK(gemm2_nt(G2_256x256, ap, c.batch, c.s, KS_B));
+        }
+        return DION_OK;
+      }
       // (equal parts: unequal ones, a short first part of the copy or a short last part of the product, measured the same)
       const long long cols = n / K1_PARTS;
       for (int q = 0; q < K1_PARTS; ++q) {
         if (q >= 1) HIPCHK(hipStreamWaitEvent(st->side_stream, st->ev_main[q - 1], 0));
-        HIPCHK(launch_sum_bf16_cols(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, m, n, q * cols, cols, st->side_stream));
+        HIPCHK(launch_sum_bf16_cols(c.tab, NSLOTS, c.batch, SLOT_M, SLOT_G, c.gbf16, SLOT_B16, m, n, 0, m, q * cols, cols, st->side_stream));
         HIPCHK(hipEventRecord(st->ev_part[q], st->side_stream));
         HIPCHK(hipStreamWaitEvent(c.s, st->ev_part[q], 0));
         HIPCHK(hipEventRecord(st->ev_main[q], c.s));
@@ -1022,7 +1053,7 @@ int step_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   const int m = (int)g.m, n = (int)g.n, r = (int)g.r;
   if (c.ev) st->group_timed[gi] = 1;
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  const bool parts = k1_in_parts(c);
+  const int parts = k1_parts_mode(c);
   if (!parts) STAGECHK(stage_b16(c));
   const float rank_tol = mode == STEP_KEEP_STATUS ? RANK_TOL : 0.f;
   bool z_split = false;
@@ -1071,7 +1102,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   // the refresh is reported as the orthonormalisation stage; there is no separate K2 stage in this variant
   STAGECHK(mark(c, DION_STAGE_ORTH, 0));
   // (the bf16 copy of M + G either here, or in parts beside the first product that reads it)
-  const bool parts = k1_in_parts(c);
+  const int parts = k1_parts_mode(c);
   if (!parts) STAGECHK(stage_b16(c));
   if (refresh) {
     STAGECHK(stage_k1(c, true, SLOT_Q, false, nullptr, parts));                   // Z = B V
@@ -1086,7 +1117,7 @@ int lazy_rows(dion_state* st, int gi, int row0, int batch, float mu, float eta, 
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 0));
   STAGECHK(mark(c, DION_STAGE_K2_BTP, 1));
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 0));
-  STAGECHK(stage_k1(c, false, SLOT_Q, false, nullptr, parts && !refresh));        // W = B V
+  STAGECHK(stage_k1(c, false, SLOT_Q, false, nullptr, refresh ? K1_WHOLE : parts));        // W = B V
   STAGECHK(mark(c, DION_STAGE_K1_BQ, 1));
   STAGECHK(mark(c, DION_STAGE_COLNORM, 0));
   HIPCHK(launch_colnorm(c.tab, NSLOTS, batch, SLOT_Z, m, r, s));                  // d from the columns of W

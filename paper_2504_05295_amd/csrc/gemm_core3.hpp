@@ -234,7 +234,8 @@ __global__ void __launch_bounds__(Cfg::NT, Cfg::MINW) gemm3_kernel(const GemmArg
   // in the pointer table inside the loop is a memory load, and the wait for it would also wait for every tile
   // load in flight.  (Separate variables: an array indexed by the pair number would live in scratch memory.)
   const int b_fixed = g.nseg > 0 ? -1 : g.B.slot0;
-  const unsigned char* const A0 = (const unsigned char*)(tab[g.nseg > 0 ? g.segA[0] : g.A.slot0]);
+  // (a single operand pair may start at a row of its left matrix: A.off elements in, for a product over a block of rows)
+  const unsigned char* const A0 = (const unsigned char*)(tab[g.nseg > 0 ? g.segA[0] : g.A.slot0]) + (g.nseg > 0 ? 0 : g.A.off * 2);
   const unsigned char* const A1 = nseg > 1 ? (const unsigned char*)(tab[g.segA[1]]) : A0;
   const unsigned char* const A2 = nseg > 2 ? (const unsigned char*)(tab[g.segA[2]]) : A0;
   const unsigned char* const B0 = (const unsigned char*)(tab[b_fixed >= 0 ? b_fixed : g.segB[0]]);
@@ -605,6 +606,7 @@ inline hipError_t launch_gemm3(GemmArgs g, int batch, hipStream_t stream) {
                            g.slab_first + g.slab_count > g.K / Cfg::BK))
     return hipErrorInvalidValue;
   if (g.E.beta != 0.f && (g.E.beta != 1.f || g.slab_count <= 0)) return hipErrorInvalidValue;
+  if (g.A.off != 0 && (AKS || g.nseg > 0 || g.A.off < 0 || g.A.off % 8)) return hipErrorInvalidValue;   // (k-fast single pair, 16-byte aligned)
   if (g.slab_count > 0) g.tail_slot = -1;   // (no split last round for a part of a contraction)
   const int kseg = g.nseg > 0 ? g.kseg : g.K;
   g.tiles_m = g.M / Cfg::BM;

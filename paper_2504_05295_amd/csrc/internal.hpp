@@ -127,9 +127,10 @@ hipError_t launch_copy_gated(void* const* table, int nslots, int batch, int slot
 // out16 = bf16(M + G) as [rows][cols]  (rows * cols a multiple of 8)
 hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
                            long long rows, long long cols, hipStream_t s);
-// ... for the columns [col_first, col_first + col_count) of every row only (multiples of 8)
+// ... for the columns [col_first, col_first + col_count) (multiples of 8) of the rows [row_first, row_first + row_count) only
 hipError_t launch_sum_bf16_cols(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
-                                long long rows, long long cols, long long col_first, long long col_count, hipStream_t s);
+                                long long rows, long long cols, long long row_first, long long row_count, long long col_first,
+                                long long col_count, hipStream_t s);
 hipError_t launch_fill_i32(void* const* table, int nslots, int batch, int slot, long long count, int value, hipStream_t s);
 // C[j][j] += shift_rel * trace(C[0:r,0:r]) for j < r (shifted Cholesky-QR); the trace is summed in a fixed order
 // (skip_slot >= 0 here and below: the int32 there non-zero means that the launch leaves this matrix alone)

@@ -453,18 +453,19 @@ __global__ void __launch_bounds__(256) sum_bf16_stream_kernel(void* const* table
     out[i] = u32x4_t{pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3])};
   }
 }
-// The same for the columns [8 c8_first, 8 (c8_first + c8_count)) of every row only (cols8 = columns / 8): one part of the
-// copy, so that the product over the part before it can run meanwhile.
+// The same for the columns [8 c8_first, 8 (c8_first + c8_count)) of the rows [row_first, row_first + rows) only
+// (cols8 = columns / 8): one part of the copy, so that the product over the part before it can run meanwhile.
 template <bool GBF16>
 __global__ void __launch_bounds__(256) sum_bf16_cols_kernel(void* const* table, int nslots, int slot_m, int slot_g, int slot_out16,
-                                                            long long rows, long long cols8, long long c8_first, long long c8_count) {
+                                                            long long row_first, long long rows, long long cols8, long long c8_first,
+                                                            long long c8_count) {
   void* const* tab = table + (size_t)blockIdx.y * nslots;
   const f32x4_t* M = (const f32x4_t*)tab[slot_m];
   const void* G = tab[slot_g];
   u32x4_t* out = (u32x4_t*)tab[slot_out16];
   const long long stride = (long long)gridDim.x * blockDim.x, total = rows * c8_count;
   for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < total; w += stride) {
-    const long long row = w / c8_count, i = row * cols8 + c8_first + (w - row * c8_count);
+    const long long row = w / c8_count, i = (row_first + row) * cols8 + c8_first + (w - row * c8_count);
     f32x4_t a = gload_nt<f32x4_t>(M + 2 * i), b = gload_nt<f32x4_t>(M + 2 * i + 1);
     if constexpr (GBF16) {
       const u32x4_t g4 = gload_nt<u32x4_t>((const u32x4_t*)G + i);
@@ -478,11 +479,12 @@ __global__ void __launch_bounds__(256) sum_bf16_cols_kernel(void* const* table, 
   }
 }
 hipError_t launch_sum_bf16_cols(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
-                                long long rows, long long cols, long long col_first, long long col_count, hipStream_t s) {
+                                long long rows, long long cols, long long row_first, long long row_count, long long col_first,
+                                long long col_count, hipStream_t s) {
   if (cols % 8 || col_first % 8 || col_count % 8 || col_first < 0 || col_count < 1 || col_first + col_count > cols || batch > 65535 ||
-      batch < 1)
+      batch < 1 || row_first < 0 || row_count < 1 || row_first + row_count > rows)
     return hipErrorInvalidValue;
-  const long long total = rows * (col_count / 8);
+  const long long total = row_count * (col_count / 8);
   long long blocks = (total + 255) / 256;
   // Many short-lived workgroups (one or two steps per thread) and non-temporal accesses: this pass runs beside a product,
   // and that is how it disturbs it least (C4 r = 1024, the K1 stage: 2.59 ms with 4097 workgroups per launch, 2.43 ms with
@@ -490,8 +492,8 @@ hipError_t launch_sum_bf16_cols(void* const* table, int nslots, int batch, int s
   const long long cap = 256LL * 256 / (batch < 16 ? batch : 16) + 1;
   if (blocks > cap) blocks = cap;
   const dim3 grid((unsigned)blocks, batch);
-  if (gbf16) hipLaunchKernelGGL(sum_bf16_cols_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, rows, cols / 8, col_first / 8, col_count / 8);
-  else hipLaunchKernelGGL(sum_bf16_cols_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, rows, cols / 8, col_first / 8, col_count / 8);
+  if (gbf16) hipLaunchKernelGGL(sum_bf16_cols_kernel<true>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, row_first, row_count, cols / 8, col_first / 8, col_count / 8);
+  else hipLaunchKernelGGL(sum_bf16_cols_kernel<false>, grid, dim3(256), 0, s, table, nslots, slot_m, slot_g, slot_out16, row_first, row_count, cols / 8, col_first / 8, col_count / 8);
   return hipGetLastError();
 }
 hipError_t launch_sum_bf16(void* const* table, int nslots, int batch, int slot_m, int slot_g, bool gbf16, int slot_out16,
