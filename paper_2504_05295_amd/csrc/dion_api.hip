@@ -741,7 +741,7 @@ bool k1_in_parts(const RowCtx& c);
 int k1_parts_mode(const RowCtx& c) {
   const Group& g = *c.g;
   if (direct12(c) && c.st->side_stream && (g.m / 256) % K1_PARTS == 0) {
-    const long long tiles = (g.m / 256 / K1_PARTS) * (g.r / 256) * c.batch;
+    const long long tiles = (g.m / 256 / K1_PARTS) * (g.r / 256);   // (per matrix, as below: alone and in a batch alike)
     const double hidden = 0.35 * (8.0 * (double)g.m * (double)g.n / 5.2e12);
     if (tiles % c.st->cus == 0 && hidden > 1.25 * (K1_PARTS - 1) * 50e-6) return K1_ROW_PARTS;
   }
